@@ -1,0 +1,226 @@
+/*
+ * tkv - decode-time attention of TailorKV's hybrid KV cache (arxiv 2505.19586)
+ * for AMD MI355X (gfx950).  C ABI.
+ *
+ * Two kinds of layers (Sec. 4.1 of the paper):
+ *   - quantization-friendly layers keep the whole cache on the GPU, quantized with
+ *     the uniform asymmetric quantizer of Sec. 2.2 (Eq. 4), keys per channel and
+ *     values per token (Sec. 4.3), zero-point and scaler in fp16 (Sec. 4.4);
+ *   - sparsity-friendly layers keep the full fp16 cache in pinned host memory and a
+ *     small critical-key summary on the GPU; each decode step scores every cached
+ *     token approximately, takes the Top-K, fetches only those tokens' K/V rows from
+ *     the host and attends exactly over n_local + n_topk tokens (Sec. 4.2, Sec. 5.1).
+ *
+ * Conventions
+ *   - Every function returns a tkv_status (0 = ok, negative = error).  Argument
+ *     errors are reported before anything is enqueued and never touch the GPU.
+ *   - The caller owns every buffer.  Unless an argument says "host", pointers are
+ *     device pointers.  The library allocates nothing and keeps no state between
+ *     calls (a few process-wide device queries are cached).
+ *   - Calls enqueue work on the given hipStream_t (passed as void*) and return
+ *     without synchronizing.  Sequence lengths live in caller-owned HOST int32
+ *     arrays; kernels receive them by value, so the arrays may be changed as soon as
+ *     a call returns.  At most TKV_MAX_BATCH sequences per call.
+ *   - fp16 is IEEE binary16 everywhere.  head_dim must be 128, the quantization
+ *     group 32, n_q_heads / n_kv_heads one of 1, 2, 4.
+ *   - Token t of sequence b, KV head h.  "group j" is tokens [32j, 32j+32).
+ */
+#ifndef TKV_H
+#define TKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TKV_MAX_BATCH 64
+
+typedef enum {
+  TKV_OK = 0,
+  TKV_E_INVAL = -1,       /* NULL pointer, bad struct_size, inconsistent shapes            */
+  TKV_E_UNSUPPORTED = -2, /* valid request the kernels are not built for (bits, dims, ...) */
+  TKV_E_CAPACITY = -3,    /* sequence length would exceed the cache capacity               */
+  TKV_E_WORKSPACE = -4,   /* workspace smaller than tkv_*_cache_sizes reports              */
+  TKV_E_NOTPINNED = -5,   /* kv_host is not device-accessible pinned host memory           */
+  TKV_E_HIP = -6          /* a HIP runtime call failed (also: no usable GPU)               */
+} tkv_status;
+
+const char* tkv_strerror(int32_t status);
+
+/* ---------------------------------------------------------------------------------
+ * Quantization-friendly layers
+ * ------------------------------------------------------------------------------- */
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(tkv_quant_desc)                                        */
+  int32_t n_q_heads;    /* Hq                                                            */
+  int32_t n_kv_heads;   /* Hkv; query head i reads KV head i / (Hq/Hkv)                  */
+  int32_t head_dim;     /* D = 128                                                       */
+  int32_t bits;         /* b = 2 or 4 (Eq. 4)                                            */
+  int32_t group_size;   /* g = 32: tokens per key group, channels per value group        */
+  int32_t residual;     /* W: newest tokens kept fp16; multiple of g, g <= W <= 992      */
+  int32_t capacity;     /* max tokens per sequence, multiple of g                        */
+  int32_t batch;        /* B, 1..TKV_MAX_BATCH                                           */
+} tkv_quant_desc;
+
+/*
+ * Cache buffers of one layer.  With N tokens in a sequence, the first
+ * Nq = g*floor((N-W)/g) (0 if N < W) are quantized, the last N-Nq (W..W+g-1 once
+ * N >= W) are fp16 in a ring: token t >= Nq sits at ring slot t mod (W+g).
+ *
+ * Packed layouts (J = capacity/32 groups; t = token inside its group, c = channel;
+ * a code takes `bits` bits at field F, i.e. bits [bits*F, bits*F+bits) of a
+ * little-endian 32-bit word).  The order inside a group is the order in which a
+ * wave64 feeds 16x16x32 matrix-core operands from one 128-bit load per lane.
+ *
+ *  k_codes uint32 [B][Hkv][J][128*bits/... = 32*128*bits/32 words]
+ *    2 bit: word = 4*lane + 2*tau + wd,  F = f + 8*e, with
+ *           r = 4*(t/8) + t%4, tau = (t%8)/4, lane = r + 16*((c%32)/8),
+ *           wd = c/64, f = (c%8)/2 + 4*((c/32)%2), e = c%2
+ *    4 bit: word = 256*tau + 4*lane + c/32, F = (c%8)/2 + 4*(c%2)   (r, tau, lane as above)
+ *  v_codes uint32 [B][Hkv][J][32*128*bits/32 words]
+ *    2 bit: word = 4*lane + wd, F = f + 8*e, with
+ *           lane = c%16 + 16*(t/8), wd = c/32, f = (t%8)/2 + 4*((c/16)%2), e = t%2
+ *    4 bit: word = 256*(c/64) + 4*lane + (c/16)%4, F = (t%8)/2 + 4*(t%2)
+ *  k_scale, k_zero  fp16 [B][Hkv][J][128]      one (s, z) per group and channel
+ *  v_scale, v_zero  fp16 [B][Hkv][J][4][32]    one (s, z) per token and 32-channel
+ *                                              group u = c/32, stored [u][t]
+ *  k_resid, v_resid fp16 [B][Hkv][W+g][128]    ring of unquantized tokens
+ */
+typedef struct {
+  void* k_codes;
+  void* k_scale;
+  void* k_zero;
+  void* v_codes;
+  void* v_scale;
+  void* v_zero;
+  void* k_resid;
+  void* v_resid;
+  int32_t* seq_len_host; /* HOST int32 [B]: tokens in each sequence; append updates it */
+} tkv_quant_cache;
+
+/*
+ * Bytes of each tkv_quant_cache buffer in field order (k_codes ... v_resid) and of
+ * the workspace tkv_quant_attn_decode needs.  The code and scaler/zero-point bytes
+ * add up to the memory model of Sec. 4.4, Table 2: 2*n*h*d_h*(b/16 + 2/g) fp16
+ * elements per layer.  Either output pointer may be NULL.
+ */
+int32_t tkv_quant_cache_sizes(const tkv_quant_desc* desc, size_t bytes_out[8], size_t* workspace_bytes);
+
+/*
+ * Sec. 2.1 Eq. 2 (cache update) + Sec. 2.2 Eq. 4 / Sec. 4.3 (static quantization).
+ * Appends n_new tokens to every sequence: k_new, v_new fp16 [B][n_new][Hkv][128]
+ * (device).  Every token group that becomes complete and older than the residual is
+ * quantized: keys per channel over the group's 32 tokens, values per token over each
+ * 32-channel group, with
+ *     z = min X (stored as is), s = fp16( (f32(max X) - f32(min X)) / f32(2^b - 1) ),
+ *     code = clamp( rint( (f32(x) - f32(z)) / f32(s) ), 0, 2^b - 1 ), rint ties-to-even,
+ *     code = 0 where the stored s is 0,
+ * every operation a single float32 operation.  seq_len_host[b] += n_new on success.
+ * n_new == 0 is a no-op.  Errors: TKV_E_CAPACITY if any seq_len + n_new > capacity.
+ */
+int32_t tkv_quantize_append(const tkv_quant_desc* desc, tkv_quant_cache* cache, const void* k_new,
+                            const void* v_new, int32_t n_new, void* stream);
+
+/* Same, for a padded batch: k_new, v_new hold n_new rows per sequence of which only
+ * the first n_valid_host[b] (HOST int32 [B], 0 <= n_valid <= n_new) are appended to
+ * sequence b.  n_valid_host == NULL means n_new for every sequence. */
+int32_t tkv_quantize_append_ragged(const tkv_quant_desc* desc, tkv_quant_cache* cache, const void* k_new,
+                                   const void* v_new, int32_t n_new, const int32_t* n_valid_host, void* stream);
+
+/*
+ * Sec. 2.1 Eq. 3 over the dequantized cache (Sec. 4.3): for every query head,
+ * logits = sm_scale * q . (code*s + z) over the quantized tokens and sm_scale * q . k
+ * over the fp16 tail, one softmax over all N tokens, out = weights . V-hat.
+ * q, out: fp16 [B][Hq][128].  A sequence with 0 tokens yields zeros.
+ * The work is split over token chunks whose partial (max, sum, weighted V) results
+ * go through `workspace` and are merged with a log-sum-exp merge.
+ */
+int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache* cache, const void* q,
+                              void* out, float sm_scale, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Sparsity-friendly layers
+ * ------------------------------------------------------------------------------- */
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(tkv_sparse_desc)                                        */
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;     /* 128                                                            */
+  int32_t n_channels;   /* d_s: critical channels kept on the GPU; 16 (or 8)              */
+  int32_t top_k;        /* n_topk: tokens fetched per KV head, 1..4096                    */
+  int32_t n_sink;       /* first tokens always resident; with n_window this is n_local    */
+  int32_t n_window;     /* newest tokens always resident; 1..1024                         */
+  int32_t capacity;     /* max tokens per sequence                                        */
+  int32_t batch;
+} tkv_sparse_desc;
+
+typedef struct {
+  void* key_summary;     /* fp16 [B][Hkv][capacity][d_s]: channels channel_idx of every key */
+  int32_t* channel_idx;  /* int32 [B][Hkv][d_s] ascending, an input                          */
+  void* kv_host;         /* PINNED HOST fp16 [B][Hkv][capacity][2][128]: K row then V row     */
+  void* kv_local;        /* fp16 [B][Hkv][n_sink + n_window][2][128]: token t < n_sink at
+                            slot t, any other token at slot n_sink + t mod n_window          */
+  int32_t* seq_len_host; /* HOST int32 [B]                                                   */
+} tkv_sparse_cache;
+
+/* Bytes of key_summary, channel_idx, kv_host, kv_local; workspace bytes for
+ * tkv_sparse_estimate_topk and tkv_sparse_gather_attn (the larger of the two). */
+int32_t tkv_sparse_cache_sizes(const tkv_sparse_desc* desc, size_t bytes_out[4], size_t* workspace_bytes);
+
+/*
+ * Eq. 2 for a sparsity-friendly layer: k_new, v_new fp16 [B][n_new][Hkv][128] (device)
+ * are written to the host cache, their critical channels to key_summary and the rows
+ * that belong to sinks/window to kv_local.  seq_len_host[b] += n_new.
+ */
+int32_t tkv_sparse_append(const tkv_sparse_desc* desc, tkv_sparse_cache* cache, const void* k_new,
+                          const void* v_new, int32_t n_new, void* stream);
+/* Padded-batch form, as tkv_quantize_append_ragged. */
+int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* desc, tkv_sparse_cache* cache, const void* k_new,
+                                 const void* v_new, int32_t n_new, const int32_t* n_valid_host, void* stream);
+
+/*
+ * Stage 2 of Sec. 4.2: approximate scores from the critical query channels and the
+ * critical key cache, then Top-K.  For KV head h and candidate token
+ * t in [n_sink, N - n_window):
+ *     a_j  = (((p_0 + p_1) + p_2) + ... ),  p_i = f32(q_j[c_i]) * f32(summary[t][i]),
+ *     S(t) = ((a_0 + a_1) + ...) over the group's query heads j ascending, + 0.0f,
+ * all float32, products exact.  The k = min(top_k, #candidates) tokens with the
+ * largest S (ties: lower index first) are written to topk_idx [B][Hkv][top_k] in
+ * ASCENDING token order, padded with -1; topk_count [B][Hkv] gets k.
+ * Scores must be finite.
+ */
+int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,
+                                 int32_t* topk_idx, int32_t* topk_count, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/*
+ * Fetch of the Top-K tokens from the host cache (Sec. 4.2; the one transfer that
+ * cannot be hidden) and exact attention (Eq. 3) of every query head over
+ * sinks [0, n_sink) U selected U window [N - n_window, N) (Sec. 5.1: n_local + n_topk).
+ * staging: fp16 [B][Hkv][top_k][2][128] device buffer the rows are gathered into.
+ * The gather kernel runs on gather_stream after everything already enqueued on
+ * compute_stream (which produced topk_idx); attention runs on compute_stream after
+ * the gather.  The two streams may be the same.  out: fp16 [B][Hq][128].
+ */
+int32_t tkv_sparse_gather_attn(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,
+                               const int32_t* topk_idx, const int32_t* topk_count, void* out,
+                               float sm_scale, void* staging, void* workspace, size_t workspace_bytes,
+                               void* gather_stream, void* compute_stream);
+
+/* The two halves of tkv_sparse_gather_attn as separate calls (for pipelining the
+ * gather of one layer under other layers' compute, and for timing the link alone). */
+int32_t tkv_sparse_gather(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const int32_t* topk_idx,
+                          const int32_t* topk_count, void* staging, void* stream);
+int32_t tkv_sparse_attn(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,
+                        const int32_t* topk_count, const void* staging, void* out, float sm_scale,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TKV_H */

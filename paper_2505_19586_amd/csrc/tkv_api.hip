@@ -1,0 +1,103 @@
+// Status strings, descriptor validation and buffer-size helpers of the tkv C ABI.
+#include "tkv_common.h"
+
+extern "C" const char* tkv_strerror(int32_t status) {
+  switch (status) {
+    case TKV_OK: return "ok";
+    case TKV_E_INVAL: return "invalid argument";
+    case TKV_E_UNSUPPORTED: return "configuration not supported by the gfx950 kernels";
+    case TKV_E_CAPACITY: return "sequence length exceeds cache capacity";
+    case TKV_E_WORKSPACE: return "workspace too small";
+    case TKV_E_NOTPINNED: return "kv_host is not device-accessible pinned host memory";
+    case TKV_E_HIP: return "HIP runtime error";
+    default: return "unknown tkv status";
+  }
+}
+
+namespace tkv {
+
+static int32_t check_heads(int32_t hq, int32_t hkv, int32_t d, int32_t batch) {
+  if (hq <= 0 || hkv <= 0 || d <= 0 || batch <= 0) return TKV_E_INVAL;
+  if (hq % hkv != 0) return TKV_E_INVAL;
+  if (batch > TKV_MAX_BATCH) return TKV_E_UNSUPPORTED;
+  if (d != TKV_D) return TKV_E_UNSUPPORTED;
+  const int32_t g = hq / hkv;
+  if (g != 1 && g != 2 && g != 4) return TKV_E_UNSUPPORTED;
+  return TKV_OK;
+}
+
+int32_t check_quant_desc(const tkv_quant_desc* d) {
+  if (!d || d->struct_size != sizeof(tkv_quant_desc)) return TKV_E_INVAL;
+  int32_t st = check_heads(d->n_q_heads, d->n_kv_heads, d->head_dim, d->batch);
+  if (st != TKV_OK) return st;
+  if (d->group_size <= 0 || d->residual < 0 || d->capacity <= 0 || d->bits <= 0) return TKV_E_INVAL;
+  if (d->bits != 2 && d->bits != 4) return TKV_E_UNSUPPORTED;
+  if (d->group_size != TKV_G) return TKV_E_UNSUPPORTED;
+  if (d->residual % TKV_G != 0 || d->capacity % TKV_G != 0) return TKV_E_INVAL;
+  if (d->residual < TKV_G || d->residual > 992) return TKV_E_UNSUPPORTED;
+  return TKV_OK;
+}
+
+int32_t check_sparse_desc(const tkv_sparse_desc* d) {
+  if (!d || d->struct_size != sizeof(tkv_sparse_desc)) return TKV_E_INVAL;
+  int32_t st = check_heads(d->n_q_heads, d->n_kv_heads, d->head_dim, d->batch);
+  if (st != TKV_OK) return st;
+  if (d->n_channels <= 0 || d->top_k <= 0 || d->n_sink < 0 || d->n_window <= 0 || d->capacity <= 0)
+    return TKV_E_INVAL;
+  if (d->n_channels != 16 && d->n_channels != 8) return TKV_E_UNSUPPORTED;
+  if (d->top_k > 4096 || d->n_window > 1024 || d->n_sink > 1024) return TKV_E_UNSUPPORTED;
+  return TKV_OK;
+}
+
+}  // namespace tkv
+
+extern "C" int32_t tkv_quant_cache_sizes(const tkv_quant_desc* d, size_t bytes_out[8], size_t* workspace_bytes) {
+  int32_t st = tkv::check_quant_desc(d);
+  if (st != TKV_OK) return st;
+  const size_t bh = (size_t)d->batch * d->n_kv_heads;
+  const size_t cap = (size_t)d->capacity;
+  const size_t codes = bh * cap * TKV_D * d->bits / 8;
+  const size_t kmeta = bh * (cap / TKV_G) * TKV_D * 2;
+  const size_t vmeta = bh * cap * (TKV_D / TKV_G) * 2;
+  const size_t resid = bh * (size_t)(d->residual + TKV_G) * TKV_D * 2;
+  if (bytes_out) {
+    bytes_out[0] = codes;
+    bytes_out[1] = kmeta;
+    bytes_out[2] = kmeta;
+    bytes_out[3] = codes;
+    bytes_out[4] = vmeta;
+    bytes_out[5] = vmeta;
+    bytes_out[6] = resid;
+    bytes_out[7] = resid;
+  }
+  if (workspace_bytes) {
+    // split-K partials: [B][Hq][chunks + tail][D + 2] float, plus one arrival
+    // counter per (sequence, KV head)
+    *workspace_bytes = (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float) +
+                       bh * sizeof(uint32_t) + 256;
+  }
+  return TKV_OK;
+}
+
+extern "C" int32_t tkv_sparse_cache_sizes(const tkv_sparse_desc* d, size_t bytes_out[4], size_t* workspace_bytes) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  const size_t bh = (size_t)d->batch * d->n_kv_heads;
+  const size_t cap = (size_t)d->capacity;
+  if (bytes_out) {
+    bytes_out[0] = bh * cap * d->n_channels * 2;
+    bytes_out[1] = bh * d->n_channels * sizeof(int32_t);
+    bytes_out[2] = bh * cap * 2 * TKV_D * 2;
+    bytes_out[3] = bh * (size_t)(d->n_sink + d->n_window) * 2 * TKV_D * 2;
+  }
+  if (workspace_bytes) {
+    // estimate_topk: score keys uint32 [B][Hkv][capacity] + histograms / counters;
+    // gather_attn: split partials.  See tkv_sparse.hip for the carve-up.
+    const size_t keys = bh * cap * sizeof(uint32_t);
+    const size_t hist = bh * (size_t)(3 * 2048 + 64) * sizeof(uint32_t);
+    const size_t blocks = bh * (size_t)((cap + 1023) / 1024 + 1) * 2 * sizeof(uint32_t);
+    const size_t parts = (size_t)d->batch * d->n_q_heads * 64 * TKV_PART_STRIDE * sizeof(float);
+    *workspace_bytes = keys + hist + blocks + parts + 1024;
+  }
+  return TKV_OK;
+}

@@ -1,0 +1,108 @@
+// Internal helpers shared by the tkv HIP sources (gfx950 only).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tkv.h"
+
+#define TKV_D 128      // head_dim
+#define TKV_G 32       // quantization group
+#define TKV_WAVE 64
+
+// Partial attention result of one chunk and one query head: max logit (in log2
+// units after scaling), sum of weights, weighted V sum.
+#define TKV_PART_STRIDE (TKV_D + 2)
+
+// Upper bound on split-K chunks per (sequence, KV head), tail chunk excluded.
+#define TKV_MAX_CHUNKS 256
+
+#define TKV_HIP_TRY(expr)                      \
+  do {                                         \
+    hipError_t _e = (expr);                    \
+    if (_e != hipSuccess) return TKV_E_HIP;    \
+  } while (0)
+
+struct TkvSeqLens {
+  int32_t n[TKV_MAX_BATCH];
+};
+
+namespace tkv {
+
+// Number of quantized tokens of a sequence of n tokens (residual w, group 32).
+__host__ __device__ inline int32_t n_quantized(int32_t n, int32_t w) {
+  return n >= w ? ((n - w) / TKV_G) * TKV_G : 0;
+}
+
+inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? TKV_OK : TKV_E_HIP; }
+
+int32_t check_quant_desc(const tkv_quant_desc* d);
+// Merges [n_heads_total][n_parts][D + 2] float partials (max in log2 units, sum,
+// weighted V) into fp16 [n_heads_total][D].
+int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, int n_parts, hipStream_t s);
+int32_t check_sparse_desc(const tkv_sparse_desc* d);
+
+// Position of logical element (t, c) of a 32x128 group inside the packed block:
+// word index and field index.  Mirrors the layout text of tkv.h.
+__host__ __device__ inline void k_code_pos(int bits, int t, int c, int& word, int& field) {
+  const int r = 4 * (t / 8) + t % 4, tau = (t % 8) / 4;
+  const int lane = r + 16 * ((c % 32) / 8);
+  if (bits == 2) {
+    word = 4 * lane + 2 * tau + c / 64;
+    field = (c % 8) / 2 + 4 * ((c / 32) % 2) + 8 * (c % 2);
+  } else {
+    word = 256 * tau + 4 * lane + c / 32;
+    field = (c % 8) / 2 + 4 * (c % 2);
+  }
+}
+
+__host__ __device__ inline void v_code_pos(int bits, int t, int c, int& word, int& field) {
+  const int lane = c % 16 + 16 * (t / 8);
+  if (bits == 2) {
+    word = 4 * lane + c / 32;
+    field = (t % 8) / 2 + 4 * ((c / 16) % 2) + 8 * (t % 2);
+  } else {
+    word = 256 * (c / 64) + 4 * lane + (c / 16) % 4;
+    field = (t % 8) / 2 + 4 * (t % 2);
+  }
+}
+
+// Inverse maps: which (t, c) does field F of word w hold.
+__host__ __device__ inline void k_code_elem(int bits, int w, int F, int& t, int& c) {
+  int lane, tau, r, kb;
+  if (bits == 2) {
+    lane = w / 4;
+    tau = (w % 4) / 2;
+    const int wd = w % 2, f = F % 8, e = F / 8;
+    r = lane % 16;
+    kb = lane / 16;
+    c = 64 * wd + 32 * (f / 4) + 8 * kb + 2 * (f % 4) + e;
+  } else {
+    tau = w / 256;
+    lane = (w % 256) / 4;
+    const int m = w % 4, f = F % 4, e = F / 4;
+    r = lane % 16;
+    kb = lane / 16;
+    c = 32 * m + 8 * kb + 2 * f + e;
+  }
+  t = 8 * (r / 4) + 4 * tau + r % 4;
+}
+
+__host__ __device__ inline void v_code_elem(int bits, int w, int F, int& t, int& c) {
+  if (bits == 2) {
+    const int lane = w / 4, wd = w % 4, f = F % 8, e = F / 8;
+    const int r = lane % 16, kb = lane / 16;
+    const int cb = 2 * wd + f / 4;
+    t = 8 * kb + 2 * (f % 4) + e;
+    c = 16 * cb + r;
+  } else {
+    const int lam = w / 256, lane = (w % 256) / 4, f = F % 4, e = F / 4;
+    const int r = lane % 16, kb = lane / 16;
+    const int cb = 4 * lam + w % 4;
+    t = 8 * kb + 2 * f + e;
+    c = 16 * cb + r;
+  }
+}
+
+}  // namespace tkv

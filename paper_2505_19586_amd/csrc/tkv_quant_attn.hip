@@ -1,0 +1,299 @@
+// tkv_quant_attn_decode: Eq. 3 (Sec. 2.1) over the dequantized cache of a
+// quantization-friendly layer (Sec. 4.3), split over token chunks with a
+// log-sum-exp merge.
+#include "tkv_common.h"
+
+namespace tkv {
+// matrix-core path (tkv_quant_attn_mfma.hip); returns TKV_E_UNSUPPORTED when the
+// shape is not one it is built for.
+int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, float scale2,
+                               float* parts, int groups_per_chunk, int n_chunks, const TkvSeqLens& lens,
+                               hipStream_t s);
+}  // namespace tkv
+
+namespace {
+
+struct QuantAttnParams {
+  const uint32_t* k_codes;
+  const uint32_t* v_codes;
+  const __half* k_scale;
+  const __half* k_zero;
+  const __half* v_scale;
+  const __half* v_zero;
+  const __half* k_resid;
+  const __half* v_resid;
+  const __half* q;
+  float* parts;  // [B][Hq][n_chunks + 1][D + 2]
+  float scale2;  // sm_scale * log2(e)
+  int32_t hq, hkv, bits, residual, capacity;
+  int32_t groups_per_chunk, n_chunks;
+  TkvSeqLens lens;
+};
+
+__device__ inline float wave_half_max(float v) {
+  // max over the 32 lanes that share l / 32
+  for (int m = 16; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+
+// Shape-generic reference kernel: plain float32 arithmetic, one wave per 32-token
+// block, no matrix cores.  Correct for every supported descriptor; the tuned
+// kernel takes over where it applies.
+__global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams p) {
+  __shared__ float qs[4][TKV_D];            // query heads of this KV head, zero padded
+  __shared__ float ksz[4][TKV_D][2];        // per wave: K scale, zero of the current group
+  __shared__ float pw[4][4][TKV_G];         // per wave: weights p[h][t]
+  __shared__ float alpha_s[4][4];           // per wave: rescale factors
+  __shared__ uint32_t vblk[4][TKV_D * 4];   // per wave: packed V block (<= 512 words)
+  __shared__ float red_m[4][4], red_l[4][4];
+  __shared__ float red_o[4][4][TKV_D];
+
+  const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+  const int G = p.hq / p.hkv;
+  const int n = p.lens.n[b];
+  const int nq = tkv::n_quantized(n, p.residual);
+  const int jq = nq / TKV_G;
+  const size_t bh = (size_t)b * p.hkv + h;
+  const int n_groups_cap = p.capacity / TKV_G;
+  const int nwords = TKV_D * p.bits;
+  const int ring = p.residual + TKV_G;
+  const bool tail = chunk == p.n_chunks;
+
+  for (int i = tid; i < 4 * TKV_D; i += 256) {
+    const int hh = i / TKV_D, c = i % TKV_D;
+    qs[hh][c] = hh < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c]) : 0.f;
+  }
+  __syncthreads();
+
+  // blocks of 32 tokens this workgroup owns: [blk0, blk1)
+  int blk0, blk1;
+  if (!tail) {
+    blk0 = chunk * p.groups_per_chunk;
+    blk1 = min(blk0 + p.groups_per_chunk, jq);
+  } else {
+    blk0 = 0;
+    blk1 = (n - nq + TKV_G - 1) / TKV_G;
+  }
+
+  const int t = lane % 32, hp = lane / 32;
+  float m_run[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  float l_run[4] = {0.f, 0.f, 0.f, 0.f};
+  float o_run[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
+  const int c0 = 2 * lane, u = c0 / TKV_G;
+
+  for (int blk = blk0 + wave; blk < blk1; blk += 4) {
+    float acc0 = 0.f, acc1 = 0.f;
+    bool valid = true;
+    if (!tail) {
+      const size_t grp = bh * n_groups_cap + blk;
+      // K scale / zero of this group -> LDS
+      for (int c = lane; c < TKV_D; c += 64) {
+        ksz[wave][c][0] = __half2float(p.k_scale[grp * TKV_D + c]);
+        ksz[wave][c][1] = __half2float(p.k_zero[grp * TKV_D + c]);
+      }
+      for (int w = lane; w < nwords; w += 64) vblk[wave][w] = p.v_codes[grp * nwords + w];
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_s_waitcnt(0);
+      const uint32_t* kblk = p.k_codes + grp * nwords;
+      const uint32_t cmask = (1u << p.bits) - 1u;
+      for (int c = 0; c < TKV_D; ++c) {
+        int w, f;
+        tkv::k_code_pos(p.bits, t, c, w, f);
+        const float code = (float)((kblk[w] >> (p.bits * f)) & cmask);
+        const float kh = code * ksz[wave][c][0] + ksz[wave][c][1];
+        acc0 += qs[2 * hp][c] * kh;
+        acc1 += qs[2 * hp + 1][c] * kh;
+      }
+    } else {
+      const int tok = nq + blk * TKV_G + t;
+      valid = tok < n;
+      if (valid) {
+        const __half* krow = p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D;
+        for (int c = 0; c < TKV_D; ++c) {
+          const float kh = __half2float(krow[c]);
+          acc0 += qs[2 * hp][c] * kh;
+          acc1 += qs[2 * hp + 1][c] * kh;
+        }
+      }
+    }
+    const float x0 = valid ? acc0 * p.scale2 : -INFINITY;
+    const float x1 = valid ? acc1 * p.scale2 : -INFINITY;
+    const float g0 = wave_half_max(x0), g1 = wave_half_max(x1);
+    // publish p and alpha for this wave
+    {
+      const float mo0 = m_run[2 * hp], mo1 = m_run[2 * hp + 1];
+      const float mn0 = fmaxf(mo0, g0), mn1 = fmaxf(mo1, g1);
+      pw[wave][2 * hp][t] = exp2f(x0 - mn0);
+      pw[wave][2 * hp + 1][t] = exp2f(x1 - mn1);
+      if (t == 0) {
+        alpha_s[wave][2 * hp] = exp2f(mo0 - mn0);
+        alpha_s[wave][2 * hp + 1] = exp2f(mo1 - mn1);
+      }
+      // every lane tracks all four maxima; fetch the other half's via LDS below
+      red_m[wave][2 * hp] = mn0;
+      red_m[wave][2 * hp + 1] = mn1;
+    }
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0);
+    float al[4];
+    for (int hh = 0; hh < 4; ++hh) {
+      al[hh] = alpha_s[wave][hh];
+      m_run[hh] = red_m[wave][hh];
+    }
+    // P.V for channels c0, c0+1
+    float s0[4] = {0.f, 0.f, 0.f, 0.f}, s1[4] = {0.f, 0.f, 0.f, 0.f}, ls[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int tt = 0; tt < TKV_G; ++tt) {
+      float v0, v1;
+      if (!tail) {
+        const size_t grp = bh * n_groups_cap + blk;
+        const float sc = __half2float(p.v_scale[(grp * 4 + u) * TKV_G + tt]);
+        const float ze = __half2float(p.v_zero[(grp * 4 + u) * TKV_G + tt]);
+        const uint32_t cmask = (1u << p.bits) - 1u;
+        int w, f;
+        tkv::v_code_pos(p.bits, tt, c0, w, f);
+        v0 = (float)((vblk[wave][w] >> (p.bits * f)) & cmask) * sc + ze;
+        tkv::v_code_pos(p.bits, tt, c0 + 1, w, f);
+        v1 = (float)((vblk[wave][w] >> (p.bits * f)) & cmask) * sc + ze;
+      } else {
+        const int tok = nq + blk * TKV_G + tt;
+        if (tok < n) {
+          const __half* vrow = p.v_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D;
+          v0 = __half2float(vrow[c0]);
+          v1 = __half2float(vrow[c0 + 1]);
+        } else {
+          v0 = v1 = 0.f;
+        }
+      }
+      for (int hh = 0; hh < 4; ++hh) {
+        const float pp = pw[wave][hh][tt];
+        s0[hh] += pp * v0;
+        s1[hh] += pp * v1;
+        ls[hh] += pp;
+      }
+    }
+    for (int hh = 0; hh < 4; ++hh) {
+      o_run[hh][0] = o_run[hh][0] * al[hh] + s0[hh];
+      o_run[hh][1] = o_run[hh][1] * al[hh] + s1[hh];
+      l_run[hh] = l_run[hh] * al[hh] + ls[hh];
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  // merge the four waves
+  __syncthreads();
+  if (lane == 0)
+    for (int hh = 0; hh < 4; ++hh) {
+      red_m[wave][hh] = m_run[hh];
+      red_l[wave][hh] = l_run[hh];
+    }
+  for (int hh = 0; hh < 4; ++hh) {
+    red_o[wave][hh][c0] = o_run[hh][0];
+    red_o[wave][hh][c0 + 1] = o_run[hh][1];
+  }
+  __syncthreads();
+  const int n_parts = p.n_chunks + 1;
+  for (int i = tid; i < G * TKV_D; i += 256) {
+    const int hh = i / TKV_D, c = i % TKV_D;
+    float M = -INFINITY;
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, red_m[w][hh]);
+    float L = 0.f, O = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      const float mw = red_m[w][hh];
+      const float wgt = mw == -INFINITY ? 0.f : exp2f(mw - M);
+      L += red_l[w][hh] * wgt;
+      O += red_o[w][hh][c] * wgt;
+    }
+    float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * n_parts + chunk) * TKV_PART_STRIDE;
+    dst[2 + c] = O;
+    if (c == 0) {
+      dst[0] = M;
+      dst[1] = L;
+    }
+  }
+}
+
+// Log-sum-exp merge of the chunk partials of one query head; writes fp16.
+__global__ __launch_bounds__(TKV_D) void attn_merge_kernel(const float* parts, __half* out, int n_parts) {
+  const size_t head = blockIdx.x;  // b * Hq + i
+  const int c = threadIdx.x;
+  const float* base = parts + head * n_parts * TKV_PART_STRIDE;
+  float M = -INFINITY;
+  for (int k = 0; k < n_parts; ++k) M = fmaxf(M, base[(size_t)k * TKV_PART_STRIDE]);
+  float L = 0.f, O = 0.f;
+  for (int k = 0; k < n_parts; ++k) {
+    const float* pk = base + (size_t)k * TKV_PART_STRIDE;
+    const float mk = pk[0];
+    const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
+    L += pk[1] * w;
+    O += pk[2 + c] * w;
+  }
+  out[head * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
+}
+
+}  // namespace
+
+namespace tkv {
+int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, int n_parts, hipStream_t s) {
+  attn_merge_kernel<<<dim3(n_heads_total), TKV_D, 0, s>>>(parts, out, n_parts);
+  return launch_status();
+}
+}  // namespace tkv
+
+extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q,
+                                         void* out, float sm_scale, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+  int32_t st = tkv::check_quant_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->seq_len_host || !q || !out || !workspace) return TKV_E_INVAL;
+  if (!c->k_codes || !c->k_scale || !c->k_zero || !c->v_codes || !c->v_scale || !c->v_zero || !c->k_resid ||
+      !c->v_resid)
+    return TKV_E_INVAL;
+  size_t need = 0;
+  tkv_quant_cache_sizes(d, nullptr, &need);
+  if (workspace_bytes < need) return TKV_E_WORKSPACE;
+
+  QuantAttnParams p;
+  int max_groups = 0;
+  for (int b = 0; b < d->batch; ++b) {
+    const int32_t n = c->seq_len_host[b];
+    if (n < 0) return TKV_E_INVAL;
+    if (n > d->capacity) return TKV_E_CAPACITY;
+    p.lens.n[b] = n;
+    const int g = tkv::n_quantized(n, d->residual) / TKV_G;
+    if (g > max_groups) max_groups = g;
+  }
+  // Chunking: aim at ~4 workgroups per compute unit over the whole launch.
+  const int bh = d->batch * d->n_kv_heads;
+  int target = (1024 + bh - 1) / bh;
+  if (target > TKV_MAX_CHUNKS) target = TKV_MAX_CHUNKS;
+  if (target < 1) target = 1;
+  int gpc = (max_groups + target - 1) / target;
+  if (gpc < 4) gpc = 4;
+  int n_chunks = (max_groups + gpc - 1) / gpc;
+  if (n_chunks < 1) n_chunks = 1;
+
+  p.k_codes = (const uint32_t*)c->k_codes;
+  p.v_codes = (const uint32_t*)c->v_codes;
+  p.k_scale = (const __half*)c->k_scale;
+  p.k_zero = (const __half*)c->k_zero;
+  p.v_scale = (const __half*)c->v_scale;
+  p.v_zero = (const __half*)c->v_zero;
+  p.k_resid = (const __half*)c->k_resid;
+  p.v_resid = (const __half*)c->v_resid;
+  p.q = (const __half*)q;
+  p.parts = (float*)workspace;
+  p.scale2 = sm_scale * 1.44269504088896340736f;
+  p.hq = d->n_q_heads;
+  p.hkv = d->n_kv_heads;
+  p.bits = d->bits;
+  p.residual = d->residual;
+  p.capacity = d->capacity;
+  p.groups_per_chunk = gpc;
+  p.n_chunks = n_chunks;
+
+  hipStream_t s = (hipStream_t)stream;
+  quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+  if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+  return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, n_chunks + 1, s);
+}

@@ -1,0 +1,726 @@
+// Sparsity-friendly layers (Sec. 4.2): cache update, Stage 2 approximate scoring +
+// Top-K, fetch of the selected rows from pinned host memory, exact attention over
+// n_local + n_topk tokens (Sec. 5.1).
+#include "tkv_common.h"
+
+namespace {
+
+constexpr int kTokPerBlock = 1024;  // tokens scored per workgroup (256 threads x 4)
+constexpr int kBins = 2048;
+
+// Workspace carve-up of tkv_sparse_estimate_topk (uint32 units, per (b, kv head) = bh):
+//   keys  [BH][capacity]            order-preserving image of the float32 scores
+//   hist  [BH][3][2048]             radix histograms, most significant digit first
+//   blk   [BH][nblk_cap][2]         per block: #keys above threshold, #keys equal
+struct TopkWs {
+  uint32_t* keys;
+  uint32_t* hist;
+  uint32_t* blk;
+  int32_t nblk_cap;
+};
+
+__host__ __device__ inline int nblk_cap_of(int capacity) { return (capacity + kTokPerBlock - 1) / kTokPerBlock + 1; }
+
+struct SparseParams {
+  const __half* summary;
+  const int32_t* channel_idx;
+  const __half* q;
+  int32_t* topk_idx;
+  int32_t* topk_count;
+  TopkWs ws;
+  int32_t hq, hkv, ds, top_k, n_sink, n_window, capacity;
+  TkvSeqLens lens;
+};
+
+// Larger float <-> larger unsigned key; +0 and -0 were already merged by "+ 0.0f".
+__device__ inline uint32_t score_key(float s) {
+  const uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ inline void candidate_range(const SparseParams& p, int n, int& lo, int& hi) {
+  lo = min(p.n_sink, n);
+  hi = max(n - p.n_window, lo);
+}
+
+__global__ void zero_u32_kernel(uint32_t* ptr, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) ptr[i] = 0u;
+}
+
+// Pass 1: approximate score of every candidate in the pinned float32 order, key
+// written to the workspace, histogram of the top 11 key bits.
+template <int DS>
+__global__ __launch_bounds__(256) void score_hist_kernel(SparseParams p) {
+  __shared__ uint32_t hist[kBins];
+  __shared__ float qc[4][DS];
+  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const int n = p.lens.n[b];
+  int lo, hi;
+  candidate_range(p, n, lo, hi);
+  const int t0 = blockIdx.x * kTokPerBlock;
+  if (t0 >= n) return;
+  const int G = p.hq / p.hkv;
+  const size_t bh = (size_t)b * p.hkv + h;
+  for (int i = tid; i < kBins; i += 256) hist[i] = 0u;
+  if (tid < 4 * DS) {
+    const int j = tid / DS, i = tid % DS;
+    const int c = p.channel_idx[bh * DS + i];
+    qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
+  }
+  __syncthreads();
+
+  const __half* srow = p.summary + (bh * p.capacity) * DS;
+  uint32_t* keys = p.ws.keys + bh * p.capacity;
+#pragma unroll
+  for (int it = 0; it < kTokPerBlock / 256; ++it) {
+    const int t = t0 + it * 256 + tid;
+    if (t >= n) break;
+    uint32_t key = 0u;  // non-candidates: below every finite score
+    if (t >= lo && t < hi) {
+      union {
+        uint4 v[DS / 8];
+        __half hx[DS];
+      } row;
+#pragma unroll
+      for (int x = 0; x < DS / 8; ++x) row.v[x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
+      float total = 0.f;
+      for (int j = 0; j < G; ++j) {
+        // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k
+        float a = qc[j][0] * __half2float(row.hx[0]);
+#pragma unroll
+        for (int i = 1; i < DS; ++i) a = __builtin_fmaf(qc[j][i], __half2float(row.hx[i]), a);
+        total = j == 0 ? a : total + a;
+      }
+      total = total + 0.0f;
+      key = score_key(total);
+      atomicAdd(&hist[key >> 21], 1u);
+    }
+    keys[t] = key;
+  }
+  __syncthreads();
+  uint32_t* gh = p.ws.hist + bh * 3 * kBins;
+  for (int i = tid; i < kBins; i += 256)
+    if (hist[i]) atomicAdd(&gh[i], hist[i]);
+}
+
+// Finds the bin holding the k-th largest key: bins above it hold `above` < k keys,
+// bins above-or-equal hold >= k.  Every thread of the block gets the result.
+__device__ inline void find_bin(const uint32_t* gh, int nbins, uint32_t k, uint32_t* scratch /*nbins+2*/,
+                                uint32_t& bin, uint32_t& above) {
+  const int tid = threadIdx.x;
+  // suffix sums by 256 threads over nbins (<= 2048) bins: each thread owns a run
+  const int per = nbins / 256;
+  uint32_t local = 0;
+  for (int i = 0; i < per; ++i) local += gh[tid * per + i];
+  scratch[tid] = local;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t run = 0;
+    int seg = 255;
+    for (; seg > 0; --seg) {
+      if (run + scratch[seg] >= k) break;
+      run += scratch[seg];
+    }
+    // seg is the segment containing the k-th key (or 0)
+    int bsel = seg * per + per - 1;
+    for (; bsel > seg * per; --bsel) {
+      const uint32_t c = gh[bsel];
+      if (run + c >= k) break;
+      run += c;
+    }
+    scratch[256] = (uint32_t)bsel;
+    scratch[257] = run;
+  }
+  __syncthreads();
+  bin = scratch[256];
+  above = scratch[257];
+  __syncthreads();
+}
+
+__device__ inline uint32_t k_eff_of(const SparseParams& p, int n) {
+  int lo, hi;
+  candidate_range(p, n, lo, hi);
+  return (uint32_t)min(p.top_k, hi - lo);
+}
+
+// Pass 2 / 3: histogram of the next digit among keys matching the prefix so far.
+template <int LEVEL>
+__global__ __launch_bounds__(256) void refine_hist_kernel(SparseParams p) {
+  __shared__ uint32_t hist[kBins];
+  __shared__ uint32_t scratch[258];
+  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const int n = p.lens.n[b];
+  const int t0 = blockIdx.x * kTokPerBlock;
+  if (t0 >= n) return;
+  const uint32_t k = k_eff_of(p, n);
+  if (k == 0) return;
+  const size_t bh = (size_t)b * p.hkv + h;
+  const uint32_t* gh = p.ws.hist + bh * 3 * kBins;
+  uint32_t b1, above1, prefix, k_rem;
+  find_bin(gh, kBins, k, scratch, b1, above1);
+  k_rem = k - above1;
+  prefix = b1;
+  if (LEVEL == 2) {
+    uint32_t b2, above2;
+    find_bin(gh + kBins, kBins, k_rem, scratch, b2, above2);
+    k_rem -= above2;
+    prefix = (b1 << 11) | b2;
+  }
+  for (int i = tid; i < kBins; i += 256) hist[i] = 0u;
+  __syncthreads();
+  const uint32_t* keys = p.ws.keys + bh * p.capacity;
+  for (int it = 0; it < kTokPerBlock / 256; ++it) {
+    const int t = t0 + it * 256 + tid;
+    if (t >= n) break;
+    const uint32_t key = keys[t];
+    if (LEVEL == 1) {
+      if ((key >> 21) == prefix) atomicAdd(&hist[(key >> 10) & 0x7FFu], 1u);
+    } else {
+      if ((key >> 10) == prefix) atomicAdd(&hist[key & 0x3FFu], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* out = p.ws.hist + bh * 3 * kBins + LEVEL * kBins;
+  for (int i = tid; i < kBins; i += 256)
+    if (hist[i]) atomicAdd(&out[i], hist[i]);
+}
+
+// Threshold key T and the number of keys equal to T that are selected.
+__device__ inline void find_threshold(const SparseParams& p, size_t bh, uint32_t k, uint32_t* scratch,
+                                      uint32_t& T, uint32_t& n_eq_take) {
+  const uint32_t* gh = p.ws.hist + bh * 3 * kBins;
+  uint32_t b1, a1, b2, a2, b3, a3;
+  find_bin(gh, kBins, k, scratch, b1, a1);
+  find_bin(gh + kBins, kBins, k - a1, scratch, b2, a2);
+  find_bin(gh + 2 * kBins, 1024, k - a1 - a2, scratch, b3, a3);
+  T = (b1 << 21) | (b2 << 10) | b3;
+  n_eq_take = k - a1 - a2 - a3;
+}
+
+// Pass 4: per block, how many keys lie above the threshold and how many equal it.
+__global__ __launch_bounds__(256) void count_kernel(SparseParams p) {
+  __shared__ uint32_t scratch[258];
+  __shared__ uint32_t cnt[2];
+  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const int n = p.lens.n[b];
+  const int t0 = blockIdx.x * kTokPerBlock;
+  if (t0 >= n) return;
+  const uint32_t k = k_eff_of(p, n);
+  if (k == 0) return;
+  const size_t bh = (size_t)b * p.hkv + h;
+  uint32_t T, take;
+  find_threshold(p, bh, k, scratch, T, take);
+  if (tid < 2) cnt[tid] = 0u;
+  __syncthreads();
+  const uint32_t* keys = p.ws.keys + bh * p.capacity;
+  uint32_t gt = 0, eq = 0;
+  for (int it = 0; it < kTokPerBlock / 256; ++it) {
+    const int t = t0 + it * 256 + tid;
+    if (t >= n) break;
+    const uint32_t key = keys[t];
+    gt += key > T;
+    eq += key == T;
+  }
+  if (gt) atomicAdd(&cnt[0], gt);
+  if (eq) atomicAdd(&cnt[1], eq);
+  __syncthreads();
+  if (tid < 2) p.ws.blk[(bh * p.ws.nblk_cap + blockIdx.x) * 2 + tid] = cnt[tid];
+}
+
+// Pass 5: ordered compaction.  Thread i of a block owns tokens [t0 + 4i, t0 + 4i + 4),
+// so positions follow token order.
+__global__ __launch_bounds__(256) void compact_kernel(SparseParams p) {
+  __shared__ uint32_t scratch[258];
+  __shared__ uint32_t sgt[256], seq[256];
+  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const int n = p.lens.n[b];
+  const size_t bh = (size_t)b * p.hkv + h;
+  const uint32_t k = k_eff_of(p, n);
+  int32_t* out = p.topk_idx + bh * p.top_k;
+  if (blockIdx.x == 0) {
+    for (int i = (int)k + tid; i < p.top_k; i += 256) out[i] = -1;
+    if (tid == 0) p.topk_count[bh] = (int32_t)k;
+  }
+  const int t0 = blockIdx.x * kTokPerBlock;
+  if (t0 >= n || k == 0) return;
+  uint32_t T, take;
+  find_threshold(p, bh, k, scratch, T, take);
+  // keys above / equal in earlier blocks
+  uint32_t gt_before = 0, eq_before = 0;
+  for (int i = tid; i < (int)blockIdx.x; i += 256) {
+    gt_before += p.ws.blk[(bh * p.ws.nblk_cap + i) * 2];
+    eq_before += p.ws.blk[(bh * p.ws.nblk_cap + i) * 2 + 1];
+  }
+  sgt[tid] = gt_before;
+  seq[tid] = eq_before;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) {
+      sgt[tid] += sgt[tid + s];
+      seq[tid] += seq[tid + s];
+    }
+    __syncthreads();
+  }
+  gt_before = sgt[0];
+  eq_before = seq[0];
+  __syncthreads();
+
+  const uint32_t* keys = p.ws.keys + bh * p.capacity;
+  uint32_t key[4];
+  uint32_t gt = 0, eq = 0;
+  for (int x = 0; x < 4; ++x) {
+    const int t = t0 + 4 * tid + x;
+    key[x] = t < n ? keys[t] : 0u;
+    gt += key[x] > T;
+    eq += (t < n) && key[x] == T;
+  }
+  // exclusive scan over threads (Hillis-Steele, 256 entries)
+  sgt[tid] = gt;
+  seq[tid] = eq;
+  __syncthreads();
+  for (int s = 1; s < 256; s <<= 1) {
+    uint32_t a = 0, c = 0;
+    if (tid >= s) {
+      a = sgt[tid - s];
+      c = seq[tid - s];
+    }
+    __syncthreads();
+    sgt[tid] += a;
+    seq[tid] += c;
+    __syncthreads();
+  }
+  uint32_t gt_run = gt_before + sgt[tid] - gt;
+  uint32_t eq_run = eq_before + seq[tid] - eq;
+  for (int x = 0; x < 4; ++x) {
+    const int t = t0 + 4 * tid + x;
+    if (t >= n) break;
+    if (key[x] > T) {
+      out[gt_run + min(eq_run, take)] = t;
+      ++gt_run;
+    } else if (key[x] == T) {
+      if (eq_run < take) out[gt_run + eq_run] = t;
+      ++eq_run;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+
+struct AppendParams {
+  __half* summary;
+  const int32_t* channel_idx;
+  __half* kv_host;
+  __half* kv_local;
+  const __half* k_new;
+  const __half* v_new;
+  int32_t hkv, ds, n_sink, n_window, capacity;
+  int32_t n_stride;  // rows per sequence in k_new / v_new
+  TkvSeqLens n_old;
+  TkvSeqLens n_add;  // valid new rows per sequence
+};
+
+__global__ __launch_bounds__(256) void sparse_append_kernel(AppendParams p) {
+  const int b = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
+  if (i >= p.n_add.n[b]) return;
+  const int n0 = p.n_old.n[b], n1 = n0 + p.n_add.n[b];
+  const int tok = n0 + i;
+  const int chunks = p.hkv * 16;
+  const bool local = tok < p.n_sink || tok >= n1 - p.n_window;
+  const int slot = tok < p.n_sink ? tok : p.n_sink + tok % p.n_window;
+  for (int x = tid; x < 2 * chunks; x += 256) {
+    const int kv = x / chunks, rem = x % chunks, h = rem / 16, part = rem % 16;
+    const size_t bh = (size_t)b * p.hkv + h;
+    const uint4 v = reinterpret_cast<const uint4*>((kv ? p.v_new : p.k_new) +
+                                                   (((size_t)b * p.n_stride + i) * p.hkv + h) * TKV_D)[part];
+    reinterpret_cast<uint4*>(p.kv_host + ((bh * p.capacity + tok) * 2 + kv) * TKV_D)[part] = v;
+    if (local)
+      reinterpret_cast<uint4*>(p.kv_local + ((bh * (p.n_sink + p.n_window) + slot) * 2 + kv) * TKV_D)[part] = v;
+  }
+  for (int x = tid; x < p.hkv * p.ds; x += 256) {
+    const int h = x / p.ds, ci = x % p.ds;
+    const size_t bh = (size_t)b * p.hkv + h;
+    const int c = p.channel_idx[bh * p.ds + ci];
+    p.summary[(bh * p.capacity + tok) * p.ds + ci] = p.k_new[(((size_t)b * p.n_stride + i) * p.hkv + h) * TKV_D + c];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+
+struct GatherParams {
+  const __half* kv_host;  // device-visible address of the pinned host cache
+  const int32_t* topk_idx;
+  const int32_t* topk_count;
+  __half* staging;
+  int32_t hkv, top_k, capacity;
+};
+
+// Each 64-lane wave moves two 512-byte rows (K row + V row) per step with 16-byte
+// loads straight from pinned host memory.
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
+  const int b = blockIdx.z, h = blockIdx.y;
+  const size_t bh = (size_t)b * p.hkv + h;
+  const int cnt = p.topk_count[bh];
+  const int row = blockIdx.x * 8 + threadIdx.x / 32;  // 32 lanes x 16 B = one row
+  if (row >= cnt) return;
+  const int part = threadIdx.x % 32;
+  const int tok = p.topk_idx[bh * p.top_k + row];
+  const uint4 v = reinterpret_cast<const uint4*>(p.kv_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D)[part];
+  reinterpret_cast<uint4*>(p.staging + (bh * p.top_k + (size_t)row) * 2 * TKV_D)[part] = v;
+}
+
+struct SparseAttnParams {
+  const __half* q;
+  const __half* staging;
+  const __half* kv_local;
+  const int32_t* topk_count;
+  float* parts;
+  float scale2;
+  int32_t hq, hkv, top_k, n_sink, n_window, n_chunks;
+  TkvSeqLens lens;
+};
+
+constexpr int kAttnTokPerBlock = 128;
+
+__device__ inline float half_wave_max(float v) {
+  for (int m = 16; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+
+// Exact attention over sinks + gathered rows + window.  One workgroup handles 128
+// attended tokens of one KV head; lane (t, hp) scores token t for query heads
+// 2hp, 2hp+1; then every lane accumulates two output channels.
+__global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
+  __shared__ float qs[4][TKV_D];
+  __shared__ float pw[4][4][32];
+  __shared__ const __half* vrow_s[4][32];
+  __shared__ float red_m[4][4], red_l[4][4];
+  __shared__ float red_o[4][4][TKV_D];
+  const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+  const int G = p.hq / p.hkv;
+  const size_t bh = (size_t)b * p.hkv + h;
+  const int n = p.lens.n[b];
+  const int n_sk = min(p.n_sink, n);
+  const int cnt = p.topk_count[bh];
+  const int w0 = max(n - p.n_window, n_sk);
+  const int n_att = n_sk + cnt + (n - w0);
+
+  for (int i = tid; i < 4 * TKV_D; i += 256) {
+    const int hh = i / TKV_D, c = i % TKV_D;
+    qs[hh][c] = hh < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c]) : 0.f;
+  }
+  __syncthreads();
+
+  const int t = lane % 32, hp = lane / 32;
+  const int i = chunk * kAttnTokPerBlock + wave * 32 + t;
+  const bool valid = i < n_att;
+  const __half* krow = nullptr;
+  if (valid) {
+    if (i < n_sk)
+      krow = p.kv_local + (bh * (p.n_sink + p.n_window) + i) * 2 * TKV_D;
+    else if (i < n_sk + cnt)
+      krow = p.staging + (bh * p.top_k + (size_t)(i - n_sk)) * 2 * TKV_D;
+    else {
+      const int tok = w0 + (i - n_sk - cnt);
+      krow = p.kv_local + (bh * (p.n_sink + p.n_window) + p.n_sink + tok % p.n_window) * 2 * TKV_D;
+    }
+  }
+  float x0 = -INFINITY, x1 = -INFINITY;
+  if (valid) {
+    float a0 = 0.f, a1 = 0.f;
+    for (int c8 = 0; c8 < TKV_D / 8; ++c8) {
+      union {
+        uint4 v;
+        __half hx[8];
+      } u;
+      u.v = reinterpret_cast<const uint4*>(krow)[c8];
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const float kx = __half2float(u.hx[x]);
+        a0 += qs[2 * hp][c8 * 8 + x] * kx;
+        a1 += qs[2 * hp + 1][c8 * 8 + x] * kx;
+      }
+    }
+    x0 = a0 * p.scale2;
+    x1 = a1 * p.scale2;
+  }
+  const float m0 = half_wave_max(x0), m1 = half_wave_max(x1);
+  const bool any = m0 != -INFINITY;  // this wave has at least one valid token (uniform per wave)
+  pw[wave][2 * hp][t] = valid ? exp2f(x0 - m0) : 0.f;
+  pw[wave][2 * hp + 1][t] = valid ? exp2f(x1 - m1) : 0.f;
+  if (hp == 0) vrow_s[wave][t] = valid ? krow + TKV_D : nullptr;
+  if (t == 0) {
+    red_m[wave][2 * hp] = m0;
+    red_m[wave][2 * hp + 1] = m1;
+  }
+  __syncthreads();
+  const int c0 = 2 * lane;
+  float o0[4] = {0.f, 0.f, 0.f, 0.f}, o1[4] = {0.f, 0.f, 0.f, 0.f}, ls[4] = {0.f, 0.f, 0.f, 0.f};
+  if (any) {
+    for (int tt = 0; tt < 32; ++tt) {
+      const __half* vr = vrow_s[wave][tt];
+      if (!vr) continue;
+      const __half2 v2 = reinterpret_cast<const __half2*>(vr)[lane];
+      const float v0 = __low2float(v2), v1 = __high2float(v2);
+      for (int hh = 0; hh < 4; ++hh) {
+        const float pp = pw[wave][hh][tt];
+        o0[hh] += pp * v0;
+        o1[hh] += pp * v1;
+        ls[hh] += pp;
+      }
+    }
+  }
+  for (int hh = 0; hh < 4; ++hh) {
+    red_o[wave][hh][c0] = o0[hh];
+    red_o[wave][hh][c0 + 1] = o1[hh];
+    if (lane == 0) red_l[wave][hh] = ls[hh];
+  }
+  __syncthreads();
+  for (int x = tid; x < G * TKV_D; x += 256) {
+    const int hh = x / TKV_D, c = x % TKV_D;
+    float M = -INFINITY;
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, red_m[w][hh]);
+    float L = 0.f, O = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      const float mw = red_m[w][hh];
+      const float wgt = mw == -INFINITY ? 0.f : exp2f(mw - M);
+      L += red_l[w][hh] * wgt;
+      O += red_o[w][hh][c] * wgt;
+    }
+    float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
+    dst[2 + c] = O;
+    if (c == 0) {
+      dst[0] = M;
+      dst[1] = L;
+    }
+  }
+}
+
+int32_t fill_lens(const tkv_sparse_desc* d, const tkv_sparse_cache* c, TkvSeqLens& lens, int& max_n) {
+  max_n = 0;
+  for (int b = 0; b < d->batch; ++b) {
+    const int32_t n = c->seq_len_host[b];
+    if (n < 0) return TKV_E_INVAL;
+    if (n > d->capacity) return TKV_E_CAPACITY;
+    lens.n[b] = n;
+    if (n > max_n) max_n = n;
+  }
+  return TKV_OK;
+}
+
+// Device-visible address of a pinned host allocation; TKV_E_NOTPINNED otherwise.
+int32_t device_view_of_host(const void* host, const void** dev) {
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, host);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
+  }
+  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
+  *dev = attr.devicePointer;
+  return TKV_OK;
+}
+
+TopkWs carve_topk_ws(const tkv_sparse_desc* d, void* workspace) {
+  const size_t bh = (size_t)d->batch * d->n_kv_heads;
+  TopkWs ws;
+  ws.keys = (uint32_t*)workspace;
+  ws.hist = ws.keys + bh * (size_t)d->capacity;
+  ws.nblk_cap = nblk_cap_of(d->capacity);
+  ws.blk = ws.hist + bh * 3 * kBins;
+  return ws;
+}
+
+}  // namespace
+
+extern "C" int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* d, tkv_sparse_cache* c, const void* k_new,
+                                            const void* v_new, int32_t n_new, const int32_t* n_valid_host,
+                                            void* stream) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->seq_len_host || n_new < 0) return TKV_E_INVAL;
+  if (n_new == 0) return TKV_OK;
+  if (!k_new || !v_new || !c->key_summary || !c->channel_idx || !c->kv_host || !c->kv_local) return TKV_E_INVAL;
+  AppendParams p;
+  for (int b = 0; b < d->batch; ++b) {
+    const int64_t n0 = c->seq_len_host[b];
+    const int32_t add = n_valid_host ? n_valid_host[b] : n_new;
+    if (n0 < 0 || add < 0 || add > n_new) return TKV_E_INVAL;
+    if (n0 + add > d->capacity) return TKV_E_CAPACITY;
+    p.n_old.n[b] = (int32_t)n0;
+    p.n_add.n[b] = add;
+  }
+  const void* host_dev = nullptr;
+  st = device_view_of_host(c->kv_host, &host_dev);
+  if (st != TKV_OK) return st;
+  p.summary = (__half*)c->key_summary;
+  p.channel_idx = c->channel_idx;
+  p.kv_host = (__half*)host_dev;
+  p.kv_local = (__half*)c->kv_local;
+  p.k_new = (const __half*)k_new;
+  p.v_new = (const __half*)v_new;
+  p.hkv = d->n_kv_heads;
+  p.ds = d->n_channels;
+  p.n_sink = d->n_sink;
+  p.n_window = d->n_window;
+  p.capacity = d->capacity;
+  p.n_stride = n_new;
+  sparse_append_kernel<<<dim3(n_new, d->batch), 256, 0, (hipStream_t)stream>>>(p);
+  if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+  for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += p.n_add.n[b];
+  return TKV_OK;
+}
+
+extern "C" int32_t tkv_sparse_append(const tkv_sparse_desc* d, tkv_sparse_cache* c, const void* k_new,
+                                     const void* v_new, int32_t n_new, void* stream) {
+  return tkv_sparse_append_ragged(d, c, k_new, v_new, n_new, nullptr, stream);
+}
+
+extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
+                                            int32_t* topk_idx, int32_t* topk_count, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->seq_len_host || !c->key_summary || !c->channel_idx || !q || !topk_idx || !topk_count || !workspace)
+    return TKV_E_INVAL;
+  size_t need = 0;
+  tkv_sparse_cache_sizes(d, nullptr, &need);
+  if (workspace_bytes < need) return TKV_E_WORKSPACE;
+  SparseParams p;
+  int max_n = 0;
+  st = fill_lens(d, c, p.lens, max_n);
+  if (st != TKV_OK) return st;
+  p.summary = (const __half*)c->key_summary;
+  p.channel_idx = c->channel_idx;
+  p.q = (const __half*)q;
+  p.topk_idx = topk_idx;
+  p.topk_count = topk_count;
+  p.ws = carve_topk_ws(d, workspace);
+  p.hq = d->n_q_heads;
+  p.hkv = d->n_kv_heads;
+  p.ds = d->n_channels;
+  p.top_k = d->top_k;
+  p.n_sink = d->n_sink;
+  p.n_window = d->n_window;
+  p.capacity = d->capacity;
+
+  hipStream_t s = (hipStream_t)stream;
+  const size_t bh = (size_t)d->batch * d->n_kv_heads;
+  const size_t nhist = bh * 3 * kBins;
+  zero_u32_kernel<<<dim3((unsigned)((nhist + 255) / 256)), 256, 0, s>>>(p.ws.hist, nhist);
+  int nblk = (max_n + kTokPerBlock - 1) / kTokPerBlock;
+  if (nblk < 1) nblk = 1;
+  const dim3 grid(nblk, d->n_kv_heads, d->batch);
+  if (d->n_channels == 16)
+    score_hist_kernel<16><<<grid, 256, 0, s>>>(p);
+  else
+    score_hist_kernel<8><<<grid, 256, 0, s>>>(p);
+  refine_hist_kernel<1><<<grid, 256, 0, s>>>(p);
+  refine_hist_kernel<2><<<grid, 256, 0, s>>>(p);
+  count_kernel<<<grid, 256, 0, s>>>(p);
+  compact_kernel<<<grid, 256, 0, s>>>(p);
+  return tkv::launch_status();
+}
+
+extern "C" int32_t tkv_sparse_gather(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const int32_t* topk_idx,
+                                     const int32_t* topk_count, void* staging, void* stream) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->kv_host || !topk_idx || !topk_count || !staging) return TKV_E_INVAL;
+  const void* host_dev = nullptr;
+  st = device_view_of_host(c->kv_host, &host_dev);
+  if (st != TKV_OK) return st;
+  GatherParams p;
+  p.kv_host = (const __half*)host_dev;
+  p.topk_idx = topk_idx;
+  p.topk_count = topk_count;
+  p.staging = (__half*)staging;
+  p.hkv = d->n_kv_heads;
+  p.top_k = d->top_k;
+  p.capacity = d->capacity;
+  gather_rows_kernel<<<dim3((d->top_k + 7) / 8, d->n_kv_heads, d->batch), 256, 0, (hipStream_t)stream>>>(p);
+  return tkv::launch_status();
+}
+
+extern "C" int32_t tkv_sparse_attn(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
+                                   const int32_t* topk_count, const void* staging, void* out, float sm_scale,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->seq_len_host || !c->kv_local || !q || !topk_count || !staging || !out || !workspace)
+    return TKV_E_INVAL;
+  size_t need = 0;
+  tkv_sparse_cache_sizes(d, nullptr, &need);
+  if (workspace_bytes < need) return TKV_E_WORKSPACE;
+  SparseAttnParams p;
+  int max_n = 0;
+  st = fill_lens(d, c, p.lens, max_n);
+  if (st != TKV_OK) return st;
+  const int max_att = d->n_sink + d->top_k + d->n_window;
+  int n_chunks = (max_att + kAttnTokPerBlock - 1) / kAttnTokPerBlock;
+  if (n_chunks > 64) return TKV_E_UNSUPPORTED;
+  // partials live behind the Top-K scratch so that one workspace serves both calls
+  TopkWs ws = carve_topk_ws(d, workspace);
+  const size_t bh = (size_t)d->batch * d->n_kv_heads;
+  float* parts = (float*)(ws.blk + bh * (size_t)ws.nblk_cap * 2);
+  p.q = (const __half*)q;
+  p.staging = (const __half*)staging;
+  p.kv_local = (const __half*)c->kv_local;
+  p.topk_count = topk_count;
+  p.parts = parts;
+  p.scale2 = sm_scale * 1.44269504088896340736f;
+  p.hq = d->n_q_heads;
+  p.hkv = d->n_kv_heads;
+  p.top_k = d->top_k;
+  p.n_sink = d->n_sink;
+  p.n_window = d->n_window;
+  p.n_chunks = n_chunks;
+  hipStream_t s = (hipStream_t)stream;
+  sparse_attn_kernel<<<dim3(n_chunks, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+  if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+  return tkv::launch_attn_merge(parts, (__half*)out, d->batch * d->n_q_heads, n_chunks, s);
+}
+
+namespace {
+// Two process-wide events order the gather stream against the compute stream.
+// They carry no data; re-recording an event only affects waits enqueued later.
+struct StreamLink {
+  hipEvent_t topk_ready = nullptr, rows_ready = nullptr;
+  int32_t init() {
+    if (topk_ready) return TKV_OK;
+    if (hipEventCreateWithFlags(&topk_ready, hipEventDisableTiming) != hipSuccess) return TKV_E_HIP;
+    if (hipEventCreateWithFlags(&rows_ready, hipEventDisableTiming) != hipSuccess) return TKV_E_HIP;
+    return TKV_OK;
+  }
+};
+StreamLink g_link;
+}  // namespace
+
+extern "C" int32_t tkv_sparse_gather_attn(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
+                                          const int32_t* topk_idx, const int32_t* topk_count, void* out,
+                                          float sm_scale, void* staging, void* workspace, size_t workspace_bytes,
+                                          void* gather_stream, void* compute_stream) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->seq_len_host || !c->kv_local || !c->kv_host || !q || !topk_idx || !topk_count || !staging || !out ||
+      !workspace)
+    return TKV_E_INVAL;
+  size_t need = 0;
+  tkv_sparse_cache_sizes(d, nullptr, &need);
+  if (workspace_bytes < need) return TKV_E_WORKSPACE;
+  hipStream_t gs = (hipStream_t)gather_stream, cs = (hipStream_t)compute_stream;
+  const bool two = gs != cs;
+  if (two) {
+    if (g_link.init() != TKV_OK) return TKV_E_HIP;
+    TKV_HIP_TRY(hipEventRecord(g_link.topk_ready, cs));
+    TKV_HIP_TRY(hipStreamWaitEvent(gs, g_link.topk_ready, 0));
+  }
+  st = tkv_sparse_gather(d, c, topk_idx, topk_count, staging, gs);
+  if (st != TKV_OK) return st;
+  if (two) {
+    TKV_HIP_TRY(hipEventRecord(g_link.rows_ready, gs));
+    TKV_HIP_TRY(hipStreamWaitEvent(cs, g_link.rows_ready, 0));
+  }
+  return tkv_sparse_attn(d, c, q, topk_count, staging, out, sm_scale, workspace, workspace_bytes, cs);
+}

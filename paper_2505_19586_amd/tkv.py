@@ -1,0 +1,260 @@
+"""ctypes binding of libtkv.so: same entry points as include/tkv.h, argument
+marshalling only.  Every step of the path runs in the library's HIP kernels; there
+is no CPU or PyTorch fallback - a missing library or GPU raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+TKV_MAX_BATCH = 64
+
+
+class TkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().tkv_strerror(status).decode() if _LIB is not None else "?"
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libtkv.so")
+
+
+class QuantDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("bits", C.c_int32), ("group_size", C.c_int32),
+                ("residual", C.c_int32), ("capacity", C.c_int32), ("batch", C.c_int32)]
+
+
+class QuantCache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero",
+                                          "k_resid", "v_resid")] + [("seq_len_host", C.POINTER(C.c_int32))]
+
+
+class SparseDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("n_channels", C.c_int32), ("top_k", C.c_int32),
+                ("n_sink", C.c_int32), ("n_window", C.c_int32), ("capacity", C.c_int32), ("batch", C.c_int32)]
+
+
+class SparseCache(C.Structure):
+    _fields_ = [("key_summary", C.c_void_p), ("channel_idx", C.c_void_p), ("kv_host", C.c_void_p),
+                ("kv_local", C.c_void_p), ("seq_len_host", C.POINTER(C.c_int32))]
+
+
+def lib() -> C.CDLL:
+    """Loads libtkv.so (built by paper_2505_19586_amd/build.py); raises if absent."""
+    global _LIB
+    if _LIB is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2505_19586_amd.build`")
+        L = C.CDLL(path)
+        L.tkv_strerror.restype = C.c_char_p
+        L.tkv_strerror.argtypes = [C.c_int32]
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        L.tkv_quant_cache_sizes.argtypes = [C.POINTER(QuantDesc), C.POINTER(sz), C.POINTER(sz)]
+        L.tkv_quantize_append.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, i32, vp]
+        L.tkv_quantize_append_ragged.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, i32,
+                                                 C.POINTER(i32), vp]
+        L.tkv_sparse_append_ragged.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32,
+                                               C.POINTER(i32), vp]
+        L.tkv_quant_attn_decode.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, C.c_float, vp, sz, vp]
+        L.tkv_sparse_cache_sizes.argtypes = [C.POINTER(SparseDesc), C.POINTER(sz), C.POINTER(sz)]
+        L.tkv_sparse_append.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32, vp]
+        L.tkv_sparse_estimate_topk.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp, sz, vp]
+        L.tkv_sparse_gather_attn.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp,
+                                             C.c_float, vp, vp, sz, vp, vp]
+        L.tkv_sparse_gather.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp]
+        L.tkv_sparse_attn.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp, C.c_float,
+                                      vp, sz, vp]
+        for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
+                     "tkv_quantize_append_ragged", "tkv_sparse_append_ragged",
+                     "tkv_sparse_cache_sizes", "tkv_sparse_append", "tkv_sparse_estimate_topk",
+                     "tkv_sparse_gather_attn", "tkv_sparse_gather", "tkv_sparse_attn"):
+            getattr(L, name).restype = C.c_int32
+        _LIB = L
+    return _LIB
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise TkvError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _require_gpu(device) -> torch.device:
+    if not torch.cuda.is_available():
+        raise RuntimeError("tkv needs an AMD GPU (gfx950); no CPU fallback exists")
+    return torch.device(device)
+
+
+class QuantLayer:
+    """Buffers of one quantization-friendly layer plus the three entry points that
+    act on them (tkv_quant_cache_sizes, tkv_quantize_append, tkv_quant_attn_decode)."""
+
+    def __init__(self, *, n_q_heads=32, n_kv_heads=8, head_dim=128, bits=2, group_size=32, residual=128,
+                 capacity, batch=1, device="cuda:0"):
+        dev = _require_gpu(device)
+        self.desc = QuantDesc(C.sizeof(QuantDesc), n_q_heads, n_kv_heads, head_dim, bits, group_size, residual,
+                              capacity, batch)
+        sizes = (C.c_size_t * 8)()
+        ws = C.c_size_t()
+        _check(lib().tkv_quant_cache_sizes(C.byref(self.desc), sizes, C.byref(ws)), "tkv_quant_cache_sizes")
+        self.sizes = [int(s) for s in sizes]
+        self.workspace_bytes = int(ws.value)
+        names = ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_resid", "v_resid")
+        self.buffers = {n: torch.zeros(max(s, 16), dtype=torch.uint8, device=dev) for n, s in zip(names, self.sizes)}
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        self.seq_len = np.zeros(batch, dtype=np.int32)
+        self.cache = QuantCache(*[self.buffers[n].data_ptr() for n in names],
+                                self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)))
+        self.device = dev
+
+    def append(self, k_new: torch.Tensor, v_new: torch.Tensor, n_valid=None, stream=None) -> None:
+        """k_new, v_new: fp16 [B, n_new, Hkv, D] on the device; n_valid: optional
+        per-sequence row counts (padded batch)."""
+        d = self.desc
+        assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16
+        assert k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous()
+        assert tuple(k_new.shape) == tuple(v_new.shape) and k_new.shape[0] == d.batch
+        assert tuple(k_new.shape[2:]) == (d.n_kv_heads, d.head_dim)
+        if n_valid is None:
+            _check(lib().tkv_quantize_append(C.byref(d), C.byref(self.cache), k_new.data_ptr(), v_new.data_ptr(),
+                                             int(k_new.shape[1]), _stream(stream)), "tkv_quantize_append")
+        else:
+            nv = np.ascontiguousarray(n_valid, dtype=np.int32)
+            assert nv.shape == (d.batch,)
+            _check(lib().tkv_quantize_append_ragged(C.byref(d), C.byref(self.cache), k_new.data_ptr(),
+                                                    v_new.data_ptr(), int(k_new.shape[1]),
+                                                    nv.ctypes.data_as(C.POINTER(C.c_int32)), _stream(stream)),
+                   "tkv_quantize_append_ragged")
+
+    def attn_decode(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor | None = None, stream=None):
+        d = self.desc
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        if out is None:
+            out = torch.empty_like(q)
+        _check(lib().tkv_quant_attn_decode(C.byref(d), C.byref(self.cache), q.data_ptr(), out.data_ptr(),
+                                           float(sm_scale), self.workspace.data_ptr(), self.workspace_bytes,
+                                           _stream(stream)), "tkv_quant_attn_decode")
+        return out
+
+    # typed views of the raw buffers (for tests)
+    def view(self, name: str) -> torch.Tensor:
+        d = self.desc
+        bh = (d.batch, d.n_kv_heads)
+        j = d.capacity // 32
+        buf = self.buffers[name]
+        if name in ("k_codes", "v_codes"):
+            return buf.view(torch.int32).view(*bh, j, 128 * d.bits)
+        if name in ("k_scale", "k_zero"):
+            return buf.view(torch.float16).view(*bh, j, 128)
+        if name in ("v_scale", "v_zero"):
+            return buf.view(torch.float16).view(*bh, j, 4, 32)
+        return buf.view(torch.float16).view(*bh, d.residual + 32, 128)
+
+
+class SparseLayer:
+    """Buffers of one sparsity-friendly layer (GPU key summary, pinned host K/V,
+    resident sink/window rows) and the entry points that act on them."""
+
+    def __init__(self, *, n_q_heads=32, n_kv_heads=8, head_dim=128, n_channels=16, top_k=1024, n_sink=4,
+                 n_window=64, capacity, batch=1, device="cuda:0", kv_host: torch.Tensor | None = None):
+        dev = _require_gpu(device)
+        self.desc = SparseDesc(C.sizeof(SparseDesc), n_q_heads, n_kv_heads, head_dim, n_channels, top_k, n_sink,
+                               n_window, capacity, batch)
+        sizes = (C.c_size_t * 4)()
+        ws = C.c_size_t()
+        _check(lib().tkv_sparse_cache_sizes(C.byref(self.desc), sizes, C.byref(ws)), "tkv_sparse_cache_sizes")
+        self.sizes = [int(s) for s in sizes]
+        self.workspace_bytes = int(ws.value)
+        self.key_summary = torch.zeros(self.sizes[0] // 2, dtype=torch.float16, device=dev).view(
+            batch, n_kv_heads, capacity, n_channels)
+        self.channel_idx = torch.zeros(batch, n_kv_heads, n_channels, dtype=torch.int32, device=dev)
+        if kv_host is None:
+            kv_host = torch.empty(self.sizes[2] // 2, dtype=torch.float16, pin_memory=True)
+        assert kv_host.is_pinned() and kv_host.numel() * 2 >= self.sizes[2]
+        self.kv_host = kv_host.view(-1)[: self.sizes[2] // 2].view(batch, n_kv_heads, capacity, 2, head_dim)
+        self.kv_local = torch.zeros(batch, n_kv_heads, n_sink + n_window, 2, head_dim, dtype=torch.float16, device=dev)
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        self.staging = torch.empty(batch, n_kv_heads, top_k, 2, head_dim, dtype=torch.float16, device=dev)
+        self.topk_idx = torch.empty(batch, n_kv_heads, top_k, dtype=torch.int32, device=dev)
+        self.topk_count = torch.zeros(batch, n_kv_heads, dtype=torch.int32, device=dev)
+        self.seq_len = np.zeros(batch, dtype=np.int32)
+        self.cache = SparseCache(self.key_summary.data_ptr(), self.channel_idx.data_ptr(), self.kv_host.data_ptr(),
+                                 self.kv_local.data_ptr(), self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)))
+        self.device = dev
+
+    def set_channels(self, channel_idx) -> None:
+        self.channel_idx.copy_(torch.as_tensor(np.asarray(channel_idx), dtype=torch.int32).view_as(self.channel_idx))
+
+    def append(self, k_new: torch.Tensor, v_new: torch.Tensor, n_valid=None, stream=None) -> None:
+        d = self.desc
+        assert k_new.dtype == torch.float16 and k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous()
+        assert tuple(k_new.shape) == tuple(v_new.shape) and k_new.shape[0] == d.batch
+        assert tuple(k_new.shape[2:]) == (d.n_kv_heads, d.head_dim)
+        if n_valid is None:
+            _check(lib().tkv_sparse_append(C.byref(d), C.byref(self.cache), k_new.data_ptr(), v_new.data_ptr(),
+                                           int(k_new.shape[1]), _stream(stream)), "tkv_sparse_append")
+        else:
+            nv = np.ascontiguousarray(n_valid, dtype=np.int32)
+            assert nv.shape == (d.batch,)
+            _check(lib().tkv_sparse_append_ragged(C.byref(d), C.byref(self.cache), k_new.data_ptr(),
+                                                  v_new.data_ptr(), int(k_new.shape[1]),
+                                                  nv.ctypes.data_as(C.POINTER(C.c_int32)), _stream(stream)),
+                   "tkv_sparse_append_ragged")
+
+    def estimate_topk(self, q: torch.Tensor, stream=None):
+        d = self.desc
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        _check(lib().tkv_sparse_estimate_topk(C.byref(d), C.byref(self.cache), q.data_ptr(),
+                                              self.topk_idx.data_ptr(), self.topk_count.data_ptr(),
+                                              self.workspace.data_ptr(), self.workspace_bytes, _stream(stream)),
+               "tkv_sparse_estimate_topk")
+        return self.topk_idx, self.topk_count
+
+    def gather_attn(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor | None = None,
+                    gather_stream=None, compute_stream=None):
+        d = self.desc
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        if out is None:
+            out = torch.empty_like(q)
+        cs = _stream(compute_stream)
+        gs = cs if gather_stream is None else _stream(gather_stream)
+        _check(lib().tkv_sparse_gather_attn(C.byref(d), C.byref(self.cache), q.data_ptr(), self.topk_idx.data_ptr(),
+                                            self.topk_count.data_ptr(), out.data_ptr(), float(sm_scale),
+                                            self.staging.data_ptr(), self.workspace.data_ptr(),
+                                            self.workspace_bytes, gs, cs), "tkv_sparse_gather_attn")
+        return out
+
+    def gather(self, stream=None) -> None:
+        _check(lib().tkv_sparse_gather(C.byref(self.desc), C.byref(self.cache), self.topk_idx.data_ptr(),
+                                       self.topk_count.data_ptr(), self.staging.data_ptr(), _stream(stream)),
+               "tkv_sparse_gather")
+
+    def attn(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor | None = None, stream=None):
+        if out is None:
+            out = torch.empty_like(q)
+        _check(lib().tkv_sparse_attn(C.byref(self.desc), C.byref(self.cache), q.data_ptr(),
+                                     self.topk_count.data_ptr(), self.staging.data_ptr(), out.data_ptr(),
+                                     float(sm_scale), self.workspace.data_ptr(), self.workspace_bytes,
+                                     _stream(stream)), "tkv_sparse_attn")
+        return out

@@ -1,0 +1,160 @@
+"""The C-ABI library loads, exports every symbol include/tkv.h declares, and reports
+argument errors without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2505_19586_amd as tkv
+from paper_2505_19586_amd import build as tkv_build
+from paper_2505_19586_amd.tkv import QuantCache, QuantDesc, SparseCache, SparseDesc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(tkv.library_path()):
+        tkv_build.build_library()
+    return tkv.lib()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "tkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tkv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = _declared_functions()
+    for required in ("tkv_quantize_append", "tkv_quant_attn_decode", "tkv_sparse_estimate_topk",
+                     "tkv_sparse_gather_attn"):
+        assert required in names
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_strerror(L):
+    assert L.tkv_strerror(0) == b"ok"
+    seen = {L.tkv_strerror(s) for s in range(-6, 1)}
+    assert len(seen) == 7
+    assert b"unknown" in L.tkv_strerror(-99)
+
+
+def _qdesc(**kw):
+    d = dict(n_q_heads=32, n_kv_heads=8, head_dim=128, bits=2, group_size=32, residual=128, capacity=4096, batch=1)
+    d.update(kw)
+    return QuantDesc(C.sizeof(QuantDesc), d["n_q_heads"], d["n_kv_heads"], d["head_dim"], d["bits"],
+                     d["group_size"], d["residual"], d["capacity"], d["batch"])
+
+
+def _sdesc(**kw):
+    d = dict(n_q_heads=32, n_kv_heads=8, head_dim=128, n_channels=16, top_k=128, n_sink=4, n_window=64,
+             capacity=4096, batch=1)
+    d.update(kw)
+    return SparseDesc(C.sizeof(SparseDesc), d["n_q_heads"], d["n_kv_heads"], d["head_dim"], d["n_channels"],
+                      d["top_k"], d["n_sink"], d["n_window"], d["capacity"], d["batch"])
+
+
+def test_quant_sizes_follow_table2(L):
+    """Sec. 4.4 Table 2: 2*n*h*d_h*(b/16 + 2/g) fp16 elements."""
+    for bits, per_tok_head in ((2, 96), (4, 160)):
+        d = _qdesc(bits=bits, capacity=131072)
+        sizes = (C.c_size_t * 8)()
+        ws = C.c_size_t()
+        assert L.tkv_quant_cache_sizes(C.byref(d), sizes, C.byref(ws)) == 0
+        total = sum(sizes[:6])
+        assert total == per_tok_head * 131072 * 8
+        assert total == int(2 * 131072 * 8 * 128 * (bits / 16 + 2 / 32) * 2)
+        assert sizes[6] == sizes[7] == 8 * 160 * 128 * 2
+        assert ws.value > 0
+
+
+def test_sparse_sizes(L):
+    d = _sdesc(capacity=131072, top_k=1024)
+    sizes = (C.c_size_t * 4)()
+    ws = C.c_size_t()
+    assert L.tkv_sparse_cache_sizes(C.byref(d), sizes, C.byref(ws)) == 0
+    assert sizes[0] == 131072 * 8 * 16 * 2              # one buffer of Table 2's 2*n*h*d_s elements
+    assert sizes[2] == 512 * 1024 * 1024
+    assert sizes[3] == 8 * 68 * 2 * 128 * 2
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(bits=3), -2), (dict(bits=1), -2), (dict(bits=0), -1), (dict(head_dim=64), -2), (dict(group_size=64), -2),
+    (dict(n_q_heads=30), -1), (dict(n_q_heads=64), -2), (dict(batch=0), -1), (dict(batch=65), -2),
+    (dict(capacity=100), -1), (dict(residual=100), -1), (dict(residual=0), -2), (dict(capacity=0), -1),
+])
+def test_quant_desc_errors(L, kw, status):
+    d = _qdesc(**kw)
+    assert L.tkv_quant_cache_sizes(C.byref(d), None, None) == status
+
+
+def test_bad_struct_size_and_null(L):
+    d = _qdesc()
+    d.struct_size = 12
+    assert L.tkv_quant_cache_sizes(C.byref(d), None, None) == -1
+    assert L.tkv_quant_cache_sizes(None, None, None) == -1
+    s = _sdesc()
+    s.struct_size = 0
+    assert L.tkv_sparse_cache_sizes(C.byref(s), None, None) == -1
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_channels=12), -2), (dict(n_channels=0), -1), (dict(top_k=0), -1), (dict(top_k=5000), -2),
+    (dict(n_window=0), -1), (dict(n_sink=-1), -1), (dict(head_dim=96), -2),
+])
+def test_sparse_desc_errors(L, kw, status):
+    assert L.tkv_sparse_cache_sizes(C.byref(_sdesc(**kw)), None, None) == status
+
+
+def test_call_errors_before_any_gpu_work(L):
+    d = _qdesc(capacity=64 * 32)
+    lens = (C.c_int32 * 1)(2040)
+    fake = 0x1000
+    cache = QuantCache(*([fake] * 8), lens)
+    # NULL inputs
+    assert L.tkv_quantize_append(C.byref(d), C.byref(cache), None, fake, 4, None) == -1
+    assert L.tkv_quantize_append(C.byref(d), None, fake, fake, 4, None) == -1
+    # capacity
+    assert L.tkv_quantize_append(C.byref(d), C.byref(cache), fake, fake, 9, None) == -3
+    assert lens[0] == 2040
+    # n_new == 0 is a no-op, negative is invalid
+    assert L.tkv_quantize_append(C.byref(d), C.byref(cache), fake, fake, 0, None) == 0
+    assert L.tkv_quantize_append(C.byref(d), C.byref(cache), fake, fake, -1, None) == -1
+    # ragged: n_valid > n_new
+    nv = (C.c_int32 * 1)(5)
+    assert L.tkv_quantize_append_ragged(C.byref(d), C.byref(cache), fake, fake, 4, nv, None) == -1
+    # workspace too small / NULL
+    assert L.tkv_quant_attn_decode(C.byref(d), C.byref(cache), fake, fake, 0.1, fake, 16, None) == -4
+    assert L.tkv_quant_attn_decode(C.byref(d), C.byref(cache), fake, None, 0.1, fake, 1 << 30, None) == -1
+    lens[0] = 5000
+    assert L.tkv_quant_attn_decode(C.byref(d), C.byref(cache), fake, fake, 0.1, fake, 1 << 30, None) == -3
+
+    s = _sdesc()
+    slens = (C.c_int32 * 1)(4090)
+    sc = SparseCache(fake, fake, fake, fake, slens)
+    assert L.tkv_sparse_append(C.byref(s), C.byref(sc), fake, fake, 10, None) == -3
+    assert L.tkv_sparse_estimate_topk(C.byref(s), C.byref(sc), fake, fake, fake, fake, 8, None) == -4
+    assert L.tkv_sparse_estimate_topk(C.byref(s), C.byref(sc), None, fake, fake, fake, 1 << 30, None) == -1
+    assert L.tkv_sparse_gather_attn(C.byref(s), C.byref(sc), fake, fake, fake, fake, 0.1, fake, fake, 8,
+                                    None, None) == -4
+    assert L.tkv_sparse_gather_attn(C.byref(s), C.byref(sc), fake, fake, fake, None, 0.1, fake, fake, 1 << 30,
+                                    None, None) == -1
+    assert L.tkv_sparse_attn(C.byref(s), C.byref(sc), fake, fake, fake, fake, 0.1, fake, 8, None) == -4
+    # a plain (unpinned) host pointer is rejected, never dereferenced
+    import numpy as np
+    plain = np.zeros(1024, np.uint8)
+    sc2 = SparseCache(fake, fake, plain.ctypes.data, fake, slens)
+    assert L.tkv_sparse_gather(C.byref(s), C.byref(sc2), fake, fake, fake, None) in (-5, -6)
+
+
+def test_binding_refuses_to_run_without_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        tkv.QuantLayer(capacity=4096)
+    with pytest.raises(RuntimeError):
+        tkv.SparseLayer(capacity=4096)

@@ -1,0 +1,108 @@
+"""GPU parity of tkv_quantize_append and tkv_quant_attn_decode against the oracle
+(through the C ABI).  Codes, scalers, zero-points: bit-exact.  Attention: max
+relative error <= 2e-3 per query head (fp16 I/O, fp32 accumulate)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_19586_amd as tkv
+from oracle import attention, quant
+from synth import HeadShape, make_layer
+
+from gpu_util import attn_err, check_quant_cache, to_new, to_new_batch
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+SM = 1.0 / np.sqrt(128.0)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("n", [4096, 1, 127, 128, 159, 160, 161, 1000])
+def test_bulk_append_and_attention(bits, n):
+    print(f"case bulk bits={bits} n={n}", flush=True)
+    inp = make_layer(n, config=0, layer=0, seq=n % 97)
+    layer = tkv.QuantLayer(bits=bits, capacity=4096 + 64)
+    layer.append(to_new(inp.k), to_new(inp.v))
+    ref = check_quant_cache(layer, 0, inp.k, inp.v)
+    out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    want = attention.quant_attention(inp.q, ref, SM)
+    err = attn_err(out[0], want)
+    print(f"   err {err:.3e}", flush=True)
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_incremental_append_equals_bulk(bits):
+    """Decode loop: 8 single-token steps that cross no group boundary, then 40 that
+    cross one, then uneven multi-token appends; after each phase the cache must be
+    the oracle's cache of the whole prefix."""
+    print(f"case incremental bits={bits}", flush=True)
+    n0, total = 4096, 4096 + 8 + 40 + 7 + 90 + 300
+    inp = make_layer(total, config=0, layer=0, seq=5)
+    layer = tkv.QuantLayer(bits=bits, capacity=8192)
+    kd, vd = to_new(inp.k), to_new(inp.v)
+    layer.append(kd[:, :n0].contiguous(), vd[:, :n0].contiguous())
+    pos = n0
+    q = torch.from_numpy(inp.q)[None].cuda()
+    for step_sizes in ([1] * 8, [1] * 40, [7], [90], [300]):
+        for s in step_sizes:
+            layer.append(kd[:, pos:pos + s].contiguous(), vd[:, pos:pos + s].contiguous())
+            pos += s
+        ref = check_quant_cache(layer, 0, inp.k[:, :pos], inp.v[:, :pos])
+        out = layer.attn_decode(q, SM)
+        assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
+    assert pos == total
+
+
+def test_append_from_empty_in_small_steps():
+    inp = make_layer(400, seq=6)
+    layer = tkv.QuantLayer(bits=2, capacity=512)
+    kd, vd = to_new(inp.k), to_new(inp.v)
+    pos = 0
+    for s in [1, 1, 30, 96, 31, 1, 1, 200, 39]:
+        layer.append(kd[:, pos:pos + s].contiguous(), vd[:, pos:pos + s].contiguous())
+        pos += s
+        check_quant_cache(layer, 0, inp.k[:, :pos], inp.v[:, :pos])
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_ragged_batch(bits):
+    print(f"case ragged bits={bits}", flush=True)
+    lens = [700, 1, 2048, 333, 160]
+    inps = [make_layer(n, config=4, layer=0, seq=b) for b, n in enumerate(lens)]
+    layer = tkv.QuantLayer(bits=bits, capacity=2048, batch=len(lens))
+    layer.append(to_new_batch([i.k for i in inps], 2048), to_new_batch([i.v for i in inps], 2048), n_valid=lens)
+    q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
+    out = layer.attn_decode(q, SM)
+    for b, inp in enumerate(inps):
+        ref = check_quant_cache(layer, b, inp.k, inp.v)
+        assert attn_err(out[b], attention.quant_attention(inp.q, ref, SM)) <= TOL
+
+
+def test_empty_sequence_gives_zeros():
+    layer = tkv.QuantLayer(bits=2, capacity=256)
+    q = torch.randn(1, 32, 128, dtype=torch.float16, device="cuda")
+    out = layer.attn_decode(q, SM)
+    torch.cuda.synchronize()
+    assert (out == 0).all()
+
+
+@pytest.mark.parametrize("shape", [HeadShape(8, 8, 128), HeadShape(16, 8, 128), HeadShape(4, 1, 128)])
+def test_other_head_groupings(shape):
+    inp = make_layer(777, shape=shape, seq=8)
+    layer = tkv.QuantLayer(n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads, bits=2, capacity=1024)
+    layer.append(to_new(inp.k), to_new(inp.v))
+    ref = check_quant_cache(layer, 0, inp.k, inp.v)
+    out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
+
+
+def test_peaked_attention_and_extreme_values():
+    """A dominant token (large logit) and large-magnitude keys: softmax must not overflow."""
+    inp = make_layer(2048, seq=9, dominance_gain=6.0)
+    inp.k[:, 100] *= np.float16(8)
+    layer = tkv.QuantLayer(bits=4, capacity=2048)
+    layer.append(to_new(inp.k), to_new(inp.v))
+    ref = check_quant_cache(layer, 0, inp.k, inp.v)
+    out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL

@@ -1,0 +1,147 @@
+"""GPU parity of the sparse path against the oracle (through the C ABI).
+Top-K indices and counts: bit-exact.  Attention: <= 2e-3."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_19586_amd as tkv
+from oracle import attention, sparse
+from synth import HeadShape, make_layer, static_channels
+
+from gpu_util import attn_err, to_new, to_new_batch
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+SM = 1.0 / np.sqrt(128.0)
+
+
+def _build(inp, *, top_k, capacity, n_channels=16, shape=None, n_sink=4, n_window=64):
+    shape = shape or HeadShape(inp.q.shape[0], inp.k.shape[0], 128)
+    layer = tkv.SparseLayer(n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads, n_channels=n_channels,
+                            top_k=top_k, n_sink=n_sink, n_window=n_window, capacity=capacity)
+    ch = static_channels(inp.k, n_channels)
+    layer.set_channels(ch[None])
+    layer.append(to_new(inp.k), to_new(inp.v))
+    return layer, ch
+
+
+def _check_layer(layer, b, inp, ch, q_dev, out):
+    d = layer.desc
+    n = inp.k.shape[1]
+    summ = sparse.key_summary(inp.k, ch)
+    idx, cnt = sparse.estimate_topk(inp.q, summ, ch, n, top_k=d.top_k, n_sink=d.n_sink, n_window=d.n_window)
+    torch.cuda.synchronize()
+    got_idx = layer.topk_idx[b].cpu().numpy()
+    got_cnt = layer.topk_count[b].cpu().numpy()
+    assert np.array_equal(got_cnt, cnt)
+    assert np.array_equal(got_idx, idx)
+    want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, n, SM, n_sink=d.n_sink, n_window=d.n_window)
+    err = attn_err(out[b], want)
+    print(f"   n={n} err {err:.3e}", flush=True)
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("n,top_k", [(4096, 128), (1, 128), (3, 16), (68, 16), (69, 16), (70, 128), (1500, 1024),
+                                     (5000, 1024), (1024, 128), (1025, 128)])
+def test_estimate_topk_gather_attention(n, top_k):
+    print(f"case sparse n={n} k={top_k}", flush=True)
+    inp = make_layer(n, config=0, layer=1, seq=n % 89)
+    layer, ch = _build(inp, top_k=top_k, capacity=max(n, 64) + 37)
+    # cache contents: summary, host rows, resident rows
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.key_summary[0, :, :n].cpu().numpy().view(np.uint16),
+                          sparse.key_summary(inp.k, ch).view(np.uint16))
+    host = layer.kv_host[0, :, :n].numpy()
+    assert np.array_equal(host[:, :, 0].view(np.uint16), inp.k.view(np.uint16))
+    assert np.array_equal(host[:, :, 1].view(np.uint16), inp.v.view(np.uint16))
+    q = torch.from_numpy(inp.q)[None].cuda()
+    layer.estimate_topk(q)
+    out = layer.gather_attn(q, SM)
+    _check_layer(layer, 0, inp, ch, q, out)
+    # the staged rows are the selected rows
+    cnt = int(layer.topk_count[0, 0])
+    if cnt:
+        sel = layer.topk_idx[0, 0, :cnt].cpu().numpy()
+        st = layer.staging[0, 0, :cnt].cpu().numpy()
+        assert np.array_equal(st[:, 0].view(np.uint16), inp.k[0, sel].view(np.uint16))
+        assert np.array_equal(st[:, 1].view(np.uint16), inp.v[0, sel].view(np.uint16))
+
+
+def test_ties_take_lowest_indices():
+    """All-equal summaries -> all scores equal -> indices n_sink .. n_sink+k-1."""
+    n, top_k = 3000, 128
+    inp = make_layer(n, seq=3)
+    ch = static_channels(inp.k, 16)
+    for h in range(8):
+        inp.k[h][:, ch[h]] = inp.k[h][0, ch[h]]
+    layer = tkv.SparseLayer(top_k=top_k, capacity=n)
+    layer.set_channels(ch[None])
+    layer.append(to_new(inp.k), to_new(inp.v))
+    q = torch.from_numpy(inp.q)[None].cuda()
+    idx, cnt = layer.estimate_topk(q)
+    torch.cuda.synchronize()
+    assert (cnt.cpu().numpy() == top_k).all()
+    assert np.array_equal(idx[0].cpu().numpy(), np.tile(np.arange(4, 4 + top_k, dtype=np.int32), (8, 1)))
+    out = layer.gather_attn(q, SM)
+    _check_layer(layer, 0, inp, ch, q, out)
+
+
+def test_heavy_ties_quantized_scores():
+    """Integer-valued keys/queries give many exactly equal scores at the threshold."""
+    rng = np.random.default_rng(2)
+    n = 4000
+    inp = make_layer(n, seq=4)
+    inp.k[:] = rng.integers(-2, 3, size=inp.k.shape).astype(np.float16)
+    inp.q[:] = rng.integers(-2, 3, size=inp.q.shape).astype(np.float16)
+    layer, ch = _build(inp, top_k=256, capacity=n)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    layer.estimate_topk(q)
+    out = layer.gather_attn(q, SM)
+    _check_layer(layer, 0, inp, ch, q, out)
+
+
+def test_two_streams_and_incremental_append():
+    print("case sparse two streams", flush=True)
+    n0, extra = 3000, 70
+    inp = make_layer(n0 + extra, config=0, layer=1, seq=7)
+    layer = tkv.SparseLayer(top_k=128, capacity=4096)
+    ch = static_channels(inp.k, 16)
+    layer.set_channels(ch[None])
+    kd, vd = to_new(inp.k), to_new(inp.v)
+    layer.append(kd[:, :n0].contiguous(), vd[:, :n0].contiguous())
+    q = torch.from_numpy(inp.q)[None].cuda()
+    side = torch.cuda.Stream()
+    pos = n0
+    for s in [1, 1, 5, 63]:
+        layer.append(kd[:, pos:pos + s].contiguous(), vd[:, pos:pos + s].contiguous())
+        pos += s
+        layer.estimate_topk(q)
+        out = layer.gather_attn(q, SM, gather_stream=side)
+        sub = make_layer.__globals__["LayerInputs"](inp.q, inp.k[:, :pos], inp.v[:, :pos], inp.outlier_channels,
+                                                    inp.dominant_tokens)
+        _check_layer(layer, 0, sub, ch, q, out)
+
+
+def test_ragged_batch():
+    print("case sparse ragged", flush=True)
+    lens = [900, 5, 2000, 68, 1311]
+    inps = [make_layer(n, config=4, layer=2, seq=b) for b, n in enumerate(lens)]
+    layer = tkv.SparseLayer(top_k=256, capacity=2048, batch=len(lens))
+    chs = [static_channels(i.k, 16) for i in inps]
+    layer.set_channels(np.stack(chs))
+    layer.append(to_new_batch([i.k for i in inps], 2000), to_new_batch([i.v for i in inps], 2000), n_valid=lens)
+    q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
+    layer.estimate_topk(q)
+    out = layer.gather_attn(q, SM)
+    for b, inp in enumerate(inps):
+        _check_layer(layer, b, inp, chs[b], q, out)
+
+
+@pytest.mark.parametrize("shape,n_channels", [(HeadShape(8, 8, 128), 16), (HeadShape(16, 8, 128), 8)])
+def test_other_shapes(shape, n_channels):
+    inp = make_layer(2500, shape=shape, seq=11)
+    layer, ch = _build(inp, top_k=200, capacity=2500, n_channels=n_channels, shape=shape)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    layer.estimate_topk(q)
+    out = layer.gather_attn(q, SM)
+    _check_layer(layer, 0, inp, ch, q, out)
