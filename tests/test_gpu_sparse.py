@@ -6,7 +6,7 @@ import torch
 
 import paper_2505_19586_amd as tkv
 from oracle import attention, sparse
-from synth import HeadShape, make_layer, static_channels
+from synth import HeadShape, LayerInputs, make_layer, static_channels
 
 from gpu_util import attn_err, to_new, to_new_batch
 
@@ -117,8 +117,7 @@ def test_two_streams_and_incremental_append():
         pos += s
         layer.estimate_topk(q)
         out = layer.gather_attn(q, SM, gather_stream=side)
-        sub = make_layer.__globals__["LayerInputs"](inp.q, inp.k[:, :pos], inp.v[:, :pos], inp.outlier_channels,
-                                                    inp.dominant_tokens)
+        sub = LayerInputs(inp.q, inp.k[:, :pos], inp.v[:, :pos], inp.outlier_channels, inp.dominant_tokens)
         _check_layer(layer, 0, sub, ch, q, out)
 
 
