@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Decode-attention benchmark of the hybrid KV cache on one MI355X.
+
+Workload (default): the full 32-layer decode step at 128k context, batch 1, with
+Llama-3.1-8B attention shapes: layers 0-1 quantization-friendly (2 bit, g = 32,
+128-token fp16 tail), layers 2-31 sparsity-friendly (16 summary channels on the
+GPU, Top-K 1024 + 4 sinks + 64-token window, full fp16 K/V in pinned host memory).
+One step = every call of the hot path for every layer.  Metric: microseconds per
+layer-token (step time / 32).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+N_LAYERS = 32
+QUANT_LAYERS = (0, 1)
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--context", type=int, default=131072)
+    ap.add_argument("--bits", type=int, default=2)
+    ap.add_argument("--top-k", type=int, default=1024)
+    ap.add_argument("--host-layers", type=int, default=30,
+                    help="distinct pinned host K/V caches (30 = one per sparse layer)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--schedule", choices=["chained", "overlapped"], default="chained")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(the path shards by KV head, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2505_19586_amd as tkv
+    from synth.device import make_layer_device, static_channels_device
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(tkv.library_path()):
+        from paper_2505_19586_amd import build as b
+        b.build_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    N = args.context
+    CAP = N + 32 * ((args.steps * 2 + args.warmup + 64 + 31) // 32)
+    sm = 1.0 / np.sqrt(128.0)
+    t_build = time.time()
+
+    # ---- measured host-link ceiling: one pinned 1 GiB H2D copy
+    pin = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    h2d = 0.0
+    for _ in range(3):
+        e0.record(); dst.copy_(pin, non_blocking=True); e1.record(); e1.synchronize()
+        h2d = max(h2d, (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del pin, dst
+
+    # ---- build the caches
+    layers = []
+    qs = []
+    host_pool = []
+    sample = {}
+    for l in range(N_LAYERS):
+        q, k, v = make_layer_device(N, seed=1000 + l, device=dev)
+        qs.append(q[None].contiguous())
+        if l in QUANT_LAYERS:
+            L = tkv.QuantLayer(bits=args.bits, capacity=CAP, device=dev)
+            L.append(k[None], v[None])
+            if l == 0:
+                sample["quant"] = (q.cpu().numpy(), k.permute(1, 0, 2).contiguous().cpu().numpy(),
+                                   v.permute(1, 0, 2).contiguous().cpu().numpy())
+        else:
+            si = l - len(QUANT_LAYERS)
+            kv_host = None
+            if si >= args.host_layers:
+                kv_host = host_pool[si % args.host_layers]
+            L = tkv.SparseLayer(top_k=args.top_k, capacity=CAP, device=dev, kv_host=kv_host)
+            if kv_host is None:
+                host_pool.append(L.kv_host)
+            L.set_channels(static_channels_device(k, 16)[None])
+            if kv_host is None:
+                L.append(k[None], v[None])
+            else:  # aliased host cache: keep its rows, refresh only the GPU-side state
+                tmp = tkv.SparseLayer(top_k=args.top_k, capacity=CAP, device=dev)
+                tmp.set_channels(L.channel_idx)
+                tmp.append(k[None], v[None])
+                L.key_summary.copy_(tmp.key_summary); L.kv_local.copy_(tmp.kv_local); L.seq_len[:] = tmp.seq_len
+                del tmp
+            if l == len(QUANT_LAYERS):
+                sample["sparse"] = (q.cpu().numpy(), k.permute(1, 0, 2).contiguous().cpu().numpy(),
+                                    v.permute(1, 0, 2).contiguous().cpu().numpy(), L.channel_idx[0].cpu().numpy())
+        layers.append(L)
+        del k, v
+    torch.cuda.synchronize()
+    t_build = time.time() - t_build
+
+    outs = [torch.empty(1, 32, 128, dtype=torch.float16, device=dev) for _ in range(N_LAYERS)]
+    g = torch.Generator(device=dev); g.manual_seed(7)
+    new_k = [torch.randn(1, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
+    new_v = [torch.randn(1, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
+    compute = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    chained = args.schedule == "chained"
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(rec=None):
+        for l, L in enumerate(layers):
+            L.append(new_k[l], new_v[l])      # Eq. 2: the step's new token joins the cache first
+            if l in QUANT_LAYERS:
+                if rec is not None:
+                    a, b = ev(), ev(); a.record()
+                L.attn_decode(qs[l], sm, out=outs[l])
+                if rec is not None:
+                    b.record(); rec["quant"].append((a, b))
+            else:
+                if rec is not None:
+                    a, b = ev(), ev(); a.record()
+                L.estimate_topk(qs[l])
+                if rec is not None:
+                    b.record(); rec["topk"].append((a, b))
+                if chained:
+                    if rec is not None:
+                        g0, g1 = ev(), ev(); g0.record()
+                    L.gather()
+                    if rec is not None:
+                        g1.record(); rec["gather"].append((g0, g1))
+                    L.attn(qs[l], sm, out=outs[l])
+                else:
+                    L.gather_attn(qs[l], sm, out=outs[l], gather_stream=side, compute_stream=compute)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # timed region: exactly K steps
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # per-kernel durations with events on the launching stream (separate passes so the
+    # events do not perturb the step time above)
+    rec = {"quant": [], "topk": [], "gather": []}
+    chained_was = chained
+    chained = True
+    for _ in range(max(3, args.steps // 2)):
+        step(rec)
+    torch.cuda.synchronize()
+    chained = chained_was
+    dur = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) * 1e3 for k, v in rec.items() if v}  # us
+
+    nq = (N - 128) // 32 * 32
+    per_tok_head = {2: 96, 4: 160}[args.bits]
+    quant_bytes = 8 * nq * per_tok_head + 8 * (N - nq) * 512 + 2 * 32 * 128 * 2
+    summary_bytes = 8 * N * 32
+    gather_bytes = 8 * args.top_k * 512
+    roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    extra = {
+        "quant_attn_us": dur["quant"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"],
+        "estimate_topk_GBs": summary_bytes / dur["topk"] / 1e3,
+        "host_link": {"bound": "host_link", "kernel": "tkv_sparse_gather", "achieved": gather_bytes / dur["gather"] / 1e3,
+                      "peak": h2d, "unit": "GB/s", "frac": gather_bytes / dur["gather"] / 1e3 / h2d,
+                      "peak_source": "pinned 1 GiB hipMemcpy H2D measured in this run"},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(sample, N, args, sm)
+
+    line = {
+        "metric": "decode attention us per layer-token at 128k ctx", "value": ms_per_step * 1e3 / N_LAYERS,
+        "unit": "us/layer-token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"configs[3]: 32-layer hybrid decode step, batch 1, N={N}, layers 0-1 {args.bits}-bit "
+                               f"quantized (g=32, W=128), layers 2-31 sparse (d_s=16, k={args.top_k}, 4 sinks, "
+                               f"64 window)", "schedule": args.schedule, "distinct_host_caches": len(host_pool),
+                   "build_s": round(t_build, 1)},
+        "roofline": roof, "cpu_baseline": cpu, **extra,
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(sample, N, args, sm):
+    """The oracle as it stands on the host cores, on a bounded sample: one whole
+    quantized layer and one whole sparse layer at the full context, a few repetitions
+    each, weighted 2 : 30 over the 32 layers."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import attention, quant, sparse
+
+    q, k, v = sample["quant"]
+    t0 = time.perf_counter()
+    c = quant.quantize_kv(k, v, bits=args.bits, group=32, residual=128)
+    t_quantize = time.perf_counter() - t0
+    reps = 6
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        attention.quant_attention(q, c, sm)
+    t_quant = (time.perf_counter() - t0) / reps
+    q, k, v, ch = sample["sparse"]
+    summ = sparse.key_summary(k, ch)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        idx, cnt = sparse.estimate_topk(q, summ, ch, N, top_k=args.top_k, n_sink=4, n_window=64)
+        sparse.sparse_attention(q, k, v, idx, cnt, N, sm, n_sink=4, n_window=64)
+    t_sparse = (time.perf_counter() - t0) / reps
+    per_layer_token_us = (2 * t_quant + 30 * t_sparse) / 32 * 1e6
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": per_layer_token_us, "unit": "us/layer-token", "cores": threads, "kind": "oracle",
+            "sample": "one whole quantized layer and one whole sparse layer (8 KV heads, 32 query heads) at N=%d, "
+                      "%d repetitions each, weighted 2:30 over the 32 layers; quant attention %.2fs, sparse "
+                      "estimate+topk+attention %.2fs per layer-token (quantizing the layer once: %.1fs, "
+                      "not counted)" % (N, reps, t_quant, t_sparse, t_quantize)}
+
+
+if __name__ == "__main__":
+    main()

@@ -203,7 +203,9 @@ class SparseLayer:
         self.device = dev
 
     def set_channels(self, channel_idx) -> None:
-        self.channel_idx.copy_(torch.as_tensor(np.asarray(channel_idx), dtype=torch.int32).view_as(self.channel_idx))
+        if not isinstance(channel_idx, torch.Tensor):
+            channel_idx = torch.from_numpy(np.ascontiguousarray(channel_idx, dtype=np.int32))
+        self.channel_idx.copy_(channel_idx.to(torch.int32).reshape(self.channel_idx.shape))
 
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor, n_valid=None, stream=None) -> None:
         d = self.desc
