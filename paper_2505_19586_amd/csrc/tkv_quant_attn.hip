@@ -7,11 +7,14 @@ namespace tkv {
 // matrix-core path (tkv_quant_attn_mfma.hip); returns TKV_E_UNSUPPORTED when the
 // shape is not one it is built for.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, float scale2,
-                               float* parts, int groups_per_chunk, int n_chunks, const TkvSeqLens& lens,
-                               hipStream_t s);
+                               float* parts, int groups_per_chunk, int n_chunks, int n_parts,
+                               const TkvSeqLens& lens, hipStream_t s);
 }  // namespace tkv
 
 namespace {
+
+int g_kernel_choice = 0;      // 0: matrix-core kernel (+ reference kernel for the tail), 1: reference kernel only
+int g_target_blocks = 1024;   // workgroups the split-K launch aims at
 
 struct QuantAttnParams {
   const uint32_t* k_codes;
@@ -27,6 +30,7 @@ struct QuantAttnParams {
   float scale2;  // sm_scale * log2(e)
   int32_t hq, hkv, bits, residual, capacity;
   int32_t groups_per_chunk, n_chunks;
+  int32_t chunk_offset;  // blockIdx.x + chunk_offset is the chunk; chunk == n_chunks is the fp16 tail
   TkvSeqLens lens;
 };
 
@@ -48,7 +52,7 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
   __shared__ float red_m[4][4], red_l[4][4];
   __shared__ float red_o[4][4][TKV_D];
 
-  const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
+  const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x + p.chunk_offset;
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int G = p.hq / p.hkv;
   const int n = p.lens.n[b];
@@ -240,6 +244,13 @@ int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, in
 }
 }  // namespace tkv
 
+extern "C" int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks) {
+  if (kernel_choice < 0 || kernel_choice > 1 || target_blocks < 0) return TKV_E_INVAL;
+  g_kernel_choice = kernel_choice;
+  if (target_blocks > 0) g_target_blocks = target_blocks;
+  return TKV_OK;
+}
+
 extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q,
                                          void* out, float sm_scale, void* workspace, size_t workspace_bytes,
                                          void* stream) {
@@ -265,7 +276,7 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   }
   // Chunking: aim at ~4 workgroups per compute unit over the whole launch.
   const int bh = d->batch * d->n_kv_heads;
-  int target = (1024 + bh - 1) / bh;
+  int target = (g_target_blocks + bh - 1) / bh;
   if (target > TKV_MAX_CHUNKS) target = TKV_MAX_CHUNKS;
   if (target < 1) target = 1;
   int gpc = (max_groups + target - 1) / target;
@@ -293,7 +304,16 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   p.n_chunks = n_chunks;
 
   hipStream_t s = (hipStream_t)stream;
-  quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+  if (g_kernel_choice == 0) {
+    // matrix-core kernel over the quantized groups, reference kernel for the fp16 tail
+    st = tkv::launch_quant_attn_mfma(d, c, p.q, p.scale2, p.parts, gpc, n_chunks, n_chunks + 1, p.lens, s);
+    if (st != TKV_OK) return st;
+    p.chunk_offset = n_chunks;
+    quant_attn_generic_kernel<<<dim3(1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+  } else {
+    p.chunk_offset = 0;
+    quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+  }
   if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, n_chunks + 1, s);
 }

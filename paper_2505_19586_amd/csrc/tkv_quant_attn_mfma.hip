@@ -1,0 +1,402 @@
+// Matrix-core kernel of tkv_quant_attn_decode (Sec. 2.1 Eq. 3 over the quantized cache
+// of Sec. 4.3) for gfx950, G = Hq/Hkv <= 4, D = 128, g = 32, bits 2 or 4.
+//
+// One wave64 owns one 32-token group at a time.  Both contractions run on
+// v_mfma_f32_16x16x32_f16 with the packed codes as the A operand:
+//
+//   * a b-bit code c sitting at mantissa bits [bp, bp+b) of an otherwise zero fp16 IS
+//     the subnormal number c * 2^bp * 2^-24, so one v_and_b32 per register turns two
+//     codes into two exact fp16 operands (no bias, no convert); the 2^bp factor is
+//     compensated in the other operand;
+//   * q.K-hat = sum_c code[t][c] * (q[c] s[c]) + sum_c q[c] z[c]: the scaler moves into
+//     the query operand (split into fp16 hi + lo parts so the product keeps ~22 bits),
+//     the zero-point term is a second tiny MFMA per group;
+//   * p.V-hat = sum_t code[t][d] * (p[t] s_v[t][u]) + sum_t p[t] z_v[t][u]: the 16
+//     operand columns are the 4 query heads x 4 channel groups u, so the weights never
+//     leave the lanes that produced them (the D layout of the first product is the B
+//     layout of the second); z_v and the softmax denominator ride on one more MFMA.
+//
+// Softmax is online per wave with lazy rescaling; the four waves of a workgroup and the
+// chunks of a sequence are merged with log-sum-exp merges.
+#include "tkv_common.h"
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+struct MfmaParams {
+  const uint32_t* k_codes;
+  const uint32_t* v_codes;
+  const __half* k_scale;
+  const __half* k_zero;
+  const __half* v_scale;
+  const __half* v_zero;
+  const __half* q;
+  float* parts;
+  float scale2;
+  int32_t hq, hkv, residual, capacity;
+  int32_t groups_per_chunk, n_parts;
+  float* dbg;
+  TkvSeqLens lens;
+};
+
+__device__ inline floatx4 mfma(uintx4 a, uintx4 b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+}
+
+// Reinterpret one 32-bit register as two fp16.  Takes the word BY VALUE: applying
+// __builtin_bit_cast directly to an element of an ext-vector (vec[j]) reads element 0
+// for every j with this compiler.
+__device__ inline half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+
+__device__ inline uint32_t pack2(_Float16 lo, _Float16 hi) {
+  half2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// Two MFMA operands (8 registers) out of one 32-bit word of packed codes.
+template <int BITS>
+__device__ inline void extract(uint32_t w, uintx4& a0, uintx4& a1) {
+  if (BITS == 2) {
+    const uint32_t w8 = w >> 8;
+    a0[0] = w & 0x00030003u;
+    a0[1] = w & 0x000C000Cu;
+    a0[2] = w & 0x00300030u;
+    a0[3] = w & 0x00C000C0u;
+    a1[0] = w8 & 0x00030003u;
+    a1[1] = w8 & 0x000C000Cu;
+    a1[2] = w8 & 0x00300030u;
+    a1[3] = w8 & 0x00C000C0u;
+  }
+}
+// 4 bit: one operand per word.
+__device__ inline void extract4(uint32_t w, uintx4& a) {
+  const uint32_t w8 = w >> 8;
+  a[0] = w & 0x000F000Fu;
+  a[1] = w & 0x00F000F0u;
+  a[2] = w8 & 0x000F000Fu;
+  a[3] = w8 & 0x00F000F0u;
+}
+
+constexpr int kEK = 4;       // query-side operands carry 2^kEK
+constexpr int kEP = 6;       // weight-side operands carry 2^kEP
+constexpr float kHeadroom = 4.0f;  // lazy rescale: weights may reach 2^kHeadroom
+
+template <int BITS>
+__global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
+  constexpr int NW = 2 * BITS;          // 32-bit words per lane per group, for K and for V: 4 or 8
+  constexpr int NWORDS = TKV_D * BITS;  // words per group block
+  // per wave: query-side operand [hi/lo][4 heads][128 ch] fp16 + zero-points [128] fp16
+  __shared__ __attribute__((aligned(16))) uint32_t bk_s[4][2][4][TKV_D / 2];
+  __shared__ __attribute__((aligned(16))) uint32_t kz_s[4][TKV_D / 2];
+  __shared__ float red_m[4][4], red_l[4][4], red_z[4][4][4];
+  __shared__ float red_o[4][4][TKV_D];
+
+  const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+  const int G = p.hq / p.hkv;
+  const int n = p.lens.n[b];
+  const int jq = tkv::n_quantized(n, p.residual) / TKV_G;
+  const size_t bh = (size_t)b * p.hkv + h;
+  const size_t grp_base = bh * (size_t)(p.capacity / TKV_G);
+  const int blk0 = chunk * p.groups_per_chunk;
+  const int blk1 = min(blk0 + p.groups_per_chunk, jq);
+
+  const int slot = lane % 16, rb = lane / 16;
+  const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, channel group
+  const __half* qrow = p.q + ((size_t)b * p.hq + (size_t)h * G) * TKV_D;
+
+  // query as exact fp16 B operand (zero-point term) and as scaled float (scaler term)
+  uintx4 bq[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    if (hs < G) {
+      bq[m] = *reinterpret_cast<const uintx4*>(qrow + (size_t)hs * TKV_D + 32 * m + 8 * rb);
+    } else {
+      bq[m] = uintx4{0u, 0u, 0u, 0u};
+    }
+  }
+  // K-prep role: this lane owns channels 2*lane, 2*lane+1; their field position is lane%4
+  // (2 bit: 4^pos) or lane%2 (4 bit: 16^pos).
+  float qf[4][2];
+  {
+    const int pos = BITS == 2 ? lane % 4 : lane % 2;
+    const float comp = BITS == 2 ? (float)(1 << kEK) / (float)(1 << (2 * pos)) : (float)(1 << kEK) / (float)(1 << (4 * pos));
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh) {
+      qf[hh][0] = hh < G ? __half2float(qrow[(size_t)hh * TKV_D + 2 * lane]) * comp : 0.f;
+      qf[hh][1] = hh < G ? __half2float(qrow[(size_t)hh * TKV_D + 2 * lane + 1]) * comp : 0.f;
+    }
+  }
+  // codes carry 2^-24, query side 2^kEK, so S = acc * 2^(24-kEK)
+  const float K1 = p.scale2 * (float)(1 << (24 - kEK));
+
+  floatx4 acc_o[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc_o[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+  floatx4 acc_z = {0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY;
+
+  // A operand of the z_v / denominator MFMA: rows 0..3 hold z_v[u = row] (loaded per group)
+  // times the constant that undoes the weight-side scaling, row 4 holds that constant
+  // alone (denominator), rows 5.. are zero.  Built branch-free as load * zmul + zadd.
+  const int zrow = slot;                   // as A operand this lane holds row `slot`
+  const int zrow_ld = zrow < 4 ? zrow : 3;  // rows >= 4 load a valid row and multiply it by 0
+  half2_t zmul[4], zadd[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    // element k = 2j + e of this lane carries 2^-kEP * (4^j | 16^(j%2))
+    const float w = BITS == 2 ? (float)(1 << (2 * j)) / (float)(1 << kEP) : (float)(1 << (4 * (j % 2))) / (float)(1 << kEP);
+    const _Float16 wm = (_Float16)(zrow < 4 ? w : 0.f), wa = (_Float16)(zrow == 4 ? w : 0.f);
+    zmul[j] = half2_t{wm, wm};
+    zadd[j] = half2_t{wa, wa};
+  }
+  // exponent offsets that put 2^kEP / (4^j | 16^(j%2)) into the weights; value i of the
+  // lane (tile tau = i/4, row x = i%4) is element kappa = 4 tau + x, register j = kappa/2
+  float off[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int j = i / 2;
+    off[i] = BITS == 2 ? (float)(kEP - 2 * j) : (float)(kEP - 4 * (j % 2));
+  }
+
+  for (int blk = blk0 + wave; blk < blk1; blk += 4) {
+    const size_t grp = grp_base + blk;
+    // ---- loads of this group
+    uint32_t kw[NW], vw[NW];
+    {
+      const uint32_t* kc = p.k_codes + grp * NWORDS;
+      const uint32_t* vc = p.v_codes + grp * NWORDS;
+#pragma unroll
+      for (int x = 0; x < NW / 4; ++x) {
+        const uintx4 t = *reinterpret_cast<const uintx4*>(kc + 256 * x + 4 * lane);
+        const uintx4 u = *reinterpret_cast<const uintx4*>(vc + 256 * x + 4 * lane);
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+          kw[4 * x + y] = t[y];
+          vw[4 * x + y] = u[y];
+        }
+      }
+    }
+    const uint32_t ks2 = reinterpret_cast<const uint32_t*>(p.k_scale + grp * TKV_D)[lane];
+    const uint32_t kz2 = reinterpret_cast<const uint32_t*>(p.k_zero + grp * TKV_D)[lane];
+    const uintx4 sv = *reinterpret_cast<const uintx4*>(p.v_scale + (grp * 4 + us) * TKV_G + 8 * rb);
+    const uintx4 zv_raw = *reinterpret_cast<const uintx4*>(p.v_zero + (grp * 4 + zrow_ld) * TKV_G + 8 * rb);
+
+    // ---- query-side operand of this group: (q s) split into hi + lo, through LDS
+    {
+      const half2_t s2 = as_half2(ks2);
+      const float s0 = (float)s2[0], s1 = (float)s2[1];
+#pragma unroll
+      for (int hh = 0; hh < 4; ++hh) {
+        const float p0 = qf[hh][0] * s0, p1 = qf[hh][1] * s1;  // exact: 11 x 11 bit mantissas
+        const _Float16 h0 = (_Float16)p0, h1 = (_Float16)p1;
+        const _Float16 l0 = (_Float16)(p0 - (float)h0), l1 = (_Float16)(p1 - (float)h1);
+        bk_s[wave][0][hh][lane] = pack2(h0, h1);
+        bk_s[wave][1][hh][lane] = pack2(l0, l1);
+      }
+      kz_s[wave][lane] = kz2;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- zero-point term: cz[slot] = sum_c z[c] q[c], identical in every row
+    floatx4 acc_cz = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const uintx4 az = *reinterpret_cast<const uintx4*>(&kz_s[wave][(32 * m + 8 * rb) / 2]);
+      acc_cz = mfma(az, bq[m], acc_cz);
+    }
+    // ---- scaler term for the two 16-token tiles
+    floatx4 acc_s[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int m2 = 0; m2 < 2; ++m2) {  // pairs of MFMA steps m = 2*m2, 2*m2+1
+      uintx4 bh[2], bl[2];
+#pragma unroll
+      for (int y = 0; y < 2; ++y) {
+        const int m = 2 * m2 + y;
+        bh[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][0][hs][(32 * m + 8 * rb) / 2]);
+        bl[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][1][hs][(32 * m + 8 * rb) / 2]);
+      }
+#pragma unroll
+      for (int tau = 0; tau < 2; ++tau) {
+        uintx4 a[2];
+        if (BITS == 2) {
+          extract<2>(kw[2 * tau + m2], a[0], a[1]);
+        } else {
+          extract4(kw[4 * tau + 2 * m2], a[0]);
+          extract4(kw[4 * tau + 2 * m2 + 1], a[1]);
+        }
+#pragma unroll
+        for (int y = 0; y < 2; ++y) {
+          acc_s[tau] = mfma(a[y], bh[y], acc_s[tau]);
+          acc_s[tau] = mfma(a[y], bl[y], acc_s[tau]);
+        }
+      }
+    }
+
+    // ---- online softmax (log2 domain), lazy rescale
+    const float cz = acc_cz[0] * p.scale2;
+    float mx = fmaxf(fmaxf(fmaxf(acc_s[0][0], acc_s[0][1]), fmaxf(acc_s[0][2], acc_s[0][3])),
+                     fmaxf(fmaxf(acc_s[1][0], acc_s[1][1]), fmaxf(acc_s[1][2], acc_s[1][3])));
+    const float xmax = __builtin_fmaf(mx, K1, cz);  // largest logit among this lane's 8 tokens
+    if (__builtin_amdgcn_ballot_w64(xmax - m_run > kHeadroom) != 0ull) {
+      // new reference maximum, uniform over the lanes that share a query head
+      float mn = fmaxf(m_run, xmax);
+      mn = fmaxf(mn, __shfl_xor(mn, 4, 64));
+      mn = fmaxf(mn, __shfl_xor(mn, 8, 64));
+      mn = fmaxf(mn, __shfl_xor(mn, 16, 64));
+      mn = fmaxf(mn, __shfl_xor(mn, 32, 64));
+      const float alpha = exp2f(m_run - mn);  // 0 on the first group
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc_o[i] *= alpha;
+      acc_z *= alpha;
+      m_run = mn;
+    }
+    const float czm = cz - m_run;
+    float pw[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pw[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[i / 4][i % 4], K1, czm + off[i]));
+
+    // ---- weight-side operands: p*s_v (hi, lo) and p (hi, lo)
+    uintx4 b2h, b2l, bph, bpl;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t svj = sv[j];
+      const half2_t s2 = as_half2(svj);
+      const float w0 = pw[2 * j], w1 = pw[2 * j + 1];
+      const float x0 = w0 * (float)s2[0], x1 = w1 * (float)s2[1];
+      const _Float16 xh0 = (_Float16)x0, xh1 = (_Float16)x1;
+      b2h[j] = pack2(xh0, xh1);
+      b2l[j] = pack2((_Float16)(x0 - (float)xh0), (_Float16)(x1 - (float)xh1));
+      const _Float16 ph0 = (_Float16)w0, ph1 = (_Float16)w1;
+      bph[j] = pack2(ph0, ph1);
+      bpl[j] = pack2((_Float16)(w0 - (float)ph0), (_Float16)(w1 - (float)ph1));
+    }
+    uintx4 a_zv;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t zvj = zv_raw[j];
+      const half2_t t = __builtin_elementwise_fma(as_half2(zvj), zmul[j], zadd[j]);
+      a_zv[j] = __builtin_bit_cast(uint32_t, t);
+    }
+    acc_z = mfma(a_zv, bph, acc_z);
+    acc_z = mfma(a_zv, bpl, acc_z);
+
+    if (p.dbg && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && wave == 0 && blk == blk0) {
+      float* d = p.dbg + lane * 64;
+      for (int i = 0; i < 8; ++i) d[i] = acc_s[i / 4][i % 4];
+      for (int i = 0; i < 8; ++i) d[8 + i] = pw[i];
+      d[16] = acc_cz[0]; d[17] = m_run; d[18] = cz; d[19] = xmax;
+      for (int i = 0; i < 4; ++i) d[20 + i] = acc_z[i];
+      for (int i = 0; i < 4; ++i) d[24 + i] = __uint_as_float(a_zv[i]);
+      for (int i = 0; i < 4; ++i) d[28 + i] = __uint_as_float(bph[i]);
+      for (int i = 0; i < 4; ++i) d[32 + i] = __uint_as_float(bpl[i]);
+    }
+    // ---- P.V: 8 blocks of 16 channels
+#pragma unroll
+    for (int wd = 0; wd < 4; ++wd) {
+      uintx4 a[2];
+      if (BITS == 2) {
+        extract<2>(vw[wd], a[0], a[1]);
+      } else {
+        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
+        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
+      }
+#pragma unroll
+      for (int y = 0; y < 2; ++y) {
+        acc_o[2 * wd + y] = mfma(a[y], b2h, acc_o[2 * wd + y]);
+        acc_o[2 * wd + y] = mfma(a[y], b2l, acc_o[2 * wd + y]);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  // ---- per-wave results -> LDS.  acc_z rows: lanes 0..15 (rb 0) hold rows 0..3 = z-terms
+  // for u = row; lanes 16..31 register 0 hold row 4 = denominator.
+  if (rb == 0) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+      if (x == us) red_z[wave][hs][us] = acc_z[x];
+    if (us == 0) red_m[wave][hs] = m_run;
+  }
+  if (rb == 1 && us == 0) red_l[wave][hs] = acc_z[0];
+  __syncthreads();
+  {
+    const float zt = red_z[wave][hs][us];
+    const float unscale = (float)(1 << (24 - kEP));
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+      if (cb / 2 == us) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) red_o[wave][hs][16 * cb + 4 * rb + x] = __builtin_fmaf(acc_o[cb][x], unscale, zt);
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < G * TKV_D; i += 256) {
+    const int hh = i / TKV_D, c = i % TKV_D;
+    float M = -INFINITY;
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, red_m[w][hh]);
+    float L = 0.f, O = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      const float mw = red_m[w][hh];
+      if (mw == -INFINITY) continue;
+      const float wgt = exp2f(mw - M);
+      L += red_l[w][hh] * wgt;
+      O += red_o[w][hh][c] * wgt;
+    }
+    float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_parts + chunk) * TKV_PART_STRIDE;
+    dst[2 + c] = O;
+    if (c == 0) {
+      dst[0] = M;
+      dst[1] = L;
+    }
+  }
+}
+
+}  // namespace
+
+namespace tkv {
+float* g_mfma_dbg = nullptr;
+
+int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, float scale2,
+                               float* parts, int groups_per_chunk, int n_chunks, int n_parts,
+                               const TkvSeqLens& lens, hipStream_t s) {
+  if (d->head_dim != TKV_D || d->group_size != TKV_G) return TKV_E_UNSUPPORTED;
+  if (d->n_q_heads / d->n_kv_heads > 4) return TKV_E_UNSUPPORTED;
+  MfmaParams p;
+  p.k_codes = (const uint32_t*)c->k_codes;
+  p.v_codes = (const uint32_t*)c->v_codes;
+  p.k_scale = (const __half*)c->k_scale;
+  p.k_zero = (const __half*)c->k_zero;
+  p.v_scale = (const __half*)c->v_scale;
+  p.v_zero = (const __half*)c->v_zero;
+  p.q = q;
+  p.parts = parts;
+  p.scale2 = scale2;
+  p.hq = d->n_q_heads;
+  p.hkv = d->n_kv_heads;
+  p.residual = d->residual;
+  p.capacity = d->capacity;
+  p.groups_per_chunk = groups_per_chunk;
+  p.n_parts = n_parts;
+  p.dbg = g_mfma_dbg;
+  p.lens = lens;
+  const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
+  if (d->bits == 2)
+    quant_attn_mfma_kernel<2><<<grid, 256, 0, s>>>(p);
+  else if (d->bits == 4)
+    quant_attn_mfma_kernel<4><<<grid, 256, 0, s>>>(p);
+  else
+    return TKV_E_UNSUPPORTED;
+  return launch_status();
+}
+
+}  // namespace tkv
+
+extern "C" void tkv_debug_set_dump(float* ptr) { tkv::g_mfma_dbg = ptr; }

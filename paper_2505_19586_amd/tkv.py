@@ -74,6 +74,8 @@ def lib() -> C.CDLL:
         L.tkv_sparse_gather.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp]
         L.tkv_sparse_attn.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp, C.c_float,
                                       vp, sz, vp]
+        L.tkv_debug_quant_attn_config.argtypes = [i32, i32]
+        L.tkv_debug_quant_attn_config.restype = i32
         for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
                      "tkv_quantize_append_ragged", "tkv_sparse_append_ragged",
                      "tkv_sparse_cache_sizes", "tkv_sparse_append", "tkv_sparse_estimate_topk",
@@ -81,6 +83,11 @@ def lib() -> C.CDLL:
             getattr(L, name).restype = C.c_int32
         _LIB = L
     return _LIB
+
+
+def debug_quant_attn_config(kernel_choice: int = 0, target_blocks: int = 0) -> None:
+    """0 = matrix-core kernel (default), 1 = reference kernel; see tkv.h."""
+    _check(lib().tkv_debug_quant_attn_config(int(kernel_choice), int(target_blocks)), "tkv_debug_quant_attn_config")
 
 
 def _check(status: int, where: str) -> None:

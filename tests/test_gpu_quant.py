@@ -13,6 +13,15 @@ from gpu_util import attn_err, check_quant_cache, to_new, to_new_batch
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
+
+
+@pytest.fixture(autouse=True, params=["mfma", "reference"])
+def kernel_choice(request):
+    """Every case runs with the matrix-core kernel and with the reference kernel."""
+    tkv.debug_quant_attn_config(0 if request.param == "mfma" else 1)
+    yield request.param
+    tkv.debug_quant_attn_config(0)
+
 SM = 1.0 / np.sqrt(128.0)
 
 
