@@ -7,14 +7,13 @@ namespace tkv {
 // matrix-core path (tkv_quant_attn_mfma.hip); returns TKV_E_UNSUPPORTED when the
 // shape is not one it is built for.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, float scale2,
-                               float* parts, int groups_per_chunk, int n_chunks, int n_parts,
-                               const TkvSeqLens& lens, hipStream_t s);
+                               float* parts, int n_chunks, const TkvSeqLens& lens, hipStream_t s);
 }  // namespace tkv
 
 namespace {
 
 int g_kernel_choice = 0;      // 0: matrix-core kernel (+ reference kernel for the tail), 1: reference kernel only
-int g_target_blocks = 1024;   // workgroups the split-K launch aims at
+int g_target_blocks = 256;    // workgroups the split-K launch aims at (one per compute unit)
 
 struct QuantAttnParams {
   const uint32_t* k_codes;
@@ -218,20 +217,42 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
 }
 
 // Log-sum-exp merge of the chunk partials of one query head; writes fp16.
+// One workgroup per query head, one thread per channel; the per-part maxima and sums
+// are staged in LDS so that the channel loop issues independent loads.
 __global__ __launch_bounds__(TKV_D) void attn_merge_kernel(const float* parts, __half* out, int n_parts) {
+  __shared__ float wgt[TKV_MAX_CHUNKS + 1];
+  __shared__ float red[2];
   const size_t head = blockIdx.x;  // b * Hq + i
   const int c = threadIdx.x;
   const float* base = parts + head * n_parts * TKV_PART_STRIDE;
+  for (int k = c; k < n_parts; k += TKV_D) wgt[k] = base[(size_t)k * TKV_PART_STRIDE];
+  __syncthreads();
   float M = -INFINITY;
-  for (int k = 0; k < n_parts; ++k) M = fmaxf(M, base[(size_t)k * TKV_PART_STRIDE]);
-  float L = 0.f, O = 0.f;
-  for (int k = 0; k < n_parts; ++k) {
-    const float* pk = base + (size_t)k * TKV_PART_STRIDE;
-    const float mk = pk[0];
+  for (int k = 0; k < n_parts; ++k) M = fmaxf(M, wgt[k]);
+  __syncthreads();
+  float lsum = 0.f;
+  for (int k = c; k < n_parts; k += TKV_D) {
+    const float mk = wgt[k];
     const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
-    L += pk[1] * w;
-    O += pk[2 + c] * w;
+    wgt[k] = w;
+    lsum += w * base[(size_t)k * TKV_PART_STRIDE + 1];
   }
+  for (int m = 32; m >= 1; m >>= 1) lsum += __shfl_xor(lsum, m, 64);
+  if (c % 64 == 0) red[c / 64] = lsum;
+  __syncthreads();
+  const float L = red[0] + red[1];
+  float O0 = 0.f, O1 = 0.f, O2 = 0.f, O3 = 0.f;
+  int k = 0;
+  for (; k + 4 <= n_parts; k += 4) {
+    const float* pk = base + (size_t)k * TKV_PART_STRIDE + 2 + c;
+    const float v0 = pk[0], v1 = pk[TKV_PART_STRIDE], v2 = pk[2 * TKV_PART_STRIDE], v3 = pk[3 * TKV_PART_STRIDE];
+    O0 = __builtin_fmaf(v0, wgt[k], O0);
+    O1 = __builtin_fmaf(v1, wgt[k + 1], O1);
+    O2 = __builtin_fmaf(v2, wgt[k + 2], O2);
+    O3 = __builtin_fmaf(v3, wgt[k + 3], O3);
+  }
+  for (; k < n_parts; ++k) O0 = __builtin_fmaf(base[(size_t)k * TKV_PART_STRIDE + 2 + c], wgt[k], O0);
+  const float O = (O0 + O1) + (O2 + O3);
   out[head * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
 }
 
@@ -274,9 +295,9 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
     const int g = tkv::n_quantized(n, d->residual) / TKV_G;
     if (g > max_groups) max_groups = g;
   }
-  // Chunking: aim at ~4 workgroups per compute unit over the whole launch.
+  // Chunking of the reference kernel: about 1024 workgroups over the whole launch.
   const int bh = d->batch * d->n_kv_heads;
-  int target = (g_target_blocks + bh - 1) / bh;
+  int target = (1024 + bh - 1) / bh;
   if (target > TKV_MAX_CHUNKS) target = TKV_MAX_CHUNKS;
   if (target < 1) target = 1;
   int gpc = (max_groups + target - 1) / target;
@@ -305,11 +326,17 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
 
   hipStream_t s = (hipStream_t)stream;
   if (g_kernel_choice == 0) {
-    // matrix-core kernel over the quantized groups, reference kernel for the fp16 tail
-    st = tkv::launch_quant_attn_mfma(d, c, p.q, p.scale2, p.parts, gpc, n_chunks, n_chunks + 1, p.lens, s);
+    // matrix-core kernel: one launch covers the quantized groups and the fp16 tail.
+    // Chunks per (sequence, KV head): about one workgroup per compute unit in total,
+    // and at least eight 32-token groups (one per wave) per workgroup.
+    int c_target = (g_target_blocks + bh - 1) / bh;
+    const int c_work = (max_groups + 40 + 7) / 8;
+    if (c_target > c_work) c_target = c_work;
+    if (c_target > 64) c_target = 64;
+    if (c_target < 1) c_target = 1;
+    st = tkv::launch_quant_attn_mfma(d, c, p.q, p.scale2, p.parts, c_target, p.lens, s);
     if (st != TKV_OK) return st;
-    p.chunk_offset = n_chunks;
-    quant_attn_generic_kernel<<<dim3(1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+    return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, c_target, s);
   } else {
     p.chunk_offset = 0;
     quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);

@@ -34,12 +34,13 @@ struct MfmaParams {
   const __half* k_zero;
   const __half* v_scale;
   const __half* v_zero;
+  const __half* k_resid;
+  const __half* v_resid;
   const __half* q;
-  float* parts;
+  float* parts;  // [B][Hq][n_chunks][D + 2]
   float scale2;
   int32_t hq, hkv, residual, capacity;
-  int32_t groups_per_chunk, n_parts;
-  float* dbg;
+  int32_t n_chunks;
   TkvSeqLens lens;
 };
 
@@ -81,33 +82,196 @@ __device__ inline void extract4(uint32_t w, uintx4& a) {
   a[3] = w8 & 0x00F000F0u;
 }
 
-constexpr int kEK = 4;       // query-side operands carry 2^kEK
-constexpr int kEP = 6;       // weight-side operands carry 2^kEP
+constexpr int kEK = 4;             // query-side operands carry 2^kEK
+constexpr int kEP = 6;             // weight-side operands carry 2^kEP
 constexpr float kHeadroom = 4.0f;  // lazy rescale: weights may reach 2^kHeadroom
+constexpr int kWaves = 8;          // waves per workgroup
+constexpr int kThreads = kWaves * 64;
+constexpr int kTailEntry = kWaves;  // slot of the fp16 tail in the workgroup merge
+
+// Everything one wave loads for one 32-token group (held in registers so that the
+// next group's loads are in flight while the current one is computed).
+template <int BITS>
+struct GroupRegs {
+  uint32_t kw[2 * BITS], vw[2 * BITS];  // packed codes: one (2 bit) or two (4 bit) 128-bit loads each
+  uint32_t ks2, kz2;                    // K scaler / zero-point of channels 2*lane, 2*lane+1
+  uintx4 sv, zv;                        // V scalers (column's u) and zero-points (row's u) of 8 tokens
+};
 
 template <int BITS>
-__global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
-  constexpr int NW = 2 * BITS;          // 32-bit words per lane per group, for K and for V: 4 or 8
-  constexpr int NWORDS = TKV_D * BITS;  // words per group block
+__device__ inline void load_group(GroupRegs<BITS>& g, const MfmaParams& p, size_t grp, int lane, int us, int rb,
+                                  int zrow_ld) {
+  constexpr int NWORDS = TKV_D * BITS;
+  const uint32_t* kc = p.k_codes + grp * NWORDS;
+  const uint32_t* vc = p.v_codes + grp * NWORDS;
+#pragma unroll
+  for (int x = 0; x < BITS / 2; ++x) {
+    const uintx4 t = *reinterpret_cast<const uintx4*>(kc + 256 * x + 4 * lane);
+    const uintx4 u = *reinterpret_cast<const uintx4*>(vc + 256 * x + 4 * lane);
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+      g.kw[4 * x + y] = t[y];
+      g.vw[4 * x + y] = u[y];
+    }
+  }
+  g.ks2 = reinterpret_cast<const uint32_t*>(p.k_scale + grp * TKV_D)[lane];
+  g.kz2 = reinterpret_cast<const uint32_t*>(p.k_zero + grp * TKV_D)[lane];
+  g.sv = *reinterpret_cast<const uintx4*>(p.v_scale + (grp * 4 + us) * TKV_G + 8 * rb);
+  g.zv = *reinterpret_cast<const uintx4*>(p.v_zero + (grp * 4 + zrow_ld) * TKV_G + 8 * rb);
+}
+
+struct MergeSmem {
+  float m[kWaves + 1][4];
+  float l[kWaves + 1][4];
+  float z[kWaves][4][4];
+  float o[kWaves + 1][4][TKV_D];
+};
+
+// fp16 tail (ring of unquantized tokens) of one KV head, computed by the whole workgroup
+// with plain float math; result goes to entry kTailEntry of the merge arrays.
+__device__ inline void tail_attention(const MfmaParams& p, MergeSmem& ms, float (*q_s)[TKV_D], float (*x_s)[kThreads],
+                                      float (*w_s)[4], size_t bh, int nq, int n, int G) {
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+  const int ring = p.residual + TKV_G;
+  const int r_total = n - nq;
+  bool first = true;
+  for (int sb0 = 0; sb0 < r_total; sb0 += kThreads) {
+    const int cnt = min(kThreads, r_total - sb0);
+    // phase 1: logits of token sb0 + tid for the 4 heads
+    float x[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (tid < cnt) {
+      const int tok = nq + sb0 + tid;
+      const uintx4* krow = reinterpret_cast<const uintx4*>(p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D);
+      float a[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+      for (int c8 = 0; c8 < TKV_D / 8; ++c8) {
+        const uintx4 kv = krow[c8];
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+          const uint32_t w = kv[y];
+          const half2_t k2 = as_half2(w);
+          const float k0 = (float)k2[0], k1 = (float)k2[1];
+#pragma unroll
+          for (int hh = 0; hh < 4; ++hh) {
+            a[hh] = __builtin_fmaf(q_s[hh][8 * c8 + 2 * y], k0, a[hh]);
+            a[hh] = __builtin_fmaf(q_s[hh][8 * c8 + 2 * y + 1], k1, a[hh]);
+          }
+        }
+      }
+#pragma unroll
+      for (int hh = 0; hh < 4; ++hh) x[hh] = a[hh] * p.scale2;
+    }
+    // phase 2: workgroup max and weights
+    float wm[4];
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh) {
+      float v = x[hh];
+      for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+      wm[hh] = v;
+    }
+    if (lane == 0)
+      for (int hh = 0; hh < 4; ++hh) w_s[wave][hh] = wm[hh];
+    __syncthreads();
+    float mx[4], pw[4];
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh) {
+      float v = w_s[0][hh];
+      for (int w = 1; w < kWaves; ++w) v = fmaxf(v, w_s[w][hh]);
+      mx[hh] = v;  // finite: the sub-block holds at least one token
+      pw[hh] = tid < cnt ? exp2f(x[hh] - v) : 0.f;
+      x_s[hh][tid] = pw[hh];
+    }
+    __syncthreads();
+    // phase 3: weighted V sum; thread = (channel pair, token residue class)
+    float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
+    float ls[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int t = wave; t < cnt; t += kWaves) {
+      const int tok = nq + sb0 + t;
+      const uint32_t v2 = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D)[lane];
+      const half2_t vv = as_half2(v2);
+      const float v0 = (float)vv[0], v1 = (float)vv[1];
+#pragma unroll
+      for (int hh = 0; hh < 4; ++hh) {
+        const float pp = x_s[hh][t];
+        acc[hh][0] = __builtin_fmaf(pp, v0, acc[hh][0]);
+        acc[hh][1] = __builtin_fmaf(pp, v1, acc[hh][1]);
+        ls[hh] += pp;
+      }
+    }
+    // reduce over the 8 waves through the (still unused) per-wave merge slots
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh) {
+      ms.o[wave][hh][2 * lane] = acc[hh][0];
+      ms.o[wave][hh][2 * lane + 1] = acc[hh][1];
+      if (lane == 0) ms.l[wave][hh] = ls[hh];
+    }
+    __syncthreads();
+    {
+      const int hh = tid / TKV_D, c = tid % TKV_D;  // 512 threads = 4 heads x 128 channels
+      float O = 0.f, L = 0.f;
+      for (int w = 0; w < kWaves; ++w) {
+        O += ms.o[w][hh][c];
+        L += ms.l[w][hh];
+      }
+      if (first) {
+        ms.o[kTailEntry][hh][c] = O;
+        if (c == 0) {
+          ms.m[kTailEntry][hh] = mx[hh];
+          ms.l[kTailEntry][hh] = L;
+        }
+      } else {
+        const float mo = ms.m[kTailEntry][hh], mn = fmaxf(mo, mx[hh]);
+        const float a_old = exp2f(mo - mn), a_new = exp2f(mx[hh] - mn);
+        ms.o[kTailEntry][hh][c] = ms.o[kTailEntry][hh][c] * a_old + O * a_new;
+        __syncthreads();  // every channel has read the old max before it is replaced
+        if (c == 0) {
+          ms.l[kTailEntry][hh] = ms.l[kTailEntry][hh] * a_old + L * a_new;
+          ms.m[kTailEntry][hh] = mn;
+        }
+      }
+    }
+    first = false;
+    __syncthreads();
+  }
+  (void)G;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p) {
   // per wave: query-side operand [hi/lo][4 heads][128 ch] fp16 + zero-points [128] fp16
-  __shared__ __attribute__((aligned(16))) uint32_t bk_s[4][2][4][TKV_D / 2];
-  __shared__ __attribute__((aligned(16))) uint32_t kz_s[4][TKV_D / 2];
-  __shared__ float red_m[4][4], red_l[4][4], red_z[4][4][4];
-  __shared__ float red_o[4][4][TKV_D];
+  __shared__ __attribute__((aligned(16))) uint32_t bk_s[kWaves][2][4][TKV_D / 2];
+  __shared__ __attribute__((aligned(16))) uint32_t kz_s[kWaves][TKV_D / 2];
+  __shared__ MergeSmem ms;
+  __shared__ float q_s[4][TKV_D];
+  __shared__ float x_s[4][kThreads];
+  __shared__ float w_s[kWaves][4];
 
   const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int G = p.hq / p.hkv;
   const int n = p.lens.n[b];
-  const int jq = tkv::n_quantized(n, p.residual) / TKV_G;
+  const int nq = tkv::n_quantized(n, p.residual);
+  const int jq = nq / TKV_G;
   const size_t bh = (size_t)b * p.hkv + h;
   const size_t grp_base = bh * (size_t)(p.capacity / TKV_G);
-  const int blk0 = chunk * p.groups_per_chunk;
-  const int blk1 = min(blk0 + p.groups_per_chunk, jq);
+  // Work split of this sequence: the tail counts as (n - nq)/4 groups and belongs to
+  // the last chunk, so that chunk gets correspondingly fewer quantized groups.
+  const bool has_tail = chunk == p.n_chunks - 1;
+  const int tail_equiv = (n - nq + 3) / 4;
+  const int gpc = max(1, (jq + tail_equiv + p.n_chunks - 1) / p.n_chunks);
+  const int blk0 = min(chunk * gpc, jq);
+  const int blk1 = has_tail ? jq : min(blk0 + gpc, jq);
 
   const int slot = lane % 16, rb = lane / 16;
   const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, channel group
   const __half* qrow = p.q + ((size_t)b * p.hq + (size_t)h * G) * TKV_D;
+
+  if (has_tail) {
+    for (int i = tid; i < 4 * TKV_D; i += kThreads) {
+      const int hh = i / TKV_D, c = i % TKV_D;
+      q_s[hh][c] = hh < G ? __half2float(qrow[(size_t)hh * TKV_D + c]) : 0.f;
+    }
+  }
 
   // query as exact fp16 B operand (zero-point term) and as scaled float (scaler term)
   uintx4 bq[4];
@@ -163,32 +327,20 @@ __global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
     off[i] = BITS == 2 ? (float)(kEP - 2 * j) : (float)(kEP - 4 * (j % 2));
   }
 
-  for (int blk = blk0 + wave; blk < blk1; blk += 4) {
-    const size_t grp = grp_base + blk;
-    // ---- loads of this group
-    uint32_t kw[NW], vw[NW];
+  GroupRegs<BITS> cur;
+  int blk = blk0 + wave;
+  if (blk < blk1) load_group<BITS>(cur, p, grp_base + blk, lane, us, rb, zrow_ld);
+  for (; blk < blk1; blk += kWaves) {
+    // prefetch the wave's next group (or re-read this one when there is none)
+    GroupRegs<BITS> nxt;
     {
-      const uint32_t* kc = p.k_codes + grp * NWORDS;
-      const uint32_t* vc = p.v_codes + grp * NWORDS;
-#pragma unroll
-      for (int x = 0; x < NW / 4; ++x) {
-        const uintx4 t = *reinterpret_cast<const uintx4*>(kc + 256 * x + 4 * lane);
-        const uintx4 u = *reinterpret_cast<const uintx4*>(vc + 256 * x + 4 * lane);
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-          kw[4 * x + y] = t[y];
-          vw[4 * x + y] = u[y];
-        }
-      }
+      const int nb = blk + kWaves;
+      load_group<BITS>(nxt, p, grp_base + (nb < blk1 ? nb : blk), lane, us, rb, zrow_ld);
     }
-    const uint32_t ks2 = reinterpret_cast<const uint32_t*>(p.k_scale + grp * TKV_D)[lane];
-    const uint32_t kz2 = reinterpret_cast<const uint32_t*>(p.k_zero + grp * TKV_D)[lane];
-    const uintx4 sv = *reinterpret_cast<const uintx4*>(p.v_scale + (grp * 4 + us) * TKV_G + 8 * rb);
-    const uintx4 zv_raw = *reinterpret_cast<const uintx4*>(p.v_zero + (grp * 4 + zrow_ld) * TKV_G + 8 * rb);
 
     // ---- query-side operand of this group: (q s) split into hi + lo, through LDS
     {
-      const half2_t s2 = as_half2(ks2);
+      const half2_t s2 = as_half2(cur.ks2);
       const float s0 = (float)s2[0], s1 = (float)s2[1];
 #pragma unroll
       for (int hh = 0; hh < 4; ++hh) {
@@ -198,7 +350,7 @@ __global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
         bk_s[wave][0][hh][lane] = pack2(h0, h1);
         bk_s[wave][1][hh][lane] = pack2(l0, l1);
       }
-      kz_s[wave][lane] = kz2;
+      kz_s[wave][lane] = cur.kz2;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -215,26 +367,26 @@ __global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
     floatx4 acc_s[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
     for (int m2 = 0; m2 < 2; ++m2) {  // pairs of MFMA steps m = 2*m2, 2*m2+1
-      uintx4 bh[2], bl[2];
+      uintx4 bh2[2], bl2[2];
 #pragma unroll
       for (int y = 0; y < 2; ++y) {
         const int m = 2 * m2 + y;
-        bh[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][0][hs][(32 * m + 8 * rb) / 2]);
-        bl[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][1][hs][(32 * m + 8 * rb) / 2]);
+        bh2[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][0][hs][(32 * m + 8 * rb) / 2]);
+        bl2[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][1][hs][(32 * m + 8 * rb) / 2]);
       }
 #pragma unroll
       for (int tau = 0; tau < 2; ++tau) {
         uintx4 a[2];
         if (BITS == 2) {
-          extract<2>(kw[2 * tau + m2], a[0], a[1]);
+          extract<2>(cur.kw[2 * tau + m2], a[0], a[1]);
         } else {
-          extract4(kw[4 * tau + 2 * m2], a[0]);
-          extract4(kw[4 * tau + 2 * m2 + 1], a[1]);
+          extract4(cur.kw[4 * tau + 2 * m2], a[0]);
+          extract4(cur.kw[4 * tau + 2 * m2 + 1], a[1]);
         }
 #pragma unroll
         for (int y = 0; y < 2; ++y) {
-          acc_s[tau] = mfma(a[y], bh[y], acc_s[tau]);
-          acc_s[tau] = mfma(a[y], bl[y], acc_s[tau]);
+          acc_s[tau] = mfma(a[y], bh2[y], acc_s[tau]);
+          acc_s[tau] = mfma(a[y], bl2[y], acc_s[tau]);
         }
       }
     }
@@ -263,10 +415,10 @@ __global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
     for (int i = 0; i < 8; ++i) pw[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[i / 4][i % 4], K1, czm + off[i]));
 
     // ---- weight-side operands: p*s_v (hi, lo) and p (hi, lo)
-    uintx4 b2h, b2l, bph, bpl;
+    uintx4 b2h, b2l, bph, bpl, a_zv;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t svj = sv[j];
+      const uint32_t svj = cur.sv[j];
       const half2_t s2 = as_half2(svj);
       const float w0 = pw[2 * j], w1 = pw[2 * j + 1];
       const float x0 = w0 * (float)s2[0], x1 = w1 * (float)s2[1];
@@ -276,36 +428,22 @@ __global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
       const _Float16 ph0 = (_Float16)w0, ph1 = (_Float16)w1;
       bph[j] = pack2(ph0, ph1);
       bpl[j] = pack2((_Float16)(w0 - (float)ph0), (_Float16)(w1 - (float)ph1));
-    }
-    uintx4 a_zv;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t zvj = zv_raw[j];
+      const uint32_t zvj = cur.zv[j];
       const half2_t t = __builtin_elementwise_fma(as_half2(zvj), zmul[j], zadd[j]);
       a_zv[j] = __builtin_bit_cast(uint32_t, t);
     }
     acc_z = mfma(a_zv, bph, acc_z);
     acc_z = mfma(a_zv, bpl, acc_z);
 
-    if (p.dbg && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && wave == 0 && blk == blk0) {
-      float* d = p.dbg + lane * 64;
-      for (int i = 0; i < 8; ++i) d[i] = acc_s[i / 4][i % 4];
-      for (int i = 0; i < 8; ++i) d[8 + i] = pw[i];
-      d[16] = acc_cz[0]; d[17] = m_run; d[18] = cz; d[19] = xmax;
-      for (int i = 0; i < 4; ++i) d[20 + i] = acc_z[i];
-      for (int i = 0; i < 4; ++i) d[24 + i] = __uint_as_float(a_zv[i]);
-      for (int i = 0; i < 4; ++i) d[28 + i] = __uint_as_float(bph[i]);
-      for (int i = 0; i < 4; ++i) d[32 + i] = __uint_as_float(bpl[i]);
-    }
     // ---- P.V: 8 blocks of 16 channels
 #pragma unroll
     for (int wd = 0; wd < 4; ++wd) {
       uintx4 a[2];
       if (BITS == 2) {
-        extract<2>(vw[wd], a[0], a[1]);
+        extract<2>(cur.vw[wd], a[0], a[1]);
       } else {
-        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
-        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
+        extract4(cur.vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
+        extract4(cur.vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
       }
 #pragma unroll
       for (int y = 0; y < 2; ++y) {
@@ -314,43 +452,53 @@ __global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
       }
     }
     __builtin_amdgcn_wave_barrier();
+    cur = nxt;
   }
+
+  __syncthreads();
+  if (has_tail && n > nq) {
+    tail_attention(p, ms, q_s, x_s, w_s, bh, nq, n, G);
+  } else if (tid < 4) {
+    ms.m[kTailEntry][tid] = -INFINITY;
+    ms.l[kTailEntry][tid] = 0.f;
+  }
+  __syncthreads();
 
   // ---- per-wave results -> LDS.  acc_z rows: lanes 0..15 (rb 0) hold rows 0..3 = z-terms
   // for u = row; lanes 16..31 register 0 hold row 4 = denominator.
   if (rb == 0) {
 #pragma unroll
     for (int x = 0; x < 4; ++x)
-      if (x == us) red_z[wave][hs][us] = acc_z[x];
-    if (us == 0) red_m[wave][hs] = m_run;
+      if (x == us) ms.z[wave][hs][us] = acc_z[x];
+    if (us == 0) ms.m[wave][hs] = m_run;
   }
-  if (rb == 1 && us == 0) red_l[wave][hs] = acc_z[0];
+  if (rb == 1 && us == 0) ms.l[wave][hs] = acc_z[0];
   __syncthreads();
   {
-    const float zt = red_z[wave][hs][us];
+    const float zt = ms.z[wave][hs][us];
     const float unscale = (float)(1 << (24 - kEP));
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb) {
       if (cb / 2 == us) {
 #pragma unroll
-        for (int x = 0; x < 4; ++x) red_o[wave][hs][16 * cb + 4 * rb + x] = __builtin_fmaf(acc_o[cb][x], unscale, zt);
+        for (int x = 0; x < 4; ++x) ms.o[wave][hs][16 * cb + 4 * rb + x] = __builtin_fmaf(acc_o[cb][x], unscale, zt);
       }
     }
   }
   __syncthreads();
-  for (int i = tid; i < G * TKV_D; i += 256) {
+  for (int i = tid; i < G * TKV_D; i += kThreads) {
     const int hh = i / TKV_D, c = i % TKV_D;
     float M = -INFINITY;
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, red_m[w][hh]);
+    for (int w = 0; w <= kWaves; ++w) M = fmaxf(M, ms.m[w][hh]);
     float L = 0.f, O = 0.f;
-    for (int w = 0; w < 4; ++w) {
-      const float mw = red_m[w][hh];
+    for (int w = 0; w <= kWaves; ++w) {
+      const float mw = ms.m[w][hh];
       if (mw == -INFINITY) continue;
       const float wgt = exp2f(mw - M);
-      L += red_l[w][hh] * wgt;
-      O += red_o[w][hh][c] * wgt;
+      L += ms.l[w][hh] * wgt;
+      O += ms.o[w][hh][c] * wgt;
     }
-    float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_parts + chunk) * TKV_PART_STRIDE;
+    float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
     dst[2 + c] = O;
     if (c == 0) {
       dst[0] = M;
@@ -362,11 +510,9 @@ __global__ __launch_bounds__(256) void quant_attn_mfma_kernel(MfmaParams p) {
 }  // namespace
 
 namespace tkv {
-float* g_mfma_dbg = nullptr;
 
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, float scale2,
-                               float* parts, int groups_per_chunk, int n_chunks, int n_parts,
-                               const TkvSeqLens& lens, hipStream_t s) {
+                               float* parts, int n_chunks, const TkvSeqLens& lens, hipStream_t s) {
   if (d->head_dim != TKV_D || d->group_size != TKV_G) return TKV_E_UNSUPPORTED;
   if (d->n_q_heads / d->n_kv_heads > 4) return TKV_E_UNSUPPORTED;
   MfmaParams p;
@@ -376,6 +522,8 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.k_zero = (const __half*)c->k_zero;
   p.v_scale = (const __half*)c->v_scale;
   p.v_zero = (const __half*)c->v_zero;
+  p.k_resid = (const __half*)c->k_resid;
+  p.v_resid = (const __half*)c->v_resid;
   p.q = q;
   p.parts = parts;
   p.scale2 = scale2;
@@ -383,20 +531,16 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.hkv = d->n_kv_heads;
   p.residual = d->residual;
   p.capacity = d->capacity;
-  p.groups_per_chunk = groups_per_chunk;
-  p.n_parts = n_parts;
-  p.dbg = g_mfma_dbg;
+  p.n_chunks = n_chunks;
   p.lens = lens;
   const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
   if (d->bits == 2)
-    quant_attn_mfma_kernel<2><<<grid, 256, 0, s>>>(p);
+    quant_attn_mfma_kernel<2><<<grid, kThreads, 0, s>>>(p);
   else if (d->bits == 4)
-    quant_attn_mfma_kernel<4><<<grid, 256, 0, s>>>(p);
+    quant_attn_mfma_kernel<4><<<grid, kThreads, 0, s>>>(p);
   else
     return TKV_E_UNSUPPORTED;
   return launch_status();
 }
 
 }  // namespace tkv
-
-extern "C" void tkv_debug_set_dump(float* ptr) { tkv::g_mfma_dbg = ptr; }
