@@ -199,6 +199,9 @@ int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* desc, tkv_sparse_cache* 
  * largest S (ties: lower index first) are written to topk_idx [B][Hkv][top_k] in
  * ASCENDING token order, padded with -1; topk_count [B][Hkv] gets k.
  * Scores must be finite.
+ * workspace: at least the size tkv_sparse_cache_sizes reports, ZERO-FILLED by the caller
+ * before its first use (it holds histograms and counters that every call leaves zero
+ * again); concurrent calls need separate workspaces.
  */
 int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,
                                  int32_t* topk_idx, int32_t* topk_count, void* workspace,

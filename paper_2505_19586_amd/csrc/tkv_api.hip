@@ -91,13 +91,9 @@ extern "C" int32_t tkv_sparse_cache_sizes(const tkv_sparse_desc* d, size_t bytes
     bytes_out[3] = bh * (size_t)(d->n_sink + d->n_window) * 2 * TKV_D * 2;
   }
   if (workspace_bytes) {
-    // estimate_topk: score keys uint32 [B][Hkv][capacity] + histograms / counters;
-    // gather_attn: split partials.  See tkv_sparse.hip for the carve-up.
-    const size_t keys = bh * cap * sizeof(uint32_t);
-    const size_t hist = bh * (size_t)(3 * 2048 + 64) * sizeof(uint32_t);
-    const size_t blocks = bh * (size_t)((cap + 1023) / 1024 + 1) * 2 * sizeof(uint32_t);
-    const size_t parts = (size_t)d->batch * d->n_q_heads * 64 * TKV_PART_STRIDE * sizeof(float);
-    *workspace_bytes = keys + hist + blocks + parts + 1024;
+    // Top-K scratch and attention partials; layout in tkv_common.h
+    size_t off[6];
+    *workspace_bytes = tkv::sparse_ws_layout(d, off, nullptr) + 256;
   }
   return TKV_OK;
 }

@@ -43,6 +43,50 @@ int32_t check_quant_desc(const tkv_quant_desc* d);
 int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, int n_parts, hipStream_t s);
 int32_t check_sparse_desc(const tkv_sparse_desc* d);
 
+// Carve-up of the sparse-layer workspace (per bh = (sequence, KV head)):
+//   keys  uint32 [BH][capacity]   order-preserving image of the approximate scores
+//   cand  uint2  [BH][capacity]   (key, token) pairs inside the threshold bin
+//   hist  uint32 [BH][8192]       histogram of the 13-bit key prefix
+//   ctrl  uint32 [BH][8]          arrival counter, candidate count, bin, keys above the bin
+//   blk   uint32 [BH][nblk_cap]   per 1024-token block: keys above the bin
+//   parts float  [B][Hq][64][D+2] split partials of the sparse attention
+struct SparseWs {
+  uint32_t* keys;
+  uint2* cand;
+  uint32_t* hist;
+  uint32_t* ctrl;
+  uint32_t* blk;
+  float* parts;
+  int32_t nblk_cap;
+};
+inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+inline size_t sparse_ws_layout(const tkv_sparse_desc* d, size_t off[6], int32_t* nblk_cap) {
+  const size_t bh = (size_t)d->batch * d->n_kv_heads, cap = (size_t)d->capacity;
+  const int32_t nb = (int32_t)((cap + 1023) / 1024 + 1);
+  size_t o = 0;
+  off[0] = o; o = align16(o + bh * cap * 4);
+  off[1] = o; o = align16(o + bh * cap * 8);
+  off[2] = o; o += bh * 8192 * 4;
+  off[3] = o; o = align16(o + bh * 8 * 4);
+  off[4] = o; o = align16(o + bh * (size_t)nb * 4);
+  off[5] = o; o = align16(o + (size_t)d->batch * d->n_q_heads * 64 * TKV_PART_STRIDE * 4);
+  if (nblk_cap) *nblk_cap = nb;
+  return o;
+}
+inline SparseWs carve_sparse_ws(const tkv_sparse_desc* d, void* workspace) {
+  size_t off[6];
+  SparseWs ws;
+  sparse_ws_layout(d, off, &ws.nblk_cap);
+  char* base = (char*)workspace;
+  ws.keys = (uint32_t*)(base + off[0]);
+  ws.cand = (uint2*)(base + off[1]);
+  ws.hist = (uint32_t*)(base + off[2]);
+  ws.ctrl = (uint32_t*)(base + off[3]);
+  ws.blk = (uint32_t*)(base + off[4]);
+  ws.parts = (float*)(base + off[5]);
+  return ws;
+}
+
 // Position of logical element (t, c) of a 32x128 group inside the packed block:
 // word index and field index.  Mirrors the layout text of tkv.h.
 __host__ __device__ inline void k_code_pos(int bits, int t, int c, int& word, int& field) {

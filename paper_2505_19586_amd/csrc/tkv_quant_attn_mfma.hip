@@ -18,6 +18,8 @@
 //
 // Softmax is online per wave with lazy rescaling; the four waves of a workgroup and the
 // chunks of a sequence are merged with log-sum-exp merges.
+#include <cstdlib>
+
 #include "tkv_common.h"
 
 namespace {
@@ -41,6 +43,7 @@ struct MfmaParams {
   float scale2;
   int32_t hq, hkv, residual, capacity;
   int32_t n_chunks;
+  int32_t dbg_mode;
   TkvSeqLens lens;
 };
 
@@ -87,7 +90,8 @@ constexpr int kEP = 6;             // weight-side operands carry 2^kEP
 constexpr float kHeadroom = 4.0f;  // lazy rescale: weights may reach 2^kHeadroom
 constexpr int kWaves = 8;          // waves per workgroup
 constexpr int kThreads = kWaves * 64;
-constexpr int kTailEntry = kWaves;  // slot of the fp16 tail in the workgroup merge
+constexpr int kTailEntry = kWaves;
+constexpr int kBkStride = 80;      // words per head row of the query-side operand in LDS  // slot of the fp16 tail in the workgroup merge
 
 // Everything one wave loads for one 32-token group (held in registers so that the
 // next group's loads are in flight while the current one is computed).
@@ -239,7 +243,9 @@ __device__ inline void tail_attention(const MfmaParams& p, MergeSmem& ms, float 
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p) {
   // per wave: query-side operand [hi/lo][4 heads][128 ch] fp16 + zero-points [128] fp16
-  __shared__ __attribute__((aligned(16))) uint32_t bk_s[kWaves][2][4][TKV_D / 2];
+  // head rows are padded from 64 to 80 words: the 16 (head, k-block) operand reads of one
+  // ds_read_b128 then fall into 16 different 16-byte bank groups
+  __shared__ __attribute__((aligned(16))) uint32_t bk_s[kWaves][2][4][kBkStride];
   __shared__ __attribute__((aligned(16))) uint32_t kz_s[kWaves][TKV_D / 2];
   __shared__ MergeSmem ms;
   __shared__ float q_s[4][TKV_D];
@@ -247,7 +253,8 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   __shared__ float w_s[kWaves][4];
 
   const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
-  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);  // wave-uniform: keeps group addresses scalar
   const int G = p.hq / p.hkv;
   const int n = p.lens.n[b];
   const int nq = tkv::n_quantized(n, p.residual);
@@ -276,12 +283,11 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   // query as exact fp16 B operand (zero-point term) and as scaled float (scaler term)
   uintx4 bq[4];
 #pragma unroll
-  for (int m = 0; m < 4; ++m) {
-    if (hs < G) {
-      bq[m] = *reinterpret_cast<const uintx4*>(qrow + (size_t)hs * TKV_D + 32 * m + 8 * rb);
-    } else {
-      bq[m] = uintx4{0u, 0u, 0u, 0u};
-    }
+  for (int m = 0; m < 4; ++m)
+    bq[m] = *reinterpret_cast<const uintx4*>(qrow + (size_t)(hs < G ? hs : G - 1) * TKV_D + 32 * m + 8 * rb);
+  if (hs >= G) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) bq[m] = uintx4{0u, 0u, 0u, 0u};
   }
   // K-prep role: this lane owns channels 2*lane, 2*lane+1; their field position is lane%4
   // (2 bit: 4^pos) or lane%2 (4 bit: 16^pos).
@@ -289,10 +295,15 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   {
     const int pos = BITS == 2 ? lane % 4 : lane % 2;
     const float comp = BITS == 2 ? (float)(1 << kEK) / (float)(1 << (2 * pos)) : (float)(1 << kEK) / (float)(1 << (4 * pos));
+    uint32_t q2[4];
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh)  // heads >= G re-read head G-1 (in bounds) and are zeroed below
+      q2[hh] = reinterpret_cast<const uint32_t*>(qrow + (size_t)(hh < G ? hh : G - 1) * TKV_D)[lane];
 #pragma unroll
     for (int hh = 0; hh < 4; ++hh) {
-      qf[hh][0] = hh < G ? __half2float(qrow[(size_t)hh * TKV_D + 2 * lane]) * comp : 0.f;
-      qf[hh][1] = hh < G ? __half2float(qrow[(size_t)hh * TKV_D + 2 * lane + 1]) * comp : 0.f;
+      const half2_t qq = as_half2(q2[hh]);
+      qf[hh][0] = hh < G ? (float)qq[0] * comp : 0.f;
+      qf[hh][1] = hh < G ? (float)qq[1] * comp : 0.f;
     }
   }
   // codes carry 2^-24, query side 2^kEK, so S = acc * 2^(24-kEK)
@@ -327,17 +338,8 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
     off[i] = BITS == 2 ? (float)(kEP - 2 * j) : (float)(kEP - 4 * (j % 2));
   }
 
-  GroupRegs<BITS> cur;
-  int blk = blk0 + wave;
-  if (blk < blk1) load_group<BITS>(cur, p, grp_base + blk, lane, us, rb, zrow_ld);
-  for (; blk < blk1; blk += kWaves) {
-    // prefetch the wave's next group (or re-read this one when there is none)
-    GroupRegs<BITS> nxt;
-    {
-      const int nb = blk + kWaves;
-      load_group<BITS>(nxt, p, grp_base + (nb < blk1 ? nb : blk), lane, us, rb, zrow_ld);
-    }
-
+  // One group's worth of work for this wave; `cur` was loaded two iterations earlier.
+  auto process = [&](const GroupRegs<BITS>& cur) {
     // ---- query-side operand of this group: (q s) split into hi + lo, through LDS
     {
       const half2_t s2 = as_half2(cur.ks2);
@@ -452,7 +454,34 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
       }
     }
     __builtin_amdgcn_wave_barrier();
-    cur = nxt;
+  };
+
+  // Three-deep register ring: while one group is computed the wave's next two groups
+  // are in flight (about 6 KiB per wave, 48 KiB per compute unit).
+  {
+    GroupRegs<BITS> r0, r1, r2;
+    const int last = p.dbg_mode == 1 ? blk0 : blk1 - 1;  // loads past the chunk are clamped to its last group and ignored
+    int blk = blk0 + wave;
+    if (p.dbg_mode >= 2 && wave >= 4) __builtin_amdgcn_s_sleep(8);
+    if (p.dbg_mode >= 3 && wave >= 4) __builtin_amdgcn_s_sleep(8);
+    if (blk < blk1) {
+      load_group<BITS>(r0, p, grp_base + min(blk, last), lane, us, rb, zrow_ld);
+      load_group<BITS>(r1, p, grp_base + min(blk + kWaves, last), lane, us, rb, zrow_ld);
+      for (;;) {
+        load_group<BITS>(r2, p, grp_base + min(blk + 2 * kWaves, last), lane, us, rb, zrow_ld);
+        process(r0);
+        blk += kWaves;
+        if (blk >= blk1) break;
+        load_group<BITS>(r0, p, grp_base + min(blk + 2 * kWaves, last), lane, us, rb, zrow_ld);
+        process(r1);
+        blk += kWaves;
+        if (blk >= blk1) break;
+        load_group<BITS>(r1, p, grp_base + min(blk + 2 * kWaves, last), lane, us, rb, zrow_ld);
+        process(r2);
+        blk += kWaves;
+        if (blk >= blk1) break;
+      }
+    }
   }
 
   __syncthreads();
@@ -532,6 +561,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.residual = d->residual;
   p.capacity = d->capacity;
   p.n_chunks = n_chunks;
+  p.dbg_mode = getenv("TKV_DEBUG_MODE") ? atoi(getenv("TKV_DEBUG_MODE")) : 0;
   p.lens = lens;
   const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
   if (d->bits == 2)

@@ -1,309 +1,9 @@
-// Sparsity-friendly layers (Sec. 4.2): cache update, Stage 2 approximate scoring +
-// Top-K, fetch of the selected rows from pinned host memory, exact attention over
-// n_local + n_topk tokens (Sec. 5.1).
+// Sparsity-friendly layers (Sec. 4.2): cache update, fetch of the selected rows from
+// pinned host memory, exact attention over n_local + n_topk tokens (Sec. 5.1).
+// Scoring and Top-K live in tkv_sparse_topk.hip.
 #include "tkv_common.h"
 
 namespace {
-
-constexpr int kTokPerBlock = 1024;  // tokens scored per workgroup (256 threads x 4)
-constexpr int kBins = 2048;
-
-// Workspace carve-up of tkv_sparse_estimate_topk (uint32 units, per (b, kv head) = bh):
-//   keys  [BH][capacity]            order-preserving image of the float32 scores
-//   hist  [BH][3][2048]             radix histograms, most significant digit first
-//   blk   [BH][nblk_cap][2]         per block: #keys above threshold, #keys equal
-struct TopkWs {
-  uint32_t* keys;
-  uint32_t* hist;
-  uint32_t* blk;
-  int32_t nblk_cap;
-};
-
-__host__ __device__ inline int nblk_cap_of(int capacity) { return (capacity + kTokPerBlock - 1) / kTokPerBlock + 1; }
-
-struct SparseParams {
-  const __half* summary;
-  const int32_t* channel_idx;
-  const __half* q;
-  int32_t* topk_idx;
-  int32_t* topk_count;
-  TopkWs ws;
-  int32_t hq, hkv, ds, top_k, n_sink, n_window, capacity;
-  TkvSeqLens lens;
-};
-
-// Larger float <-> larger unsigned key; +0 and -0 were already merged by "+ 0.0f".
-__device__ inline uint32_t score_key(float s) {
-  const uint32_t u = __float_as_uint(s);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ inline void candidate_range(const SparseParams& p, int n, int& lo, int& hi) {
-  lo = min(p.n_sink, n);
-  hi = max(n - p.n_window, lo);
-}
-
-__global__ void zero_u32_kernel(uint32_t* ptr, size_t n) {
-  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (i < n) ptr[i] = 0u;
-}
-
-// Pass 1: approximate score of every candidate in the pinned float32 order, key
-// written to the workspace, histogram of the top 11 key bits.
-template <int DS>
-__global__ __launch_bounds__(256) void score_hist_kernel(SparseParams p) {
-  __shared__ uint32_t hist[kBins];
-  __shared__ float qc[4][DS];
-  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int n = p.lens.n[b];
-  int lo, hi;
-  candidate_range(p, n, lo, hi);
-  const int t0 = blockIdx.x * kTokPerBlock;
-  if (t0 >= n) return;
-  const int G = p.hq / p.hkv;
-  const size_t bh = (size_t)b * p.hkv + h;
-  for (int i = tid; i < kBins; i += 256) hist[i] = 0u;
-  if (tid < 4 * DS) {
-    const int j = tid / DS, i = tid % DS;
-    const int c = p.channel_idx[bh * DS + i];
-    qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
-  }
-  __syncthreads();
-
-  const __half* srow = p.summary + (bh * p.capacity) * DS;
-  uint32_t* keys = p.ws.keys + bh * p.capacity;
-#pragma unroll
-  for (int it = 0; it < kTokPerBlock / 256; ++it) {
-    const int t = t0 + it * 256 + tid;
-    if (t >= n) break;
-    uint32_t key = 0u;  // non-candidates: below every finite score
-    if (t >= lo && t < hi) {
-      union {
-        uint4 v[DS / 8];
-        __half hx[DS];
-      } row;
-#pragma unroll
-      for (int x = 0; x < DS / 8; ++x) row.v[x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
-      float total = 0.f;
-      for (int j = 0; j < G; ++j) {
-        // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k
-        float a = qc[j][0] * __half2float(row.hx[0]);
-#pragma unroll
-        for (int i = 1; i < DS; ++i) a = __builtin_fmaf(qc[j][i], __half2float(row.hx[i]), a);
-        total = j == 0 ? a : total + a;
-      }
-      total = total + 0.0f;
-      key = score_key(total);
-      atomicAdd(&hist[key >> 21], 1u);
-    }
-    keys[t] = key;
-  }
-  __syncthreads();
-  uint32_t* gh = p.ws.hist + bh * 3 * kBins;
-  for (int i = tid; i < kBins; i += 256)
-    if (hist[i]) atomicAdd(&gh[i], hist[i]);
-}
-
-// Finds the bin holding the k-th largest key: bins above it hold `above` < k keys,
-// bins above-or-equal hold >= k.  Every thread of the block gets the result.
-__device__ inline void find_bin(const uint32_t* gh, int nbins, uint32_t k, uint32_t* scratch /*nbins+2*/,
-                                uint32_t& bin, uint32_t& above) {
-  const int tid = threadIdx.x;
-  // suffix sums by 256 threads over nbins (<= 2048) bins: each thread owns a run
-  const int per = nbins / 256;
-  uint32_t local = 0;
-  for (int i = 0; i < per; ++i) local += gh[tid * per + i];
-  scratch[tid] = local;
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t run = 0;
-    int seg = 255;
-    for (; seg > 0; --seg) {
-      if (run + scratch[seg] >= k) break;
-      run += scratch[seg];
-    }
-    // seg is the segment containing the k-th key (or 0)
-    int bsel = seg * per + per - 1;
-    for (; bsel > seg * per; --bsel) {
-      const uint32_t c = gh[bsel];
-      if (run + c >= k) break;
-      run += c;
-    }
-    scratch[256] = (uint32_t)bsel;
-    scratch[257] = run;
-  }
-  __syncthreads();
-  bin = scratch[256];
-  above = scratch[257];
-  __syncthreads();
-}
-
-__device__ inline uint32_t k_eff_of(const SparseParams& p, int n) {
-  int lo, hi;
-  candidate_range(p, n, lo, hi);
-  return (uint32_t)min(p.top_k, hi - lo);
-}
-
-// Pass 2 / 3: histogram of the next digit among keys matching the prefix so far.
-template <int LEVEL>
-__global__ __launch_bounds__(256) void refine_hist_kernel(SparseParams p) {
-  __shared__ uint32_t hist[kBins];
-  __shared__ uint32_t scratch[258];
-  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int n = p.lens.n[b];
-  const int t0 = blockIdx.x * kTokPerBlock;
-  if (t0 >= n) return;
-  const uint32_t k = k_eff_of(p, n);
-  if (k == 0) return;
-  const size_t bh = (size_t)b * p.hkv + h;
-  const uint32_t* gh = p.ws.hist + bh * 3 * kBins;
-  uint32_t b1, above1, prefix, k_rem;
-  find_bin(gh, kBins, k, scratch, b1, above1);
-  k_rem = k - above1;
-  prefix = b1;
-  if (LEVEL == 2) {
-    uint32_t b2, above2;
-    find_bin(gh + kBins, kBins, k_rem, scratch, b2, above2);
-    k_rem -= above2;
-    prefix = (b1 << 11) | b2;
-  }
-  for (int i = tid; i < kBins; i += 256) hist[i] = 0u;
-  __syncthreads();
-  const uint32_t* keys = p.ws.keys + bh * p.capacity;
-  for (int it = 0; it < kTokPerBlock / 256; ++it) {
-    const int t = t0 + it * 256 + tid;
-    if (t >= n) break;
-    const uint32_t key = keys[t];
-    if (LEVEL == 1) {
-      if ((key >> 21) == prefix) atomicAdd(&hist[(key >> 10) & 0x7FFu], 1u);
-    } else {
-      if ((key >> 10) == prefix) atomicAdd(&hist[key & 0x3FFu], 1u);
-    }
-  }
-  __syncthreads();
-  uint32_t* out = p.ws.hist + bh * 3 * kBins + LEVEL * kBins;
-  for (int i = tid; i < kBins; i += 256)
-    if (hist[i]) atomicAdd(&out[i], hist[i]);
-}
-
-// Threshold key T and the number of keys equal to T that are selected.
-__device__ inline void find_threshold(const SparseParams& p, size_t bh, uint32_t k, uint32_t* scratch,
-                                      uint32_t& T, uint32_t& n_eq_take) {
-  const uint32_t* gh = p.ws.hist + bh * 3 * kBins;
-  uint32_t b1, a1, b2, a2, b3, a3;
-  find_bin(gh, kBins, k, scratch, b1, a1);
-  find_bin(gh + kBins, kBins, k - a1, scratch, b2, a2);
-  find_bin(gh + 2 * kBins, 1024, k - a1 - a2, scratch, b3, a3);
-  T = (b1 << 21) | (b2 << 10) | b3;
-  n_eq_take = k - a1 - a2 - a3;
-}
-
-// Pass 4: per block, how many keys lie above the threshold and how many equal it.
-__global__ __launch_bounds__(256) void count_kernel(SparseParams p) {
-  __shared__ uint32_t scratch[258];
-  __shared__ uint32_t cnt[2];
-  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int n = p.lens.n[b];
-  const int t0 = blockIdx.x * kTokPerBlock;
-  if (t0 >= n) return;
-  const uint32_t k = k_eff_of(p, n);
-  if (k == 0) return;
-  const size_t bh = (size_t)b * p.hkv + h;
-  uint32_t T, take;
-  find_threshold(p, bh, k, scratch, T, take);
-  if (tid < 2) cnt[tid] = 0u;
-  __syncthreads();
-  const uint32_t* keys = p.ws.keys + bh * p.capacity;
-  uint32_t gt = 0, eq = 0;
-  for (int it = 0; it < kTokPerBlock / 256; ++it) {
-    const int t = t0 + it * 256 + tid;
-    if (t >= n) break;
-    const uint32_t key = keys[t];
-    gt += key > T;
-    eq += key == T;
-  }
-  if (gt) atomicAdd(&cnt[0], gt);
-  if (eq) atomicAdd(&cnt[1], eq);
-  __syncthreads();
-  if (tid < 2) p.ws.blk[(bh * p.ws.nblk_cap + blockIdx.x) * 2 + tid] = cnt[tid];
-}
-
-// Pass 5: ordered compaction.  Thread i of a block owns tokens [t0 + 4i, t0 + 4i + 4),
-// so positions follow token order.
-__global__ __launch_bounds__(256) void compact_kernel(SparseParams p) {
-  __shared__ uint32_t scratch[258];
-  __shared__ uint32_t sgt[256], seq[256];
-  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int n = p.lens.n[b];
-  const size_t bh = (size_t)b * p.hkv + h;
-  const uint32_t k = k_eff_of(p, n);
-  int32_t* out = p.topk_idx + bh * p.top_k;
-  if (blockIdx.x == 0) {
-    for (int i = (int)k + tid; i < p.top_k; i += 256) out[i] = -1;
-    if (tid == 0) p.topk_count[bh] = (int32_t)k;
-  }
-  const int t0 = blockIdx.x * kTokPerBlock;
-  if (t0 >= n || k == 0) return;
-  uint32_t T, take;
-  find_threshold(p, bh, k, scratch, T, take);
-  // keys above / equal in earlier blocks
-  uint32_t gt_before = 0, eq_before = 0;
-  for (int i = tid; i < (int)blockIdx.x; i += 256) {
-    gt_before += p.ws.blk[(bh * p.ws.nblk_cap + i) * 2];
-    eq_before += p.ws.blk[(bh * p.ws.nblk_cap + i) * 2 + 1];
-  }
-  sgt[tid] = gt_before;
-  seq[tid] = eq_before;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s) {
-      sgt[tid] += sgt[tid + s];
-      seq[tid] += seq[tid + s];
-    }
-    __syncthreads();
-  }
-  gt_before = sgt[0];
-  eq_before = seq[0];
-  __syncthreads();
-
-  const uint32_t* keys = p.ws.keys + bh * p.capacity;
-  uint32_t key[4];
-  uint32_t gt = 0, eq = 0;
-  for (int x = 0; x < 4; ++x) {
-    const int t = t0 + 4 * tid + x;
-    key[x] = t < n ? keys[t] : 0u;
-    gt += key[x] > T;
-    eq += (t < n) && key[x] == T;
-  }
-  // exclusive scan over threads (Hillis-Steele, 256 entries)
-  sgt[tid] = gt;
-  seq[tid] = eq;
-  __syncthreads();
-  for (int s = 1; s < 256; s <<= 1) {
-    uint32_t a = 0, c = 0;
-    if (tid >= s) {
-      a = sgt[tid - s];
-      c = seq[tid - s];
-    }
-    __syncthreads();
-    sgt[tid] += a;
-    seq[tid] += c;
-    __syncthreads();
-  }
-  uint32_t gt_run = gt_before + sgt[tid] - gt;
-  uint32_t eq_run = eq_before + seq[tid] - eq;
-  for (int x = 0; x < 4; ++x) {
-    const int t = t0 + 4 * tid + x;
-    if (t >= n) break;
-    if (key[x] > T) {
-      out[gt_run + min(eq_run, take)] = t;
-      ++gt_run;
-    } else if (key[x] == T) {
-      if (eq_run < take) out[gt_run + eq_run] = t;
-      ++eq_run;
-    }
-  }
-}
 
 // ---------------------------------------------------------------------------------
 
@@ -380,15 +80,15 @@ struct SparseAttnParams {
   TkvSeqLens lens;
 };
 
-constexpr int kAttnTokPerBlock = 128;
+constexpr int kAttnMaxWaves = 4;  // a workgroup of W waves handles 32*W attended tokens
 
 __device__ inline float half_wave_max(float v) {
   for (int m = 16; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
   return v;
 }
 
-// Exact attention over sinks + gathered rows + window.  One workgroup handles 128
-// attended tokens of one KV head; lane (t, hp) scores token t for query heads
+// Exact attention over sinks + gathered rows + window.  One workgroup of W <= 4 waves
+// handles 32*W attended tokens of one KV head; lane (t, hp) scores token t for query heads
 // 2hp, 2hp+1; then every lane accumulates two output channels.
 __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   __shared__ float qs[4][TKV_D];
@@ -406,14 +106,15 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   const int w0 = max(n - p.n_window, n_sk);
   const int n_att = n_sk + cnt + (n - w0);
 
-  for (int i = tid; i < 4 * TKV_D; i += 256) {
+  const int nthr = blockDim.x, W = nthr / 64;
+  for (int i = tid; i < 4 * TKV_D; i += nthr) {
     const int hh = i / TKV_D, c = i % TKV_D;
     qs[hh][c] = hh < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c]) : 0.f;
   }
   __syncthreads();
 
   const int t = lane % 32, hp = lane / 32;
-  const int i = chunk * kAttnTokPerBlock + wave * 32 + t;
+  const int i = (chunk * W + wave) * 32 + t;
   const bool valid = i < n_att;
   const __half* krow = nullptr;
   if (valid) {
@@ -449,7 +150,8 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   const bool any = m0 != -INFINITY;  // this wave has at least one valid token (uniform per wave)
   pw[wave][2 * hp][t] = valid ? exp2f(x0 - m0) : 0.f;
   pw[wave][2 * hp + 1][t] = valid ? exp2f(x1 - m1) : 0.f;
-  if (hp == 0) vrow_s[wave][t] = valid ? krow + TKV_D : nullptr;
+  // invalid tokens point at a real row and carry weight 0, so the V loop needs no branches
+  if (hp == 0) vrow_s[wave][t] = valid ? krow + TKV_D : p.kv_local + bh * (size_t)(p.n_sink + p.n_window) * 2 * TKV_D;
   if (t == 0) {
     red_m[wave][2 * hp] = m0;
     red_m[wave][2 * hp + 1] = m1;
@@ -458,16 +160,21 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   const int c0 = 2 * lane;
   float o0[4] = {0.f, 0.f, 0.f, 0.f}, o1[4] = {0.f, 0.f, 0.f, 0.f}, ls[4] = {0.f, 0.f, 0.f, 0.f};
   if (any) {
-    for (int tt = 0; tt < 32; ++tt) {
-      const __half* vr = vrow_s[wave][tt];
-      if (!vr) continue;
-      const __half2 v2 = reinterpret_cast<const __half2*>(vr)[lane];
-      const float v0 = __low2float(v2), v1 = __high2float(v2);
-      for (int hh = 0; hh < 4; ++hh) {
-        const float pp = pw[wave][hh][tt];
-        o0[hh] += pp * v0;
-        o1[hh] += pp * v1;
-        ls[hh] += pp;
+#pragma unroll
+    for (int t8 = 0; t8 < 32; t8 += 8) {
+      __half2 v2[8];
+#pragma unroll
+      for (int y = 0; y < 8; ++y) v2[y] = reinterpret_cast<const __half2*>(vrow_s[wave][t8 + y])[lane];
+#pragma unroll
+      for (int y = 0; y < 8; ++y) {
+        const float v0 = __low2float(v2[y]), v1 = __high2float(v2[y]);
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh) {
+          const float pp = pw[wave][hh][t8 + y];
+          o0[hh] += pp * v0;
+          o1[hh] += pp * v1;
+          ls[hh] += pp;
+        }
       }
     }
   }
@@ -477,12 +184,12 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
     if (lane == 0) red_l[wave][hh] = ls[hh];
   }
   __syncthreads();
-  for (int x = tid; x < G * TKV_D; x += 256) {
+  for (int x = tid; x < G * TKV_D; x += nthr) {
     const int hh = x / TKV_D, c = x % TKV_D;
     float M = -INFINITY;
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, red_m[w][hh]);
+    for (int w = 0; w < W; ++w) M = fmaxf(M, red_m[w][hh]);
     float L = 0.f, O = 0.f;
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < W; ++w) {
       const float mw = red_m[w][hh];
       const float wgt = mw == -INFINITY ? 0.f : exp2f(mw - M);
       L += red_l[w][hh] * wgt;
@@ -520,16 +227,6 @@ int32_t device_view_of_host(const void* host, const void** dev) {
   if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
   *dev = attr.devicePointer;
   return TKV_OK;
-}
-
-TopkWs carve_topk_ws(const tkv_sparse_desc* d, void* workspace) {
-  const size_t bh = (size_t)d->batch * d->n_kv_heads;
-  TopkWs ws;
-  ws.keys = (uint32_t*)workspace;
-  ws.hist = ws.keys + bh * (size_t)d->capacity;
-  ws.nblk_cap = nblk_cap_of(d->capacity);
-  ws.blk = ws.hist + bh * 3 * kBins;
-  return ws;
 }
 
 }  // namespace
@@ -577,52 +274,6 @@ extern "C" int32_t tkv_sparse_append(const tkv_sparse_desc* d, tkv_sparse_cache*
   return tkv_sparse_append_ragged(d, c, k_new, v_new, n_new, nullptr, stream);
 }
 
-extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
-                                            int32_t* topk_idx, int32_t* topk_count, void* workspace,
-                                            size_t workspace_bytes, void* stream) {
-  int32_t st = tkv::check_sparse_desc(d);
-  if (st != TKV_OK) return st;
-  if (!c || !c->seq_len_host || !c->key_summary || !c->channel_idx || !q || !topk_idx || !topk_count || !workspace)
-    return TKV_E_INVAL;
-  size_t need = 0;
-  tkv_sparse_cache_sizes(d, nullptr, &need);
-  if (workspace_bytes < need) return TKV_E_WORKSPACE;
-  SparseParams p;
-  int max_n = 0;
-  st = fill_lens(d, c, p.lens, max_n);
-  if (st != TKV_OK) return st;
-  p.summary = (const __half*)c->key_summary;
-  p.channel_idx = c->channel_idx;
-  p.q = (const __half*)q;
-  p.topk_idx = topk_idx;
-  p.topk_count = topk_count;
-  p.ws = carve_topk_ws(d, workspace);
-  p.hq = d->n_q_heads;
-  p.hkv = d->n_kv_heads;
-  p.ds = d->n_channels;
-  p.top_k = d->top_k;
-  p.n_sink = d->n_sink;
-  p.n_window = d->n_window;
-  p.capacity = d->capacity;
-
-  hipStream_t s = (hipStream_t)stream;
-  const size_t bh = (size_t)d->batch * d->n_kv_heads;
-  const size_t nhist = bh * 3 * kBins;
-  zero_u32_kernel<<<dim3((unsigned)((nhist + 255) / 256)), 256, 0, s>>>(p.ws.hist, nhist);
-  int nblk = (max_n + kTokPerBlock - 1) / kTokPerBlock;
-  if (nblk < 1) nblk = 1;
-  const dim3 grid(nblk, d->n_kv_heads, d->batch);
-  if (d->n_channels == 16)
-    score_hist_kernel<16><<<grid, 256, 0, s>>>(p);
-  else
-    score_hist_kernel<8><<<grid, 256, 0, s>>>(p);
-  refine_hist_kernel<1><<<grid, 256, 0, s>>>(p);
-  refine_hist_kernel<2><<<grid, 256, 0, s>>>(p);
-  count_kernel<<<grid, 256, 0, s>>>(p);
-  compact_kernel<<<grid, 256, 0, s>>>(p);
-  return tkv::launch_status();
-}
-
 extern "C" int32_t tkv_sparse_gather(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const int32_t* topk_idx,
                                      const int32_t* topk_count, void* staging, void* stream) {
   int32_t st = tkv::check_sparse_desc(d);
@@ -658,12 +309,13 @@ extern "C" int32_t tkv_sparse_attn(const tkv_sparse_desc* d, const tkv_sparse_ca
   st = fill_lens(d, c, p.lens, max_n);
   if (st != TKV_OK) return st;
   const int max_att = d->n_sink + d->top_k + d->n_window;
-  int n_chunks = (max_att + kAttnTokPerBlock - 1) / kAttnTokPerBlock;
+  // fewest waves per workgroup that keep the number of chunks within the 64 partial slots
+  int W = 1;
+  while (W < kAttnMaxWaves && (max_att + 32 * W - 1) / (32 * W) > 64) ++W;
+  const int n_chunks = (max_att + 32 * W - 1) / (32 * W);
   if (n_chunks > 64) return TKV_E_UNSUPPORTED;
   // partials live behind the Top-K scratch so that one workspace serves both calls
-  TopkWs ws = carve_topk_ws(d, workspace);
-  const size_t bh = (size_t)d->batch * d->n_kv_heads;
-  float* parts = (float*)(ws.blk + bh * (size_t)ws.nblk_cap * 2);
+  float* parts = tkv::carve_sparse_ws(d, workspace).parts;
   p.q = (const __half*)q;
   p.staging = (const __half*)staging;
   p.kv_local = (const __half*)c->kv_local;
@@ -677,7 +329,7 @@ extern "C" int32_t tkv_sparse_attn(const tkv_sparse_desc* d, const tkv_sparse_ca
   p.n_window = d->n_window;
   p.n_chunks = n_chunks;
   hipStream_t s = (hipStream_t)stream;
-  sparse_attn_kernel<<<dim3(n_chunks, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+  sparse_attn_kernel<<<dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s>>>(p);
   if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   return tkv::launch_attn_merge(parts, (__half*)out, d->batch * d->n_q_heads, n_chunks, s);
 }

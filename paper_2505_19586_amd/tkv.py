@@ -200,7 +200,8 @@ class SparseLayer:
         assert kv_host.is_pinned() and kv_host.numel() * 2 >= self.sizes[2]
         self.kv_host = kv_host.view(-1)[: self.sizes[2] // 2].view(batch, n_kv_heads, capacity, 2, head_dim)
         self.kv_local = torch.zeros(batch, n_kv_heads, n_sink + n_window, 2, head_dim, dtype=torch.float16, device=dev)
-        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        # zero once: the Top-K histogram and counters must start at zero (each call leaves them zero)
+        self.workspace = torch.zeros(self.workspace_bytes, dtype=torch.uint8, device=dev)
         self.staging = torch.empty(batch, n_kv_heads, top_k, 2, head_dim, dtype=torch.float16, device=dev)
         self.topk_idx = torch.empty(batch, n_kv_heads, top_k, dtype=torch.int32, device=dev)
         self.topk_count = torch.zeros(batch, n_kv_heads, dtype=torch.int32, device=dev)
