@@ -136,7 +136,9 @@ int32_t tkv_quantize_append_ragged(const tkv_quant_desc* desc, tkv_quant_cache* 
  * over the fp16 tail, one softmax over all N tokens, out = weights . V-hat.
  * q, out: fp16 [B][Hq][128].  A sequence with 0 tokens yields zeros.
  * The work is split over token chunks whose partial (max, sum, weighted V) results
- * go through `workspace` and are merged with a log-sum-exp merge.
+ * go through `workspace` and are merged with a log-sum-exp merge.  The workspace must be
+ * ZERO-FILLED by the caller before its first use (it ends in arrival counters that every
+ * call leaves zero); concurrent calls need separate workspaces.
  */
 int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache* cache, const void* q,
                               void* out, float sm_scale, void* workspace, size_t workspace_bytes,

@@ -6,8 +6,9 @@
 namespace tkv {
 // matrix-core path (tkv_quant_attn_mfma.hip); returns TKV_E_UNSUPPORTED when the
 // shape is not one it is built for.
-int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, float scale2,
-                               float* parts, int n_chunks, const TkvSeqLens& lens, hipStream_t s);
+int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
+                               float scale2, float* parts, uint32_t* arrivals, int n_chunks,
+                               const TkvSeqLens& lens, hipStream_t s);
 }  // namespace tkv
 
 namespace {
@@ -334,9 +335,11 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
     if (c_target > c_work) c_target = c_work;
     if (c_target > 64) c_target = 64;
     if (c_target < 1) c_target = 1;
-    st = tkv::launch_quant_attn_mfma(d, c, p.q, p.scale2, p.parts, c_target, p.lens, s);
-    if (st != TKV_OK) return st;
-    return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, c_target, s);
+    // arrival counters sit behind the partials (zero before first use, left zero by every call)
+    const size_t parts_bytes =
+        (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
+    uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_bytes + 255) & ~(size_t)255));
+    return tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, c_target, p.lens, s);
   } else {
     p.chunk_offset = 0;
     quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);

@@ -40,6 +40,8 @@ struct MfmaParams {
   const __half* v_resid;
   const __half* q;
   float* parts;  // [B][Hq][n_chunks][D + 2]
+  uint32_t* arrivals;  // [B][Hkv], zero between calls
+  __half* out;         // [B][Hq][D]
   float scale2;
   int32_t hq, hkv, residual, capacity;
   int32_t n_chunks;
@@ -59,6 +61,27 @@ __device__ inline half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2
 __device__ inline uint32_t pack2(_Float16 lo, _Float16 hi) {
   half2_t v = {lo, hi};
   return __builtin_bit_cast(uint32_t, v);
+}
+
+// fp16 hi/lo split of a product, written so that each part is one fused multiply-add
+// with an fp16 result (the compiler selects v_fma_mixlo/mixhi_f16 for this shape):
+//   hi = f16(a * b), lo = f16(a * b - hi)   (the FMA makes the residual exact)
+// s2 holds two fp16 scalers; the results are packed the same way.  No inline assembly:
+// the operands come straight from MFMA / transcendental results, whose read hazards
+// only the compiler's own instructions are checked for.
+__device__ inline uint32_t mix_hi_pair(float a0, float a1, uint32_t s2) {
+  const half2_t s = as_half2(s2);
+  return pack2((_Float16)__builtin_fmaf(a0, (float)s[0], 0.0f), (_Float16)__builtin_fmaf(a1, (float)s[1], 0.0f));
+}
+__device__ inline uint32_t mix_lo_pair(float a0, float a1, uint32_t s2, uint32_t hi) {
+  const half2_t s = as_half2(s2), h = as_half2(hi);
+  return pack2((_Float16)__builtin_fmaf(a0, (float)s[0], -(float)h[0]),
+               (_Float16)__builtin_fmaf(a1, (float)s[1], -(float)h[1]));
+}
+// residual of rounding two floats to the packed fp16 pair `hi`: f16(a - hi)
+__device__ inline uint32_t residual_pair(float a0, float a1, uint32_t hi) {
+  const half2_t h = as_half2(hi);
+  return pack2((_Float16)__builtin_fmaf(a0, 1.0f, -(float)h[0]), (_Float16)__builtin_fmaf(a1, 1.0f, -(float)h[1]));
 }
 
 // Two MFMA operands (8 registers) out of one 32-bit word of packed codes.
@@ -189,17 +212,26 @@ __device__ inline void tail_attention(const MfmaParams& p, MergeSmem& ms, float 
     // phase 3: weighted V sum; thread = (channel pair, token residue class)
     float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
     float ls[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int t = wave; t < cnt; t += kWaves) {
-      const int tok = nq + sb0 + t;
-      const uint32_t v2 = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D)[lane];
-      const half2_t vv = as_half2(v2);
-      const float v0 = (float)vv[0], v1 = (float)vv[1];
+    // four rows in flight per wave (rows past the end are re-reads of the last one, weight 0)
+    for (int t4 = wave; t4 < cnt; t4 += 4 * kWaves) {
+      uint32_t v2[4];
 #pragma unroll
-      for (int hh = 0; hh < 4; ++hh) {
-        const float pp = x_s[hh][t];
-        acc[hh][0] = __builtin_fmaf(pp, v0, acc[hh][0]);
-        acc[hh][1] = __builtin_fmaf(pp, v1, acc[hh][1]);
-        ls[hh] += pp;
+      for (int y = 0; y < 4; ++y) {
+        const int tok = nq + sb0 + min(t4 + y * kWaves, cnt - 1);
+        v2[y] = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D)[lane];
+      }
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        const int t = t4 + y * kWaves;
+        const half2_t vv = as_half2(v2[y]);
+        const float v0 = (float)vv[0], v1 = (float)vv[1];
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh) {
+          const float pp = t < cnt ? x_s[hh][t] : 0.f;
+          acc[hh][0] = __builtin_fmaf(pp, v0, acc[hh][0]);
+          acc[hh][1] = __builtin_fmaf(pp, v1, acc[hh][1]);
+          ls[hh] += pp;
+        }
       }
     }
     // reduce over the 8 waves through the (still unused) per-wave merge slots
@@ -342,15 +374,11 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   auto process = [&](const GroupRegs<BITS>& cur) {
     // ---- query-side operand of this group: (q s) split into hi + lo, through LDS
     {
-      const half2_t s2 = as_half2(cur.ks2);
-      const float s0 = (float)s2[0], s1 = (float)s2[1];
 #pragma unroll
       for (int hh = 0; hh < 4; ++hh) {
-        const float p0 = qf[hh][0] * s0, p1 = qf[hh][1] * s1;  // exact: 11 x 11 bit mantissas
-        const _Float16 h0 = (_Float16)p0, h1 = (_Float16)p1;
-        const _Float16 l0 = (_Float16)(p0 - (float)h0), l1 = (_Float16)(p1 - (float)h1);
-        bk_s[wave][0][hh][lane] = pack2(h0, h1);
-        bk_s[wave][1][hh][lane] = pack2(l0, l1);
+        const uint32_t hi = mix_hi_pair(qf[hh][0], qf[hh][1], cur.ks2);  // products are exact in float32
+        bk_s[wave][0][hh][lane] = hi;
+        bk_s[wave][1][hh][lane] = mix_lo_pair(qf[hh][0], qf[hh][1], cur.ks2, hi);
       }
       kz_s[wave][lane] = cur.kz2;
     }
@@ -360,10 +388,12 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
 
     // ---- zero-point term: cz[slot] = sum_c z[c] q[c], identical in every row
     floatx4 acc_cz = {0.f, 0.f, 0.f, 0.f};
+    {
+      uintx4 az[4];
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      const uintx4 az = *reinterpret_cast<const uintx4*>(&kz_s[wave][(32 * m + 8 * rb) / 2]);
-      acc_cz = mfma(az, bq[m], acc_cz);
+      for (int m = 0; m < 4; ++m) az[m] = *reinterpret_cast<const uintx4*>(&kz_s[wave][(32 * m + 8 * rb) / 2]);
+#pragma unroll
+      for (int m = 0; m < 4; ++m) acc_cz = mfma(az[m], bq[m], acc_cz);
     }
     // ---- scaler term for the two 16-token tiles
     floatx4 acc_s[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
@@ -395,8 +425,8 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
 
     // ---- online softmax (log2 domain), lazy rescale
     const float cz = acc_cz[0] * p.scale2;
-    float mx = fmaxf(fmaxf(fmaxf(acc_s[0][0], acc_s[0][1]), fmaxf(acc_s[0][2], acc_s[0][3])),
-                     fmaxf(fmaxf(acc_s[1][0], acc_s[1][1]), fmaxf(acc_s[1][2], acc_s[1][3])));
+    const float mx = fmaxf(fmaxf(fmaxf(acc_s[0][0], acc_s[0][1]), fmaxf(acc_s[0][2], acc_s[0][3])),
+                           fmaxf(fmaxf(acc_s[1][0], acc_s[1][1]), fmaxf(acc_s[1][2], acc_s[1][3])));
     const float xmax = __builtin_fmaf(mx, K1, cz);  // largest logit among this lane's 8 tokens
     if (__builtin_amdgcn_ballot_w64(xmax - m_run > kHeadroom) != 0ull) {
       // new reference maximum, uniform over the lanes that share a query head
@@ -421,15 +451,11 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t svj = cur.sv[j];
-      const half2_t s2 = as_half2(svj);
       const float w0 = pw[2 * j], w1 = pw[2 * j + 1];
-      const float x0 = w0 * (float)s2[0], x1 = w1 * (float)s2[1];
-      const _Float16 xh0 = (_Float16)x0, xh1 = (_Float16)x1;
-      b2h[j] = pack2(xh0, xh1);
-      b2l[j] = pack2((_Float16)(x0 - (float)xh0), (_Float16)(x1 - (float)xh1));
-      const _Float16 ph0 = (_Float16)w0, ph1 = (_Float16)w1;
-      bph[j] = pack2(ph0, ph1);
-      bpl[j] = pack2((_Float16)(w0 - (float)ph0), (_Float16)(w1 - (float)ph1));
+      b2h[j] = mix_hi_pair(w0, w1, svj);
+      b2l[j] = mix_lo_pair(w0, w1, svj, b2h[j]);
+      bph[j] = pack2((_Float16)w0, (_Float16)w1);
+      bpl[j] = residual_pair(w0, w1, bph[j]);
       const uint32_t zvj = cur.zv[j];
       const half2_t t = __builtin_elementwise_fma(as_half2(zvj), zmul[j], zadd[j]);
       a_zv[j] = __builtin_bit_cast(uint32_t, t);
@@ -528,11 +554,42 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
       O += ms.o[w][hh][c] * wgt;
     }
     float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
-    dst[2 + c] = O;
+    // device-scope stores: visible to the merging workgroup without a cache write-back
+    __hip_atomic_store(dst + 2 + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
-      dst[0] = M;
-      dst[1] = L;
+      __hip_atomic_store(dst, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(dst + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+  }
+
+  // ---- the last workgroup of this (sequence, KV head) to arrive merges all chunks.
+  // Partials travel through device-scope (cache-bypassing) stores and loads, ordered by
+  // waiting for the stores to complete before the arrival counter is bumped: a release /
+  // acquire fence pair would write back and invalidate the whole L2 (tens of microseconds).
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0) w_s[0][0] = __uint_as_float(atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(p.n_chunks - 1) ? 1u : 0u);
+  __syncthreads();
+  if (__float_as_uint(w_s[0][0]) == 0u) return;
+  if (tid == 0) p.arrivals[bh] = 0u;
+  if (tid < G * TKV_D) {
+    const int hh = tid / TKV_D, c = tid % TKV_D;
+    const size_t head = (size_t)b * p.hq + (size_t)h * G + hh;
+    const float* base = p.parts + head * p.n_chunks * TKV_PART_STRIDE;
+    float M = -INFINITY;
+    auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+#pragma unroll 8
+    for (int k = 0; k < p.n_chunks; ++k) M = fmaxf(M, ld(base + (size_t)k * TKV_PART_STRIDE));
+    float L = 0.f, O = 0.f;
+#pragma unroll 8
+    for (int k = 0; k < p.n_chunks; ++k) {
+      const float* pk = base + (size_t)k * TKV_PART_STRIDE;
+      const float mk = ld(pk);
+      const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
+      L = __builtin_fmaf(ld(pk + 1), w, L);
+      O = __builtin_fmaf(ld(pk + 2 + c), w, O);
+    }
+    p.out[head * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
   }
 }
 
@@ -540,8 +597,9 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
 
 namespace tkv {
 
-int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, float scale2,
-                               float* parts, int n_chunks, const TkvSeqLens& lens, hipStream_t s) {
+int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
+                               float scale2, float* parts, uint32_t* arrivals, int n_chunks,
+                               const TkvSeqLens& lens, hipStream_t s) {
   if (d->head_dim != TKV_D || d->group_size != TKV_G) return TKV_E_UNSUPPORTED;
   if (d->n_q_heads / d->n_kv_heads > 4) return TKV_E_UNSUPPORTED;
   MfmaParams p;
@@ -555,6 +613,8 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.v_resid = (const __half*)c->v_resid;
   p.q = q;
   p.parts = parts;
+  p.arrivals = arrivals;
+  p.out = out;
   p.scale2 = scale2;
   p.hq = d->n_q_heads;
   p.hkv = d->n_kv_heads;

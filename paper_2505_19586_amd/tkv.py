@@ -127,7 +127,8 @@ class QuantLayer:
         self.workspace_bytes = int(ws.value)
         names = ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_resid", "v_resid")
         self.buffers = {n: torch.zeros(max(s, 16), dtype=torch.uint8, device=dev) for n, s in zip(names, self.sizes)}
-        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        # zero once: the arrival counters behind the partials must start at zero
+        self.workspace = torch.zeros(self.workspace_bytes, dtype=torch.uint8, device=dev)
         self.seq_len = np.zeros(batch, dtype=np.int32)
         self.cache = QuantCache(*[self.buffers[n].data_ptr() for n in names],
                                 self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)))
