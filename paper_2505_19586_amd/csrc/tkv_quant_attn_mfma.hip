@@ -46,6 +46,7 @@ struct MfmaParams {
   int32_t hq, hkv, residual, capacity;
   int32_t n_chunks;
   int32_t dbg_mode;
+  long long* dbg_ts;
   TkvSeqLens lens;
 };
 
@@ -113,6 +114,7 @@ constexpr int kEP = 6;             // weight-side operands carry 2^kEP
 constexpr float kHeadroom = 4.0f;  // lazy rescale: weights may reach 2^kHeadroom
 constexpr int kWaves = 8;          // waves per workgroup
 constexpr int kThreads = kWaves * 64;
+constexpr int kTailTok = kThreads / 4;  // fp16-tail tokens per pass (4 threads per token)
 constexpr int kTailEntry = kWaves;
 constexpr int kBkStride = 80;      // words per head row of the query-side operand in LDS  // slot of the fp16 tail in the workgroup merge
 
@@ -162,31 +164,39 @@ __device__ inline void tail_attention(const MfmaParams& p, MergeSmem& ms, float 
   const int ring = p.residual + TKV_G;
   const int r_total = n - nq;
   bool first = true;
-  for (int sb0 = 0; sb0 < r_total; sb0 += kThreads) {
-    const int cnt = min(kThreads, r_total - sb0);
-    // phase 1: logits of token sb0 + tid for the 4 heads
+  for (int sb0 = 0; sb0 < r_total; sb0 += kTailTok) {
+    const int cnt = min(kTailTok, r_total - sb0);
+    // phase 1: logits; 4 threads per token, each over 32 channels, combined by shuffles
+    const int tk = tid / 4, part = tid % 4;  // token in sub-block, channel quarter
     float x[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    if (tid < cnt) {
-      const int tok = nq + sb0 + tid;
-      const uintx4* krow = reinterpret_cast<const uintx4*>(p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D);
+    {
+      const int tok = nq + sb0 + min(tk, cnt - 1);
+      const uintx4* krow = reinterpret_cast<const uintx4*>(p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D) + 4 * part;
+      uintx4 kv[4];
+#pragma unroll
+      for (int c8 = 0; c8 < 4; ++c8) kv[c8] = krow[c8];
       float a[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-      for (int c8 = 0; c8 < TKV_D / 8; ++c8) {
-        const uintx4 kv = krow[c8];
+#pragma unroll
+      for (int c8 = 0; c8 < 4; ++c8) {
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
-          const uint32_t w = kv[y];
+          const uint32_t w = kv[c8][y];
           const half2_t k2 = as_half2(w);
           const float k0 = (float)k2[0], k1 = (float)k2[1];
+          const int c = 32 * part + 8 * c8 + 2 * y;
 #pragma unroll
           for (int hh = 0; hh < 4; ++hh) {
-            a[hh] = __builtin_fmaf(q_s[hh][8 * c8 + 2 * y], k0, a[hh]);
-            a[hh] = __builtin_fmaf(q_s[hh][8 * c8 + 2 * y + 1], k1, a[hh]);
+            a[hh] = __builtin_fmaf(q_s[hh][c], k0, a[hh]);
+            a[hh] = __builtin_fmaf(q_s[hh][c + 1], k1, a[hh]);
           }
         }
       }
 #pragma unroll
-      for (int hh = 0; hh < 4; ++hh) x[hh] = a[hh] * p.scale2;
+      for (int hh = 0; hh < 4; ++hh) {
+        a[hh] += __shfl_xor(a[hh], 1, 64);
+        a[hh] += __shfl_xor(a[hh], 2, 64);
+        if (tk < cnt) x[hh] = a[hh] * p.scale2;
+      }
     }
     // phase 2: workgroup max and weights
     float wm[4];
@@ -205,24 +215,26 @@ __device__ inline void tail_attention(const MfmaParams& p, MergeSmem& ms, float 
       float v = w_s[0][hh];
       for (int w = 1; w < kWaves; ++w) v = fmaxf(v, w_s[w][hh]);
       mx[hh] = v;  // finite: the sub-block holds at least one token
-      pw[hh] = tid < cnt ? exp2f(x[hh] - v) : 0.f;
-      x_s[hh][tid] = pw[hh];
+      pw[hh] = tk < cnt ? exp2f(x[hh] - v) : 0.f;
+      if (part == 0) x_s[hh][tk] = pw[hh];
     }
     __syncthreads();
     // phase 3: weighted V sum; thread = (channel pair, token residue class)
     float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
     float ls[4] = {0.f, 0.f, 0.f, 0.f};
-    // four rows in flight per wave (rows past the end are re-reads of the last one, weight 0)
-    for (int t4 = wave; t4 < cnt; t4 += 4 * kWaves) {
-      uint32_t v2[4];
+    // every wave takes tokens wave, wave + 8, ...; all of its rows (<= 16) are loaded before
+    // the first is used (rows past the end re-read the last one with weight 0)
+    {
+      constexpr int RW = kTailTok / kWaves;  // 16
+      uint32_t v2[RW];
 #pragma unroll
-      for (int y = 0; y < 4; ++y) {
-        const int tok = nq + sb0 + min(t4 + y * kWaves, cnt - 1);
+      for (int y = 0; y < RW; ++y) {
+        const int tok = nq + sb0 + min(wave + y * kWaves, cnt - 1);
         v2[y] = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D)[lane];
       }
 #pragma unroll
-      for (int y = 0; y < 4; ++y) {
-        const int t = t4 + y * kWaves;
+      for (int y = 0; y < RW; ++y) {
+        const int t = wave + y * kWaves;
         const half2_t vv = as_half2(v2[y]);
         const float v0 = (float)vv[0], v1 = (float)vv[1];
 #pragma unroll
@@ -283,6 +295,7 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   __shared__ float q_s[4][TKV_D];
   __shared__ float x_s[4][kThreads];
   __shared__ float w_s[kWaves][4];
+  __shared__ int s_next;
 
   const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
   const int tid = threadIdx.x, lane = tid % 64;
@@ -296,15 +309,19 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   // Work split of this sequence: the tail counts as (n - nq)/4 groups and belongs to
   // the last chunk, so that chunk gets correspondingly fewer quantized groups.
   const bool has_tail = chunk == p.n_chunks - 1;
-  const int tail_equiv = (n - nq + 3) / 4;
+  const int tail_equiv = (n - nq + 7) / 8;
   const int gpc = max(1, (jq + tail_equiv + p.n_chunks - 1) / p.n_chunks);
   const int blk0 = min(chunk * gpc, jq);
   const int blk1 = has_tail ? jq : min(blk0 + gpc, jq);
 
+  long long ts[8];
+  ts[0] = wall_clock64();
   const int slot = lane % 16, rb = lane / 16;
   const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, channel group
   const __half* qrow = p.q + ((size_t)b * p.hq + (size_t)h * G) * TKV_D;
 
+  if (tid == 0) s_next = blk0 + 2 * kWaves;
+  __syncthreads();
   if (has_tail) {
     for (int i = tid; i < 4 * TKV_D; i += kThreads) {
       const int hh = i / TKV_D, c = i % TKV_D;
@@ -482,35 +499,42 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
     __builtin_amdgcn_wave_barrier();
   };
 
-  // Three-deep register ring: while one group is computed the wave's next two groups
-  // are in flight (about 6 KiB per wave, 48 KiB per compute unit).
+  ts[1] = wall_clock64();
+  // Three-deep register ring: while one group is computed the wave's next two groups are in
+  // flight.  After a static first round the waves of a workgroup draw their groups from a
+  // shared LDS counter: the two waves that share a SIMD do not progress evenly, and with a
+  // static split the slower one ran alone (and poorly overlapped) for the last third.
   {
     GroupRegs<BITS> r0, r1, r2;
     const int last = p.dbg_mode == 1 ? blk0 : blk1 - 1;  // loads past the chunk are clamped to its last group and ignored
-    int blk = blk0 + wave;
-    if (p.dbg_mode >= 2 && wave >= 4) __builtin_amdgcn_s_sleep(8);
-    if (p.dbg_mode >= 3 && wave >= 4) __builtin_amdgcn_s_sleep(8);
-    if (blk < blk1) {
-      load_group<BITS>(r0, p, grp_base + min(blk, last), lane, us, rb, zrow_ld);
-      load_group<BITS>(r1, p, grp_base + min(blk + kWaves, last), lane, us, rb, zrow_ld);
+    auto grab = [&]() -> int {
+      int v = 0;
+      if (lane == 0) v = atomicAdd(&s_next, 1);
+      return __builtin_amdgcn_readfirstlane(v);
+    };
+    int i0 = blk0 + wave, i1 = blk0 + kWaves + wave, i2;
+    if (i0 < blk1) {
+      load_group<BITS>(r0, p, grp_base + min(i0, last), lane, us, rb, zrow_ld);
+      load_group<BITS>(r1, p, grp_base + min(i1, last), lane, us, rb, zrow_ld);
       for (;;) {
-        load_group<BITS>(r2, p, grp_base + min(blk + 2 * kWaves, last), lane, us, rb, zrow_ld);
+        i2 = grab();
+        load_group<BITS>(r2, p, grp_base + min(i2, last), lane, us, rb, zrow_ld);
         process(r0);
-        blk += kWaves;
-        if (blk >= blk1) break;
-        load_group<BITS>(r0, p, grp_base + min(blk + 2 * kWaves, last), lane, us, rb, zrow_ld);
+        if (i1 >= blk1) break;
+        i0 = grab();
+        load_group<BITS>(r0, p, grp_base + min(i0, last), lane, us, rb, zrow_ld);
         process(r1);
-        blk += kWaves;
-        if (blk >= blk1) break;
-        load_group<BITS>(r1, p, grp_base + min(blk + 2 * kWaves, last), lane, us, rb, zrow_ld);
+        if (i2 >= blk1) break;
+        i1 = grab();
+        load_group<BITS>(r1, p, grp_base + min(i1, last), lane, us, rb, zrow_ld);
         process(r2);
-        blk += kWaves;
-        if (blk >= blk1) break;
+        if (i0 >= blk1) break;
       }
     }
   }
-
+  ts[2] = wall_clock64();
   __syncthreads();
+  ts[3] = wall_clock64();
   if (has_tail && n > nq) {
     tail_attention(p, ms, q_s, x_s, w_s, bh, nq, n, G);
   } else if (tid < 4) {
@@ -519,6 +543,7 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   }
   __syncthreads();
 
+  ts[4] = wall_clock64();
   // ---- per-wave results -> LDS.  acc_z rows: lanes 0..15 (rb 0) hold rows 0..3 = z-terms
   // for u = row; lanes 16..31 register 0 hold row 4 = denominator.
   if (rb == 0) {
@@ -566,8 +591,14 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   // Partials travel through device-scope (cache-bypassing) stores and loads, ordered by
   // waiting for the stores to complete before the arrival counter is bumped: a release /
   // acquire fence pair would write back and invalidate the whole L2 (tens of microseconds).
+  ts[5] = wall_clock64();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  ts[6] = wall_clock64();
+  if (p.dbg_ts && lane == 0) {
+    long long* d = p.dbg_ts + ((((size_t)b * p.hkv + h) * p.n_chunks + chunk) * kWaves + wave) * 8;
+    for (int i = 0; i < 7; ++i) d[i] = ts[i];
+  }
   if (tid == 0) w_s[0][0] = __uint_as_float(atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(p.n_chunks - 1) ? 1u : 0u);
   __syncthreads();
   if (__float_as_uint(w_s[0][0]) == 0u) return;
@@ -596,6 +627,7 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
 }  // namespace
 
 namespace tkv {
+void* g_mfma_dbg = nullptr;
 
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
                                float scale2, float* parts, uint32_t* arrivals, int n_chunks,
@@ -621,6 +653,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.residual = d->residual;
   p.capacity = d->capacity;
   p.n_chunks = n_chunks;
+  p.dbg_ts = (long long*)g_mfma_dbg;
   p.dbg_mode = getenv("TKV_DEBUG_MODE") ? atoi(getenv("TKV_DEBUG_MODE")) : 0;
   p.lens = lens;
   const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
@@ -634,3 +667,5 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
 }
 
 }  // namespace tkv
+
+extern "C" void tkv_debug_set_dump(void* ptr) { tkv::g_mfma_dbg = ptr; }
