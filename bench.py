@@ -124,7 +124,36 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
+    def step_overlapped():
+        """Software-pipelined enqueue: while layer l's rows cross the host link on the side
+        stream, layer l+1's append and scoring run on the compute stream.  Legal only
+        because the synthetic queries of different layers are independent."""
+        pending = None   # (layer, event after which its staged rows are complete)
+        for l, L in enumerate(layers):
+            L.append(new_k[l], new_v[l])
+            if l in QUANT_LAYERS:
+                L.attn_decode(qs[l], sm, out=outs[l])
+                continue
+            L.estimate_topk(qs[l])
+            ready = torch.cuda.Event()
+            ready.record(compute)
+            side.wait_event(ready)
+            L.gather(stream=side)
+            done = torch.cuda.Event()
+            done.record(side)
+            if pending is not None:
+                pl, pe = pending
+                compute.wait_event(pe)
+                layers[pl].attn(qs[pl], sm, out=outs[pl])
+            pending = (l, done)
+        if pending is not None:
+            pl, pe = pending
+            compute.wait_event(pe)
+            layers[pl].attn(qs[pl], sm, out=outs[pl])
+
     def step(rec=None):
+        if not chained and rec is None:
+            return step_overlapped()
         for l, L in enumerate(layers):
             L.append(new_k[l], new_v[l])      # Eq. 2: the step's new token joins the cache first
             if l in QUANT_LAYERS:

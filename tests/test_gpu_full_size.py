@@ -1,0 +1,117 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times
+(same library defaults): quantized layer at N = 32768 (2 and 4 bit) and N = 131072,
+sparse layer at N = 131072 with k = 1024, batched ragged decode."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_19586_amd as tkv
+from oracle import attention, quant, sparse
+from synth import make_layer, ragged_lengths, static_channels
+
+from gpu_util import attn_err, check_quant_cache, to_new, to_new_batch
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+SM = 1.0 / np.sqrt(128.0)
+
+
+@pytest.mark.parametrize("n,bits", [(32768, 2), (32768, 4), (131072, 2)])
+def test_quant_layer_full_size(n, bits):
+    print(f"case full-size quant n={n} bits={bits}", flush=True)
+    inp = make_layer(n, config=1, layer=0, seq=bits)
+    layer = tkv.QuantLayer(bits=bits, capacity=n + 32)
+    layer.append(to_new(inp.k), to_new(inp.v))
+    ref = check_quant_cache(layer, 0, inp.k, inp.v)          # every code, scaler, zero-point
+    out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    err = attn_err(out[0], attention.quant_attention(inp.q, ref, SM))
+    print(f"   err {err:.3e}", flush=True)
+    assert err <= TOL
+    # one decoded token more: the single-token append path at full size
+    new = make_layer(1, config=1, layer=1, seq=bits)
+    layer.append(to_new(new.k), to_new(new.v))
+    k2 = np.concatenate([inp.k, new.k], axis=1)
+    v2 = np.concatenate([inp.v, new.v], axis=1)
+    layer2 = tkv.QuantLayer(bits=bits, capacity=n + 32)
+    layer2.append(to_new(k2), to_new(v2))
+    a = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    b = layer2.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    assert attn_err(a[0], b[0].float().cpu().numpy().astype(np.float64)) <= TOL
+
+
+def test_sparse_layer_full_size():
+    n, top_k = 131072, 1024
+    print(f"case full-size sparse n={n}", flush=True)
+    inp = make_layer(n, config=2, layer=0, seq=0)
+    layer = tkv.SparseLayer(top_k=top_k, capacity=n)
+    ch = static_channels(inp.k, 16)
+    layer.set_channels(ch[None])
+    layer.append(to_new(inp.k), to_new(inp.v))
+    q = torch.from_numpy(inp.q)[None].cuda()
+    layer.estimate_topk(q)
+    out = layer.gather_attn(q, SM, gather_stream=torch.cuda.Stream())
+    idx, cnt = sparse.estimate_topk(inp.q, sparse.key_summary(inp.k, ch), ch, n, top_k=top_k, n_sink=4, n_window=64)
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.topk_count[0].cpu().numpy(), cnt)
+    assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
+    want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, n, SM, n_sink=4, n_window=64)
+    err = attn_err(out[0], want)
+    print(f"   err {err:.3e}", flush=True)
+    assert err <= TOL
+    # a second call on the same workspace (self-cleaning counters) gives the same indices
+    layer.estimate_topk(q)
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
+
+
+def test_batched_ragged_hybrid():
+    """Batch 8, ragged lengths (scaled-down version of the batched configuration)."""
+    lens = ragged_lengths(8, 4096, 8192).tolist()
+    print(f"case batched ragged lens={lens}", flush=True)
+    nmax = max(lens)
+    inps = [make_layer(n, config=4, layer=0, seq=b) for b, n in enumerate(lens)]
+    q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
+    kb, vb = to_new_batch([i.k for i in inps], nmax), to_new_batch([i.v for i in inps], nmax)
+    ql = tkv.QuantLayer(bits=2, capacity=8192, batch=8)
+    ql.append(kb, vb, n_valid=lens)
+    out = ql.attn_decode(q, SM)
+    sl = tkv.SparseLayer(top_k=1024, capacity=8192, batch=8)
+    chs = [static_channels(i.k, 16) for i in inps]
+    sl.set_channels(np.stack(chs))
+    sl.append(kb, vb, n_valid=lens)
+    sl.estimate_topk(q)
+    out_s = sl.gather_attn(q, SM, gather_stream=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    for b, inp in enumerate(inps):
+        ref = check_quant_cache(ql, b, inp.k, inp.v)
+        assert attn_err(out[b], attention.quant_attention(inp.q, ref, SM)) <= TOL
+        idx, cnt = sparse.estimate_topk(inp.q, sparse.key_summary(inp.k, chs[b]), chs[b], lens[b],
+                                        top_k=1024, n_sink=4, n_window=64)
+        assert np.array_equal(sl.topk_idx[b].cpu().numpy(), idx)
+        want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, lens[b], SM, n_sink=4, n_window=64)
+        assert attn_err(out_s[b], want) <= TOL
+
+
+def test_limits_of_the_descriptor():
+    """Largest supported Top-K / window / residual."""
+    n = 9000
+    inp = make_layer(n, seq=21)
+    sl = tkv.SparseLayer(top_k=4096, n_sink=16, n_window=1024, capacity=n)
+    ch = static_channels(inp.k, 16)
+    sl.set_channels(ch[None])
+    sl.append(to_new(inp.k), to_new(inp.v))
+    q = torch.from_numpy(inp.q)[None].cuda()
+    sl.estimate_topk(q)
+    out = sl.gather_attn(q, SM)
+    idx, cnt = sparse.estimate_topk(inp.q, sparse.key_summary(inp.k, ch), ch, n, top_k=4096, n_sink=16, n_window=1024)
+    torch.cuda.synchronize()
+    assert np.array_equal(sl.topk_idx[0].cpu().numpy(), idx)
+    want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, n, SM, n_sink=16, n_window=1024)
+    assert attn_err(out[0], want) <= TOL
+    ql = tkv.QuantLayer(bits=4, residual=992, capacity=4096)
+    inp = make_layer(3000, seq=22)
+    ql.append(to_new(inp.k), to_new(inp.v))
+    ref = quant.quantize_kv(inp.k, inp.v, bits=4, group=32, residual=992)
+    check_quant_cache(ql, 0, inp.k, inp.v)
+    out = ql.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
