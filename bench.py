@@ -72,7 +72,12 @@ def main():
     for _ in range(3):
         e0.record(); dst.copy_(pin, non_blocking=True); e1.record(); e1.synchronize()
         h2d = max(h2d, (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    del pin, dst
+    # device-to-device copy of known size (1 GiB read + 1 GiB written): calibrates the
+    # FETCH_SIZE / WRITE_SIZE counters when this script runs under rocprofv3 --pmc
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del pin, dst, src
 
     # ---- build the caches
     layers = []
@@ -206,7 +211,9 @@ def main():
     summary_bytes = 8 * N * 32
     gather_bytes = 8 * args.top_k * 512
     roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None}
+            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "traffic": traffic_from_profile("quant_attn_mfma_kernel<%d>" % args.bits) if N == 131072 else None,
+            "algorithmic_bytes": quant_bytes}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {
         "quant_attn_us": dur["quant"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"],
@@ -232,6 +239,20 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, **extra,
     }
     print(json.dumps(line))
+
+
+def traffic_from_profile(kernel: str):
+    """HBM bytes per launch of `kernel` as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (summary committed under profiles/, already scaled by the copy-kernel calibration)."""
+    path = os.path.join(ROOT, "profiles", "bench_hybrid_step_128k_hbm_traffic.md")
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 5 and cells[1] == kernel:
+                return float(cells[3]) * 1e6 + float(cells[4]) * 1024.0
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def cpu_baseline(sample, N, args, sm):
