@@ -145,7 +145,7 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
                               void* stream);
 
 /* Test and tuning hook (process-wide, not thread-safe): kernel_choice 0 = matrix-core
- * kernel with the reference kernel on the fp16 tail (default), 1 = shape-generic
+ * kernel, which also covers the fp16 tail (default), 1 = shape-generic
  * reference kernel for everything; target_blocks > 0 sets the number of workgroups
  * the split-K launch aims at (0 keeps the current value). */
 int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks);

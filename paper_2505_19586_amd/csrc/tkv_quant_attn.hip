@@ -7,7 +7,8 @@ namespace tkv {
 // matrix-core path (tkv_quant_attn_mfma.hip); returns TKV_E_UNSUPPORTED when the
 // shape is not one it is built for.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
-                               float scale2, float* parts, uint32_t* arrivals, int n_chunks,
+                               float scale2, float* parts, uint32_t* arrivals, int target_blocks, int max_groups,
+                               int max_tail,
                                const TkvSeqLens& lens, hipStream_t s);
 }  // namespace tkv
 
@@ -287,7 +288,7 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   if (workspace_bytes < need) return TKV_E_WORKSPACE;
 
   QuantAttnParams p;
-  int max_groups = 0;
+  int max_groups = 0, max_tail = 0;
   for (int b = 0; b < d->batch; ++b) {
     const int32_t n = c->seq_len_host[b];
     if (n < 0) return TKV_E_INVAL;
@@ -295,6 +296,7 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
     p.lens.n[b] = n;
     const int g = tkv::n_quantized(n, d->residual) / TKV_G;
     if (g > max_groups) max_groups = g;
+    if (n - g * TKV_G > max_tail) max_tail = n - g * TKV_G;
   }
   // Chunking of the reference kernel: about 1024 workgroups over the whole launch.
   const int bh = d->batch * d->n_kv_heads;
@@ -327,19 +329,13 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
 
   hipStream_t s = (hipStream_t)stream;
   if (g_kernel_choice == 0) {
-    // matrix-core kernel: one launch covers the quantized groups and the fp16 tail.
-    // Chunks per (sequence, KV head): about one workgroup per compute unit in total,
-    // and at least eight 32-token groups (one per wave) per workgroup.
-    int c_target = (g_target_blocks + bh - 1) / bh;
-    const int c_work = (max_groups + 40 + 7) / 8;
-    if (c_target > c_work) c_target = c_work;
-    if (c_target > 64) c_target = 64;
-    if (c_target < 1) c_target = 1;
+    // matrix-core kernel: one launch covers the quantized groups and the fp16 tail
     // arrival counters sit behind the partials (zero before first use, left zero by every call)
     const size_t parts_bytes =
         (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
     uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_bytes + 255) & ~(size_t)255));
-    return tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, c_target, p.lens, s);
+    return tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, g_target_blocks, max_groups,
+                                       max_tail, p.lens, s);
   } else {
     p.chunk_offset = 0;
     quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);

@@ -9,23 +9,33 @@
 //     codes into two exact fp16 operands (no bias, no convert); the 2^bp factor is
 //     compensated in the other operand;
 //   * q.K-hat = sum_c code[t][c] * (q[c] s[c]) + sum_c q[c] z[c]: the scaler moves into
-//     the query operand (split into fp16 hi + lo parts so the product keeps ~22 bits),
-//     the zero-point term is a second tiny MFMA per group;
-//   * p.V-hat = sum_t code[t][d] * (p[t] s_v[t][u]) + sum_t p[t] z_v[t][u]: the 16
-//     operand columns are the 4 query heads x 4 channel groups u, so the weights never
-//     leave the lanes that produced them (the D layout of the first product is the B
-//     layout of the second); z_v and the softmax denominator ride on one more MFMA.
+//     the query operand, split into fp16 hi + lo parts so the product keeps ~22 bits.
+//     The 16 operand columns are 4 query heads x 4 column groups; even groups carry the hi
+//     part and odd groups the lo part, so ONE MFMA per (16 tokens, 32 channels) produces
+//     both partial sums and a single cross-lane add joins them.  The zero-point term does
+//     not depend on the token: it is computed once per workgroup for all of its groups
+//     (16 groups per MFMA) and kept in an LDS table;
+//   * p.V-hat = sum_t code[t][d] * (p[t] s_v[t][u]) + sum_t p[t] z_v[t][u]: here the 4
+//     column groups are the 4 channel groups u, so the weights never leave the lanes that
+//     produced them (the D layout of the first product is the B layout of the second);
+//     z_v and the softmax denominator ride on one more MFMA.  The weights go in as one
+//     fp16 number each (the product p s_v is rounded once).
 //
-// Softmax is online per wave with lazy rescaling; the four waves of a workgroup and the
-// chunks of a sequence are merged with log-sum-exp merges.
-#include <cstdlib>
-
+// The machine issues one vector or matrix instruction per SIMD at a time and a wave issues
+// in order, so the cost of a group is close to the plain sum of its instructions: the
+// design minimises instruction count first, then hides latencies with three resident
+// waves per SIMD (2 bit) and a three-deep ring of direct global->LDS loads per wave.
+//
+// Softmax is online per wave with lazy rescaling; the waves of a workgroup and the chunks
+// of a sequence are merged with log-sum-exp merges, the last workgroup of a (sequence, KV
+// head) to finish doing the cross-chunk merge.
 #include "tkv_common.h"
 
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
@@ -39,14 +49,15 @@ struct MfmaParams {
   const __half* k_resid;
   const __half* v_resid;
   const __half* q;
-  float* parts;  // [B][Hq][n_chunks][D + 2]
+  float* parts;        // [B][Hq][n_chunks][D + 2]
   uint32_t* arrivals;  // [B][Hkv], zero between calls
   __half* out;         // [B][Hq][D]
   float scale2;
   int32_t hq, hkv, residual, capacity;
   int32_t n_chunks;
-  int32_t dbg_mode;
-  long long* dbg_ts;
+#ifdef TKV_PHASE
+  long long* prof;  // phase timestamps (profiling builds only)
+#endif
   TkvSeqLens lens;
 };
 
@@ -58,17 +69,24 @@ __device__ inline floatx4 mfma(uintx4 a, uintx4 b, floatx4 c) {
 // __builtin_bit_cast directly to an element of an ext-vector (vec[j]) reads element 0
 // for every j with this compiler.
 __device__ inline half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+__device__ inline ushort2_t as_ushort2(uint32_t w) { return __builtin_bit_cast(ushort2_t, w); }
 
 __device__ inline uint32_t pack2(_Float16 lo, _Float16 hi) {
   half2_t v = {lo, hi};
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// v + (value of the lane 4 places away in the same row of 16 lanes)
+__device__ inline float ror4_add(float v) {
+  const int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124 /* row_ror:4 */, 0xF, 0xF, false);
+  return v + __builtin_bit_cast(float, r);
+}
+
 // fp16 hi/lo split of a product, written so that each part is one fused multiply-add
 // with an fp16 result (the compiler selects v_fma_mixlo/mixhi_f16 for this shape):
 //   hi = f16(a * b), lo = f16(a * b - hi)   (the FMA makes the residual exact)
 // s2 holds two fp16 scalers; the results are packed the same way.  No inline assembly:
-// the operands come straight from MFMA / transcendental results, whose read hazards
+// operands that come straight from MFMA / transcendental results have read hazards that
 // only the compiler's own instructions are checked for.
 __device__ inline uint32_t mix_hi_pair(float a0, float a1, uint32_t s2) {
   const half2_t s = as_half2(s2);
@@ -79,26 +97,18 @@ __device__ inline uint32_t mix_lo_pair(float a0, float a1, uint32_t s2, uint32_t
   return pack2((_Float16)__builtin_fmaf(a0, (float)s[0], -(float)h[0]),
                (_Float16)__builtin_fmaf(a1, (float)s[1], -(float)h[1]));
 }
-// residual of rounding two floats to the packed fp16 pair `hi`: f16(a - hi)
-__device__ inline uint32_t residual_pair(float a0, float a1, uint32_t hi) {
-  const half2_t h = as_half2(hi);
-  return pack2((_Float16)__builtin_fmaf(a0, 1.0f, -(float)h[0]), (_Float16)__builtin_fmaf(a1, 1.0f, -(float)h[1]));
-}
 
-// Two MFMA operands (8 registers) out of one 32-bit word of packed codes.
-template <int BITS>
-__device__ inline void extract(uint32_t w, uintx4& a0, uintx4& a1) {
-  if (BITS == 2) {
-    const uint32_t w8 = w >> 8;
-    a0[0] = w & 0x00030003u;
-    a0[1] = w & 0x000C000Cu;
-    a0[2] = w & 0x00300030u;
-    a0[3] = w & 0x00C000C0u;
-    a1[0] = w8 & 0x00030003u;
-    a1[1] = w8 & 0x000C000Cu;
-    a1[2] = w8 & 0x00300030u;
-    a1[3] = w8 & 0x00C000C0u;
-  }
+// 2 bit: two MFMA operands (8 registers) out of one 32-bit word of packed codes.
+__device__ inline void extract2(uint32_t w, uintx4& a0, uintx4& a1) {
+  const uint32_t w8 = w >> 8;
+  a0[0] = w & 0x00030003u;
+  a0[1] = w & 0x000C000Cu;
+  a0[2] = w & 0x00300030u;
+  a0[3] = w & 0x00C000C0u;
+  a1[0] = w8 & 0x00030003u;
+  a1[1] = w8 & 0x000C000Cu;
+  a1[2] = w8 & 0x00300030u;
+  a1[3] = w8 & 0x00C000C0u;
 }
 // 4 bit: one operand per word.
 __device__ inline void extract4(uint32_t w, uintx4& a) {
@@ -109,193 +119,171 @@ __device__ inline void extract4(uint32_t w, uintx4& a) {
   a[3] = w8 & 0x00F000F0u;
 }
 
-constexpr int kEK = 4;             // query-side operands carry 2^kEK
-constexpr int kEP = 6;             // weight-side operands carry 2^kEP
-constexpr float kHeadroom = 4.0f;  // lazy rescale: weights may reach 2^kHeadroom
-constexpr int kWaves = 8;          // waves per workgroup
-constexpr int kThreads = kWaves * 64;
-constexpr int kTailTok = kThreads / 4;  // fp16-tail tokens per pass (4 threads per token)
-constexpr int kTailEntry = kWaves;
-constexpr int kBkStride = 80;      // words per head row of the query-side operand in LDS  // slot of the fp16 tail in the workgroup merge
-
-// Everything one wave loads for one 32-token group (held in registers so that the
-// next group's loads are in flight while the current one is computed).
-template <int BITS>
-struct GroupRegs {
-  uint32_t kw[2 * BITS], vw[2 * BITS];  // packed codes: one (2 bit) or two (4 bit) 128-bit loads each
-  uint32_t ks2, kz2;                    // K scaler / zero-point of channels 2*lane, 2*lane+1
-  uintx4 sv, zv;                        // V scalers (column's u) and zero-points (row's u) of 8 tokens
-};
-
-template <int BITS>
-__device__ inline void load_group(GroupRegs<BITS>& g, const MfmaParams& p, size_t grp, int lane, int us, int rb,
-                                  int zrow_ld) {
-  constexpr int NWORDS = TKV_D * BITS;
-  const uint32_t* kc = p.k_codes + grp * NWORDS;
-  const uint32_t* vc = p.v_codes + grp * NWORDS;
-#pragma unroll
-  for (int x = 0; x < BITS / 2; ++x) {
-    const uintx4 t = *reinterpret_cast<const uintx4*>(kc + 256 * x + 4 * lane);
-    const uintx4 u = *reinterpret_cast<const uintx4*>(vc + 256 * x + 4 * lane);
-#pragma unroll
-    for (int y = 0; y < 4; ++y) {
-      g.kw[4 * x + y] = t[y];
-      g.vw[4 * x + y] = u[y];
-    }
-  }
-  g.ks2 = reinterpret_cast<const uint32_t*>(p.k_scale + grp * TKV_D)[lane];
-  g.kz2 = reinterpret_cast<const uint32_t*>(p.k_zero + grp * TKV_D)[lane];
-  g.sv = *reinterpret_cast<const uintx4*>(p.v_scale + (grp * 4 + us) * TKV_G + 8 * rb);
-  g.zv = *reinterpret_cast<const uintx4*>(p.v_zero + (grp * 4 + zrow_ld) * TKV_G + 8 * rb);
+__device__ inline void lds_load16(const void* g, void* l) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)l, 16, 0, 0);
+}
+__device__ inline void lds_load4(const void* g, void* l) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)l, 4, 0, 0);
 }
 
+constexpr int kEK = 4;            // query-side operands carry 2^kEK
+constexpr int kEP = 6;            // weight-side operands carry 2^kEP
+constexpr int kHeadroomLog2 = 4;  // lazy rescale: weights may reach 2^kHeadroomLog2
+constexpr int kBkStride = 80;     // words per head row of the query-side operand in LDS
+constexpr int kMaxGpc = 512;      // groups per chunk that the zero-point table holds
+constexpr int kTailWaves = 4;     // waves of the last chunk that share the fp16 tail
+
+struct TailEntry {
+  float m[4];
+  float l[4];
+  float o[4][TKV_D];
+};
+template <int W>
 struct MergeSmem {
-  float m[kWaves + 1][4];
-  float l[kWaves + 1][4];
-  float z[kWaves][4][4];
-  float o[kWaves + 1][4][TKV_D];
+  float m[W][4];
+  float l[W][4];
+  float z[W][4][4];
+  float o[W][4][TKV_D];
 };
 
-// fp16 tail (ring of unquantized tokens) of one KV head, computed by the whole workgroup
-// with plain float math; result goes to entry kTailEntry of the merge arrays.
-__device__ inline void tail_attention(const MfmaParams& p, MergeSmem& ms, float (*q_s)[TKV_D], float (*x_s)[kThreads],
-                                      float (*w_s)[4], size_t bh, int nq, int n, int G) {
-  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+// ---- LDS plan (dynamic shared memory) ---------------------------------------------------
+//   bk     per wave [hi/lo][4 heads][80 words]: query-side operands of the next group
+//   ring   per wave 3 K slots (codes, scalers) then 3 V slots (codes, scalers, zero-points);
+//          the direct global->LDS loads put lane l's bytes at slot + 16*l (codes) or
+//          slot + 4*l (fp16 rows), i.e. a slot is a copy of the group's packed block.  After
+//          the main loop the same bytes hold the per-wave results for the workgroup merge.
+//   cz     zero-point term of every group of the chunk, [group][4 heads] float
+//   tail   partial results of the waves that share the fp16 tail
+//   q      the 4 query rows as fp16, for the tail
+template <int BITS, int W>
+struct Cfg {
+  static constexpr int kThreads = 64 * W;
+  static constexpr int kCode = 512 * BITS;  // bytes of K (or V) codes of one group
+  static constexpr int kKPart = kCode + 256;
+  static constexpr int kVPart = kCode + 512;
+  static constexpr int kDepth = 3;
+  static constexpr int kWaveRing = kDepth * (kKPart + kVPart);
+  static constexpr int kKLoads = BITS / 2 + 1;  // direct-to-LDS load instructions per part
+  static constexpr int kVLoads = BITS / 2 + 2;
+  static constexpr int kBkWave = 2 * 4 * kBkStride * 4;
+  static constexpr int oRing = W * kBkWave;
+  static constexpr int oCz = oRing + W * kWaveRing;
+  static constexpr int oTail = oCz + kMaxGpc * 16;
+  static constexpr int oQ = oTail + kTailWaves * (int)sizeof(TailEntry);
+  static constexpr int kLdsBytes = oQ + 4 * TKV_D * 2;
+  static_assert(sizeof(MergeSmem<W>) <= (size_t)W * kWaveRing, "merge scratch must fit in the ring");
+  static_assert(kLdsBytes + 64 <= 160 * 1024, "LDS budget of one compute unit");
+};
+
+// fp16 tail (ring of unquantized tokens): wave w of the last chunk takes the 32-token
+// sub-blocks w, w + kTailWaves, ... with plain float math and an online softmax, and leaves
+// its partial result in `te`.  Lane = (token, channel half) for the logits, lane = channel
+// pair for the weighted sum.
+__device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint32_t* q_h, size_t bh, int nq, int n,
+                                 int wave, int lane) {
   const int ring = p.residual + TKV_G;
   const int r_total = n - nq;
-  bool first = true;
-  for (int sb0 = 0; sb0 < r_total; sb0 += kTailTok) {
-    const int cnt = min(kTailTok, r_total - sb0);
-    // phase 1: logits; 4 threads per token, each over 32 channels, combined by shuffles
-    const int tk = tid / 4, part = tid % 4;  // token in sub-block, channel quarter
-    float x[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    {
-      const int tok = nq + sb0 + min(tk, cnt - 1);
-      const uintx4* krow = reinterpret_cast<const uintx4*>(p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D) + 4 * part;
-      uintx4 kv[4];
+  const int t = lane / 2, half = lane % 2;
+  float M[4], Ls[4], acc[4][2];
 #pragma unroll
-      for (int c8 = 0; c8 < 4; ++c8) kv[c8] = krow[c8];
+  for (int hh = 0; hh < 4; ++hh) M[hh] = -INFINITY, Ls[hh] = 0.f, acc[hh][0] = 0.f, acc[hh][1] = 0.f;
+  for (int sb = wave; sb * 32 < r_total; sb += kTailWaves) {
+    const int cnt = min(32, r_total - 32 * sb);
+    const int t0 = nq + 32 * sb;
+    float x[4];
+    uint32_t v2[32];  // this lane's channel pair of every row: loaded up front, used last
+    {
+      const int tok = t0 + min(t, cnt - 1);
+      const uintx4* krow = reinterpret_cast<const uintx4*>(p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D + 64 * half);
+      uintx4 kv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) kv[i] = krow[i];
+#pragma unroll
+      for (int y = 0; y < 32; ++y) {
+        const int tokv = t0 + min(y, cnt - 1);  // rows past the end re-read the last one with weight 0
+        v2[y] = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tokv % ring)) * TKV_D)[lane];
+      }
       float a[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int c8 = 0; c8 < 4; ++c8) {
+      for (int i = 0; i < 8; ++i) {
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
-          const uint32_t w = kv[c8][y];
-          const half2_t k2 = as_half2(w);
-          const float k0 = (float)k2[0], k1 = (float)k2[1];
-          const int c = 32 * part + 8 * c8 + 2 * y;
+        for (int hh = 0; hh < 4; ++hh) {
+          const uintx4 q4 = *reinterpret_cast<const uintx4*>(q_h + hh * 64 + 32 * half + 4 * i);
 #pragma unroll
-          for (int hh = 0; hh < 4; ++hh) {
-            a[hh] = __builtin_fmaf(q_s[hh][c], k0, a[hh]);
-            a[hh] = __builtin_fmaf(q_s[hh][c + 1], k1, a[hh]);
+          for (int y = 0; y < 4; ++y) {
+            const uint32_t kw = kv[i][y], qw = q4[y];
+            a[hh] = __builtin_amdgcn_fdot2(as_half2(kw), as_half2(qw), a[hh], false);
           }
         }
       }
 #pragma unroll
       for (int hh = 0; hh < 4; ++hh) {
         a[hh] += __shfl_xor(a[hh], 1, 64);
-        a[hh] += __shfl_xor(a[hh], 2, 64);
-        if (tk < cnt) x[hh] = a[hh] * p.scale2;
+        x[hh] = t < cnt ? a[hh] * p.scale2 : -INFINITY;
       }
     }
-    // phase 2: workgroup max and weights
-    float wm[4];
+    float pw[4];
 #pragma unroll
     for (int hh = 0; hh < 4; ++hh) {
-      float v = x[hh];
-      for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-      wm[hh] = v;
+      float mx = x[hh];
+      for (int m = 32; m >= 2; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+      const float mn = fmaxf(M[hh], mx);  // finite: the sub-block holds at least one token
+      const float alpha = exp2f(M[hh] - mn);
+      pw[hh] = t < cnt ? exp2f(x[hh] - mn) : 0.f;
+      float sum = half == 0 ? pw[hh] : 0.f;
+      for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
+      Ls[hh] = Ls[hh] * alpha + sum;
+      acc[hh][0] *= alpha;
+      acc[hh][1] *= alpha;
+      M[hh] = mn;
     }
-    if (lane == 0)
-      for (int hh = 0; hh < 4; ++hh) w_s[wave][hh] = wm[hh];
-    __syncthreads();
-    float mx[4], pw[4];
 #pragma unroll
-    for (int hh = 0; hh < 4; ++hh) {
-      float v = w_s[0][hh];
-      for (int w = 1; w < kWaves; ++w) v = fmaxf(v, w_s[w][hh]);
-      mx[hh] = v;  // finite: the sub-block holds at least one token
-      pw[hh] = tk < cnt ? exp2f(x[hh] - v) : 0.f;
-      if (part == 0) x_s[hh][tk] = pw[hh];
-    }
-    __syncthreads();
-    // phase 3: weighted V sum; thread = (channel pair, token residue class)
-    float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
-    float ls[4] = {0.f, 0.f, 0.f, 0.f};
-    // every wave takes tokens wave, wave + 8, ...; all of its rows (<= 16) are loaded before
-    // the first is used (rows past the end re-read the last one with weight 0)
-    {
-      constexpr int RW = kTailTok / kWaves;  // 16
-      uint32_t v2[RW];
+    for (int y = 0; y < 32; ++y) {
+      const half2_t vv = as_half2(v2[y]);
+      const float v0 = (float)vv[0], v1 = (float)vv[1];
 #pragma unroll
-      for (int y = 0; y < RW; ++y) {
-        const int tok = nq + sb0 + min(wave + y * kWaves, cnt - 1);
-        v2[y] = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D)[lane];
-      }
-#pragma unroll
-      for (int y = 0; y < RW; ++y) {
-        const int t = wave + y * kWaves;
-        const half2_t vv = as_half2(v2[y]);
-        const float v0 = (float)vv[0], v1 = (float)vv[1];
-#pragma unroll
-        for (int hh = 0; hh < 4; ++hh) {
-          const float pp = t < cnt ? x_s[hh][t] : 0.f;
-          acc[hh][0] = __builtin_fmaf(pp, v0, acc[hh][0]);
-          acc[hh][1] = __builtin_fmaf(pp, v1, acc[hh][1]);
-          ls[hh] += pp;
-        }
+      for (int hh = 0; hh < 4; ++hh) {
+        const float pp = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pw[hh]), 2 * y));
+        acc[hh][0] = __builtin_fmaf(pp, v0, acc[hh][0]);
+        acc[hh][1] = __builtin_fmaf(pp, v1, acc[hh][1]);
       }
     }
-    // reduce over the 8 waves through the (still unused) per-wave merge slots
-#pragma unroll
-    for (int hh = 0; hh < 4; ++hh) {
-      ms.o[wave][hh][2 * lane] = acc[hh][0];
-      ms.o[wave][hh][2 * lane + 1] = acc[hh][1];
-      if (lane == 0) ms.l[wave][hh] = ls[hh];
-    }
-    __syncthreads();
-    {
-      const int hh = tid / TKV_D, c = tid % TKV_D;  // 512 threads = 4 heads x 128 channels
-      float O = 0.f, L = 0.f;
-      for (int w = 0; w < kWaves; ++w) {
-        O += ms.o[w][hh][c];
-        L += ms.l[w][hh];
-      }
-      if (first) {
-        ms.o[kTailEntry][hh][c] = O;
-        if (c == 0) {
-          ms.m[kTailEntry][hh] = mx[hh];
-          ms.l[kTailEntry][hh] = L;
-        }
-      } else {
-        const float mo = ms.m[kTailEntry][hh], mn = fmaxf(mo, mx[hh]);
-        const float a_old = exp2f(mo - mn), a_new = exp2f(mx[hh] - mn);
-        ms.o[kTailEntry][hh][c] = ms.o[kTailEntry][hh][c] * a_old + O * a_new;
-        __syncthreads();  // every channel has read the old max before it is replaced
-        if (c == 0) {
-          ms.l[kTailEntry][hh] = ms.l[kTailEntry][hh] * a_old + L * a_new;
-          ms.m[kTailEntry][hh] = mn;
-        }
-      }
-    }
-    first = false;
-    __syncthreads();
   }
-  (void)G;
+#pragma unroll
+  for (int hh = 0; hh < 4; ++hh) {
+    te.o[hh][2 * lane] = acc[hh][0];
+    te.o[hh][2 * lane + 1] = acc[hh][1];
+    if (lane == 0) te.m[hh] = M[hh], te.l[hh] = Ls[hh];
+  }
 }
 
-template <int BITS>
-__global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p) {
-  // per wave: query-side operand [hi/lo][4 heads][128 ch] fp16 + zero-points [128] fp16
-  // head rows are padded from 64 to 80 words: the 16 (head, k-block) operand reads of one
-  // ds_read_b128 then fall into 16 different 16-byte bank groups
-  __shared__ __attribute__((aligned(16))) uint32_t bk_s[kWaves][2][4][kBkStride];
-  __shared__ __attribute__((aligned(16))) uint32_t kz_s[kWaves][TKV_D / 2];
-  __shared__ MergeSmem ms;
-  __shared__ float q_s[4][TKV_D];
-  __shared__ float x_s[4][kThreads];
-  __shared__ float w_s[kWaves][4];
+#ifdef TKV_PHASE
+#define TKV_PH()                                \
+  do {                                          \
+    __builtin_amdgcn_sched_barrier(0);          \
+    ph[ph_n++] = wall_clock64();                \
+    __builtin_amdgcn_sched_barrier(0);          \
+  } while (0)
+#else
+#define TKV_PH() \
+  do {           \
+  } while (0)
+#endif
+
+template <int BITS, int W>
+__global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
+  using C = Cfg<BITS, W>;
+  constexpr int NWORDS = TKV_D * BITS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_next;
+  __shared__ uint32_t s_flag;
+#ifdef TKV_PHASE
+  long long ph[8];
+  int ph_n = 0;
+#endif
+  TKV_PH();  // 0 kernel start
 
   const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
   const int tid = threadIdx.x, lane = tid % 64;
@@ -306,48 +294,125 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   const int jq = nq / TKV_G;
   const size_t bh = (size_t)b * p.hkv + h;
   const size_t grp_base = bh * (size_t)(p.capacity / TKV_G);
-  // Work split of this sequence: the tail counts as (n - nq)/4 groups and belongs to
-  // the last chunk, so that chunk gets correspondingly fewer quantized groups.
+  // Work split of this sequence: a 32-token piece of the tail counts as two groups and the
+  // tail belongs to the last chunk, which gets correspondingly fewer quantized groups.
   const bool has_tail = chunk == p.n_chunks - 1;
-  const int tail_equiv = (n - nq + 7) / 8;
+  const int tail_equiv = 2 * ((n - nq + 31) / 32);
   const int gpc = max(1, (jq + tail_equiv + p.n_chunks - 1) / p.n_chunks);
   const int blk0 = min(chunk * gpc, jq);
   const int blk1 = has_tail ? jq : min(blk0 + gpc, jq);
+  const int last = max(blk1 - 1, blk0);  // groups past the chunk are clamped (and ignored); jq >= 1 here
 
-  long long ts[8];
-  ts[0] = wall_clock64();
   const int slot = lane % 16, rb = lane / 16;
-  const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, channel group
+  const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, column group
   const __half* qrow = p.q + ((size_t)b * p.hq + (size_t)h * G) * TKV_D;
+  typedef uint32_t BkArr[2][4][kBkStride];
+  uint32_t(*bk_s)[4][kBkStride] = reinterpret_cast<BkArr*>(smem)[wave];
+  float* cz_s = reinterpret_cast<float*>(smem + C::oCz);
+  TailEntry* tail_s = reinterpret_cast<TailEntry*>(smem + C::oTail);
+  uint32_t* q_h = reinterpret_cast<uint32_t*>(smem + C::oQ);
+  // Byte offsets (wave-uniform) of this wave's ring slots; the roles rotate every step.
+  const uint32_t ring_off = C::oRing + wave * C::kWaveRing;
+  const uint32_t lane16 = 16u * (uint32_t)lane, lane4 = 4u * (uint32_t)lane;  // unsigned: scalar base + 32-bit lane offset
 
-  if (tid == 0) s_next = blk0 + 2 * kWaves;
-  __syncthreads();
-  if (has_tail) {
-    for (int i = tid; i < 4 * TKV_D; i += kThreads) {
-      const int hh = i / TKV_D, c = i % TKV_D;
-      q_s[hh][c] = hh < G ? __half2float(qrow[(size_t)hh * TKV_D + c]) : 0.f;
-    }
-  }
+  // ---- loads: asynchronous global -> LDS copies of a group's K part / V part ------------
+  auto load_kpart = [&](uint32_t so, int g) {
+    const size_t grp = grp_base + min(g, last);
+    unsigned char* s = smem + so;
+    const unsigned char* kc = reinterpret_cast<const unsigned char*>(p.k_codes + grp * NWORDS);
+    uint32_t l16 = lane16, l4 = lane4;  // opaque copies: keeps "scalar base + lane offset" addressing
+    asm volatile("" : "+v"(l16), "+v"(l4));
+#pragma unroll
+    for (int x = 0; x < BITS / 2; ++x) lds_load16(kc + 1024 * x + l16, s + 1024 * x);
+    lds_load4(reinterpret_cast<const unsigned char*>(p.k_scale + grp * TKV_D) + l4, s + C::kCode);
+  };
+  auto load_vpart = [&](uint32_t so, int g) {
+    const size_t grp = grp_base + min(g, last);
+    unsigned char* s = smem + so;
+    const unsigned char* vc = reinterpret_cast<const unsigned char*>(p.v_codes + grp * NWORDS);
+    uint32_t l16 = lane16, l4 = lane4;
+    asm volatile("" : "+v"(l16), "+v"(l4));
+#pragma unroll
+    for (int x = 0; x < BITS / 2; ++x) lds_load16(vc + 1024 * x + l16, s + 1024 * x);
+    lds_load4(reinterpret_cast<const unsigned char*>(p.v_scale + grp * TKV_D) + l4, s + C::kCode);
+    lds_load4(reinterpret_cast<const unsigned char*>(p.v_zero + grp * TKV_D) + l4, s + C::kCode + 256);
+  };
 
-  // query as exact fp16 B operand (zero-point term) and as scaled float (scaler term)
-  uintx4 bq[4];
+  // The first three groups of a wave are fixed (wave, wave + W, wave + 2W), the rest come
+  // from the workgroup's counter: their loads can start before anything else is set up.
+  // ring roles: kq = K part the next QK reads, kk = K part whose scalers are prepared next,
+  // kl = K slot being loaded; vp = V part of the current group, vn = the one after, vl = V
+  // slot being loaded
+  uint32_t kl = ring_off, kq = ring_off + C::kKPart, kk = ring_off + 2 * C::kKPart;
+  uint32_t vp = ring_off + 3 * C::kKPart, vn = vp + C::kVPart, vl = vp + 2 * C::kVPart;
+  const int g0 = blk0 + wave;
+  int g1 = g0 + W, g2 = g0 + 2 * W;
+  const bool active = g0 < blk1;
+  // Set-up loads first (query rows, zero-points of this wave's first 16 groups), then the
+  // ring prologue: one memory round trip covers both.
+  const int ng = blk1 - blk0;
+  uint32_t q2[4];   // K-prep role: this lane owns channels 2*lane, 2*lane+1
+  uintx4 bq[4];     // exact fp16 query as MFMA B operand (zero-point term)
+  uintx4 az[4];     // zero-point rows of 16 groups as MFMA A operand
+#pragma unroll
+  for (int hh = 0; hh < 4; ++hh)  // heads >= G re-read head G-1 (in bounds) and are zeroed below
+    q2[hh] = reinterpret_cast<const uint32_t*>(qrow + (size_t)(hh < G ? hh : G - 1) * TKV_D)[lane];
 #pragma unroll
   for (int m = 0; m < 4; ++m)
     bq[m] = *reinterpret_cast<const uintx4*>(qrow + (size_t)(hs < G ? hs : G - 1) * TKV_D + 32 * m + 8 * rb);
+  auto load_az = [&](int t0) {
+    const size_t grp = grp_base + min(blk0 + t0 + slot, last);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) az[m] = *reinterpret_cast<const uintx4*>(p.k_zero + grp * TKV_D + 32 * m + 8 * rb);
+  };
+  if (16 * wave < ng) load_az(16 * wave);
+  __builtin_amdgcn_sched_barrier(0);
+  if (active) {
+    // issue order K0 V0 K1 K2 V1, then per step [K(i+3) V(i+2)]: the counter retires loads
+    // in order, so "at most N outstanding" names exactly which parts have landed
+    load_kpart(kl, g0);
+    load_vpart(vp, g0);
+    load_kpart(kq, g1);
+    load_kpart(kk, g2);
+    load_vpart(vn, g1);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  if (tid == 0) s_next = blk0 + 3 * W;
+  if (tid < kTailWaves * 4) {
+    tail_s[tid / 4].m[tid % 4] = -INFINITY;
+    tail_s[tid / 4].l[tid % 4] = 0.f;
+  }
+  if (tid < 4 * TKV_D / 2) {
+    const int hh = tid / (TKV_D / 2);
+    const uint32_t w = reinterpret_cast<const uint32_t*>(qrow + (size_t)(hh < G ? hh : G - 1) * TKV_D)[tid % (TKV_D / 2)];
+    q_h[tid] = hh < G ? w : 0u;
+  }
+
+  // ---- zero-point term of every group of the chunk: cz[g][head] = scale2 * sum_c q[c] z_g[c],
+  // 16 groups per MFMA (A rows = groups, B = the exact fp16 query)
   if (hs >= G) {
 #pragma unroll
     for (int m = 0; m < 4; ++m) bq[m] = uintx4{0u, 0u, 0u, 0u};
   }
-  // K-prep role: this lane owns channels 2*lane, 2*lane+1; their field position is lane%4
-  // (2 bit: 4^pos) or lane%2 (4 bit: 16^pos).
+  for (int t0 = 16 * wave; t0 < ng; t0 += 16 * W) {
+    if (t0 != 16 * wave) load_az(t0);
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < 4; ++m) acc = mfma(az[m], bq[m], acc);
+    if (us == 0) {
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int gl = t0 + 4 * rb + x;
+        if (gl < ng) cz_s[gl * 4 + hs] = acc[x] * p.scale2;
+      }
+    }
+  }
+  // query times the factor that undoes the field position of this lane's channels
+  // (2 bit: 4^(lane%4), 4 bit: 16^(lane%2))
   float qf[4][2];
   {
     const int pos = BITS == 2 ? lane % 4 : lane % 2;
     const float comp = BITS == 2 ? (float)(1 << kEK) / (float)(1 << (2 * pos)) : (float)(1 << kEK) / (float)(1 << (4 * pos));
-    uint32_t q2[4];
-#pragma unroll
-    for (int hh = 0; hh < 4; ++hh)  // heads >= G re-read head G-1 (in bounds) and are zeroed below
-      q2[hh] = reinterpret_cast<const uint32_t*>(qrow + (size_t)(hh < G ? hh : G - 1) * TKV_D)[lane];
 #pragma unroll
     for (int hh = 0; hh < 4; ++hh) {
       const half2_t qq = as_half2(q2[hh]);
@@ -355,6 +420,12 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
       qf[hh][1] = hh < G ? (float)qq[1] * comp : 0.f;
     }
   }
+  __syncthreads();  // cz table, tail slots, query copy and group counter are in place
+  TKV_PH();  // 1 set-up done
+
+  if (has_tail && wave < kTailWaves && wave * 32 < n - nq) tail_wave(p, tail_s[wave], q_h, bh, nq, n, wave, lane);
+  TKV_PH();  // 2 tail done
+
   // codes carry 2^-24, query side 2^kEK, so S = acc * 2^(24-kEK)
   const float K1 = p.scale2 * (float)(1 << (24 - kEK));
 
@@ -367,7 +438,7 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   // A operand of the z_v / denominator MFMA: rows 0..3 hold z_v[u = row] (loaded per group)
   // times the constant that undoes the weight-side scaling, row 4 holds that constant
   // alone (denominator), rows 5.. are zero.  Built branch-free as load * zmul + zadd.
-  const int zrow = slot;                   // as A operand this lane holds row `slot`
+  const int zrow = slot;                    // as A operand this lane holds row `slot`
   const int zrow_ld = zrow < 4 ? zrow : 3;  // rows >= 4 load a valid row and multiply it by 0
   half2_t zmul[4], zadd[4];
 #pragma unroll
@@ -387,165 +458,196 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
     off[i] = BITS == 2 ? (float)(kEP - 2 * j) : (float)(kEP - 4 * (j % 2));
   }
 
-  // One group's worth of work for this wave; `cur` was loaded two iterations earlier.
-  auto process = [&](const GroupRegs<BITS>& cur) {
-    // ---- query-side operand of this group: (q s) split into hi + lo, through LDS
-    {
-#pragma unroll
-      for (int hh = 0; hh < 4; ++hh) {
-        const uint32_t hi = mix_hi_pair(qf[hh][0], qf[hh][1], cur.ks2);  // products are exact in float32
-        bk_s[wave][0][hh][lane] = hi;
-        bk_s[wave][1][hh][lane] = mix_lo_pair(qf[hh][0], qf[hh][1], cur.ks2, hi);
-      }
-      kz_s[wave][lane] = cur.kz2;
+  // Next group index from the workgroup's LDS counter.  Written as inline assembly: the
+  // compiler orders every LDS atomic it knows of behind all outstanding direct-to-LDS
+  // loads (vmcnt(0)), which would drain the prefetch ring at every step.
+  const uint32_t next_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&s_next;
+  auto grab = [&]() -> int {
+    int v = 0;
+    if (lane == 0) {
+      const int one = 1;
+      asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(next_addr), "v"(one) : "memory");
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    return __builtin_amdgcn_readfirstlane(v);
+  };
 
-    // ---- zero-point term: cz[slot] = sum_c z[c] q[c], identical in every row
-    floatx4 acc_cz = {0.f, 0.f, 0.f, 0.f};
-    {
-      uintx4 az[4];
+  // ---- pipeline stages of one group ------------------------------------------------------
+  // K: scalers x query -> hi/lo operands in LDS
+  auto stage_k = [&](uint32_t so) {
+    const uint32_t ks2 = *reinterpret_cast<const uint32_t*>(smem + so + C::kCode + lane4);
 #pragma unroll
-      for (int m = 0; m < 4; ++m) az[m] = *reinterpret_cast<const uintx4*>(&kz_s[wave][(32 * m + 8 * rb) / 2]);
-#pragma unroll
-      for (int m = 0; m < 4; ++m) acc_cz = mfma(az[m], bq[m], acc_cz);
+    for (int hh = 0; hh < 4; ++hh) {
+      const uint32_t hi = mix_hi_pair(qf[hh][0], qf[hh][1], ks2);  // products are exact in float32
+      bk_s[0][hh][lane] = hi;
+      bk_s[1][hh][lane] = mix_lo_pair(qf[hh][0], qf[hh][1], ks2, hi);
     }
-    // ---- scaler term for the two 16-token tiles
-    floatx4 acc_s[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+  };
+  // QK: partial logits of the group's 32 tokens (two 16-token tiles); even column groups
+  // read the hi rows of the query-side operand, odd ones the lo rows
+  const uint32_t* bk_row = &bk_s[us & 1][hs][4 * rb];
+  auto stage_qk = [&](uint32_t so, floatx4 (&acc_s)[2]) {
+    const unsigned char* s = smem + so;
+    uint32_t kw[2 * BITS];
+#pragma unroll
+    for (int x = 0; x < BITS / 2; ++x) {
+      const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) kw[4 * x + y] = t[y];
+    }
+    acc_s[0] = floatx4{0.f, 0.f, 0.f, 0.f};
+    acc_s[1] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int m2 = 0; m2 < 2; ++m2) {  // pairs of MFMA steps m = 2*m2, 2*m2+1
-      uintx4 bh2[2], bl2[2];
+      uintx4 bk2[2];
 #pragma unroll
-      for (int y = 0; y < 2; ++y) {
-        const int m = 2 * m2 + y;
-        bh2[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][0][hs][(32 * m + 8 * rb) / 2]);
-        bl2[y] = *reinterpret_cast<const uintx4*>(&bk_s[wave][1][hs][(32 * m + 8 * rb) / 2]);
-      }
+      for (int y = 0; y < 2; ++y) bk2[y] = *reinterpret_cast<const uintx4*>(bk_row + 16 * (2 * m2 + y));
 #pragma unroll
       for (int tau = 0; tau < 2; ++tau) {
         uintx4 a[2];
         if (BITS == 2) {
-          extract<2>(cur.kw[2 * tau + m2], a[0], a[1]);
+          extract2(kw[2 * tau + m2], a[0], a[1]);
         } else {
-          extract4(cur.kw[4 * tau + 2 * m2], a[0]);
-          extract4(cur.kw[4 * tau + 2 * m2 + 1], a[1]);
+          extract4(kw[4 * tau + 2 * m2], a[0]);
+          extract4(kw[4 * tau + 2 * m2 + 1], a[1]);
         }
 #pragma unroll
-        for (int y = 0; y < 2; ++y) {
-          acc_s[tau] = mfma(a[y], bh2[y], acc_s[tau]);
-          acc_s[tau] = mfma(a[y], bl2[y], acc_s[tau]);
-        }
+        for (int y = 0; y < 2; ++y) acc_s[tau] = mfma(a[y], bk2[y], acc_s[tau]);
       }
     }
-
-    // ---- online softmax (log2 domain), lazy rescale
-    const float cz = acc_cz[0] * p.scale2;
-    const float mx = fmaxf(fmaxf(fmaxf(acc_s[0][0], acc_s[0][1]), fmaxf(acc_s[0][2], acc_s[0][3])),
-                           fmaxf(fmaxf(acc_s[1][0], acc_s[1][1]), fmaxf(acc_s[1][2], acc_s[1][3])));
-    const float xmax = __builtin_fmaf(mx, K1, cz);  // largest logit among this lane's 8 tokens
-    if (__builtin_amdgcn_ballot_w64(xmax - m_run > kHeadroom) != 0ull) {
-      // new reference maximum, uniform over the lanes that share a query head
-      float mn = fmaxf(m_run, xmax);
-      mn = fmaxf(mn, __shfl_xor(mn, 4, 64));
-      mn = fmaxf(mn, __shfl_xor(mn, 8, 64));
-      mn = fmaxf(mn, __shfl_xor(mn, 16, 64));
-      mn = fmaxf(mn, __shfl_xor(mn, 32, 64));
-      const float alpha = exp2f(m_run - mn);  // 0 on the first group
+  };
+  // weights and weight-side operands
+  struct POps {
+    uintx4 b2, bp, a_zv;
+  };
+  // The weights 2^(x - m_run) go to the matrix cores as fp16, so m_run (a per-head reference,
+  // not necessarily the running maximum) only has to keep them below 2^kHeadroomLog2: that
+  // is checked on the packed fp16 weights themselves, and only a failed check (rare after
+  // the first groups) pays for the exact maximum, the accumulator rescale and a second pass.
+  auto stage_soft = [&](uint32_t so, const floatx4 (&acc_s)[2], float cz, POps& o) {
+    const unsigned char* s = smem + so;
+    const uintx4 sv = *reinterpret_cast<const uintx4*>(s + C::kCode + (us * TKV_G + 8 * rb) * 2);
+    const uintx4 zv = *reinterpret_cast<const uintx4*>(s + C::kCode + 256 + (zrow_ld * TKV_G + 8 * rb) * 2);
+    float xs[8];  // hi + lo partial sums: every lane of a head ends up with the full logit
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc_o[i] *= alpha;
-      acc_z *= alpha;
-      m_run = mn;
+    for (int x = 0; x < 8; ++x) xs[x] = ror4_add(acc_s[x / 4][x % 4]);
+    auto weights = [&]() {
+      const float czm = cz - m_run;
+      float pw[8];
+#pragma unroll
+      for (int x = 0; x < 8; ++x) pw[x] = __builtin_amdgcn_exp2f(__builtin_fmaf(xs[x], K1, czm + off[x]));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o.bp[j] = pack2((_Float16)pw[2 * j], (_Float16)pw[2 * j + 1]);
+    };
+    weights();
+    {
+      // fp16 bit patterns of non-negative numbers (and of inf / NaN) order like integers
+      const ushort2_t m01 = __builtin_elementwise_max(as_ushort2(o.bp[0]), as_ushort2(o.bp[1]));
+      const ushort2_t m23 = __builtin_elementwise_max(as_ushort2(o.bp[2]), as_ushort2(o.bp[3]));
+      const uint32_t mm = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(m01, m23));
+      constexpr uint32_t kLimit = (uint32_t)(15 + kEP + kHeadroomLog2) << 26;  // fp16 2^(kEP + headroom), upper half
+      const bool over = mm >= kLimit || (mm << 16) >= kLimit;
+      if (__builtin_amdgcn_ballot_w64(over) != 0ull) {
+        const float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
+        float mn = fmaxf(m_run, __builtin_fmaf(mx, K1, cz));  // largest logit among this lane's 8 tokens
+        mn = fmaxf(mn, __shfl_xor(mn, 4, 64));
+        mn = fmaxf(mn, __shfl_xor(mn, 8, 64));
+        mn = fmaxf(mn, __shfl_xor(mn, 16, 64));
+        mn = fmaxf(mn, __shfl_xor(mn, 32, 64));
+        const float alpha = exp2f(m_run - mn);  // 0 on the first group
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc_o[i] *= alpha;
+        acc_z *= alpha;
+        m_run = mn;
+        weights();
+      }
     }
-    const float czm = cz - m_run;
-    float pw[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) pw[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[i / 4][i % 4], K1, czm + off[i]));
-
-    // ---- weight-side operands: p*s_v (hi, lo) and p (hi, lo)
-    uintx4 b2h, b2l, bph, bpl, a_zv;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t svj = cur.sv[j];
-      const float w0 = pw[2 * j], w1 = pw[2 * j + 1];
-      b2h[j] = mix_hi_pair(w0, w1, svj);
-      b2l[j] = mix_lo_pair(w0, w1, svj, b2h[j]);
-      bph[j] = pack2((_Float16)w0, (_Float16)w1);
-      bpl[j] = residual_pair(w0, w1, bph[j]);
-      const uint32_t zvj = cur.zv[j];
+      // weight x scaler: one rounding of the exact product of two fp16 numbers
+      const uint32_t bpj = o.bp[j], svj = sv[j], zvj = zv[j];
+      o.b2[j] = __builtin_bit_cast(uint32_t, as_half2(bpj) * as_half2(svj));
       const half2_t t = __builtin_elementwise_fma(as_half2(zvj), zmul[j], zadd[j]);
-      a_zv[j] = __builtin_bit_cast(uint32_t, t);
+      o.a_zv[j] = __builtin_bit_cast(uint32_t, t);
     }
-    acc_z = mfma(a_zv, bph, acc_z);
-    acc_z = mfma(a_zv, bpl, acc_z);
-
-    // ---- P.V: 8 blocks of 16 channels
+  };
+  // P.V: 8 blocks of 16 channels + the z_v / denominator MFMA
+  auto stage_pv = [&](uint32_t so, const POps& o) {
+    const unsigned char* s = smem + so;
+    uint32_t vw[2 * BITS];
+#pragma unroll
+    for (int x = 0; x < BITS / 2; ++x) {
+      const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) vw[4 * x + y] = t[y];
+    }
+    acc_z = mfma(o.a_zv, o.bp, acc_z);
 #pragma unroll
     for (int wd = 0; wd < 4; ++wd) {
       uintx4 a[2];
       if (BITS == 2) {
-        extract<2>(cur.vw[wd], a[0], a[1]);
+        extract2(vw[wd], a[0], a[1]);
       } else {
-        extract4(cur.vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
-        extract4(cur.vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
+        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
+        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
       }
 #pragma unroll
-      for (int y = 0; y < 2; ++y) {
-        acc_o[2 * wd + y] = mfma(a[y], b2h, acc_o[2 * wd + y]);
-        acc_o[2 * wd + y] = mfma(a[y], b2l, acc_o[2 * wd + y]);
-      }
+      for (int y = 0; y < 2; ++y) acc_o[2 * wd + y] = mfma(a[y], o.b2, acc_o[2 * wd + y]);
     }
-    __builtin_amdgcn_wave_barrier();
   };
+#define TKV_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory")
+  constexpr int L = C::kKLoads + C::kVLoads;  // load instructions issued per pipeline step
 
-  ts[1] = wall_clock64();
-  // Three-deep register ring: while one group is computed the wave's next two groups are in
-  // flight.  After a static first round the waves of a workgroup draw their groups from a
-  // shared LDS counter: the two waves that share a SIMD do not progress evenly, and with a
-  // static split the slower one ran alone (and poorly overlapped) for the last third.
-  {
-    GroupRegs<BITS> r0, r1, r2;
-    const int last = p.dbg_mode == 1 ? blk0 : blk1 - 1;  // loads past the chunk are clamped to its last group and ignored
-    auto grab = [&]() -> int {
-      int v = 0;
-      if (lane == 0) v = atomicAdd(&s_next, 1);
-      return __builtin_amdgcn_readfirstlane(v);
+  // ---- software pipeline over this wave's groups g[0], g[1], ...  Step i computes the
+  // logits of group i+1, the weights and P.V of group i and the query-side operand of
+  // group i+2, while the K part of group i+3 and the V part of group i+2 are in flight.
+  if (active) {
+    floatx4 acc_a[2], acc_b[2];
+    TKV_WAIT_VMCNT(2 * C::kKLoads + C::kVLoads);  // K0, V0 landed
+    stage_k(kl);
+    stage_qk(kl, acc_a);
+    TKV_WAIT_VMCNT(L);  // + K1
+    stage_k(kq);
+    // One step is one straight-line block; groups past the chunk are clamped copies whose
+    // results are dropped by leaving the loop.  gc = group i (valid), gn3 / gv2 = groups
+    // whose K / V part is fetched now.
+    auto step = [&](int gc, int gn3, int gv2, floatx4 (&acc_c)[2], floatx4 (&acc_n)[2]) {
+      load_kpart(kl, gn3);
+      load_vpart(vl, gv2);
+      const float cz = cz_s[(gc - blk0) * 4 + hs];
+      POps po;
+      TKV_WAIT_VMCNT(2 * L);  // K(i+1), V(i) landed
+      stage_qk(kq, acc_n);
+      stage_soft(vp, acc_c, cz, po);
+      stage_pv(vp, po);
+      TKV_WAIT_VMCNT(L + C::kVLoads);  // + K(i+2)
+      stage_k(kk);
+      uint32_t t = kq;
+      kq = kk, kk = kl, kl = t;
+      t = vp;
+      vp = vn, vn = vl, vl = t;
     };
-    int i0 = blk0 + wave, i1 = blk0 + kWaves + wave, i2;
-    if (i0 < blk1) {
-      load_group<BITS>(r0, p, grp_base + min(i0, last), lane, us, rb, zrow_ld);
-      load_group<BITS>(r1, p, grp_base + min(i1, last), lane, us, rb, zrow_ld);
-      for (;;) {
-        i2 = grab();
-        load_group<BITS>(r2, p, grp_base + min(i2, last), lane, us, rb, zrow_ld);
-        process(r0);
-        if (i1 >= blk1) break;
-        i0 = grab();
-        load_group<BITS>(r0, p, grp_base + min(i0, last), lane, us, rb, zrow_ld);
-        process(r1);
-        if (i2 >= blk1) break;
-        i1 = grab();
-        load_group<BITS>(r1, p, grp_base + min(i1, last), lane, us, rb, zrow_ld);
-        process(r2);
-        if (i0 >= blk1) break;
-      }
+    int gc = g0;
+    for (;;) {
+      const int g3 = grab();
+      step(gc, g3, g2, acc_a, acc_b);
+      if (g1 >= blk1) break;
+      const int g4 = grab();
+      step(g1, g4, g3, acc_b, acc_a);
+      if (g2 >= blk1) break;
+      gc = g2;  // rotate: group i+2 becomes the current one
+      g1 = g3;
+      g2 = g4;
     }
   }
-  ts[2] = wall_clock64();
+#undef TKV_WAIT_VMCNT
+  TKV_PH();  // 3 this wave's groups done
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct-to-LDS load may land after the ring is reused
   __syncthreads();
-  ts[3] = wall_clock64();
-  if (has_tail && n > nq) {
-    tail_attention(p, ms, q_s, x_s, w_s, bh, nq, n, G);
-  } else if (tid < 4) {
-    ms.m[kTailEntry][tid] = -INFINITY;
-    ms.l[kTailEntry][tid] = 0.f;
-  }
-  __syncthreads();
+  TKV_PH();  // 4 all waves done
 
-  ts[4] = wall_clock64();
   // ---- per-wave results -> LDS.  acc_z rows: lanes 0..15 (rb 0) hold rows 0..3 = z-terms
   // for u = row; lanes 16..31 register 0 hold row 4 = denominator.
+  MergeSmem<W>& ms = *reinterpret_cast<MergeSmem<W>*>(smem + C::oRing);
   if (rb == 0) {
 #pragma unroll
     for (int x = 0; x < 4; ++x)
@@ -566,24 +668,32 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
     }
   }
   __syncthreads();
-  for (int i = tid; i < G * TKV_D; i += kThreads) {
+  for (int i = tid; i < G * TKV_D; i += C::kThreads) {
     const int hh = i / TKV_D, c = i % TKV_D;
     float M = -INFINITY;
-    for (int w = 0; w <= kWaves; ++w) M = fmaxf(M, ms.m[w][hh]);
-    float L = 0.f, O = 0.f;
-    for (int w = 0; w <= kWaves; ++w) {
+    for (int w = 0; w < W; ++w) M = fmaxf(M, ms.m[w][hh]);
+    for (int w = 0; w < kTailWaves; ++w) M = fmaxf(M, tail_s[w].m[hh]);
+    float Lsum = 0.f, O = 0.f;
+    for (int w = 0; w < W; ++w) {
       const float mw = ms.m[w][hh];
       if (mw == -INFINITY) continue;
       const float wgt = exp2f(mw - M);
-      L += ms.l[w][hh] * wgt;
+      Lsum += ms.l[w][hh] * wgt;
       O += ms.o[w][hh][c] * wgt;
+    }
+    for (int w = 0; w < kTailWaves; ++w) {
+      const float mw = tail_s[w].m[hh];
+      if (mw == -INFINITY) continue;
+      const float wgt = exp2f(mw - M);
+      Lsum += tail_s[w].l[hh] * wgt;
+      O += tail_s[w].o[hh][c] * wgt;
     }
     float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
     // device-scope stores: visible to the merging workgroup without a cache write-back
     __hip_atomic_store(dst + 2 + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
       __hip_atomic_store(dst, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(dst + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(dst + 1, Lsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 
@@ -591,17 +701,18 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
   // Partials travel through device-scope (cache-bypassing) stores and loads, ordered by
   // waiting for the stores to complete before the arrival counter is bumped: a release /
   // acquire fence pair would write back and invalidate the whole L2 (tens of microseconds).
-  ts[5] = wall_clock64();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  ts[6] = wall_clock64();
-  if (p.dbg_ts && lane == 0) {
-    long long* d = p.dbg_ts + ((((size_t)b * p.hkv + h) * p.n_chunks + chunk) * kWaves + wave) * 8;
-    for (int i = 0; i < 7; ++i) d[i] = ts[i];
+  TKV_PH();  // 5 partial written
+#ifdef TKV_PHASE
+  if (p.prof && lane == 0) {
+    long long* dst = p.prof + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * W + wave) * 8;
+    for (int i = 0; i < 6; ++i) dst[i] = ph[i];
   }
-  if (tid == 0) w_s[0][0] = __uint_as_float(atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(p.n_chunks - 1) ? 1u : 0u);
+#endif
   __syncthreads();
-  if (__float_as_uint(w_s[0][0]) == 0u) return;
+  if (tid == 0) s_flag = atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(p.n_chunks - 1) ? 1u : 0u;
+  __syncthreads();
+  if (s_flag == 0u) return;
   if (tid == 0) p.arrivals[bh] = 0u;
   if (tid < G * TKV_D) {
     const int hh = tid / TKV_D, c = tid % TKV_D;
@@ -611,29 +722,55 @@ __global__ __launch_bounds__(kThreads) void quant_attn_mfma_kernel(MfmaParams p)
     auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
 #pragma unroll 8
     for (int k = 0; k < p.n_chunks; ++k) M = fmaxf(M, ld(base + (size_t)k * TKV_PART_STRIDE));
-    float L = 0.f, O = 0.f;
+    float Lsum = 0.f, O = 0.f;
 #pragma unroll 8
     for (int k = 0; k < p.n_chunks; ++k) {
       const float* pk = base + (size_t)k * TKV_PART_STRIDE;
       const float mk = ld(pk);
       const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
-      L = __builtin_fmaf(ld(pk + 1), w, L);
+      Lsum = __builtin_fmaf(ld(pk + 1), w, Lsum);
       O = __builtin_fmaf(ld(pk + 2 + c), w, O);
     }
-    p.out[head * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
+    p.out[head * TKV_D + c] = __float2half_rn(Lsum > 0.f ? O / Lsum : 0.f);
   }
+}
+
+template <int BITS, int W>
+int32_t launch_variant(const MfmaParams& p, dim3 grid, hipStream_t s) {
+  using C = Cfg<BITS, W>;
+  // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
+  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_attn_mfma_kernel<BITS, W>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes) == hipSuccess;
+  if (!lds_ok) return TKV_E_HIP;
+  quant_attn_mfma_kernel<BITS, W><<<grid, C::kThreads, C::kLdsBytes, s>>>(p);
+  return tkv::launch_status();
 }
 
 }  // namespace
 
 namespace tkv {
-void* g_mfma_dbg = nullptr;
+#ifdef TKV_PHASE
+void* g_mfma_prof = nullptr;
+#endif
 
+// Chunks per (sequence, KV head): about `target_blocks` workgroups in total (one per
+// compute unit), at least one 32-token group per wave, and no more groups per chunk than
+// the zero-point table of a workgroup holds.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
-                               float scale2, float* parts, uint32_t* arrivals, int n_chunks,
-                               const TkvSeqLens& lens, hipStream_t s) {
+                               float scale2, float* parts, uint32_t* arrivals, int target_blocks, int max_groups,
+                               int max_tail, const TkvSeqLens& lens, hipStream_t s) {
   if (d->head_dim != TKV_D || d->group_size != TKV_G) return TKV_E_UNSUPPORTED;
   if (d->n_q_heads / d->n_kv_heads > 4) return TKV_E_UNSUPPORTED;
+  const int waves = d->bits == 2 ? 12 : 8;
+  const int bh = d->batch * d->n_kv_heads;
+  const int work = max_groups + 2 * ((max_tail + 31) / 32);  // in groups, as the kernel counts it
+  int n_chunks = (target_blocks + bh - 1) / bh;
+  const int c_work = (work + waves - 1) / waves;
+  if (n_chunks > c_work) n_chunks = c_work;
+  if (n_chunks > 64) n_chunks = 64;
+  if (n_chunks < 1) n_chunks = 1;
+  if ((work + n_chunks - 1) / n_chunks > kMaxGpc) n_chunks = (work + kMaxGpc - 1) / kMaxGpc;
+  if (n_chunks > TKV_MAX_CHUNKS) return TKV_E_UNSUPPORTED;
   MfmaParams p;
   p.k_codes = (const uint32_t*)c->k_codes;
   p.v_codes = (const uint32_t*)c->v_codes;
@@ -653,19 +790,19 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.residual = d->residual;
   p.capacity = d->capacity;
   p.n_chunks = n_chunks;
-  p.dbg_ts = (long long*)g_mfma_dbg;
-  p.dbg_mode = getenv("TKV_DEBUG_MODE") ? atoi(getenv("TKV_DEBUG_MODE")) : 0;
+#ifdef TKV_PHASE
+  p.prof = (long long*)g_mfma_prof;
+#endif
   p.lens = lens;
   const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
-  if (d->bits == 2)
-    quant_attn_mfma_kernel<2><<<grid, kThreads, 0, s>>>(p);
-  else if (d->bits == 4)
-    quant_attn_mfma_kernel<4><<<grid, kThreads, 0, s>>>(p);
-  else
-    return TKV_E_UNSUPPORTED;
-  return launch_status();
+  if (d->bits == 2) return launch_variant<2, 12>(p, grid, s);
+  if (d->bits == 4) return launch_variant<4, 8>(p, grid, s);
+  return TKV_E_UNSUPPORTED;
 }
 
 }  // namespace tkv
 
-extern "C" void tkv_debug_set_dump(void* ptr) { tkv::g_mfma_dbg = ptr; }
+#ifdef TKV_PHASE
+// profiling builds: device buffer that receives [workgroup][wave][8] wall-clock stamps
+extern "C" void tkv_debug_set_dump(void* ptr) { tkv::g_mfma_prof = ptr; }
+#endif
