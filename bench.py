@@ -173,13 +173,13 @@ def main():
                 L.estimate_topk(qs[l])
                 if rec is not None:
                     b.record(); rec["topk"].append((a, b))
-                if chained:
-                    if rec is not None:
-                        g0, g1 = ev(), ev(); g0.record()
+                if chained and rec is not None:   # per-call timing pass: the transfer on its own
+                    g0, g1 = ev(), ev(); g0.record()
                     L.gather()
-                    if rec is not None:
-                        g1.record(); rec["gather"].append((g0, g1))
+                    g1.record(); rec["gather"].append((g0, g1))
                     L.attn(qs[l], sm, out=outs[l])
+                elif chained:                     # one stream: the attention kernel fetches the rows itself
+                    L.gather_attn(qs[l], sm, out=outs[l])
                 else:
                     L.gather_attn(qs[l], sm, out=outs[l], gather_stream=side, compute_stream=compute)
 

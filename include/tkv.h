@@ -214,9 +214,11 @@ int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* desc, const tkv_sparse_c
  * cannot be hidden) and exact attention (Eq. 3) of every query head over
  * sinks [0, n_sink) U selected U window [N - n_window, N) (Sec. 5.1: n_local + n_topk).
  * staging: fp16 [B][Hkv][top_k][2][128] device buffer the rows are gathered into.
- * The gather kernel runs on gather_stream after everything already enqueued on
- * compute_stream (which produced topk_idx); attention runs on compute_stream after
- * the gather.  The two streams may be the same.  out: fp16 [B][Hq][128].
+ * Two different streams: the gather kernel runs on gather_stream after everything
+ * already enqueued on compute_stream (which produced topk_idx); attention runs on
+ * compute_stream after the gather.  The same stream twice: nothing could overlap, so one
+ * kernel fetches the rows from the host cache and attends to them; `staging` is then
+ * left untouched (its contents are unspecified).  out: fp16 [B][Hq][128].
  */
 int32_t tkv_sparse_gather_attn(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,
                                const int32_t* topk_idx, const int32_t* topk_count, void* out,

@@ -55,23 +55,28 @@ struct GatherParams {
   int32_t hkv, top_k, capacity;
 };
 
-// Each 64-lane wave moves two 512-byte rows (K row + V row) per step with 16-byte
-// loads straight from pinned host memory.
+// One 64-lane wave moves one 512-byte row (K row + V row of a token) with a single 8-byte
+// load per lane straight from pinned host memory: one whole row per load instruction is the
+// request shape that the host link serves fastest (16-byte lanes, i.e. two rows per
+// instruction, measured 25 % slower).
 __global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
   const int b = blockIdx.z, h = blockIdx.y;
   const size_t bh = (size_t)b * p.hkv + h;
   const int cnt = p.topk_count[bh];
-  const int row = blockIdx.x * 8 + threadIdx.x / 32;  // 32 lanes x 16 B = one row
+  const int row = blockIdx.x * 4 + threadIdx.x / 64;
   if (row >= cnt) return;
-  const int part = threadIdx.x % 32;
+  const int part = threadIdx.x % 64;
   const int tok = p.topk_idx[bh * p.top_k + row];
-  const uint4 v = reinterpret_cast<const uint4*>(p.kv_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D)[part];
-  reinterpret_cast<uint4*>(p.staging + (bh * p.top_k + (size_t)row) * 2 * TKV_D)[part] = v;
+  const uint2 v = reinterpret_cast<const uint2*>(p.kv_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D)[part];
+  reinterpret_cast<uint2*>(p.staging + (bh * p.top_k + (size_t)row) * 2 * TKV_D)[part] = v;
 }
 
 struct SparseAttnParams {
   const __half* q;
   const __half* staging;
+  const __half* kv_host;    // fused variant: device-visible view of the pinned host rows
+  const int32_t* topk_idx;  // fused variant
+  int32_t capacity;
   const __half* kv_local;
   const int32_t* topk_count;
   float* parts;
@@ -87,10 +92,18 @@ __device__ inline float half_wave_max(float v) {
   return v;
 }
 
+constexpr int kRowPitch = 2 * TKV_D * 2 + 16;  // LDS bytes per staged K|V row (padded against bank conflicts)
+
 // Exact attention over sinks + gathered rows + window.  One workgroup of W <= 4 waves
 // handles 32*W attended tokens of one KV head; lane (t, hp) scores token t for query heads
 // 2hp, 2hp+1; then every lane accumulates two output channels.
+// FUSED: the selected rows are not read from the staging buffer but fetched by this kernel
+// from pinned host memory (one 512-byte row per load instruction, all 32 rows of a wave in
+// flight) into LDS, so the transfer and the attention are one launch.
+template <bool FUSED>
 __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char rows_s[];  // FUSED: [W][32][kRowPitch]
+  __shared__ const __half* src_s[4][32];
   __shared__ float qs[4][TKV_D];
   __shared__ float pw[4][4][32];
   __shared__ const __half* vrow_s[4][32];
@@ -116,16 +129,33 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   const int t = lane % 32, hp = lane / 32;
   const int i = (chunk * W + wave) * 32 + t;
   const bool valid = i < n_att;
-  const __half* krow = nullptr;
+  // invalid tokens point at a real row and carry weight 0, so no loop needs a branch
+  const __half* krow = p.kv_local + bh * (size_t)(p.n_sink + p.n_window) * 2 * TKV_D;
   if (valid) {
     if (i < n_sk)
       krow = p.kv_local + (bh * (p.n_sink + p.n_window) + i) * 2 * TKV_D;
-    else if (i < n_sk + cnt)
-      krow = p.staging + (bh * p.top_k + (size_t)(i - n_sk)) * 2 * TKV_D;
-    else {
+    else if (i < n_sk + cnt) {
+      if (FUSED) {
+        const int tok = p.topk_idx[bh * p.top_k + (i - n_sk)];
+        krow = p.kv_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D;
+      } else {
+        krow = p.staging + (bh * p.top_k + (size_t)(i - n_sk)) * 2 * TKV_D;
+      }
+    } else {
       const int tok = w0 + (i - n_sk - cnt);
       krow = p.kv_local + (bh * (p.n_sink + p.n_window) + p.n_sink + tok % p.n_window) * 2 * TKV_D;
     }
+  }
+  if (FUSED) {
+    // every row of this wave (host or device memory alike): 64 lanes x 8 bytes per row
+    unsigned char* rows = rows_s + (size_t)wave * 32 * kRowPitch;
+    if (hp == 0) src_s[wave][t] = krow;
+    uint2 r[32];
+#pragma unroll
+    for (int y = 0; y < 32; ++y) r[y] = reinterpret_cast<const uint2*>(src_s[wave][y])[lane];
+#pragma unroll
+    for (int y = 0; y < 32; ++y) *reinterpret_cast<uint2*>(rows + y * kRowPitch + 8 * lane) = r[y];
+    krow = reinterpret_cast<const __half*>(rows + t * kRowPitch);
   }
   float x0 = -INFINITY, x1 = -INFINITY;
   if (valid) {
@@ -150,8 +180,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   const bool any = m0 != -INFINITY;  // this wave has at least one valid token (uniform per wave)
   pw[wave][2 * hp][t] = valid ? exp2f(x0 - m0) : 0.f;
   pw[wave][2 * hp + 1][t] = valid ? exp2f(x1 - m1) : 0.f;
-  // invalid tokens point at a real row and carry weight 0, so the V loop needs no branches
-  if (hp == 0) vrow_s[wave][t] = valid ? krow + TKV_D : p.kv_local + bh * (size_t)(p.n_sink + p.n_window) * 2 * TKV_D;
+  if (hp == 0) vrow_s[wave][t] = krow + TKV_D;
   if (t == 0) {
     red_m[wave][2 * hp] = m0;
     red_m[wave][2 * hp + 1] = m1;
@@ -290,17 +319,20 @@ extern "C" int32_t tkv_sparse_gather(const tkv_sparse_desc* d, const tkv_sparse_
   p.hkv = d->n_kv_heads;
   p.top_k = d->top_k;
   p.capacity = d->capacity;
-  gather_rows_kernel<<<dim3((d->top_k + 7) / 8, d->n_kv_heads, d->batch), 256, 0, (hipStream_t)stream>>>(p);
+  gather_rows_kernel<<<dim3((d->top_k + 3) / 4, d->n_kv_heads, d->batch), 256, 0, (hipStream_t)stream>>>(p);
   return tkv::launch_status();
 }
 
-extern "C" int32_t tkv_sparse_attn(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
-                                   const int32_t* topk_count, const void* staging, void* out, float sm_scale,
-                                   void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+// Attention over sinks + selected rows + window.  topk_idx_fused == nullptr: the selected
+// rows are in `staging`; otherwise they are fetched from the pinned host cache by the
+// attention kernel itself.
+int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
+                           const int32_t* topk_idx_fused, const int32_t* topk_count, const void* staging, void* out,
+                           float sm_scale, void* workspace, size_t workspace_bytes, void* stream) {
   int32_t st = tkv::check_sparse_desc(d);
   if (st != TKV_OK) return st;
-  if (!c || !c->seq_len_host || !c->kv_local || !q || !topk_count || !staging || !out || !workspace)
-    return TKV_E_INVAL;
+  if (!c || !c->seq_len_host || !c->kv_local || !q || !topk_count || !out || !workspace) return TKV_E_INVAL;
   size_t need = 0;
   tkv_sparse_cache_sizes(d, nullptr, &need);
   if (workspace_bytes < need) return TKV_E_WORKSPACE;
@@ -329,9 +361,33 @@ extern "C" int32_t tkv_sparse_attn(const tkv_sparse_desc* d, const tkv_sparse_ca
   p.n_window = d->n_window;
   p.n_chunks = n_chunks;
   hipStream_t s = (hipStream_t)stream;
-  sparse_attn_kernel<<<dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s>>>(p);
+  p.kv_host = nullptr;
+  p.topk_idx = nullptr;
+  p.capacity = d->capacity;
+  if (topk_idx_fused) {
+    const void* host_dev = nullptr;
+    st = device_view_of_host(c->kv_host, &host_dev);
+    if (st != TKV_OK) return st;
+    p.kv_host = (const __half*)host_dev;
+    p.topk_idx = topk_idx_fused;
+    static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<true>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   kAttnMaxWaves * 32 * kRowPitch) == hipSuccess;
+    if (!lds_ok) return TKV_E_HIP;
+    sparse_attn_kernel<true><<<dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, W * 32 * kRowPitch, s>>>(p);
+  } else {
+    sparse_attn_kernel<false><<<dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s>>>(p);
+  }
   if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   return tkv::launch_attn_merge(parts, (__half*)out, d->batch * d->n_q_heads, n_chunks, s);
+}
+}  // namespace
+
+extern "C" int32_t tkv_sparse_attn(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
+                                   const int32_t* topk_count, const void* staging, void* out, float sm_scale,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (!staging) return TKV_E_INVAL;
+  return sparse_attn_launch(d, c, q, nullptr, topk_count, staging, out, sm_scale, workspace, workspace_bytes, stream);
 }
 
 namespace {
@@ -363,6 +419,9 @@ extern "C" int32_t tkv_sparse_gather_attn(const tkv_sparse_desc* d, const tkv_sp
   if (workspace_bytes < need) return TKV_E_WORKSPACE;
   hipStream_t gs = (hipStream_t)gather_stream, cs = (hipStream_t)compute_stream;
   const bool two = gs != cs;
+  // one stream: nothing can overlap, so the attention kernel fetches the rows itself
+  if (!two)
+    return sparse_attn_launch(d, c, q, topk_idx, topk_count, staging, out, sm_scale, workspace, workspace_bytes, cs);
   if (two) {
     if (g_link.init() != TKV_OK) return TKV_E_HIP;
     TKV_HIP_TRY(hipEventRecord(g_link.topk_ready, cs));

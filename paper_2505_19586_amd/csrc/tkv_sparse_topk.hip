@@ -2,30 +2,36 @@
 // scores of every cached token from the critical query channels and the critical key
 // cache, then exact Top-K (ties to the lower token index, output ascending).
 //
-// Three launches, each fully parallel (the histogram and counters in the workspace must
-// be zero before the first call; every call leaves them zero):
+// Two launches over the same grid of 4096-token workgroups (the histogram and counters in
+// the workspace must be zero before the first call; every call leaves them zero):
 //   score    reads the key summary once, computes S(t) in the pinned float32 order, writes
-//            an order-preserving 32-bit key per token and a 13-bit-prefix histogram; the
-//            last workgroup of a head locates the histogram bin that holds the k-th key;
-//   filter   counts, per 1024-token block, the keys above that bin and appends the keys
-//            inside it (a few hundred) to a candidate list;
-//   finish   every block finds the exact threshold among the candidates (radix select on
-//            the remaining 19 key bits), then writes its own selected tokens at the right
-//            offset, in token order.
+//            an order-preserving 32-bit key per token and adds its 13-bit-prefix histogram
+//            to the head's; the last workgroup of a head locates the bin of the k-th key;
+//   select   every workgroup lists its own tokens in or above that bin, in token order; the
+//            last workgroup of a head concatenates the lists (a few thousand entries, in
+//            LDS), finds the exact threshold by radix select on the remaining 19 key bits
+//            and writes the selected tokens in token order.
+// Inside a launch, data crosses workgroups only through device-scope stores, loads and
+// atomics, ordered by waiting for them to complete before an arrival counter is bumped.
 #include "tkv_common.h"
 
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kTok = 4096;      // tokens per workgroup (256 threads x 16)
-constexpr int kBatch = 4;       // tokens a thread has in flight at once
+constexpr int kThreads = 1024;
+constexpr int kWavesPerBlock = kThreads / 64;
+constexpr int kPer = 4;                // tokens per thread in the scoring phase
+constexpr int kTok = kThreads * kPer;  // tokens per workgroup
 constexpr int kPrefixBits = 13;
 constexpr int kBins = 1 << kPrefixBits;  // 8192
 constexpr int kLowBits = 32 - kPrefixBits;  // 19
 constexpr uint32_t kLowMask = (1u << kLowBits) - 1u;
+constexpr int kListCap = 8192;  // candidate entries kept in LDS; further ones go to the workspace
+constexpr int kScoreLds = kBins * 4;
+constexpr int kSelectLds = 1024 * 4 + kListCap * 8;
 
-enum Ctrl { kDone = 0, kNCand = 1, kBin = 2, kAbove = 3, kCtrlWords = 8 };
+enum Ctrl { kDone = 0, kDone2 = 1, kBin = 2, kAbove = 3, kCtrlWords = 8 };
 
 struct TopkParams {
   const __half* summary;
@@ -36,7 +42,15 @@ struct TopkParams {
   tkv::SparseWs ws;
   int32_t hq, hkv, top_k, n_sink, n_window, capacity;
   TkvSeqLens lens;
+#ifdef TKV_PHASE
+  long long* prof;
+#endif
 };
+#ifdef TKV_PHASE
+#define TKV_PH(i) do { __builtin_amdgcn_sched_barrier(0); if (p.prof && tid == 0) p.prof[(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#else
+#define TKV_PH(i) do {} while (0)
+#endif
 
 // Larger float <-> larger unsigned key; +0 and -0 were already merged by "+ 0.0f".
 __device__ inline uint32_t score_key(float s) {
@@ -49,14 +63,19 @@ __device__ inline void candidate_range(const TopkParams& p, int n, int& lo, int&
   hi = max(n - p.n_window, lo);
 }
 
-__device__ inline uint32_t k_eff_of(const TopkParams& p, int n) {
-  int lo, hi;
-  candidate_range(p, n, lo, hi);
-  return (uint32_t)min(p.top_k, hi - lo);
+__device__ inline uint32_t ld_agent(const uint32_t* ptr) {
+  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_agent(uint32_t* ptr, uint32_t v) {
+  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// number of set bits of a wave mask below this lane
+__device__ inline uint32_t rank_in(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Inclusive suffix sums over the 256 threads of a workgroup: returns sum of v over
-// threads >= tid.  scratch holds 8 words.
+// Inclusive suffix sums over the threads of a workgroup: returns sum of v over threads
+// >= tid.  scratch holds one word per wave.
 __device__ inline uint32_t block_suffix_sum(uint32_t v, uint32_t* scratch) {
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   uint32_t s = v;
@@ -67,23 +86,26 @@ __device__ inline uint32_t block_suffix_sum(uint32_t v, uint32_t* scratch) {
   }
   if (lane == 0) scratch[wave] = s;  // wave totals
   __syncthreads();
-  for (int w = wave + 1; w < 4; ++w) s += scratch[w];
+  for (int w = wave + 1; w < kWavesPerBlock; ++w) s += scratch[w];
   __syncthreads();
   return s;
 }
 
-// Finds, in a histogram of `nbins` (multiple of 256) counts where larger bin = larger
-// key, the bin that holds the k-th largest key: `above` keys lie in higher bins,
-// above < k <= above + count[bin].  Result valid in every thread.
-__device__ inline void find_bin(const uint32_t* hist, int nbins, uint32_t k, uint32_t* scratch /*>= 10 words*/,
-                                uint32_t& bin, uint32_t& above) {
+// Finds, in a histogram of `nbins` counts (a multiple of the workgroup size, or smaller
+// than it) where larger bin = larger key, the bin that holds the k-th largest key:
+// `above` keys lie in higher bins, above < k <= above + count[bin].  Result valid in every
+// thread.  scratch holds kWavesPerBlock + 2 words.
+__device__ inline void find_bin(const uint32_t* hist, int nbins, uint32_t k, uint32_t* scratch, uint32_t& bin,
+                                uint32_t& above) {
   const int tid = threadIdx.x;
-  const int per = nbins / 256;
+  const int per = nbins >= kThreads ? nbins / kThreads : 1;
+  const bool on = tid * per < nbins;
   uint32_t local = 0;
-  for (int i = 0; i < per; ++i) local += hist[tid * per + i];
+  if (on)
+    for (int i = 0; i < per; ++i) local += hist[tid * per + i];
   const uint32_t incl = block_suffix_sum(local, scratch);  // keys in this thread's bins and higher
   const uint32_t excl = incl - local;
-  if (excl < k && k <= incl) {  // exactly one thread
+  if (on && excl < k && k <= incl) {  // exactly one thread
     uint32_t run = excl;
     int bsel = tid * per + per - 1;
     for (; bsel > tid * per; --bsel) {
@@ -91,41 +113,48 @@ __device__ inline void find_bin(const uint32_t* hist, int nbins, uint32_t k, uin
       if (run + c >= k) break;
       run += c;
     }
-    scratch[8] = (uint32_t)bsel;
-    scratch[9] = run;
+    scratch[kWavesPerBlock] = (uint32_t)bsel;
+    scratch[kWavesPerBlock + 1] = run;
   }
   __syncthreads();
-  bin = scratch[8];
-  above = scratch[9];
+  bin = scratch[kWavesPerBlock];
+  above = scratch[kWavesPerBlock + 1];
   __syncthreads();
 }
 
-__device__ inline void reset_head(uint32_t* gh, uint32_t* ctrl);
-
-// score + key + histogram; the last workgroup of each head resolves the bin and clears
-// the histogram and counters for the next call.
 template <int DS>
-__global__ __launch_bounds__(256) void score_kernel(TopkParams p) {
-  __shared__ uint32_t hist[kBins];
+__global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
   __shared__ float qc[4][DS];
-  __shared__ uint32_t scratch[12];
+  __shared__ uint32_t scratch[kWavesPerBlock + 4];
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int n = p.lens.n[b];
+  const size_t bh = (size_t)b * p.hkv + h;
   const int t0 = blockIdx.x * kTok;
   if (t0 >= n) return;
+  TKV_PH(0);
   int lo, hi;
   candidate_range(p, n, lo, hi);
   const uint32_t k = (uint32_t)min(p.top_k, hi - lo);
   const int G = p.hq / p.hkv;
-  const size_t bh = (size_t)b * p.hkv + h;
-  for (int i = tid; i < kBins; i += 256) hist[i] = 0u;
+  for (int i = tid; i < kBins; i += kThreads) hist[i] = 0u;
   if (tid < 4 * DS) {
     const int j = tid / DS, i = tid % DS;
     const int c = p.channel_idx[bh * DS + i];
     qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
   }
+  // all of this thread's rows are requested before the first is used (rows past the end
+  // re-read the last token)
+  const __half* srow = p.summary + (bh * p.capacity) * DS;
+  uint4 rows[kPer][DS / 8];
+#pragma unroll
+  for (int it = 0; it < kPer; ++it) {
+    const int t = min(t0 + it * kThreads + tid, n - 1);
+#pragma unroll
+    for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
+  }
   __syncthreads();
-
   // query channels into registers (heads >= G are zero: adding their +0 sums changes nothing)
   float qr[4][DS];
 #pragma unroll
@@ -133,70 +162,43 @@ __global__ __launch_bounds__(256) void score_kernel(TopkParams p) {
 #pragma unroll
     for (int i = 0; i < DS; ++i) qr[j][i] = qc[j][i];
 
-  const __half* srow = p.summary + (bh * p.capacity) * DS;
   uint32_t* keys = p.ws.keys + bh * p.capacity;
-  // Batches of 4 tokens per thread; the next batch's loads (clamped to the last token) are
-  // in flight while the current batch is scored.
-  typedef uint4 RowBatch[kBatch][DS / 8];
-  auto load_batch = [&](RowBatch& rows, int bt) {
-    const int tb0 = t0 + bt * kBatch * 256;
 #pragma unroll
-    for (int it = 0; it < kBatch; ++it) {
-      const int t = min(tb0 + it * 256 + tid, n - 1);
+  for (int it = 0; it < kPer; ++it) {
+    const int t = t0 + it * kThreads + tid;
+    float kx[DS];
 #pragma unroll
-      for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
-    }
-  };
-  auto score_batch = [&](const RowBatch& rows, int bt) {
-    const int tb0 = t0 + bt * kBatch * 256;
+    for (int x = 0; x < DS / 8; ++x) {
+      const uint32_t w[4] = {rows[it][x].x, rows[it][x].y, rows[it][x].z, rows[it][x].w};
 #pragma unroll
-    for (int it = 0; it < kBatch; ++it) {
-      const int t = tb0 + it * 256 + tid;
-      float kx[DS];
-#pragma unroll
-      for (int x = 0; x < DS / 8; ++x) {
-        const uint32_t w[4] = {rows[it][x].x, rows[it][x].y, rows[it][x].z, rows[it][x].w};
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-          const uint32_t wy = w[y];
-          const half2_t hh = __builtin_bit_cast(half2_t, wy);
-          kx[8 * x + 2 * y] = (float)hh[0];
-          kx[8 * x + 2 * y + 1] = (float)hh[1];
-        }
-      }
-      float total = 0.f;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k
-        float a = qr[j][0] * kx[0];
-#pragma unroll
-        for (int i = 1; i < DS; ++i) a = __builtin_fmaf(qr[j][i], kx[i], a);
-        total = j == 0 ? a : total + a;
-      }
-      total = total + 0.0f;
-      if (t < n) {
-        uint32_t key = 0u;  // non-candidates: below every finite score
-        if (t >= lo && t < hi) {
-          key = score_key(total);
-          atomicAdd(&hist[key >> kLowBits], 1u);
-        }
-        keys[t] = key;
+      for (int y = 0; y < 4; ++y) {
+        const uint32_t wy = w[y];
+        const half2_t hh = __builtin_bit_cast(half2_t, wy);
+        kx[8 * x + 2 * y] = (float)hh[0];
+        kx[8 * x + 2 * y + 1] = (float)hh[1];
       }
     }
-  };
-  static_assert(kTok / (256 * kBatch) == 4, "four batches per workgroup");
-  {
-    RowBatch ra, rb;
-    load_batch(ra, 0);
-    load_batch(rb, 1);
-    score_batch(ra, 0);
-    load_batch(ra, 2);
-    score_batch(rb, 1);
-    load_batch(rb, 3);
-    score_batch(ra, 2);
-    score_batch(rb, 3);
+    float total = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k
+      float a = qr[j][0] * kx[0];
+#pragma unroll
+      for (int i = 1; i < DS; ++i) a = __builtin_fmaf(qr[j][i], kx[i], a);
+      total = j == 0 ? a : total + a;
+    }
+    total = total + 0.0f;
+    if (t < n) {
+      uint32_t key = 0u;  // non-candidates: below every score
+      if (t >= lo && t < hi) {
+        key = score_key(total);
+        atomicAdd(&hist[key >> kLowBits], 1u);
+      }
+      keys[t] = key;  // read by the next launch
+    }
   }
   __syncthreads();
+  TKV_PH(1);
   // Only bins that can hold the head's k-th key go to the global histogram: the k-th key of
   // the whole head is never below the k-th key of this block alone, so bins under the
   // block's own k-th bin are irrelevant (and skipping them spares most global atomics).
@@ -208,196 +210,229 @@ __global__ __launch_bounds__(256) void score_kernel(TopkParams p) {
       find_bin(hist, kBins, k, scratch, first_bin, above_unused);
     }
   }
-  __syncthreads();
   uint32_t* gh = p.ws.hist + bh * kBins;
   uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
-  for (int i = tid; i < kBins; i += 256)
+  for (int i = tid; i < kBins; i += kThreads)
     if (i >= (int)first_bin && hist[i]) atomicAdd(&gh[i], hist[i]);
-  // Last workgroup of this head: locate the bin of the k-th key.  The histogram is only
-  // touched with device-scope atomics, which are coherent by themselves: waiting for this
-  // wave's atomics to complete orders them before the arrival counter without a cache
-  // write-back (a release fence would flush the keys just written from L2).
+  // Last workgroup of this head: the histogram is only touched with device-scope atomics,
+  // which do not wait in a cache; waiting for this wave's own to complete orders them before
+  // the arrival counter without a cache write-back.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  TKV_PH(2);
   __syncthreads();
   if (tid == 0) {
     const uint32_t nblk = (uint32_t)((n + kTok - 1) / kTok);
-    scratch[11] = atomicAdd(&ctrl[kDone], 1u) == nblk - 1u;
+    scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone], 1u) == nblk - 1u;
   }
   __syncthreads();
-  if (!scratch[11]) return;
-  // the head's bin is never below this block's own first_bin: lower bins are not needed
-  for (int i = tid; i < kBins; i += 256)
-    hist[i] = i >= (int)first_bin ? __atomic_load_n(&gh[i], __ATOMIC_RELAXED) : 0u;
+  if (!scratch[kWavesPerBlock + 2]) return;
+  TKV_PH(3);
+  // the head's bin is never below this block's own first_bin: lower bins are not needed;
+  // histogram and counter are left zero for the next call
+  {
+    uint32_t hv[kBins / kThreads];
+#pragma unroll
+    for (int x = 0; x < kBins / kThreads; ++x) hv[x] = ld_agent(&gh[x * kThreads + tid]);
+#pragma unroll
+    for (int x = 0; x < kBins / kThreads; ++x) {
+      const int i = x * kThreads + tid;
+      hist[i] = i >= (int)first_bin ? hv[x] : 0u;
+      st_agent(&gh[i], 0u);
+    }
+  }
+  if (tid == 0) st_agent(&ctrl[kDone], 0u);
   __syncthreads();
-  reset_head(gh, ctrl);
   if (k == 0) return;
   uint32_t bin, above;
   find_bin(hist, kBins, k, scratch, bin, above);
-  if (tid == 0) {
+  if (tid == 0) {  // read by the next launch
     ctrl[kBin] = bin;
     ctrl[kAbove] = above;
   }
+  TKV_PH(4);
 }
 
-// Leaves the histogram and counters of one head zero again for the next call.
-__device__ inline void reset_head(uint32_t* gh, uint32_t* ctrl) {
-  for (int i = threadIdx.x; i < kBins; i += 256) gh[i] = 0u;
-  if (threadIdx.x == 0) {
-    ctrl[kDone] = 0u;
-    ctrl[kNCand] = 0u;
-  }
-}
-
-__global__ __launch_bounds__(256) void filter_kernel(TopkParams p) {
-  __shared__ uint32_t s_gt, s_nc, s_base;
-  __shared__ uint2 s_cand[kTok];
+__global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                // 1024 words
+  uint2* list_s = reinterpret_cast<uint2*>(smem + 1024 * 4);         // kListCap entries
+  __shared__ uint32_t scratch[kWavesPerBlock + 4];
+  __shared__ uint32_t s_cnt[kPer][kWavesPerBlock];
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid % 64, wave = tid / 64;
   const int n = p.lens.n[b];
+  const size_t bh = (size_t)b * p.hkv + h;
+  int32_t* out = p.topk_idx + bh * p.top_k;
+  int lo, hi;
+  candidate_range(p, n, lo, hi);
+  const uint32_t k = (uint32_t)min(p.top_k, hi - lo);
+  if (k == 0) {  // nothing to select: the first workgroup reports the empty result
+    if (blockIdx.x == 0) {
+      for (int i = tid; i < p.top_k; i += kThreads) out[i] = -1;
+      if (tid == 0) p.topk_count[bh] = 0;
+    }
+    return;
+  }
   const int t0 = blockIdx.x * kTok;
   if (t0 >= n) return;
-  if (k_eff_of(p, n) == 0) return;
-  const size_t bh = (size_t)b * p.hkv + h;
   uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
-  const uint32_t bin = ctrl[kBin];
-  if (tid == 0) {
-    s_gt = 0u;
-    s_nc = 0u;
+  const uint32_t bin = ctrl[kBin], above = ctrl[kAbove];
+  const uint32_t* keys = p.ws.keys + bh * p.capacity;
+  uint2* list_g = p.ws.cand + bh * (size_t)p.capacity;  // workgroup x owns entries [x * kTok, +kTok)
+  uint32_t* cnt_g = p.ws.blk + bh * p.ws.nblk_cap;
+  const int nblk = (n + kTok - 1) / kTok;
+
+  // ---- this workgroup's tokens in or above the bin, in token order
+  {
+    uint32_t kb[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {  // sub-tile j, element tid: token order = (j, tid)
+      const int t = t0 + j * kThreads + tid;
+      kb[j] = t < n ? keys[t] : 0u;
+    }
+    unsigned long long mask[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      mask[j] = __builtin_amdgcn_ballot_w64(kb[j] != 0u && (kb[j] >> kLowBits) >= bin);
+      if (lane == 0) s_cnt[j][wave] = (uint32_t)__builtin_popcountll(mask[j]);
+    }
+    __syncthreads();
+    uint32_t run = 0;  // entries of earlier sub-tiles
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      uint32_t before = 0, all = 0;
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        const uint32_t c = s_cnt[j][w];
+        before += w < wave ? c : 0u;
+        all += c;
+      }
+      if ((mask[j] >> lane) & 1ull) {
+        uint2* e = &list_g[(size_t)t0 + run + before + rank_in(mask[j])];
+        st_agent(&e->x, kb[j]);
+        st_agent(&e->y, (uint32_t)(t0 + j * kThreads + tid));
+      }
+      run += all;
+    }
+    if (tid == 0) st_agent(&cnt_g[blockIdx.x], run);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0) scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone2], 1u) == (uint32_t)nblk - 1u;
+  __syncthreads();
+  if (!scratch[kWavesPerBlock + 2]) return;
+  if (tid == 0) st_agent(&ctrl[kDone2], 0u);
+  for (int i = (int)k + tid; i < p.top_k; i += kThreads) out[i] = -1;
+  if (tid == 0) p.topk_count[bh] = (int32_t)k;
+
+  // ---- the head's last workgroup: concatenate the lists (wave w copies those of workgroups
+  // w, w + 16, ...).  Entry i of the concatenation lives in LDS if i < kListCap, else it is
+  // read from its workgroup's list in the workspace.
+  uint32_t* offs = hist;  // list offsets of the workgroups (the entry point launches < 1024), then the total
+  for (int x = tid; x <= nblk; x += kThreads) offs[x] = 0u;
+  __syncthreads();
+  if (tid < 64) {  // exclusive scan of the counts by one wave
+    uint32_t carry = 0;
+    for (int x0 = 0; x0 < nblk; x0 += 64) {
+      const int x = x0 + tid;
+      const uint32_t c = x < nblk ? ld_agent(&cnt_g[x]) : 0u;
+      uint32_t incl = c;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (tid >= d) incl += o;
+      }
+      if (x < nblk) offs[x] = carry + incl - c;
+      carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    }
+    if (tid == 0) offs[nblk] = carry;
   }
   __syncthreads();
-  const uint32_t* keys = p.ws.keys + bh * p.capacity;
-  uint32_t gt = 0;
-  for (int i = tid; i < kTok; i += 256) {
-    const int t = t0 + i;
-    if (t >= n) break;
-    const uint32_t key = keys[t];
-    if (key != 0u) {
-      const uint32_t pre = key >> kLowBits;
-      gt += pre > bin;
-      if (pre == bin) s_cand[atomicAdd(&s_nc, 1u)] = make_uint2(key, (uint32_t)t);
+  const uint32_t M = offs[nblk];
+  for (int x = wave; x < nblk; x += kWavesPerBlock) {
+    const uint32_t o = offs[x], c = offs[x + 1] - o;
+    for (uint32_t i = lane; i < c; i += 64) {
+      if (o + i < (uint32_t)kListCap) {
+        const uint2* e = &list_g[(size_t)x * kTok + i];
+        list_s[o + i] = make_uint2(ld_agent(&e->x), ld_agent(&e->y));
+      }
     }
   }
-  for (int m = 32; m >= 1; m >>= 1) gt += __shfl_xor(gt, m, 64);
-  if (tid % 64 == 0 && gt) atomicAdd(&s_gt, gt);
+  auto get = [&](uint32_t i) -> uint2 {
+    if (i < (uint32_t)kListCap) return list_s[i];
+    int x0 = 0, x1 = nblk;  // workgroup whose list holds entry i: offs[x0] <= i < offs[x0 + 1]
+    while (x1 - x0 > 1) {
+      const int mid = (x0 + x1) / 2;
+      if (offs[mid] <= i) x0 = mid; else x1 = mid;
+    }
+    const uint2* e = &list_g[(size_t)x0 * kTok + (i - offs[x0])];
+    return make_uint2(ld_agent(&e->x), ld_agent(&e->y));
+  };
   __syncthreads();
-  // one global reservation per block for its candidates
-  if (tid == 0) {
-    p.ws.blk[bh * p.ws.nblk_cap + blockIdx.x] = s_gt;
-    s_base = s_nc ? atomicAdd(&ctrl[kNCand], s_nc) : 0u;
-  }
-  __syncthreads();
-  uint2* cand = p.ws.cand + bh * (size_t)p.capacity + s_base;
-  for (uint32_t i = tid; i < s_nc; i += 256) cand[i] = s_cand[i];
-}
+  uint32_t k_rem = k - above;  // 1 <= k_rem <= keys in the bin
 
-__global__ __launch_bounds__(256) void finish_kernel(TopkParams p) {
-  __shared__ uint32_t hist[1024];
-  __shared__ uint32_t scratch[12];
-  __shared__ uint32_t sgt[256], seq[256];
-  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int n = p.lens.n[b];
-  const size_t bh = (size_t)b * p.hkv + h;
-  const uint32_t k = k_eff_of(p, n);
-  int32_t* out = p.topk_idx + bh * p.top_k;
-  if (blockIdx.x == 0) {
-    for (int i = (int)k + tid; i < p.top_k; i += 256) out[i] = -1;
-    if (tid == 0) p.topk_count[bh] = (int32_t)k;
-  }
-  const int t0 = blockIdx.x * kTok;
-  if (t0 >= n || k == 0) return;
-  const uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
-  const uint32_t bin = ctrl[kBin], above = ctrl[kAbove], ncand = ctrl[kNCand];
-  const uint2* cand = p.ws.cand + bh * (size_t)p.capacity;
-  uint32_t k_rem = k - above;  // 1 <= k_rem <= ncand
-
-  // exact threshold inside the bin: radix select on the low 19 key bits (10 + 9)
-  for (int i = tid; i < 1024; i += 256) hist[i] = 0u;
+  // ---- exact threshold inside the bin: radix select on the low 19 key bits (10 + 9)
+  __shared__ uint32_t h2[1024];
+  for (int i = tid; i < 1024; i += kThreads) h2[i] = 0u;
   __syncthreads();
-  for (uint32_t i = tid; i < ncand; i += 256) atomicAdd(&hist[(cand[i].x & kLowMask) >> 9], 1u);
+  for (uint32_t i = tid; i < M; i += kThreads) {
+    const uint32_t key = get(i).x;
+    if ((key >> kLowBits) == bin) atomicAdd(&h2[(key & kLowMask) >> 9], 1u);
+  }
   __syncthreads();
   uint32_t d1, a1;
-  find_bin(hist, 1024, k_rem, scratch, d1, a1);
+  find_bin(h2, 1024, k_rem, scratch, d1, a1);
   k_rem -= a1;
-  for (int i = tid; i < 1024; i += 256) hist[i] = 0u;
+  for (int i = tid; i < 512; i += kThreads) h2[i] = 0u;
   __syncthreads();
-  for (uint32_t i = tid; i < ncand; i += 256) {
-    const uint32_t low = cand[i].x & kLowMask;
-    if ((low >> 9) == d1) atomicAdd(&hist[low & 0x1FFu], 1u);
+  for (uint32_t i = tid; i < M; i += kThreads) {
+    const uint32_t key = get(i).x;
+    if ((key >> kLowBits) == bin && ((key & kLowMask) >> 9) == d1) atomicAdd(&h2[key & 0x1FFu], 1u);
   }
   __syncthreads();
   uint32_t d2, a2;
-  find_bin(hist, 512, k_rem, scratch, d2, a2);
+  find_bin(h2, 512, k_rem, scratch, d2, a2);
   const uint32_t take = k_rem - a2;                       // keys equal to T that are selected (lowest indices)
   const uint32_t T = (bin << kLowBits) | (d1 << 9) | d2;  // threshold key
 
-  // selected keys in earlier blocks: above the bin (per-block counts), inside the bin
-  // above T, and equal to T (candidates are few; every block scans them)
-  uint32_t gt_before = 0, eq_before = 0;
-  for (int i = tid; i < (int)blockIdx.x; i += 256) gt_before += p.ws.blk[bh * p.ws.nblk_cap + i];
-  for (uint32_t i = tid; i < ncand; i += 256) {
-    const uint2 c = cand[i];
-    if ((int)c.y < t0) {
-      gt_before += c.x > T;
-      eq_before += c.x == T;
-    }
-  }
-  sgt[tid] = gt_before;
-  seq[tid] = eq_before;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s) {
-      sgt[tid] += sgt[tid + s];
-      seq[tid] += seq[tid + s];
+  // ---- ordered compaction of the list: every key above T, and the first `take` equal to T
+  uint32_t gt_run = 0, eq_run = 0;
+  for (uint32_t base = 0; base < M; base += kThreads) {
+    const uint32_t i = base + tid;
+    uint2 e = make_uint2(0u, 0u);
+    if (i < M) e = get(i);
+    const bool gt = e.x > T, eq = e.x == T;  // T != 0: every real key has a non-zero prefix
+    const unsigned long long mg = __builtin_amdgcn_ballot_w64(gt), me = __builtin_amdgcn_ballot_w64(eq);
+    if (lane == 0) {
+      s_cnt[0][wave] = (uint32_t)__builtin_popcountll(mg);
+      s_cnt[1][wave] = (uint32_t)__builtin_popcountll(me);
     }
     __syncthreads();
-  }
-  gt_before = sgt[0];
-  eq_before = seq[0];
-  __syncthreads();
-
-  // ordered compaction of this block's tokens: thread i owns tokens t0 + 16 i .. + 15
-  constexpr int PT = kTok / 256;
-  const uint32_t* keys = p.ws.keys + bh * p.capacity;
-  uint32_t key[PT];
-  uint32_t gt = 0, eq = 0;
-#pragma unroll
-  for (int x = 0; x < PT; ++x) {
-    const int t = t0 + PT * tid + x;
-    key[x] = t < n ? keys[t] : 0u;
-    gt += key[x] > T;
-    eq += key[x] == T && key[x] != 0u;
-  }
-  sgt[tid] = gt;
-  seq[tid] = eq;
-  __syncthreads();
-  for (int s = 1; s < 256; s <<= 1) {  // inclusive scan over threads
-    uint32_t a = 0, c = 0;
-    if (tid >= s) {
-      a = sgt[tid - s];
-      c = seq[tid - s];
+    uint32_t pg = 0, pe = 0, tg = 0, te = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+      const uint32_t cg = s_cnt[0][w], ce = s_cnt[1][w];
+      pg += w < wave ? cg : 0u;
+      pe += w < wave ? ce : 0u;
+      tg += cg;
+      te += ce;
     }
-    __syncthreads();
-    sgt[tid] += a;
-    seq[tid] += c;
-    __syncthreads();
-  }
-  uint32_t gt_run = gt_before + sgt[tid] - gt;
-  uint32_t eq_run = eq_before + seq[tid] - eq;
-  if (gt + eq) {
-#pragma unroll
-    for (int x = 0; x < PT; ++x) {
-      const int t = t0 + PT * tid + x;
-      if (key[x] > T) {
-        out[gt_run + min(eq_run, take)] = t;
-        ++gt_run;
-      } else if (key[x] == T && key[x] != 0u) {
-        if (eq_run < take) out[gt_run + eq_run] = t;
-        ++eq_run;
-      }
+    const uint32_t my_gt = gt_run + pg + rank_in(mg), my_eq = eq_run + pe + rank_in(me);
+    if (gt) {
+      out[my_gt + min(my_eq, take)] = (int32_t)e.y;
+    } else if (eq && my_eq < take) {
+      out[my_gt + my_eq] = (int32_t)e.y;
     }
+    gt_run += tg;
+    eq_run += te;
+    __syncthreads();
   }
 }
 
 }  // namespace
+
+#ifdef TKV_PHASE
+static void* g_topk_prof = nullptr;
+extern "C" void tkv_debug_set_dump_topk(void* ptr) { g_topk_prof = ptr; }
+#endif
 
 extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
                                             int32_t* topk_idx, int32_t* topk_count, void* workspace,
@@ -430,16 +465,23 @@ extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_
   p.n_sink = d->n_sink;
   p.n_window = d->n_window;
   p.capacity = d->capacity;
+#ifdef TKV_PHASE
+  p.prof = (long long*)g_topk_prof;
+#endif
 
   hipStream_t s = (hipStream_t)stream;
   int nblk = (max_n + kTok - 1) / kTok;
   if (nblk < 1) nblk = 1;
   const dim3 grid(nblk, d->n_kv_heads, d->batch);
+  // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
+  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
+  if (!lds_ok) return TKV_E_HIP;
+  if (nblk >= 1024) return TKV_E_UNSUPPORTED;  // 4 Mi tokens per sequence
   if (d->n_channels == 16)
-    score_kernel<16><<<grid, 256, 0, s>>>(p);
+    score_kernel<16><<<grid, kThreads, kScoreLds, s>>>(p);
   else
-    score_kernel<8><<<grid, 256, 0, s>>>(p);
-  filter_kernel<<<grid, 256, 0, s>>>(p);
-  finish_kernel<<<grid, 256, 0, s>>>(p);
+    score_kernel<8><<<grid, kThreads, kScoreLds, s>>>(p);
+  select_kernel<<<grid, kThreads, kSelectLds, s>>>(p);
   return tkv::launch_status();
 }

@@ -58,7 +58,10 @@ def test_estimate_topk_gather_attention(n, top_k):
     layer.estimate_topk(q)
     out = layer.gather_attn(q, SM)
     _check_layer(layer, 0, inp, ch, q, out)
-    # the staged rows are the selected rows
+    # the staged rows are the selected rows (the one-stream call above fetches them inside
+    # the attention kernel and leaves the staging buffer alone: gather explicitly)
+    layer.gather()
+    torch.cuda.synchronize()
     cnt = int(layer.topk_count[0, 0])
     if cnt:
         sel = layer.topk_idx[0, 0, :cnt].cpu().numpy()
