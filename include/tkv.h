@@ -226,7 +226,9 @@ int32_t tkv_sparse_gather_attn(const tkv_sparse_desc* desc, const tkv_sparse_cac
                                void* gather_stream, void* compute_stream);
 
 /* The two halves of tkv_sparse_gather_attn as separate calls (for pipelining the
- * gather of one layer under other layers' compute, and for timing the link alone). */
+ * gather of one layer under other layers' compute, and for timing the link alone).
+ * The attention calls use the same workspace as tkv_sparse_estimate_topk, with the same
+ * rule: zero-filled before its first use, left consistent by every call. */
 int32_t tkv_sparse_gather(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const int32_t* topk_idx,
                           const int32_t* topk_count, void* staging, void* stream);
 int32_t tkv_sparse_attn(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,

@@ -45,10 +45,12 @@ int32_t check_sparse_desc(const tkv_sparse_desc* d);
 
 // Carve-up of the sparse-layer workspace (per bh = (sequence, KV head)):
 //   keys  uint32 [BH][capacity]   order-preserving image of the approximate scores
-//   cand  uint2  [BH][capacity]   (key, token) pairs inside the threshold bin
+//   cand  uint2  [BH][capacity]   (key, token) pairs in or above the threshold bin; the workgroup
+//                                 that owns tokens [4096 x, 4096 x + 4096) lists them from entry 4096 x
 //   hist  uint32 [BH][8192]       histogram of the 13-bit key prefix
-//   ctrl  uint32 [BH][8]          arrival counter, candidate count, bin, keys above the bin
-//   blk   uint32 [BH][nblk_cap]   per 1024-token block: keys above the bin
+//   ctrl  uint32 [BH][8]          0, 1: arrival counters of the two Top-K launches; 2: bin of the
+//                                 k-th key; 3: keys above the bin; 4: arrival counter of the attention
+//   blk   uint32 [BH][nblk_cap]   length of each workgroup's list
 //   parts float  [B][Hq][64][D+2] split partials of the sparse attention
 struct SparseWs {
   uint32_t* keys;

@@ -173,7 +173,7 @@ struct Cfg {
   static constexpr int oTail = oCz + kMaxGpc * 16;
   static constexpr int oQ = oTail + kTailWaves * (int)sizeof(TailEntry);
   static constexpr int kLdsBytes = oQ + 4 * TKV_D * 2;
-  static_assert(sizeof(MergeSmem<W>) <= (size_t)W * kWaveRing, "merge scratch must fit in the ring");
+  static_assert(sizeof(MergeSmem<W>) + 4 * TKV_MAX_CHUNKS * 4 <= (size_t)W * kWaveRing, "merge scratch must fit in the ring");
   static_assert(kLdsBytes + 64 <= 160 * 1024, "LDS budget of one compute unit");
 };
 
@@ -420,11 +420,12 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
       qf[hh][1] = hh < G ? (float)qq[1] * comp : 0.f;
     }
   }
+  TKV_PH();  // 1 this wave's set-up work done
   __syncthreads();  // cz table, tail slots, query copy and group counter are in place
-  TKV_PH();  // 1 set-up done
+  TKV_PH();  // 2 set-up done
 
   if (has_tail && wave < kTailWaves && wave * 32 < n - nq) tail_wave(p, tail_s[wave], q_h, bh, nq, n, wave, lane);
-  TKV_PH();  // 2 tail done
+  TKV_PH();  // 3 tail done
 
   // codes carry 2^-24, query side 2^kEK, so S = acc * 2^(24-kEK)
   const float K1 = p.scale2 * (float)(1 << (24 - kEK));
@@ -640,10 +641,10 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     }
   }
 #undef TKV_WAIT_VMCNT
-  TKV_PH();  // 3 this wave's groups done
+  TKV_PH();  // 4 this wave's groups done
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct-to-LDS load may land after the ring is reused
   __syncthreads();
-  TKV_PH();  // 4 all waves done
+  TKV_PH();  // 5 all waves done
 
   // ---- per-wave results -> LDS.  acc_z rows: lanes 0..15 (rb 0) hold rows 0..3 = z-terms
   // for u = row; lanes 16..31 register 0 hold row 4 = denominator.
@@ -668,32 +669,43 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     }
   }
   __syncthreads();
-  for (int i = tid; i < G * TKV_D; i += C::kThreads) {
-    const int hh = i / TKV_D, c = i % TKV_D;
+  // merge weights of the W wave entries and the tail entries, once per (entry, head)
+  constexpr int NE = W + kTailWaves;
+  __shared__ float s_w[NE][4];
+  __shared__ float s_ml[2][4];
+  if (tid < 4) {
+    const int hh = tid;
     float M = -INFINITY;
     for (int w = 0; w < W; ++w) M = fmaxf(M, ms.m[w][hh]);
     for (int w = 0; w < kTailWaves; ++w) M = fmaxf(M, tail_s[w].m[hh]);
-    float Lsum = 0.f, O = 0.f;
-    for (int w = 0; w < W; ++w) {
-      const float mw = ms.m[w][hh];
-      if (mw == -INFINITY) continue;
-      const float wgt = exp2f(mw - M);
-      Lsum += ms.l[w][hh] * wgt;
-      O += ms.o[w][hh][c] * wgt;
+    float Lsum = 0.f;
+    for (int e = 0; e < NE; ++e) {
+      const float me = e < W ? ms.m[e][hh] : tail_s[e - W].m[hh];
+      const float le = e < W ? ms.l[e][hh] : tail_s[e - W].l[hh];
+      const float wgt = me == -INFINITY ? 0.f : exp2f(me - M);
+      s_w[e][hh] = wgt;
+      Lsum += le * wgt;
     }
-    for (int w = 0; w < kTailWaves; ++w) {
-      const float mw = tail_s[w].m[hh];
-      if (mw == -INFINITY) continue;
-      const float wgt = exp2f(mw - M);
-      Lsum += tail_s[w].l[hh] * wgt;
-      O += tail_s[w].o[hh][c] * wgt;
+    s_ml[0][hh] = M;
+    s_ml[1][hh] = Lsum;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * TKV_D; i += C::kThreads) {
+    const int hh = i / TKV_D, c = i % TKV_D;
+    float O = 0.f;
+#pragma unroll
+    for (int w = 0; w < W; ++w) O = __builtin_fmaf(ms.o[w][hh][c], s_w[w][hh], O);
+#pragma unroll
+    for (int w = 0; w < kTailWaves; ++w) {  // unused tail slots hold no data, only a zero weight
+      const float wgt = s_w[W + w][hh];
+      O = __builtin_fmaf(wgt != 0.f ? tail_s[w].o[hh][c] : 0.f, wgt, O);
     }
     float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
     // device-scope stores: visible to the merging workgroup without a cache write-back
     __hip_atomic_store(dst + 2 + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
-      __hip_atomic_store(dst, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(dst + 1, Lsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(dst, s_ml[0][hh], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(dst + 1, s_ml[1][hh], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 
@@ -702,37 +714,67 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   // waiting for the stores to complete before the arrival counter is bumped: a release /
   // acquire fence pair would write back and invalidate the whole L2 (tens of microseconds).
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  TKV_PH();  // 5 partial written
-#ifdef TKV_PHASE
-  if (p.prof && lane == 0) {
-    long long* dst = p.prof + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * W + wave) * 8;
-    for (int i = 0; i < 6; ++i) dst[i] = ph[i];
-  }
-#endif
+  TKV_PH();  // 6 partial written
   __syncthreads();
   if (tid == 0) s_flag = atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(p.n_chunks - 1) ? 1u : 0u;
   __syncthreads();
-  if (s_flag == 0u) return;
-  if (tid == 0) p.arrivals[bh] = 0u;
-  if (tid < G * TKV_D) {
-    const int hh = tid / TKV_D, c = tid % TKV_D;
-    const size_t head = (size_t)b * p.hq + (size_t)h * G + hh;
-    const float* base = p.parts + head * p.n_chunks * TKV_PART_STRIDE;
-    float M = -INFINITY;
+  if (s_flag != 0u) {
+    if (tid == 0) p.arrivals[bh] = 0u;
     auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-#pragma unroll 8
-    for (int k = 0; k < p.n_chunks; ++k) M = fmaxf(M, ld(base + (size_t)k * TKV_PART_STRIDE));
-    float Lsum = 0.f, O = 0.f;
-#pragma unroll 8
-    for (int k = 0; k < p.n_chunks; ++k) {
-      const float* pk = base + (size_t)k * TKV_PART_STRIDE;
-      const float mk = ld(pk);
-      const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
-      Lsum = __builtin_fmaf(ld(pk + 1), w, Lsum);
-      O = __builtin_fmaf(ld(pk + 2 + c), w, O);
+    // chunk weights first (one load round for all maxima and sums), then the channels with
+    // every chunk's load independent of the others
+    float* cw = reinterpret_cast<float*>(smem + C::oRing + sizeof(MergeSmem<W>));  // [4][n_chunks] weights
+    __shared__ float s_L[4];
+    const float* head0 = p.parts + ((size_t)b * p.hq + (size_t)h * G) * p.n_chunks * TKV_PART_STRIDE;
+    if (tid < 64 * G) {  // one wave per head
+      const int hh = tid / 64;
+      const float* base = head0 + (size_t)hh * p.n_chunks * TKV_PART_STRIDE;
+      float mk[TKV_MAX_CHUNKS / 64], lk[TKV_MAX_CHUNKS / 64];
+      float M = -INFINITY;
+#pragma unroll
+      for (int x = 0; x < TKV_MAX_CHUNKS / 64; ++x) {
+        const int k = x * 64 + lane;
+        mk[x] = k < p.n_chunks ? ld(base + (size_t)k * TKV_PART_STRIDE) : -INFINITY;
+        lk[x] = k < p.n_chunks ? ld(base + (size_t)k * TKV_PART_STRIDE + 1) : 0.f;
+        M = fmaxf(M, mk[x]);
+      }
+      for (int m = 32; m >= 1; m >>= 1) M = fmaxf(M, __shfl_xor(M, m, 64));
+      float Lsum = 0.f;
+#pragma unroll
+      for (int x = 0; x < TKV_MAX_CHUNKS / 64; ++x) {
+        const int k = x * 64 + lane;
+        const float w = mk[x] == -INFINITY ? 0.f : exp2f(mk[x] - M);
+        if (k < p.n_chunks) cw[hh * p.n_chunks + k] = w;
+        Lsum = __builtin_fmaf(lk[x], w, Lsum);
+      }
+      for (int m = 32; m >= 1; m >>= 1) Lsum += __shfl_xor(Lsum, m, 64);
+      if (lane == 0) s_L[hh] = Lsum;
     }
-    p.out[head * TKV_D + c] = __float2half_rn(Lsum > 0.f ? O / Lsum : 0.f);
+    __syncthreads();
+    if (tid < G * TKV_D) {
+      const int hh = tid / TKV_D, c = tid % TKV_D;
+      const float* base = head0 + (size_t)hh * p.n_chunks * TKV_PART_STRIDE + 2 + c;
+      float O = 0.f;
+      int k = 0;
+      for (; k + 16 <= p.n_chunks; k += 16) {
+        float v[16];
+#pragma unroll
+        for (int y = 0; y < 16; ++y) v[y] = ld(base + (size_t)(k + y) * TKV_PART_STRIDE);
+#pragma unroll
+        for (int y = 0; y < 16; ++y) O = __builtin_fmaf(v[y], cw[hh * p.n_chunks + k + y], O);
+      }
+      for (; k < p.n_chunks; ++k) O = __builtin_fmaf(ld(base + (size_t)k * TKV_PART_STRIDE), cw[hh * p.n_chunks + k], O);
+      const float Lsum = s_L[hh];
+      p.out[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c] = __float2half_rn(Lsum > 0.f ? O / Lsum : 0.f);
+    }
   }
+  TKV_PH();  // 7 end
+#ifdef TKV_PHASE
+  if (p.prof && lane == 0) {
+    long long* dst = p.prof + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * W + wave) * 8;
+    for (int i = 0; i < 8; ++i) dst[i] = ph[i];
+  }
+#endif
 }
 
 template <int BITS, int W>

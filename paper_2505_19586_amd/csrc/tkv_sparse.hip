@@ -77,6 +77,8 @@ struct SparseAttnParams {
   const __half* kv_host;    // fused variant: device-visible view of the pinned host rows
   const int32_t* topk_idx;  // fused variant
   int32_t capacity;
+  uint32_t* arrivals;  // [B][Hkv] stride 8 words, zero between calls
+  __half* out;         // [B][Hq][D]
   const __half* kv_local;
   const int32_t* topk_count;
   float* parts;
@@ -225,11 +227,41 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
       O += red_o[w][hh][c] * wgt;
     }
     float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
-    dst[2 + c] = O;
+    // device-scope stores: visible to the merging workgroup without a cache write-back
+    __hip_atomic_store(dst + 2 + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
-      dst[0] = M;
-      dst[1] = L;
+      __hip_atomic_store(dst, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(dst + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+  }
+  // ---- the last workgroup of this (sequence, KV head) to arrive merges all chunks; the
+  // partials are ordered before the arrival counter by waiting for the stores to complete
+  __shared__ uint32_t s_last;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  uint32_t* arrive = p.arrivals + bh * 8 + 4;
+  if (tid == 0) s_last = atomicAdd(arrive, 1u) == (uint32_t)(p.n_chunks - 1) ? 1u : 0u;
+  __syncthreads();
+  if (s_last == 0u) return;
+  if (tid == 0) __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+  for (int x = tid; x < G * TKV_D; x += nthr) {
+    const int hh = x / TKV_D, c = x % TKV_D;
+    const size_t head = (size_t)b * p.hq + (size_t)h * G + hh;
+    const float* base = p.parts + head * p.n_chunks * TKV_PART_STRIDE;
+    float M = -INFINITY;
+#pragma unroll 8
+    for (int k = 0; k < p.n_chunks; ++k) M = fmaxf(M, ld(base + (size_t)k * TKV_PART_STRIDE));
+    float L = 0.f, O = 0.f;
+#pragma unroll 8
+    for (int k = 0; k < p.n_chunks; ++k) {
+      const float* pk = base + (size_t)k * TKV_PART_STRIDE;
+      const float mk = ld(pk);
+      const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
+      L = __builtin_fmaf(ld(pk + 1), w, L);
+      O = __builtin_fmaf(ld(pk + 2 + c), w, O);
+    }
+    p.out[head * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
   }
 }
 
@@ -341,9 +373,9 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
   st = fill_lens(d, c, p.lens, max_n);
   if (st != TKV_OK) return st;
   const int max_att = d->n_sink + d->top_k + d->n_window;
-  // fewest waves per workgroup that keep the number of chunks within the 64 partial slots
-  int W = 1;
-  while (W < kAttnMaxWaves && (max_att + 32 * W - 1) / (32 * W) > 64) ++W;
+  // four waves per workgroup once there is work for them: few chunks keep the final merge
+  // short (and their number must stay within the 64 partial slots)
+  int W = max_att > 256 ? kAttnMaxWaves : 1;
   const int n_chunks = (max_att + 32 * W - 1) / (32 * W);
   if (n_chunks > 64) return TKV_E_UNSUPPORTED;
   // partials live behind the Top-K scratch so that one workspace serves both calls
@@ -364,6 +396,8 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
   p.kv_host = nullptr;
   p.topk_idx = nullptr;
   p.capacity = d->capacity;
+  p.arrivals = tkv::carve_sparse_ws(d, workspace).ctrl;  // word 4 of each head's 8 control words
+  p.out = (__half*)out;
   if (topk_idx_fused) {
     const void* host_dev = nullptr;
     st = device_view_of_host(c->kv_host, &host_dev);
@@ -378,8 +412,7 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
   } else {
     sparse_attn_kernel<false><<<dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s>>>(p);
   }
-  if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
-  return tkv::launch_attn_merge(parts, (__half*)out, d->batch * d->n_q_heads, n_chunks, s);
+  return tkv::launch_status();
 }
 }  // namespace
 
