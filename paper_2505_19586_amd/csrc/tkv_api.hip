@@ -71,7 +71,7 @@ extern "C" int32_t tkv_quant_cache_sizes(const tkv_quant_desc* d, size_t bytes_o
     bytes_out[7] = resid;
   }
   if (workspace_bytes) {
-    // split-K partials: [B][Hq][chunks + tail][D + 2] float, plus one arrival
+    // split-K partials: [B][Hq][chunks + tail][D + 4] float, plus one arrival
     // counter per (sequence, KV head)
     *workspace_bytes = (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float) +
                        bh * sizeof(uint32_t) + 512;

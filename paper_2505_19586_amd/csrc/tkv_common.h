@@ -11,9 +11,11 @@
 #define TKV_G 32       // quantization group
 #define TKV_WAVE 64
 
-// Partial attention result of one chunk and one query head: max logit (in log2
-// units after scaling), sum of weights, weighted V sum.
-#define TKV_PART_STRIDE (TKV_D + 2)
+// Partial attention result of one chunk and one query head, in floats: max logit (in log2
+// units after scaling), sum of weights, two unused words, then the weighted V sum (so that
+// it starts on a 16-byte boundary).
+#define TKV_PART_O 4
+#define TKV_PART_STRIDE (TKV_D + TKV_PART_O)
 
 // Upper bound on split-K chunks per (sequence, KV head), tail chunk excluded.
 #define TKV_MAX_CHUNKS 256
@@ -38,10 +40,97 @@ __host__ __device__ inline int32_t n_quantized(int32_t n, int32_t w) {
 inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? TKV_OK : TKV_E_HIP; }
 
 int32_t check_quant_desc(const tkv_quant_desc* d);
-// Merges [n_heads_total][n_parts][D + 2] float partials (max in log2 units, sum,
+// Merges [n_heads_total][n_parts][TKV_PART_STRIDE] float partials (max in log2 units, sum,
 // weighted V) into fp16 [n_heads_total][D].
 int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, int n_parts, hipStream_t s);
 int32_t check_sparse_desc(const tkv_sparse_desc* d);
+
+// ---- cross-chunk merge by the last workgroup of a (sequence, KV head) --------------------
+// Partials cross workgroups through device-scope stores and loads (they bypass the caches
+// that are not coherent between workgroups).  Such loads are served slowly, one load
+// instruction after the other, so the merge uses as few and as wide ones as it can: all of
+// them are issued before the first is used.
+
+typedef float tkv_floatx4 __attribute__((ext_vector_type(4)));
+
+// 16-byte device-scope load.  The compiler does not see it as a memory access: the value
+// may only be used after tkv_wait_x4 on it.
+__device__ inline void ld_agent_x4(tkv_floatx4& v, const float* ptr) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(ptr) : "memory");
+}
+__device__ inline void tkv_wait_x4(tkv_floatx4& v) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)::"memory"); }
+
+// head0: partials of the G heads of this KV head, [G][n_chunks][TKV_PART_STRIDE]; out0: fp16
+// [G][128].  lds: 3 * G * n_chunks + 4 * 4 * 128 + 4 floats.  Called by every thread of the
+// workgroup (nthr a multiple of 64, at least 64 * G).
+__device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __half* out0, float* lds, int tid,
+                                    int nthr) {
+  float* ml = lds;                       // [G][n_chunks][2]
+  float* cw = ml + 2 * G * n_chunks;     // [G][n_chunks] weights
+  float* red = cw + G * n_chunks;        // [4 heads][4 classes][128]
+  float* Ls = red + 4 * 4 * TKV_D;       // [4]
+  const int lane = tid % 64, wave = tid / 64;
+  // round 1: maxima and sums of all chunks, and (for up to 64 chunks) this thread's channels
+  for (int i = tid; i < G * n_chunks; i += nthr) {
+    const float* pk = head0 + (size_t)i * TKV_PART_STRIDE;
+    ml[2 * i] = __hip_atomic_load(pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ml[2 * i + 1] = __hip_atomic_load(pk + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // item = (head, chunk class ks, channel quad c4): chunks ks, ks + 4, ...
+  constexpr int kPer = 16;
+  for (int item0 = 0; item0 < G * TKV_D; item0 += nthr) {
+    const int item = item0 + tid;
+    const bool on = item < G * TKV_D;
+    const int hh = on ? item / TKV_D : 0, r = item % TKV_D;
+    const int ks = r / 32, c4 = r % 32;
+    const float* base = head0 + (size_t)hh * n_chunks * TKV_PART_STRIDE + TKV_PART_O + 4 * c4;
+    tkv_floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < n_chunks; k0 += 4 * kPer) {
+      tkv_floatx4 ov[kPer];
+#pragma unroll
+      for (int y = 0; y < kPer; ++y) {
+        const int k = k0 + 4 * y + ks;
+        ov[y] = tkv_floatx4{0.f, 0.f, 0.f, 0.f};
+        if (on && k < n_chunks) ld_agent_x4(ov[y], base + (size_t)k * TKV_PART_STRIDE);
+      }
+      if (item0 == 0 && k0 == 0) {
+        // weights: one wave per head (the loads above are in flight meanwhile)
+        __syncthreads();
+        if (wave < G) {
+          float M = -INFINITY;
+          for (int k = lane; k < n_chunks; k += 64) M = fmaxf(M, ml[2 * (wave * n_chunks + k)]);
+          for (int m = 32; m >= 1; m >>= 1) M = fmaxf(M, __shfl_xor(M, m, 64));
+          float Lsum = 0.f;
+          for (int k = lane; k < n_chunks; k += 64) {
+            const float mk = ml[2 * (wave * n_chunks + k)];
+            const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
+            cw[wave * n_chunks + k] = w;
+            Lsum = __builtin_fmaf(ml[2 * (wave * n_chunks + k) + 1], w, Lsum);
+          }
+          for (int m = 32; m >= 1; m >>= 1) Lsum += __shfl_xor(Lsum, m, 64);
+          if (lane == 0) Ls[wave] = Lsum;
+        }
+        __syncthreads();
+      }
+#pragma unroll
+      for (int y = 0; y < kPer; ++y) {
+        const int k = k0 + 4 * y + ks;
+        tkv_wait_x4(ov[y]);
+        const float w = (on && k < n_chunks) ? cw[hh * n_chunks + k] : 0.f;
+        acc += ov[y] * w;
+      }
+    }
+    if (on) *reinterpret_cast<tkv_floatx4*>(red + (hh * 4 + ks) * TKV_D + 4 * c4) = acc;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * TKV_D; i += nthr) {
+    const int hh = i / TKV_D, c = i % TKV_D;
+    const float O = (red[(hh * 4 + 0) * TKV_D + c] + red[(hh * 4 + 1) * TKV_D + c]) +
+                    (red[(hh * 4 + 2) * TKV_D + c] + red[(hh * 4 + 3) * TKV_D + c]);
+    const float Lsum = Ls[hh];
+    out0[(size_t)hh * TKV_D + c] = __float2half_rn(Lsum > 0.f ? O / Lsum : 0.f);
+  }
+}
 
 // Carve-up of the sparse-layer workspace (per bh = (sequence, KV head)):
 //   keys  uint32 [BH][capacity]   order-preserving image of the approximate scores
@@ -51,7 +140,7 @@ int32_t check_sparse_desc(const tkv_sparse_desc* d);
 //   ctrl  uint32 [BH][8]          0, 1: arrival counters of the two Top-K launches; 2: bin of the
 //                                 k-th key; 3: keys above the bin; 4: arrival counter of the attention
 //   blk   uint32 [BH][nblk_cap]   length of each workgroup's list
-//   parts float  [B][Hq][64][D+2] split partials of the sparse attention
+//   parts float  [B][Hq][64][D+4] split partials of the sparse attention
 struct SparseWs {
   uint32_t* keys;
   uint2* cand;

@@ -27,7 +27,7 @@ struct QuantAttnParams {
   const __half* k_resid;
   const __half* v_resid;
   const __half* q;
-  float* parts;  // [B][Hq][n_chunks + 1][D + 2]
+  float* parts;  // [B][Hq][n_chunks + 1][D + 4]
   float scale2;  // sm_scale * log2(e)
   int32_t hq, hkv, bits, residual, capacity;
   int32_t groups_per_chunk, n_chunks;
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
       O += red_o[w][hh][c] * wgt;
     }
     float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * n_parts + chunk) * TKV_PART_STRIDE;
-    dst[2 + c] = O;
+    dst[TKV_PART_O + c] = O;
     if (c == 0) {
       dst[0] = M;
       dst[1] = L;
@@ -246,14 +246,14 @@ __global__ __launch_bounds__(TKV_D) void attn_merge_kernel(const float* parts, _
   float O0 = 0.f, O1 = 0.f, O2 = 0.f, O3 = 0.f;
   int k = 0;
   for (; k + 4 <= n_parts; k += 4) {
-    const float* pk = base + (size_t)k * TKV_PART_STRIDE + 2 + c;
+    const float* pk = base + (size_t)k * TKV_PART_STRIDE + TKV_PART_O + c;
     const float v0 = pk[0], v1 = pk[TKV_PART_STRIDE], v2 = pk[2 * TKV_PART_STRIDE], v3 = pk[3 * TKV_PART_STRIDE];
     O0 = __builtin_fmaf(v0, wgt[k], O0);
     O1 = __builtin_fmaf(v1, wgt[k + 1], O1);
     O2 = __builtin_fmaf(v2, wgt[k + 2], O2);
     O3 = __builtin_fmaf(v3, wgt[k + 3], O3);
   }
-  for (; k < n_parts; ++k) O0 = __builtin_fmaf(base[(size_t)k * TKV_PART_STRIDE + 2 + c], wgt[k], O0);
+  for (; k < n_parts; ++k) O0 = __builtin_fmaf(base[(size_t)k * TKV_PART_STRIDE + TKV_PART_O + c], wgt[k], O0);
   const float O = (O0 + O1) + (O2 + O3);
   out[head * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
 }

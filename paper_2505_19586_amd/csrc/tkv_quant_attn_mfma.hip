@@ -49,14 +49,14 @@ struct MfmaParams {
   const __half* k_resid;
   const __half* v_resid;
   const __half* q;
-  float* parts;        // [B][Hq][n_chunks][D + 2]
+  float* parts;        // [B][Hq][n_chunks][D + 4]
   uint32_t* arrivals;  // [B][Hkv], zero between calls
   __half* out;         // [B][Hq][D]
   float scale2;
   int32_t hq, hkv, residual, capacity;
   int32_t n_chunks;
-#ifdef TKV_PHASE
-  long long* prof;  // phase timestamps (profiling builds only)
+#if defined(TKV_PHASE) || defined(TKV_PROF)
+  long long* prof;  // timestamps (profiling builds only)
 #endif
   TkvSeqLens lens;
 };
@@ -173,7 +173,7 @@ struct Cfg {
   static constexpr int oTail = oCz + kMaxGpc * 16;
   static constexpr int oQ = oTail + kTailWaves * (int)sizeof(TailEntry);
   static constexpr int kLdsBytes = oQ + 4 * TKV_D * 2;
-  static_assert(sizeof(MergeSmem<W>) + 4 * TKV_MAX_CHUNKS * 4 <= (size_t)W * kWaveRing, "merge scratch must fit in the ring");
+  static_assert(sizeof(MergeSmem<W>) + (3 * 4 * TKV_MAX_CHUNKS + 4 * 4 * TKV_D + 4) * 4 <= (size_t)W * kWaveRing, "merge scratch must fit in the ring");
   static_assert(kLdsBytes + 64 <= 160 * 1024, "LDS budget of one compute unit");
 };
 
@@ -279,6 +279,24 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_next;
   __shared__ uint32_t s_flag;
+#ifdef TKV_PROF
+  __shared__ long long s_prof[W][80];
+  int prof_n = 0;
+#define TKV_TS()                                   \
+  do {                                             \
+    __builtin_amdgcn_sched_barrier(0);             \
+    if (prof_n < 80) {                             \
+      const long long t_ = clock64();              \
+      if (lane == 0) s_prof[wave][prof_n] = t_;    \
+      ++prof_n;                                    \
+    }                                              \
+    __builtin_amdgcn_sched_barrier(0);             \
+  } while (0)
+#else
+#define TKV_TS() \
+  do {           \
+  } while (0)
+#endif
 #ifdef TKV_PHASE
   long long ph[8];
   int ph_n = 0;
@@ -301,7 +319,11 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   const int gpc = max(1, (jq + tail_equiv + p.n_chunks - 1) / p.n_chunks);
   const int blk0 = min(chunk * gpc, jq);
   const int blk1 = has_tail ? jq : min(blk0 + gpc, jq);
+#ifdef TKV_ABL_NOMEM  // timing experiment: every load hits the chunk's first group (results are wrong)
+  const int last = blk0;
+#else
   const int last = max(blk1 - 1, blk0);  // groups past the chunk are clamped (and ignored); jq >= 1 here
+#endif
 
   const int slot = lane % 16, rb = lane / 16;
   const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, column group
@@ -472,10 +494,14 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     return __builtin_amdgcn_readfirstlane(v);
   };
 
-  // ---- pipeline stages of one group ------------------------------------------------------
+  // ---- pipeline stages of one group.  Every stage is split into its LDS reads and its
+  // arithmetic, so that a step can issue the reads well ahead of their use (a wave issues in
+  // order: a read that is waited for right away stalls it for the whole LDS latency).
   // K: scalers x query -> hi/lo operands in LDS
-  auto stage_k = [&](uint32_t so) {
-    const uint32_t ks2 = *reinterpret_cast<const uint32_t*>(smem + so + C::kCode + lane4);
+  auto read_ks = [&](uint32_t so) -> uint32_t {
+    return *reinterpret_cast<const uint32_t*>(smem + so + C::kCode + lane4);
+  };
+  auto stage_k = [&](uint32_t ks2) {
 #pragma unroll
     for (int hh = 0; hh < 4; ++hh) {
       const uint32_t hi = mix_hi_pair(qf[hh][0], qf[hh][1], ks2);  // products are exact in float32
@@ -486,37 +512,58 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   // QK: partial logits of the group's 32 tokens (two 16-token tiles); even column groups
   // read the hi rows of the query-side operand, odd ones the lo rows
   const uint32_t* bk_row = &bk_s[us & 1][hs][4 * rb];
-  auto stage_qk = [&](uint32_t so, floatx4 (&acc_s)[2]) {
-    const unsigned char* s = smem + so;
+  struct QkIn {
     uint32_t kw[2 * BITS];
+    uintx4 bk[4];
+  };
+  auto read_qk = [&](uint32_t so, QkIn& in) {
+    const unsigned char* s = smem + so;
 #pragma unroll
     for (int x = 0; x < BITS / 2; ++x) {
       const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
 #pragma unroll
-      for (int y = 0; y < 4; ++y) kw[4 * x + y] = t[y];
+      for (int y = 0; y < 4; ++y) in.kw[4 * x + y] = t[y];
     }
+#pragma unroll
+    for (int m = 0; m < 4; ++m) in.bk[m] = *reinterpret_cast<const uintx4*>(bk_row + 16 * m);
+  };
+  auto stage_qk = [&](const QkIn& in, floatx4 (&acc_s)[2]) {
     acc_s[0] = floatx4{0.f, 0.f, 0.f, 0.f};
     acc_s[1] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int m2 = 0; m2 < 2; ++m2) {  // pairs of MFMA steps m = 2*m2, 2*m2+1
-      uintx4 bk2[2];
-#pragma unroll
-      for (int y = 0; y < 2; ++y) bk2[y] = *reinterpret_cast<const uintx4*>(bk_row + 16 * (2 * m2 + y));
 #pragma unroll
       for (int tau = 0; tau < 2; ++tau) {
         uintx4 a[2];
         if (BITS == 2) {
-          extract2(kw[2 * tau + m2], a[0], a[1]);
+          extract2(in.kw[2 * tau + m2], a[0], a[1]);
         } else {
-          extract4(kw[4 * tau + 2 * m2], a[0]);
-          extract4(kw[4 * tau + 2 * m2 + 1], a[1]);
+          extract4(in.kw[4 * tau + 2 * m2], a[0]);
+          extract4(in.kw[4 * tau + 2 * m2 + 1], a[1]);
         }
 #pragma unroll
-        for (int y = 0; y < 2; ++y) acc_s[tau] = mfma(a[y], bk2[y], acc_s[tau]);
+        for (int y = 0; y < 2; ++y) acc_s[tau] = mfma(a[y], in.bk[2 * m2 + y], acc_s[tau]);
       }
     }
   };
   // weights and weight-side operands
+  struct PvIn {
+    uintx4 sv, zv;
+    uint32_t vw[2 * BITS];
+    float cz;
+  };
+  auto read_pv = [&](uint32_t so, int gc, PvIn& in) {
+    const unsigned char* s = smem + so;
+    in.sv = *reinterpret_cast<const uintx4*>(s + C::kCode + (us * TKV_G + 8 * rb) * 2);
+    in.zv = *reinterpret_cast<const uintx4*>(s + C::kCode + 256 + (zrow_ld * TKV_G + 8 * rb) * 2);
+#pragma unroll
+    for (int x = 0; x < BITS / 2; ++x) {
+      const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) in.vw[4 * x + y] = t[y];
+    }
+    in.cz = cz_s[(gc - blk0) * 4 + hs];
+  };
   struct POps {
     uintx4 b2, bp, a_zv;
   };
@@ -524,10 +571,8 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   // not necessarily the running maximum) only has to keep them below 2^kHeadroomLog2: that
   // is checked on the packed fp16 weights themselves, and only a failed check (rare after
   // the first groups) pays for the exact maximum, the accumulator rescale and a second pass.
-  auto stage_soft = [&](uint32_t so, const floatx4 (&acc_s)[2], float cz, POps& o) {
-    const unsigned char* s = smem + so;
-    const uintx4 sv = *reinterpret_cast<const uintx4*>(s + C::kCode + (us * TKV_G + 8 * rb) * 2);
-    const uintx4 zv = *reinterpret_cast<const uintx4*>(s + C::kCode + 256 + (zrow_ld * TKV_G + 8 * rb) * 2);
+  auto stage_soft = [&](const PvIn& in, const floatx4 (&acc_s)[2], POps& o) {
+    const float cz = in.cz;
     float xs[8];  // hi + lo partial sums: every lane of a head ends up with the full logit
 #pragma unroll
     for (int x = 0; x < 8; ++x) xs[x] = ror4_add(acc_s[x / 4][x % 4]);
@@ -565,31 +610,23 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       // weight x scaler: one rounding of the exact product of two fp16 numbers
-      const uint32_t bpj = o.bp[j], svj = sv[j], zvj = zv[j];
+      const uint32_t bpj = o.bp[j], svj = in.sv[j], zvj = in.zv[j];
       o.b2[j] = __builtin_bit_cast(uint32_t, as_half2(bpj) * as_half2(svj));
       const half2_t t = __builtin_elementwise_fma(as_half2(zvj), zmul[j], zadd[j]);
       o.a_zv[j] = __builtin_bit_cast(uint32_t, t);
     }
   };
   // P.V: 8 blocks of 16 channels + the z_v / denominator MFMA
-  auto stage_pv = [&](uint32_t so, const POps& o) {
-    const unsigned char* s = smem + so;
-    uint32_t vw[2 * BITS];
-#pragma unroll
-    for (int x = 0; x < BITS / 2; ++x) {
-      const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
-#pragma unroll
-      for (int y = 0; y < 4; ++y) vw[4 * x + y] = t[y];
-    }
+  auto stage_pv = [&](const PvIn& in, const POps& o) {
     acc_z = mfma(o.a_zv, o.bp, acc_z);
 #pragma unroll
     for (int wd = 0; wd < 4; ++wd) {
       uintx4 a[2];
       if (BITS == 2) {
-        extract2(vw[wd], a[0], a[1]);
+        extract2(in.vw[wd], a[0], a[1]);
       } else {
-        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
-        extract4(vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
+        extract4(in.vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
+        extract4(in.vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
       }
 #pragma unroll
       for (int y = 0; y < 2; ++y) acc_o[2 * wd + y] = mfma(a[y], o.b2, acc_o[2 * wd + y]);
@@ -604,24 +641,43 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   if (active) {
     floatx4 acc_a[2], acc_b[2];
     TKV_WAIT_VMCNT(2 * C::kKLoads + C::kVLoads);  // K0, V0 landed
-    stage_k(kl);
-    stage_qk(kl, acc_a);
+    stage_k(read_ks(kl));
+    {
+      QkIn qi;
+      read_qk(kl, qi);
+      stage_qk(qi, acc_a);
+    }
     TKV_WAIT_VMCNT(L);  // + K1
-    stage_k(kq);
+    stage_k(read_ks(kq));
     // One step is one straight-line block; groups past the chunk are clamped copies whose
     // results are dropped by leaving the loop.  gc = group i (valid), gn3 / gv2 = groups
-    // whose K / V part is fetched now.
+    // whose K / V part is fetched now.  LDS reads go out one stage ahead of their use.
     auto step = [&](int gc, int gn3, int gv2, floatx4 (&acc_c)[2], floatx4 (&acc_n)[2]) {
+      TKV_TS();  // 0
+      QkIn qi;
+      read_qk(kq, qi);  // K(i+1) landed during the previous step
+      __builtin_amdgcn_sched_barrier(0);
       load_kpart(kl, gn3);
       load_vpart(vl, gv2);
-      const float cz = cz_s[(gc - blk0) * 4 + hs];
-      POps po;
+      TKV_TS();  // 1 loads issued
       TKV_WAIT_VMCNT(2 * L);  // K(i+1), V(i) landed
-      stage_qk(kq, acc_n);
-      stage_soft(vp, acc_c, cz, po);
-      stage_pv(vp, po);
+      PvIn pi;
+      read_pv(vp, gc, pi);
+      __builtin_amdgcn_sched_barrier(0);
+      TKV_TS();  // 2
+      stage_qk(qi, acc_n);
+      TKV_TS();  // 3 QK
+      POps po;
+      stage_soft(pi, acc_c, po);
+      TKV_TS();  // 4 soft
       TKV_WAIT_VMCNT(L + C::kVLoads);  // + K(i+2)
-      stage_k(kk);
+      const uint32_t ks2 = read_ks(kk);
+      __builtin_amdgcn_sched_barrier(0);
+      stage_pv(pi, po);
+      TKV_TS();  // 5 PV
+      stage_k(ks2);
+      TKV_TS();  // 6 stage_k
+      TKV_TS();  // 7
       uint32_t t = kq;
       kq = kk, kk = kl, kl = t;
       t = vp;
@@ -642,6 +698,12 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   }
 #undef TKV_WAIT_VMCNT
   TKV_PH();  // 4 this wave's groups done
+#ifdef TKV_PROF
+  if (p.prof && lane == 0) {
+    long long* dst = p.prof + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * W + wave) * 80;
+    for (int i = 0; i < 80; ++i) dst[i] = i < prof_n ? s_prof[wave][i] : 0;
+  }
+#endif
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct-to-LDS load may land after the ring is reused
   __syncthreads();
   TKV_PH();  // 5 all waves done
@@ -673,21 +735,27 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   constexpr int NE = W + kTailWaves;
   __shared__ float s_w[NE][4];
   __shared__ float s_ml[2][4];
-  if (tid < 4) {
-    const int hh = tid;
-    float M = -INFINITY;
-    for (int w = 0; w < W; ++w) M = fmaxf(M, ms.m[w][hh]);
-    for (int w = 0; w < kTailWaves; ++w) M = fmaxf(M, tail_s[w].m[hh]);
-    float Lsum = 0.f;
-    for (int e = 0; e < NE; ++e) {
-      const float me = e < W ? ms.m[e][hh] : tail_s[e - W].m[hh];
-      const float le = e < W ? ms.l[e][hh] : tail_s[e - W].l[hh];
-      const float wgt = me == -INFINITY ? 0.f : exp2f(me - M);
-      s_w[e][hh] = wgt;
-      Lsum += le * wgt;
+  static_assert(NE <= 16, "one wave covers all (entry, head) pairs");
+  if (tid < 64) {  // lane = (entry, head)
+    const int e = tid / 4, hh = tid % 4;
+    float me = -INFINITY, le = 0.f;
+    if (e < W) {
+      me = ms.m[e][hh];
+      le = ms.l[e][hh];
+    } else if (e < NE) {
+      me = tail_s[e - W].m[hh];
+      le = tail_s[e - W].l[hh];
     }
-    s_ml[0][hh] = M;
-    s_ml[1][hh] = Lsum;
+    float M = me;
+    for (int m = 4; m <= 32; m <<= 1) M = fmaxf(M, __shfl_xor(M, m, 64));
+    const float wgt = me == -INFINITY ? 0.f : exp2f(me - M);
+    float Lsum = le * wgt;
+    for (int m = 4; m <= 32; m <<= 1) Lsum += __shfl_xor(Lsum, m, 64);
+    if (e < NE) s_w[e][hh] = wgt;
+    if (e == 0) {
+      s_ml[0][hh] = M;
+      s_ml[1][hh] = Lsum;
+    }
   }
   __syncthreads();
   for (int i = tid; i < G * TKV_D; i += C::kThreads) {
@@ -702,7 +770,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     }
     float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
     // device-scope stores: visible to the merging workgroup without a cache write-back
-    __hip_atomic_store(dst + 2 + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(dst + TKV_PART_O + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
       __hip_atomic_store(dst, s_ml[0][hh], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(dst + 1, s_ml[1][hh], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -720,53 +788,9 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   __syncthreads();
   if (s_flag != 0u) {
     if (tid == 0) p.arrivals[bh] = 0u;
-    auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-    // chunk weights first (one load round for all maxima and sums), then the channels with
-    // every chunk's load independent of the others
-    float* cw = reinterpret_cast<float*>(smem + C::oRing + sizeof(MergeSmem<W>));  // [4][n_chunks] weights
-    __shared__ float s_L[4];
     const float* head0 = p.parts + ((size_t)b * p.hq + (size_t)h * G) * p.n_chunks * TKV_PART_STRIDE;
-    if (tid < 64 * G) {  // one wave per head
-      const int hh = tid / 64;
-      const float* base = head0 + (size_t)hh * p.n_chunks * TKV_PART_STRIDE;
-      float mk[TKV_MAX_CHUNKS / 64], lk[TKV_MAX_CHUNKS / 64];
-      float M = -INFINITY;
-#pragma unroll
-      for (int x = 0; x < TKV_MAX_CHUNKS / 64; ++x) {
-        const int k = x * 64 + lane;
-        mk[x] = k < p.n_chunks ? ld(base + (size_t)k * TKV_PART_STRIDE) : -INFINITY;
-        lk[x] = k < p.n_chunks ? ld(base + (size_t)k * TKV_PART_STRIDE + 1) : 0.f;
-        M = fmaxf(M, mk[x]);
-      }
-      for (int m = 32; m >= 1; m >>= 1) M = fmaxf(M, __shfl_xor(M, m, 64));
-      float Lsum = 0.f;
-#pragma unroll
-      for (int x = 0; x < TKV_MAX_CHUNKS / 64; ++x) {
-        const int k = x * 64 + lane;
-        const float w = mk[x] == -INFINITY ? 0.f : exp2f(mk[x] - M);
-        if (k < p.n_chunks) cw[hh * p.n_chunks + k] = w;
-        Lsum = __builtin_fmaf(lk[x], w, Lsum);
-      }
-      for (int m = 32; m >= 1; m >>= 1) Lsum += __shfl_xor(Lsum, m, 64);
-      if (lane == 0) s_L[hh] = Lsum;
-    }
-    __syncthreads();
-    if (tid < G * TKV_D) {
-      const int hh = tid / TKV_D, c = tid % TKV_D;
-      const float* base = head0 + (size_t)hh * p.n_chunks * TKV_PART_STRIDE + 2 + c;
-      float O = 0.f;
-      int k = 0;
-      for (; k + 16 <= p.n_chunks; k += 16) {
-        float v[16];
-#pragma unroll
-        for (int y = 0; y < 16; ++y) v[y] = ld(base + (size_t)(k + y) * TKV_PART_STRIDE);
-#pragma unroll
-        for (int y = 0; y < 16; ++y) O = __builtin_fmaf(v[y], cw[hh * p.n_chunks + k + y], O);
-      }
-      for (; k < p.n_chunks; ++k) O = __builtin_fmaf(ld(base + (size_t)k * TKV_PART_STRIDE), cw[hh * p.n_chunks + k], O);
-      const float Lsum = s_L[hh];
-      p.out[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c] = __float2half_rn(Lsum > 0.f ? O / Lsum : 0.f);
-    }
+    float* scratch = reinterpret_cast<float*>(smem + C::oRing + sizeof(MergeSmem<W>));
+    tkv::merge_chunks(head0, G, p.n_chunks, p.out + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, scratch, tid, C::kThreads);
   }
   TKV_PH();  // 7 end
 #ifdef TKV_PHASE
@@ -791,7 +815,7 @@ int32_t launch_variant(const MfmaParams& p, dim3 grid, hipStream_t s) {
 }  // namespace
 
 namespace tkv {
-#ifdef TKV_PHASE
+#if defined(TKV_PHASE) || defined(TKV_PROF)
 void* g_mfma_prof = nullptr;
 #endif
 
@@ -832,7 +856,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.residual = d->residual;
   p.capacity = d->capacity;
   p.n_chunks = n_chunks;
-#ifdef TKV_PHASE
+#if defined(TKV_PHASE) || defined(TKV_PROF)
   p.prof = (long long*)g_mfma_prof;
 #endif
   p.lens = lens;
@@ -844,7 +868,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
 
 }  // namespace tkv
 
-#ifdef TKV_PHASE
-// profiling builds: device buffer that receives [workgroup][wave][8] wall-clock stamps
+#if defined(TKV_PHASE) || defined(TKV_PROF)
+// profiling builds: device buffer that receives per-wave time stamps
 extern "C" void tkv_debug_set_dump(void* ptr) { tkv::g_mfma_prof = ptr; }
 #endif

@@ -228,7 +228,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
     }
     float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
     // device-scope stores: visible to the merging workgroup without a cache write-back
-    __hip_atomic_store(dst + 2 + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(dst + TKV_PART_O + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
       __hip_atomic_store(dst, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(dst + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -244,24 +244,27 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   __syncthreads();
   if (s_last == 0u) return;
   if (tid == 0) __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-  for (int x = tid; x < G * TKV_D; x += nthr) {
-    const int hh = x / TKV_D, c = x % TKV_D;
-    const size_t head = (size_t)b * p.hq + (size_t)h * G + hh;
-    const float* base = p.parts + head * p.n_chunks * TKV_PART_STRIDE;
-    float M = -INFINITY;
-#pragma unroll 8
-    for (int k = 0; k < p.n_chunks; ++k) M = fmaxf(M, ld(base + (size_t)k * TKV_PART_STRIDE));
-    float L = 0.f, O = 0.f;
-#pragma unroll 8
-    for (int k = 0; k < p.n_chunks; ++k) {
-      const float* pk = base + (size_t)k * TKV_PART_STRIDE;
-      const float mk = ld(pk);
-      const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
-      L = __builtin_fmaf(ld(pk + 1), w, L);
-      O = __builtin_fmaf(ld(pk + 2 + c), w, O);
+  __shared__ float merge_s[3 * 4 * 64 + 4 * 4 * TKV_D + 4];
+  const float* head0 = p.parts + ((size_t)b * p.hq + (size_t)h * G) * p.n_chunks * TKV_PART_STRIDE;
+  if (nthr >= 64 * G) {
+    tkv::merge_chunks(head0, G, p.n_chunks, p.out + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, merge_s, tid, nthr);
+  } else {  // one-wave workgroups (few attended tokens): plain loop over the chunks
+    auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    for (int x = tid; x < G * TKV_D; x += nthr) {
+      const int hh = x / TKV_D, c = x % TKV_D;
+      const float* base = head0 + (size_t)hh * p.n_chunks * TKV_PART_STRIDE;
+      float M = -INFINITY;
+      for (int k = 0; k < p.n_chunks; ++k) M = fmaxf(M, ld(base + (size_t)k * TKV_PART_STRIDE));
+      float L = 0.f, O = 0.f;
+      for (int k = 0; k < p.n_chunks; ++k) {
+        const float* pk = base + (size_t)k * TKV_PART_STRIDE;
+        const float mk = ld(pk);
+        const float w = mk == -INFINITY ? 0.f : exp2f(mk - M);
+        L = __builtin_fmaf(ld(pk + 1), w, L);
+        O = __builtin_fmaf(ld(pk + TKV_PART_O + c), w, O);
+      }
+      p.out[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
     }
-    p.out[head * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
   }
 }
 
