@@ -193,18 +193,13 @@ __device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint3
     const int cnt = min(32, r_total - 32 * sb);
     const int t0 = nq + 32 * sb;
     float x[4];
-    uint32_t v2[32];  // this lane's channel pair of every row: loaded up front, used last
     {
       const int tok = t0 + min(t, cnt - 1);
       const uintx4* krow = reinterpret_cast<const uintx4*>(p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D + 64 * half);
       uintx4 kv[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) kv[i] = krow[i];
-#pragma unroll
-      for (int y = 0; y < 32; ++y) {
-        const int tokv = t0 + min(y, cnt - 1);  // rows past the end re-read the last one with weight 0
-        v2[y] = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tokv % ring)) * TKV_D)[lane];
-      }
+      __builtin_amdgcn_sched_barrier(0);  // all eight loads in flight before the first is used
       float a[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -239,6 +234,13 @@ __device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint3
       acc[hh][1] *= alpha;
       M[hh] = mn;
     }
+    uint32_t v2[32];  // this lane's channel pair of every row
+#pragma unroll
+    for (int y = 0; y < 32; ++y) {
+      const int tokv = t0 + min(y, cnt - 1);  // rows past the end re-read the last one with weight 0
+      v2[y] = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tokv % ring)) * TKV_D)[lane];
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int y = 0; y < 32; ++y) {
       const half2_t vv = as_half2(v2[y]);
