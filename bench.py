@@ -36,7 +36,37 @@ def parse():
                     help="distinct pinned host K/V caches (30 = one per sparse layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["chained", "overlapped"], default="chained")
+    ap.add_argument("--gather-cus", type=int, default=16,
+                    help="overlapped schedule: compute units reserved for the gather stream (0 = no masks)")
     return ap.parse_args()
+
+
+def cu_masked_streams(n_gather_cus, n_cus=256):
+    """Two HIP streams with disjoint compute-unit masks: (gather stream on the first
+    n_gather_cus units, compute stream on the others), wrapped for torch.  None if the
+    runtime refuses."""
+    import ctypes as C
+    import torch
+    if n_gather_cus <= 0 or n_gather_cus >= n_cus:
+        return None
+    try:
+        hip = C.CDLL("libamdhip64.so")
+        fn = hip.hipExtStreamCreateWithCUMask
+    except (OSError, AttributeError):
+        return None
+    fn.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_uint32)]
+    fn.restype = C.c_int
+    words = n_cus // 32
+    bits_g = (1 << n_gather_cus) - 1
+    bits_c = ((1 << n_cus) - 1) ^ bits_g
+    out = []
+    for bits in (bits_g, bits_c):
+        mask = (C.c_uint32 * words)(*[(bits >> (32 * i)) & 0xFFFFFFFF for i in range(words)])
+        h = C.c_void_p()
+        if fn(C.byref(h), words, mask) != 0 or not h.value:
+            return None
+        out.append(torch.cuda.ExternalStream(h.value))
+    return out[0], out[1]
 
 
 def main():
@@ -122,14 +152,10 @@ def main():
     g = torch.Generator(device=dev); g.manual_seed(7)
     new_k = [torch.randn(1, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
     new_v = [torch.randn(1, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
-    compute = torch.cuda.current_stream()
-    side = torch.cuda.Stream()
-    chained = args.schedule == "chained"
-
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def step_overlapped():
+    def step_overlapped(compute, side):
         """Software-pipelined enqueue: while layer l's rows cross the host link on the side
         stream, layer l+1's append and scoring run on the compute stream.  Legal only
         because the synthetic queries of different layers are independent."""
@@ -156,9 +182,8 @@ def main():
             compute.wait_event(pe)
             layers[pl].attn(qs[pl], sm, out=outs[pl])
 
-    def step(rec=None):
-        if not chained and rec is None:
-            return step_overlapped()
+    def step_chained(rec=None):
+        """Every call of a layer waits for the previous one: what a real model allows."""
         for l, L in enumerate(layers):
             L.append(new_k[l], new_v[l])      # Eq. 2: the step's new token joins the cache first
             if l in QUANT_LAYERS:
@@ -173,36 +198,52 @@ def main():
                 L.estimate_topk(qs[l])
                 if rec is not None:
                     b.record(); rec["topk"].append((a, b))
-                if chained and rec is not None:   # per-call timing pass: the transfer on its own
+                if rec is not None:   # per-call timing pass: the transfer on its own
                     g0, g1 = ev(), ev(); g0.record()
                     L.gather()
                     g1.record(); rec["gather"].append((g0, g1))
                     L.attn(qs[l], sm, out=outs[l])
-                elif chained:                     # one stream: the attention kernel fetches the rows itself
+                else:                 # one stream: the attention kernel fetches the rows itself
                     L.gather_attn(qs[l], sm, out=outs[l])
-                else:
-                    L.gather_attn(qs[l], sm, out=outs[l], gather_stream=side, compute_stream=compute)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # timed region: exactly K steps
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
+    def timed(schedule):
+        """W untimed warm-up steps, then exactly K timed steps; returns ms per step (None if
+        the schedule cannot be set up)."""
+        import contextlib
+        if schedule == "chained":
+            ctx, step = contextlib.nullcontext(), step_chained
+        else:
+            # A kernel that shares compute units with the gather is slowed to the pace of the
+            # host link (its memory instructions queue behind the gather's): the gather gets
+            # compute units of its own and everything else the rest.
+            masked = cu_masked_streams(args.gather_cus)
+            if masked is None:
+                side, compute = torch.cuda.Stream(), torch.cuda.current_stream()
+                ctx = contextlib.nullcontext()
+            else:
+                side, compute = masked
+                ctx = torch.cuda.stream(compute)
+            step = lambda: step_overlapped(compute, side)
+        with ctx:
+            for _ in range(args.warmup):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / args.steps * 1e3
+
+    ms_per_step = timed(args.schedule)
+    other = "overlapped" if args.schedule == "chained" else "chained"
+    ms_other = timed(other)
 
     # per-kernel durations with events on the launching stream (separate passes so the
     # events do not perturb the step time above)
     rec = {"quant": [], "topk": [], "gather": []}
-    chained_was = chained
-    chained = True
     for _ in range(max(3, args.steps // 2)):
-        step(rec)
+        step_chained(rec)
     torch.cuda.synchronize()
-    chained = chained_was
     dur = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) * 1e3 for k, v in rec.items() if v}  # us
 
     nq = (N - 128) // 32 * 32
@@ -218,6 +259,8 @@ def main():
     extra = {
         "quant_attn_us": dur["quant"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"],
         "estimate_topk_GBs": summary_bytes / dur["topk"] / 1e3,
+        "other_schedule": {"schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS,
+                           "gather_compute_units": args.gather_cus},
         "host_link": {"bound": "host_link", "kernel": "tkv_sparse_gather", "achieved": gather_bytes / dur["gather"] / 1e3,
                       "peak": h2d, "unit": "GB/s", "frac": gather_bytes / dur["gather"] / 1e3 / h2d,
                       "peak_source": "pinned 1 GiB hipMemcpy H2D measured in this run"},

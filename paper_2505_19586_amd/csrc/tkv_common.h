@@ -137,8 +137,8 @@ __device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __h
 //   cand  uint2  [BH][capacity]   (key, token) pairs in or above the threshold bin; the workgroup
 //                                 that owns tokens [4096 x, 4096 x + 4096) lists them from entry 4096 x
 //   hist  uint32 [BH][8192]       histogram of the 13-bit key prefix
-//   ctrl  uint32 [BH][8]          0, 1: arrival counters of the two Top-K launches; 2: bin of the
-//                                 k-th key; 3: keys above the bin; 4: arrival counter of the attention
+//   ctrl  uint32 [BH][8]          1: arrival counter of the Top-K selection; 4: arrival counter of
+//                                 the attention
 //   blk   uint32 [BH][nblk_cap]   length of each workgroup's list
 //   parts float  [B][Hq][64][D+4] split partials of the sparse attention
 struct SparseWs {

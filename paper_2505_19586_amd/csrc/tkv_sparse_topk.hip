@@ -6,8 +6,9 @@
 // the workspace must be zero before the first call; every call leaves them zero):
 //   score    reads the key summary once, computes S(t) in the pinned float32 order, writes
 //            an order-preserving 32-bit key per token and adds its 13-bit-prefix histogram
-//            to the head's; the last workgroup of a head locates the bin of the k-th key;
-//   select   every workgroup lists its own tokens in or above that bin, in token order; the
+//            to the head's;
+//   select   every workgroup locates the bin of the k-th key in the head's histogram and
+//            lists its own tokens in or above that bin, in token order; the
 //            last workgroup of a head concatenates the lists (a few thousand entries, in
 //            LDS), finds the exact threshold by radix select on the remaining 19 key bits
 //            and writes the selected tokens in token order.
@@ -31,7 +32,7 @@ constexpr int kListCap = 8192;  // candidate entries kept in LDS; further ones g
 constexpr int kScoreLds = kBins * 4;
 constexpr int kSelectLds = 1024 * 4 + kListCap * 8;
 
-enum Ctrl { kDone = 0, kDone2 = 1, kBin = 2, kAbove = 3, kCtrlWords = 8 };
+enum Ctrl { kDone2 = 1, kCtrlWords = 8 };
 
 struct TopkParams {
   const __half* summary;
@@ -211,45 +212,9 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
     }
   }
   uint32_t* gh = p.ws.hist + bh * kBins;
-  uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
   for (int i = tid; i < kBins; i += kThreads)
     if (i >= (int)first_bin && hist[i]) atomicAdd(&gh[i], hist[i]);
-  // Last workgroup of this head: the histogram is only touched with device-scope atomics,
-  // which do not wait in a cache; waiting for this wave's own to complete orders them before
-  // the arrival counter without a cache write-back.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   TKV_PH(2);
-  __syncthreads();
-  if (tid == 0) {
-    const uint32_t nblk = (uint32_t)((n + kTok - 1) / kTok);
-    scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone], 1u) == nblk - 1u;
-  }
-  __syncthreads();
-  if (!scratch[kWavesPerBlock + 2]) return;
-  TKV_PH(3);
-  // the head's bin is never below this block's own first_bin: lower bins are not needed;
-  // histogram and counter are left zero for the next call
-  {
-    uint32_t hv[kBins / kThreads];
-#pragma unroll
-    for (int x = 0; x < kBins / kThreads; ++x) hv[x] = ld_agent(&gh[x * kThreads + tid]);
-#pragma unroll
-    for (int x = 0; x < kBins / kThreads; ++x) {
-      const int i = x * kThreads + tid;
-      hist[i] = i >= (int)first_bin ? hv[x] : 0u;
-      st_agent(&gh[i], 0u);
-    }
-  }
-  if (tid == 0) st_agent(&ctrl[kDone], 0u);
-  __syncthreads();
-  if (k == 0) return;
-  uint32_t bin, above;
-  find_bin(hist, kBins, k, scratch, bin, above);
-  if (tid == 0) {  // read by the next launch
-    ctrl[kBin] = bin;
-    ctrl[kAbove] = above;
-  }
-  TKV_PH(4);
 }
 
 __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
@@ -276,20 +241,35 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   const int t0 = blockIdx.x * kTok;
   if (t0 >= n) return;
   uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
-  const uint32_t bin = ctrl[kBin], above = ctrl[kAbove];
+  uint32_t* gh = p.ws.hist + bh * kBins;
   const uint32_t* keys = p.ws.keys + bh * p.capacity;
   uint2* list_g = p.ws.cand + bh * (size_t)p.capacity;  // workgroup x owns entries [x * kTok, +kTok)
   uint32_t* cnt_g = p.ws.blk + bh * p.ws.nblk_cap;
   const int nblk = (n + kTok - 1) / kTok;
 
+  // ---- bin of the head's k-th key, found by every workgroup for itself from the head's
+  // histogram (complete for every bin that can matter: see the scoring kernel); the keys of
+  // this workgroup are requested in the same round
+  uint32_t kb[kPer];
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {  // sub-tile j, element tid: token order = (j, tid)
+    const int t = t0 + j * kThreads + tid;
+    kb[j] = t < n ? keys[t] : 0u;
+  }
+  uint32_t bin, above;
+  {
+    uint32_t* h8 = reinterpret_cast<uint32_t*>(list_s);  // the list area is not in use yet
+    uint32_t hv[kBins / kThreads];
+#pragma unroll
+    for (int x = 0; x < kBins / kThreads; ++x) hv[x] = ld_agent(&gh[x * kThreads + tid]);
+#pragma unroll
+    for (int x = 0; x < kBins / kThreads; ++x) h8[x * kThreads + tid] = hv[x];
+    __syncthreads();
+    find_bin(h8, kBins, k, scratch, bin, above);
+  }
+
   // ---- this workgroup's tokens in or above the bin, in token order
   {
-    uint32_t kb[kPer];
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {  // sub-tile j, element tid: token order = (j, tid)
-      const int t = t0 + j * kThreads + tid;
-      kb[j] = t < n ? keys[t] : 0u;
-    }
     unsigned long long mask[kPer];
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
@@ -320,7 +300,9 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   if (tid == 0) scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone2], 1u) == (uint32_t)nblk - 1u;
   __syncthreads();
   if (!scratch[kWavesPerBlock + 2]) return;
+  // every workgroup has read the histogram: leave it and the counter zero for the next call
   if (tid == 0) st_agent(&ctrl[kDone2], 0u);
+  for (int i = tid; i < kBins; i += kThreads) st_agent(&gh[i], 0u);
   for (int i = (int)k + tid; i < p.top_k; i += kThreads) out[i] = -1;
   if (tid == 0) p.topk_count[bh] = (int32_t)k;
 
