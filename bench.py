@@ -36,6 +36,7 @@ def parse():
                     help="distinct pinned host K/V caches (30 = one per sparse layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["chained", "overlapped"], default="chained")
+    ap.add_argument("--one-schedule", action="store_true", help="time only --schedule (profiling runs)")
     ap.add_argument("--gather-cus", type=int, default=16,
                     help="overlapped schedule: compute units reserved for the gather stream (0 = no masks)")
     return ap.parse_args()
@@ -59,14 +60,20 @@ def cu_masked_streams(n_gather_cus, n_cus=256):
     words = n_cus // 32
     bits_g = (1 << n_gather_cus) - 1
     bits_c = ((1 << n_cus) - 1) ^ bits_g
-    out = []
+    out, handles = [], []
     for bits in (bits_g, bits_c):
         mask = (C.c_uint32 * words)(*[(bits >> (32 * i)) & 0xFFFFFFFF for i in range(words)])
         h = C.c_void_p()
         if fn(C.byref(h), words, mask) != 0 or not h.value:
             return None
+        handles.append(h)
         out.append(torch.cuda.ExternalStream(h.value))
-    return out[0], out[1]
+
+    def destroy():
+        hip.hipStreamDestroy.argtypes = [C.c_void_p]
+        for h in handles:
+            hip.hipStreamDestroy(h)
+    return out[0], out[1], destroy
 
 
 def main():
@@ -210,6 +217,7 @@ def main():
         """W untimed warm-up steps, then exactly K timed steps; returns ms per step (None if
         the schedule cannot be set up)."""
         import contextlib
+        destroy = None
         if schedule == "chained":
             ctx, step = contextlib.nullcontext(), step_chained
         else:
@@ -221,7 +229,7 @@ def main():
                 side, compute = torch.cuda.Stream(), torch.cuda.current_stream()
                 ctx = contextlib.nullcontext()
             else:
-                side, compute = masked
+                side, compute, destroy = masked
                 ctx = torch.cuda.stream(compute)
             step = lambda: step_overlapped(compute, side)
         with ctx:
@@ -232,11 +240,14 @@ def main():
             for _ in range(args.steps):
                 step()
             torch.cuda.synchronize()
-            return (time.perf_counter() - t0) / args.steps * 1e3
+            ms = (time.perf_counter() - t0) / args.steps * 1e3
+        if destroy is not None:
+            destroy()
+        return ms
 
     ms_per_step = timed(args.schedule)
     other = "overlapped" if args.schedule == "chained" else "chained"
-    ms_other = timed(other)
+    ms_other = None if args.one_schedule else timed(other)
 
     # per-kernel durations with events on the launching stream (separate passes so the
     # events do not perturb the step time above)
@@ -253,14 +264,15 @@ def main():
     gather_bytes = 8 * args.top_k * 512
     roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "traffic": traffic_from_profile("quant_attn_mfma_kernel<%d>" % args.bits) if N == 131072 else None,
+            "traffic": traffic_from_profile("quant_attn_mfma_kernel<%d" % args.bits) if N == 131072 else None,
             "algorithmic_bytes": quant_bytes}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {
         "quant_attn_us": dur["quant"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"],
         "estimate_topk_GBs": summary_bytes / dur["topk"] / 1e3,
-        "other_schedule": {"schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS,
-                           "gather_compute_units": args.gather_cus},
+        "other_schedule": None if ms_other is None else {
+            "schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS,
+            "gather_compute_units": args.gather_cus},
         "host_link": {"bound": "host_link", "kernel": "tkv_sparse_gather", "achieved": gather_bytes / dur["gather"] / 1e3,
                       "peak": h2d, "unit": "GB/s", "frac": gather_bytes / dur["gather"] / 1e3 / h2d,
                       "peak_source": "pinned 1 GiB hipMemcpy H2D measured in this run"},
@@ -291,7 +303,7 @@ def traffic_from_profile(kernel: str):
     try:
         for line in open(path):
             cells = [c.strip() for c in line.split("|")]
-            if len(cells) > 5 and cells[1] == kernel:
+            if len(cells) > 5 and cells[1].startswith(kernel):
                 return float(cells[3]) * 1e6 + float(cells[4]) * 1024.0
     except (OSError, ValueError):
         pass
