@@ -147,7 +147,8 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
 /* Test and tuning hook (process-wide, not thread-safe): kernel_choice 0 = matrix-core
  * kernel, which also covers the fp16 tail (default), 1 = shape-generic
  * reference kernel for everything; target_blocks > 0 sets the number of workgroups
- * the split-K launch aims at (0 keeps the current value). */
+ * the split-K launch aims at (0 keeps the current value; the launch uses at most 64
+ * chunks per (sequence, KV head) unless target_blocks asks for more than that). */
 int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks);
 
 /* ---------------------------------------------------------------------------------

@@ -835,7 +835,9 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   int n_chunks = (target_blocks + bh - 1) / bh;
   const int c_work = (work + waves - 1) / waves;
   if (n_chunks > c_work) n_chunks = c_work;
-  if (n_chunks > 64) n_chunks = 64;
+  // at most 64 chunks, unless the tuning hook asks for more workgroups than that gives
+  const int chunk_cap = target_blocks > 64 * bh ? TKV_MAX_CHUNKS : 64;
+  if (n_chunks > chunk_cap) n_chunks = chunk_cap;
   if (n_chunks < 1) n_chunks = 1;
   if ((work + n_chunks - 1) / n_chunks > kMaxGpc) n_chunks = (work + kMaxGpc - 1) / kMaxGpc;
   if (n_chunks > TKV_MAX_CHUNKS) return TKV_E_UNSUPPORTED;

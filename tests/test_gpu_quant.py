@@ -115,3 +115,24 @@ def test_peaked_attention_and_extreme_values():
     ref = check_quant_cache(layer, 0, inp.k, inp.v)
     out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
     assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
+
+
+def test_many_chunks(kernel_choice):
+    """More split-K chunks than the usual cap of 64 (forced through the tuning hook): the
+    cross-chunk merge then runs in several rounds."""
+    if kernel_choice != "mfma":
+        pytest.skip("chunk count of the matrix-core kernel")
+    n = 16384 + 77
+    inp = make_layer(n, config=1, layer=1, seq=31)
+    layer = tkv.QuantLayer(bits=2, capacity=16384 + 128)
+    layer.append(to_new(inp.k), to_new(inp.v))
+    ref = quant.quantize_kv(inp.k, inp.v, bits=2, group=32, residual=128)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    want = attention.quant_attention(inp.q, ref, SM)
+    try:
+        for target in (8 * 100, 8 * 256):
+            tkv.debug_quant_attn_config(0, target)
+            out = layer.attn_decode(q, SM)
+            assert attn_err(out[0], want) <= TOL
+    finally:
+        tkv.debug_quant_attn_config(0, 256)

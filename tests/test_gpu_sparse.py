@@ -147,3 +147,24 @@ def test_other_shapes(shape, n_channels):
     layer.estimate_topk(q)
     out = layer.gather_attn(q, SM)
     _check_layer(layer, 0, inp, ch, q, out)
+
+
+def test_ties_beyond_the_on_chip_list():
+    """All scores equal at a length where the candidates (every token) do not fit the
+    selection kernel's on-chip list: indices are still n_sink .. n_sink + k - 1."""
+    n, top_k = 20000, 1024
+    inp = make_layer(n, seq=33)
+    ch = static_channels(inp.k, 16)
+    k = inp.k.copy()
+    for h in range(8):
+        k[h][:, ch[h]] = np.float16(0.5)
+    layer = tkv.SparseLayer(top_k=top_k, capacity=n)
+    layer.set_channels(ch[None])
+    layer.append(to_new(k), to_new(inp.v))
+    q = torch.from_numpy(inp.q)[None].cuda()
+    idx, cnt = layer.estimate_topk(q)
+    torch.cuda.synchronize()
+    want_idx, want_cnt = sparse.estimate_topk(inp.q, sparse.key_summary(k, ch), ch, n, top_k=top_k, n_sink=4, n_window=64)
+    assert np.array_equal(cnt[0].cpu().numpy(), want_cnt)
+    assert np.array_equal(idx[0].cpu().numpy(), want_idx)
+    assert np.array_equal(want_idx[0, :top_k], np.arange(4, 4 + top_k))
