@@ -55,8 +55,8 @@ struct MfmaParams {
   float scale2;
   int32_t hq, hkv, residual, capacity;
   int32_t n_chunks;
-#if defined(TKV_PHASE) || defined(TKV_PROF)
-  long long* prof;  // timestamps (profiling builds only)
+#ifdef TKV_PHASE
+  long long* prof;  // phase time stamps (profiling builds only)
 #endif
   TkvSeqLens lens;
 };
@@ -281,24 +281,6 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_next;
   __shared__ uint32_t s_flag;
-#ifdef TKV_PROF
-  __shared__ long long s_prof[W][80];
-  int prof_n = 0;
-#define TKV_TS()                                   \
-  do {                                             \
-    __builtin_amdgcn_sched_barrier(0);             \
-    if (prof_n < 80) {                             \
-      const long long t_ = clock64();              \
-      if (lane == 0) s_prof[wave][prof_n] = t_;    \
-      ++prof_n;                                    \
-    }                                              \
-    __builtin_amdgcn_sched_barrier(0);             \
-  } while (0)
-#else
-#define TKV_TS() \
-  do {           \
-  } while (0)
-#endif
 #ifdef TKV_PHASE
   long long ph[8];
   int ph_n = 0;
@@ -321,11 +303,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   const int gpc = max(1, (jq + tail_equiv + p.n_chunks - 1) / p.n_chunks);
   const int blk0 = min(chunk * gpc, jq);
   const int blk1 = has_tail ? jq : min(blk0 + gpc, jq);
-#ifdef TKV_ABL_NOMEM  // timing experiment: every load hits the chunk's first group (results are wrong)
-  const int last = blk0;
-#else
   const int last = max(blk1 - 1, blk0);  // groups past the chunk are clamped (and ignored); jq >= 1 here
-#endif
 
   const int slot = lane % 16, rb = lane / 16;
   const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, column group
@@ -655,31 +633,23 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     // results are dropped by leaving the loop.  gc = group i (valid), gn3 / gv2 = groups
     // whose K / V part is fetched now.  LDS reads go out one stage ahead of their use.
     auto step = [&](int gc, int gn3, int gv2, floatx4 (&acc_c)[2], floatx4 (&acc_n)[2]) {
-      TKV_TS();  // 0
       QkIn qi;
       read_qk(kq, qi);  // K(i+1) landed during the previous step
       __builtin_amdgcn_sched_barrier(0);
       load_kpart(kl, gn3);
       load_vpart(vl, gv2);
-      TKV_TS();  // 1 loads issued
       TKV_WAIT_VMCNT(2 * L);  // K(i+1), V(i) landed
       PvIn pi;
       read_pv(vp, gc, pi);
       __builtin_amdgcn_sched_barrier(0);
-      TKV_TS();  // 2
       stage_qk(qi, acc_n);
-      TKV_TS();  // 3 QK
       POps po;
       stage_soft(pi, acc_c, po);
-      TKV_TS();  // 4 soft
       TKV_WAIT_VMCNT(L + C::kVLoads);  // + K(i+2)
       const uint32_t ks2 = read_ks(kk);
       __builtin_amdgcn_sched_barrier(0);
       stage_pv(pi, po);
-      TKV_TS();  // 5 PV
       stage_k(ks2);
-      TKV_TS();  // 6 stage_k
-      TKV_TS();  // 7
       uint32_t t = kq;
       kq = kk, kk = kl, kl = t;
       t = vp;
@@ -700,12 +670,6 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   }
 #undef TKV_WAIT_VMCNT
   TKV_PH();  // 4 this wave's groups done
-#ifdef TKV_PROF
-  if (p.prof && lane == 0) {
-    long long* dst = p.prof + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * W + wave) * 80;
-    for (int i = 0; i < 80; ++i) dst[i] = i < prof_n ? s_prof[wave][i] : 0;
-  }
-#endif
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct-to-LDS load may land after the ring is reused
   __syncthreads();
   TKV_PH();  // 5 all waves done
@@ -817,7 +781,7 @@ int32_t launch_variant(const MfmaParams& p, dim3 grid, hipStream_t s) {
 }  // namespace
 
 namespace tkv {
-#if defined(TKV_PHASE) || defined(TKV_PROF)
+#ifdef TKV_PHASE
 void* g_mfma_prof = nullptr;
 #endif
 
@@ -860,7 +824,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.residual = d->residual;
   p.capacity = d->capacity;
   p.n_chunks = n_chunks;
-#if defined(TKV_PHASE) || defined(TKV_PROF)
+#ifdef TKV_PHASE
   p.prof = (long long*)g_mfma_prof;
 #endif
   p.lens = lens;
@@ -872,7 +836,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
 
 }  // namespace tkv
 
-#if defined(TKV_PHASE) || defined(TKV_PROF)
-// profiling builds: device buffer that receives per-wave time stamps
+#ifdef TKV_PHASE
+// profiling builds (-DTKV_PHASE): device buffer that receives [workgroup][wave][8] wall-clock stamps
 extern "C" void tkv_debug_set_dump(void* ptr) { tkv::g_mfma_prof = ptr; }
 #endif
