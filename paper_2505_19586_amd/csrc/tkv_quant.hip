@@ -35,7 +35,9 @@ __device__ inline float quant_code(float x, float z, float s, float qmax) {
   return s == 0.0f ? 0.0f : c;
 }
 
-// One workgroup quantizes one 32-token group of one KV head.
+// One workgroup quantizes one 32-token group of one KV head.  BITS is a template parameter so
+// that the packed-layout index arithmetic folds to shifts and masks.
+template <int BITS>
 __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p) {
   __shared__ __half kt[TKV_G][TKV_D];
   __shared__ __half vt[TKV_G][TKV_D];
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p
   }
   __syncthreads();
 
-  const float qmax = (float)((1 << p.bits) - 1);
+  constexpr float qmax = (float)((1 << BITS) - 1);
   if (tid < TKV_D) {
     // keys: one (s, z) per channel over the group's 32 tokens
     const int c = tid;
@@ -113,20 +115,23 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p
   }
   __syncthreads();
 
-  const int nwords = TKV_D * p.bits;  // 32*128*bits/32
-  const int nfields = 32 / p.bits;
+  constexpr int nwords = TKV_D * BITS;  // 32*128*bits/32
+  constexpr int nfields = 32 / BITS;
   uint32_t* kdst = p.k_codes + (bh * n_groups_cap + j) * (size_t)nwords;
   uint32_t* vdst = p.v_codes + (bh * n_groups_cap + j) * (size_t)nwords;
-  for (int w = tid; w < nwords; w += 256) {
+#pragma unroll
+  for (int w0 = 0; w0 < nwords; w0 += 256) {
+    const int w = w0 + tid;
     uint32_t kw = 0, vw = 0;
+#pragma unroll
     for (int f = 0; f < nfields; ++f) {
       int t, c;
-      tkv::k_code_elem(p.bits, w, f, t, c);
+      tkv::k_code_elem(BITS, w, f, t, c);
       const float kc = quant_code(__half2float(kt[t][c]), kz[c], ks[c], qmax);
-      kw |= (uint32_t)kc << (p.bits * f);
-      tkv::v_code_elem(p.bits, w, f, t, c);
+      kw |= (uint32_t)kc << (BITS * f);
+      tkv::v_code_elem(BITS, w, f, t, c);
       const float vc = quant_code(__half2float(vt[t][c]), vz[t][c / TKV_G], vs[t][c / TKV_G], qmax);
-      vw |= (uint32_t)vc << (p.bits * f);
+      vw |= (uint32_t)vc << (BITS * f);
     }
     kdst[w] = kw;
     vdst[w] = vw;
@@ -200,7 +205,11 @@ extern "C" int32_t tkv_quantize_append_ragged(const tkv_quant_desc* d, tkv_quant
 
   hipStream_t s = (hipStream_t)stream;
   if (max_groups > 0) {
-    quantize_group_kernel<<<dim3(max_groups, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+    const dim3 grid(max_groups, d->n_kv_heads, d->batch);
+    if (d->bits == 2)
+      quantize_group_kernel<2><<<grid, 256, 0, s>>>(p);
+    else
+      quantize_group_kernel<4><<<grid, 256, 0, s>>>(p);
     if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   }
   if (max_copy > 0) {
