@@ -35,7 +35,7 @@ namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
@@ -69,7 +69,6 @@ __device__ inline floatx4 mfma(uintx4 a, uintx4 b, floatx4 c) {
 // __builtin_bit_cast directly to an element of an ext-vector (vec[j]) reads element 0
 // for every j with this compiler.
 __device__ inline half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
-__device__ inline ushort2_t as_ushort2(uint32_t w) { return __builtin_bit_cast(ushort2_t, w); }
 
 __device__ inline uint32_t pack2(_Float16 lo, _Float16 hi) {
   half2_t v = {lo, hi};
@@ -549,30 +548,28 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   };
   // The weights 2^(x - m_run) go to the matrix cores as fp16, so m_run (a per-head reference,
   // not necessarily the running maximum) only has to keep them below 2^kHeadroomLog2: that
-  // is checked on the packed fp16 weights themselves, and only a failed check (rare after
-  // the first groups) pays for the exact maximum, the accumulator rescale and a second pass.
+  // is checked on the weights themselves (an integer maximum of their bit patterns), and
+  // only a failed check (rare after the first groups) pays for the exact maximum, the
+  // accumulator rescale and a second pass.
   auto stage_soft = [&](const PvIn& in, const floatx4 (&acc_s)[2], POps& o) {
     const float cz = in.cz;
     float xs[8];  // hi + lo partial sums: every lane of a head ends up with the full logit
 #pragma unroll
     for (int x = 0; x < 8; ++x) xs[x] = ror4_add(acc_s[x / 4][x % 4]);
+    float pw[8];
     auto weights = [&]() {
       const float czm = cz - m_run;
-      float pw[8];
 #pragma unroll
       for (int x = 0; x < 8; ++x) pw[x] = __builtin_amdgcn_exp2f(__builtin_fmaf(xs[x], K1, czm + off[x]));
-#pragma unroll
-      for (int j = 0; j < 4; ++j) o.bp[j] = pack2((_Float16)pw[2 * j], (_Float16)pw[2 * j + 1]);
     };
     weights();
     {
-      // fp16 bit patterns of non-negative numbers (and of inf / NaN) order like integers
-      const ushort2_t m01 = __builtin_elementwise_max(as_ushort2(o.bp[0]), as_ushort2(o.bp[1]));
-      const ushort2_t m23 = __builtin_elementwise_max(as_ushort2(o.bp[2]), as_ushort2(o.bp[3]));
-      const uint32_t mm = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(m01, m23));
-      constexpr uint32_t kLimit = (uint32_t)(15 + kEP + kHeadroomLog2) << 26;  // fp16 2^(kEP + headroom), upper half
-      const bool over = mm >= kLimit || (mm << 16) >= kLimit;
-      if (__builtin_amdgcn_ballot_w64(over) != 0ull) {
+      // bit patterns of non-negative floats (and of inf / NaN) order like integers
+      uint32_t mm = 0u;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) mm = max(mm, __builtin_bit_cast(uint32_t, pw[x]));
+      constexpr uint32_t kLimit = (uint32_t)(127 + kEP + kHeadroomLog2) << 23;  // 2^(kEP + headroom)
+      if (__builtin_amdgcn_ballot_w64(mm >= kLimit) != 0ull) {
         const float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
         float mn = fmaxf(m_run, __builtin_fmaf(mx, K1, cz));  // largest logit among this lane's 8 tokens
         mn = fmaxf(mn, __shfl_xor(mn, 4, 64));
@@ -589,6 +586,8 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      const float2_t w2 = {pw[2 * j], pw[2 * j + 1]};
+      o.bp[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(w2, half2_t));
       // weight x scaler: one rounding of the exact product of two fp16 numbers
       const uint32_t bpj = o.bp[j], svj = in.sv[j], zvj = in.zv[j];
       o.b2[j] = __builtin_bit_cast(uint32_t, as_half2(bpj) * as_half2(svj));
