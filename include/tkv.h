@@ -22,8 +22,9 @@
  *     arrays; kernels receive them by value, so the arrays may be changed as soon as
  *     a call returns.  At most TKV_MAX_BATCH sequences per call.
  *   - fp16 is IEEE binary16 everywhere.  head_dim must be 128, the quantization
- *     group 32, n_q_heads / n_kv_heads one of 1, 2, 4.
- *   - Token t of sequence b, KV head h.  "group j" is tokens [32j, 32j+32).
+ *     group g 32 or 64, n_q_heads / n_kv_heads one of 1, 2, 4.
+ *   - Token t of sequence b, KV head h.  "group j" is tokens [g j, g j + g); codes are
+ *     stored in "blocks" of 32 tokens whatever g is.
  */
 #ifndef TKV_H
 #define TKV_H
@@ -58,9 +59,10 @@ typedef struct {
   int32_t n_q_heads;    /* Hq                                                            */
   int32_t n_kv_heads;   /* Hkv; query head i reads KV head i / (Hq/Hkv)                  */
   int32_t head_dim;     /* D = 128                                                       */
-  int32_t bits;         /* b = 2 or 4 (Eq. 4)                                            */
-  int32_t group_size;   /* g = 32: tokens per key group, channels per value group        */
-  int32_t residual;     /* W: newest tokens kept fp16; multiple of g, g <= W <= 992      */
+  int32_t bits;         /* b = 1, 2 or 4 (Eq. 4); Sec. 5.1 runs 1 and 2                  */
+  int32_t group_size;   /* g = 32 or 64 (Sec. 5.1: 64): tokens per key group, channels
+                           per value group                                               */
+  int32_t residual;     /* W: newest tokens kept fp16; multiple of g, g <= W <= 1024 - g */
   int32_t capacity;     /* max tokens per sequence, multiple of g                        */
   int32_t batch;        /* B, 1..TKV_MAX_BATCH                                           */
 } tkv_quant_desc;
@@ -70,23 +72,27 @@ typedef struct {
  * Nq = g*floor((N-W)/g) (0 if N < W) are quantized, the last N-Nq (W..W+g-1 once
  * N >= W) are fp16 in a ring: token t >= Nq sits at ring slot t mod (W+g).
  *
- * Packed layouts (J = capacity/32 groups; t = token inside its group, c = channel;
- * a code takes `bits` bits at field F, i.e. bits [bits*F, bits*F+bits) of a
- * little-endian 32-bit word).  The order inside a group is the order in which a
- * wave64 feeds 16x16x32 matrix-core operands from one 128-bit load per lane.
+ * Packed layouts (J = capacity/32 blocks of 32 tokens; t = token inside its block,
+ * c = channel; a code takes `bits` bits at field F, i.e. bits [bits*F, bits*F+bits)
+ * of a little-endian 32-bit word).  The order inside a block is the order in which a
+ * wave64 feeds 16x16x32 matrix-core operands from its loads.
  *
- *  k_codes uint32 [B][Hkv][J][128*bits/... = 32*128*bits/32 words]
+ *  k_codes uint32 [B][Hkv][J][32*128*bits/32 words]
+ *    1 bit: word = 64*tau + lane, F = (c%8)/2 + 4*((c/32)%2) + 8*(c/64) + 16*(c%2)
+ *           (r, tau, lane as for 2 bit)
  *    2 bit: word = 4*lane + 2*tau + wd,  F = f + 8*e, with
  *           r = 4*(t/8) + t%4, tau = (t%8)/4, lane = r + 16*((c%32)/8),
  *           wd = c/64, f = (c%8)/2 + 4*((c/32)%2), e = c%2
  *    4 bit: word = 256*tau + 4*lane + c/32, F = (c%8)/2 + 4*(c%2)   (r, tau, lane as above)
  *  v_codes uint32 [B][Hkv][J][32*128*bits/32 words]
+ *    1 bit: word = 64*(c/64) + lane, F = (t%8)/2 + 4*((c/16)%2) + 8*((c/32)%2) + 16*(t%2)
+ *           (lane as for 2 bit)
  *    2 bit: word = 4*lane + wd, F = f + 8*e, with
  *           lane = c%16 + 16*(t/8), wd = c/32, f = (t%8)/2 + 4*((c/16)%2), e = t%2
  *    4 bit: word = 256*(c/64) + 4*lane + (c/16)%4, F = (t%8)/2 + 4*(t%2)
- *  k_scale, k_zero  fp16 [B][Hkv][J][128]      one (s, z) per group and channel
- *  v_scale, v_zero  fp16 [B][Hkv][J][4][32]    one (s, z) per token and 32-channel
- *                                              group u = c/32, stored [u][t]
+ *  k_scale, k_zero  fp16 [B][Hkv][capacity/g][128]   one (s, z) per group and channel
+ *  v_scale, v_zero  fp16 [B][Hkv][J][128/g][32]       one (s, z) per token and g-channel
+ *                                                     group u = c/g, stored per block [u][t]
  *  k_resid, v_resid fp16 [B][Hkv][W+g][128]    ring of unquantized tokens
  */
 typedef struct {
@@ -113,8 +119,8 @@ int32_t tkv_quant_cache_sizes(const tkv_quant_desc* desc, size_t bytes_out[8], s
  * Sec. 2.1 Eq. 2 (cache update) + Sec. 2.2 Eq. 4 / Sec. 4.3 (static quantization).
  * Appends n_new tokens to every sequence: k_new, v_new fp16 [B][n_new][Hkv][128]
  * (device).  Every token group that becomes complete and older than the residual is
- * quantized: keys per channel over the group's 32 tokens, values per token over each
- * 32-channel group, with
+ * quantized: keys per channel over the group's g tokens, values per token over each
+ * g-channel group, with
  *     z = min X (stored as is), s = fp16( (f32(max X) - f32(min X)) / f32(2^b - 1) ),
  *     code = clamp( rint( (f32(x) - f32(z)) / f32(s) ), 0, 2^b - 1 ), rint ties-to-even,
  *     code = 0 where the stored s is 0,

@@ -31,10 +31,10 @@ int32_t check_quant_desc(const tkv_quant_desc* d) {
   int32_t st = check_heads(d->n_q_heads, d->n_kv_heads, d->head_dim, d->batch);
   if (st != TKV_OK) return st;
   if (d->group_size <= 0 || d->residual < 0 || d->capacity <= 0 || d->bits <= 0) return TKV_E_INVAL;
-  if (d->bits != 2 && d->bits != 4) return TKV_E_UNSUPPORTED;
-  if (d->group_size != TKV_G) return TKV_E_UNSUPPORTED;
-  if (d->residual % TKV_G != 0 || d->capacity % TKV_G != 0) return TKV_E_INVAL;
-  if (d->residual < TKV_G || d->residual > 992) return TKV_E_UNSUPPORTED;
+  if (d->bits != 1 && d->bits != 2 && d->bits != 4) return TKV_E_UNSUPPORTED;
+  if (d->group_size != 32 && d->group_size != 64) return TKV_E_UNSUPPORTED;
+  if (d->residual % d->group_size != 0 || d->capacity % d->group_size != 0) return TKV_E_INVAL;
+  if (d->residual < d->group_size || d->residual + d->group_size > 1024) return TKV_E_UNSUPPORTED;
   return TKV_OK;
 }
 
@@ -57,9 +57,10 @@ extern "C" int32_t tkv_quant_cache_sizes(const tkv_quant_desc* d, size_t bytes_o
   const size_t bh = (size_t)d->batch * d->n_kv_heads;
   const size_t cap = (size_t)d->capacity;
   const size_t codes = bh * cap * TKV_D * d->bits / 8;
-  const size_t kmeta = bh * (cap / TKV_G) * TKV_D * 2;
-  const size_t vmeta = bh * cap * (TKV_D / TKV_G) * 2;
-  const size_t resid = bh * (size_t)(d->residual + TKV_G) * TKV_D * 2;
+  const size_t g = (size_t)d->group_size;
+  const size_t kmeta = bh * (cap / g) * TKV_D * 2;
+  const size_t vmeta = bh * cap * (TKV_D / g) * 2;
+  const size_t resid = bh * ((size_t)d->residual + g) * TKV_D * 2;
   if (bytes_out) {
     bytes_out[0] = codes;
     bytes_out[1] = kmeta;

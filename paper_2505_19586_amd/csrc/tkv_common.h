@@ -8,7 +8,7 @@
 #include "tkv.h"
 
 #define TKV_D 128      // head_dim
-#define TKV_G 32       // quantization group
+#define TKV_BLK 32     // tokens per block of packed codes (the quantization group is 32 or 64)
 #define TKV_WAVE 64
 
 // Partial attention result of one chunk and one query head, in floats: max logit (in log2
@@ -32,9 +32,9 @@ struct TkvSeqLens {
 
 namespace tkv {
 
-// Number of quantized tokens of a sequence of n tokens (residual w, group 32).
-__host__ __device__ inline int32_t n_quantized(int32_t n, int32_t w) {
-  return n >= w ? ((n - w) / TKV_G) * TKV_G : 0;
+// Number of quantized tokens of a sequence of n tokens (residual w, group g).
+__host__ __device__ inline int32_t n_quantized(int32_t n, int32_t w, int32_t g) {
+  return n >= w ? ((n - w) / g) * g : 0;
 }
 
 inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? TKV_OK : TKV_E_HIP; }
@@ -178,12 +178,15 @@ inline SparseWs carve_sparse_ws(const tkv_sparse_desc* d, void* workspace) {
   return ws;
 }
 
-// Position of logical element (t, c) of a 32x128 group inside the packed block:
-// word index and field index.  Mirrors the layout text of tkv.h.
+// Position of logical element (t, c) of a block of 32 tokens x 128 channels inside the
+// packed block: word index and field index.  Mirrors the layout text of tkv.h.
 __host__ __device__ inline void k_code_pos(int bits, int t, int c, int& word, int& field) {
   const int r = 4 * (t / 8) + t % 4, tau = (t % 8) / 4;
   const int lane = r + 16 * ((c % 32) / 8);
-  if (bits == 2) {
+  if (bits == 1) {
+    word = 64 * tau + lane;
+    field = (c % 8) / 2 + 4 * ((c / 32) % 2) + 8 * (c / 64) + 16 * (c % 2);
+  } else if (bits == 2) {
     word = 4 * lane + 2 * tau + c / 64;
     field = (c % 8) / 2 + 4 * ((c / 32) % 2) + 8 * (c % 2);
   } else {
@@ -194,7 +197,10 @@ __host__ __device__ inline void k_code_pos(int bits, int t, int c, int& word, in
 
 __host__ __device__ inline void v_code_pos(int bits, int t, int c, int& word, int& field) {
   const int lane = c % 16 + 16 * (t / 8);
-  if (bits == 2) {
+  if (bits == 1) {
+    word = 64 * (c / 64) + lane;
+    field = (t % 8) / 2 + 4 * ((c / 16) % 2) + 8 * ((c / 32) % 2) + 16 * (t % 2);
+  } else if (bits == 2) {
     word = 4 * lane + c / 32;
     field = (t % 8) / 2 + 4 * ((c / 16) % 2) + 8 * (t % 2);
   } else {
@@ -206,7 +212,14 @@ __host__ __device__ inline void v_code_pos(int bits, int t, int c, int& word, in
 // Inverse maps: which (t, c) does field F of word w hold.
 __host__ __device__ inline void k_code_elem(int bits, int w, int F, int& t, int& c) {
   int lane, tau, r, kb;
-  if (bits == 2) {
+  if (bits == 1) {
+    tau = w / 64;
+    lane = w % 64;
+    const int f = F % 16, e = F / 16;
+    r = lane % 16;
+    kb = lane / 16;
+    c = 32 * ((f / 4) % 2) + 64 * (f / 8) + 8 * kb + 2 * (f % 4) + e;
+  } else if (bits == 2) {
     lane = w / 4;
     tau = (w % 4) / 2;
     const int wd = w % 2, f = F % 8, e = F / 8;
@@ -225,7 +238,13 @@ __host__ __device__ inline void k_code_elem(int bits, int w, int F, int& t, int&
 }
 
 __host__ __device__ inline void v_code_elem(int bits, int w, int F, int& t, int& c) {
-  if (bits == 2) {
+  if (bits == 1) {
+    const int lane = w % 64, f = F % 16, e = F / 16;
+    const int r = lane % 16, kb = lane / 16;
+    const int cb = 4 * (w / 64) + (f / 4) % 2 + 2 * (f / 8);
+    t = 8 * kb + 2 * (f % 4) + e;
+    c = 16 * cb + r;
+  } else if (bits == 2) {
     const int lane = w / 4, wd = w % 4, f = F % 8, e = F / 8;
     const int r = lane % 16, kb = lane / 16;
     const int cb = 2 * wd + f / 4;

@@ -20,7 +20,7 @@ struct QuantAppendParams {
   __half* v_resid;
   const __half* k_new;
   const __half* v_new;
-  int32_t hkv, bits, residual, capacity;
+  int32_t hkv, bits, group, residual, capacity;
   int32_t n_stride;   // rows per sequence in k_new / v_new
   TkvSeqLens n_old;
   TkvSeqLens n_add;   // valid new rows per sequence (<= n_stride)
@@ -35,29 +35,32 @@ __device__ inline float quant_code(float x, float z, float s, float qmax) {
   return s == 0.0f ? 0.0f : c;
 }
 
-// One workgroup quantizes one 32-token group of one KV head.  BITS is a template parameter so
-// that the packed-layout index arithmetic folds to shifts and masks.
-template <int BITS>
+// One workgroup quantizes one group of GRP tokens of one KV head.  BITS and GRP are template
+// parameters so that the packed-layout index arithmetic folds to shifts and masks.
+template <int BITS, int GRP>
 __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p) {
-  __shared__ __half kt[TKV_G][TKV_D];
-  __shared__ __half vt[TKV_G][TKV_D];
+  constexpr int NU = TKV_D / GRP;     // channel groups of a value row
+  constexpr int NB = GRP / TKV_BLK;   // code blocks of a token group
+  __shared__ __half kt[GRP][TKV_D];
+  __shared__ __half vt[GRP][TKV_D];
   __shared__ float ks[TKV_D], kz[TKV_D];
-  __shared__ float vs[TKV_G][4], vz[TKV_G][4];
+  __shared__ float vs[GRP][NU], vz[GRP][NU];
 
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int n0 = p.n_old.n[b], n1 = n0 + p.n_add.n[b];
-  const int j0 = tkv::n_quantized(n0, p.residual) / TKV_G;
-  const int j1 = tkv::n_quantized(n1, p.residual) / TKV_G;
+  const int j0 = tkv::n_quantized(n0, p.residual, GRP) / GRP;
+  const int j1 = tkv::n_quantized(n1, p.residual, GRP) / GRP;
   const int j = j0 + (int)blockIdx.x;
   if (j >= j1) return;
-  const int ring = p.residual + TKV_G;
+  const int ring = p.residual + GRP;
   const size_t bh = (size_t)b * p.hkv + h;
-  const int n_groups_cap = p.capacity / TKV_G;
+  const size_t n_groups_cap = (size_t)(p.capacity / GRP);
+  const size_t n_blocks_cap = (size_t)(p.capacity / TKV_BLK);
 
-  // stage the group's 32 K rows and 32 V rows (16-byte chunks)
-  for (int i = tid; i < TKV_G * 16; i += 256) {
+  // stage the group's K rows and V rows (16-byte chunks)
+  for (int i = tid; i < GRP * 16; i += 256) {
     const int t = i / 16, part = i % 16;
-    const int tok = TKV_G * j + t;
+    const int tok = GRP * j + t;
     const uint4 *ksrc, *vsrc;
     if (tok < n0) {
       const size_t row = (bh * ring + (size_t)(tok % ring)) * TKV_D;
@@ -75,10 +78,10 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p
 
   constexpr float qmax = (float)((1 << BITS) - 1);
   if (tid < TKV_D) {
-    // keys: one (s, z) per channel over the group's 32 tokens
+    // keys: one (s, z) per channel over the group's tokens
     const int c = tid;
     float mn = __half2float(kt[0][c]), mx = mn;
-    for (int t = 1; t < TKV_G; ++t) {
+    for (int t = 1; t < GRP; ++t) {
       const float x = __half2float(kt[t][c]);
       mn = fminf(mn, x);
       mx = fmaxf(mx, x);
@@ -93,12 +96,12 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p
     ks[c] = __half2float(s16);
     kz[c] = __half2float(z16);
   } else {
-    // values: one (s, z) per token and 32-channel group
+    // values: one (s, z) per token and channel group; 128 threads cover GRP * NU = 128 pairs
     const int pr = tid - TKV_D;
-    const int t = pr / 4, u = pr % 4;
+    const int t = pr / NU, u = pr % NU;
     float mn = 0.f, mx = 0.f;
-    for (int i = 0; i < TKV_G; ++i) {
-      const int c = TKV_G * u + ((i + pr) % TKV_G);  // rotated start: fewer LDS bank conflicts
+    for (int i = 0; i < GRP; ++i) {
+      const int c = GRP * u + ((i + pr) % GRP);  // rotated start: fewer LDS bank conflicts
       const float x = __half2float(vt[t][c]);
       mn = i == 0 ? x : fminf(mn, x);
       mx = i == 0 ? x : fmaxf(mx, x);
@@ -107,7 +110,9 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p
     const float s32 = range / qmax;
     const __half s16 = __float2half_rn(s32);
     const __half z16 = __float2half_rn(mn);
-    const size_t o = ((bh * n_groups_cap + j) * 4 + u) * TKV_G + t;
+    // stored per block of 32 tokens as [u][t]
+    const size_t blk = (size_t)j * NB + t / TKV_BLK;
+    const size_t o = ((bh * n_blocks_cap + blk) * NU + u) * TKV_BLK + t % TKV_BLK;
     p.v_scale[o] = s16;
     p.v_zero[o] = z16;
     vs[t][u] = __half2float(s16);
@@ -115,26 +120,30 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p
   }
   __syncthreads();
 
-  constexpr int nwords = TKV_D * BITS;  // 32*128*bits/32
+  constexpr int nwords = TKV_D * BITS;  // words of one packed block: 32*128*bits/32
   constexpr int nfields = 32 / BITS;
-  uint32_t* kdst = p.k_codes + (bh * n_groups_cap + j) * (size_t)nwords;
-  uint32_t* vdst = p.v_codes + (bh * n_groups_cap + j) * (size_t)nwords;
+  uint32_t* kdst = p.k_codes + (bh * n_blocks_cap + (size_t)j * NB) * (size_t)nwords;
+  uint32_t* vdst = p.v_codes + (bh * n_blocks_cap + (size_t)j * NB) * (size_t)nwords;
 #pragma unroll
-  for (int w0 = 0; w0 < nwords; w0 += 256) {
-    const int w = w0 + tid;
+  for (int w0 = 0; w0 < NB * nwords; w0 += 256) {
+    const int wi = w0 + tid;
+    if ((NB * nwords) % 256 != 0 && wi >= NB * nwords) break;
+    const int blk = wi / nwords, w = wi % nwords;  // block of the group, word of the block
     uint32_t kw = 0, vw = 0;
 #pragma unroll
     for (int f = 0; f < nfields; ++f) {
       int t, c;
       tkv::k_code_elem(BITS, w, f, t, c);
+      t += TKV_BLK * blk;
       const float kc = quant_code(__half2float(kt[t][c]), kz[c], ks[c], qmax);
       kw |= (uint32_t)kc << (BITS * f);
       tkv::v_code_elem(BITS, w, f, t, c);
-      const float vc = quant_code(__half2float(vt[t][c]), vz[t][c / TKV_G], vs[t][c / TKV_G], qmax);
+      t += TKV_BLK * blk;
+      const float vc = quant_code(__half2float(vt[t][c]), vz[t][c / GRP], vs[t][c / GRP], qmax);
       vw |= (uint32_t)vc << (BITS * f);
     }
-    kdst[w] = kw;
-    vdst[w] = vw;
+    kdst[wi] = kw;
+    vdst[wi] = vw;
   }
 }
 
@@ -143,11 +152,11 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(QuantAppendParams p
 __global__ __launch_bounds__(256) void ring_update_kernel(QuantAppendParams p) {
   const int b = blockIdx.y, tid = threadIdx.x;
   const int n0 = p.n_old.n[b], n1 = n0 + p.n_add.n[b];
-  const int nq1 = tkv::n_quantized(n1, p.residual);
+  const int nq1 = tkv::n_quantized(n1, p.residual, p.group);
   const int tok = n1 - 1 - (int)blockIdx.x;
   const int first = n0 > nq1 ? n0 : nq1;
   if (tok < first) return;
-  const int ring = p.residual + TKV_G;
+  const int ring = p.residual + p.group;
   const int chunks = p.hkv * 16;  // 16-byte chunks per token, K or V
   for (int i = tid; i < 2 * chunks; i += 256) {
     const int kv = i / chunks, rem = i % chunks;
@@ -181,8 +190,9 @@ extern "C" int32_t tkv_quantize_append_ragged(const tkv_quant_desc* d, tkv_quant
     p.n_old.n[b] = (int32_t)n0;
     p.n_add.n[b] = add;
     const int32_t n1 = (int32_t)n0 + add;
-    const int groups = (tkv::n_quantized(n1, d->residual) - tkv::n_quantized((int32_t)n0, d->residual)) / TKV_G;
-    const int32_t nq1 = tkv::n_quantized(n1, d->residual);
+    const int32_t g = d->group_size;
+    const int groups = (tkv::n_quantized(n1, d->residual, g) - tkv::n_quantized((int32_t)n0, d->residual, g)) / g;
+    const int32_t nq1 = tkv::n_quantized(n1, d->residual, g);
     const int copy = n1 - (n0 > nq1 ? (int32_t)n0 : nq1);
     if (groups > max_groups) max_groups = groups;
     if (copy > max_copy) max_copy = copy;
@@ -199,6 +209,7 @@ extern "C" int32_t tkv_quantize_append_ragged(const tkv_quant_desc* d, tkv_quant
   p.v_new = (const __half*)v_new;
   p.hkv = d->n_kv_heads;
   p.bits = d->bits;
+  p.group = d->group_size;
   p.residual = d->residual;
   p.capacity = d->capacity;
   p.n_stride = n_new;
@@ -206,10 +217,16 @@ extern "C" int32_t tkv_quantize_append_ragged(const tkv_quant_desc* d, tkv_quant
   hipStream_t s = (hipStream_t)stream;
   if (max_groups > 0) {
     const dim3 grid(max_groups, d->n_kv_heads, d->batch);
-    if (d->bits == 2)
-      quantize_group_kernel<2><<<grid, 256, 0, s>>>(p);
-    else
-      quantize_group_kernel<4><<<grid, 256, 0, s>>>(p);
+    const int variant = d->bits * 100 + d->group_size;
+    switch (variant) {
+      case 132: quantize_group_kernel<1, 32><<<grid, 256, 0, s>>>(p); break;
+      case 232: quantize_group_kernel<2, 32><<<grid, 256, 0, s>>>(p); break;
+      case 432: quantize_group_kernel<4, 32><<<grid, 256, 0, s>>>(p); break;
+      case 164: quantize_group_kernel<1, 64><<<grid, 256, 0, s>>>(p); break;
+      case 264: quantize_group_kernel<2, 64><<<grid, 256, 0, s>>>(p); break;
+      case 464: quantize_group_kernel<4, 64><<<grid, 256, 0, s>>>(p); break;
+      default: return TKV_E_UNSUPPORTED;
+    }
     if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   }
   if (max_copy > 0) {

@@ -29,8 +29,8 @@ struct QuantAttnParams {
   const __half* q;
   float* parts;  // [B][Hq][n_chunks + 1][D + 4]
   float scale2;  // sm_scale * log2(e)
-  int32_t hq, hkv, bits, residual, capacity;
-  int32_t groups_per_chunk, n_chunks;
+  int32_t hq, hkv, bits, group, residual, capacity;
+  int32_t groups_per_chunk, n_chunks;  // chunk size in blocks of 32 tokens
   int32_t chunk_offset;  // blockIdx.x + chunk_offset is the chunk; chunk == n_chunks is the fp16 tail
   TkvSeqLens lens;
 };
@@ -47,7 +47,7 @@ __device__ inline float wave_half_max(float v) {
 __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams p) {
   __shared__ float qs[4][TKV_D];            // query heads of this KV head, zero padded
   __shared__ float ksz[4][TKV_D][2];        // per wave: K scale, zero of the current group
-  __shared__ float pw[4][4][TKV_G];         // per wave: weights p[h][t]
+  __shared__ float pw[4][4][TKV_BLK];       // per wave: weights p[h][t]
   __shared__ float alpha_s[4][4];           // per wave: rescale factors
   __shared__ uint32_t vblk[4][TKV_D * 4];   // per wave: packed V block (<= 512 words)
   __shared__ float red_m[4][4], red_l[4][4];
@@ -57,12 +57,15 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int G = p.hq / p.hkv;
   const int n = p.lens.n[b];
-  const int nq = tkv::n_quantized(n, p.residual);
-  const int jq = nq / TKV_G;
+  const int nq = tkv::n_quantized(n, p.residual, p.group);
+  const int jq = nq / TKV_BLK;  // packed blocks of 32 tokens
   const size_t bh = (size_t)b * p.hkv + h;
-  const int n_groups_cap = p.capacity / TKV_G;
+  const size_t n_blocks_cap = (size_t)(p.capacity / TKV_BLK);
+  const size_t n_groups_cap = (size_t)(p.capacity / p.group);
+  const int bpg = p.group / TKV_BLK;  // blocks per key group
+  const int nu = TKV_D / p.group;     // channel groups of a value row
   const int nwords = TKV_D * p.bits;
-  const int ring = p.residual + TKV_G;
+  const int ring = p.residual + p.group;
   const bool tail = chunk == p.n_chunks;
 
   for (int i = tid; i < 4 * TKV_D; i += 256) {
@@ -78,24 +81,25 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
     blk1 = min(blk0 + p.groups_per_chunk, jq);
   } else {
     blk0 = 0;
-    blk1 = (n - nq + TKV_G - 1) / TKV_G;
+    blk1 = (n - nq + TKV_BLK - 1) / TKV_BLK;
   }
 
   const int t = lane % 32, hp = lane / 32;
   float m_run[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   float l_run[4] = {0.f, 0.f, 0.f, 0.f};
   float o_run[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
-  const int c0 = 2 * lane, u = c0 / TKV_G;
+  const int c0 = 2 * lane, u = c0 / p.group;
 
   for (int blk = blk0 + wave; blk < blk1; blk += 4) {
     float acc0 = 0.f, acc1 = 0.f;
     bool valid = true;
     if (!tail) {
-      const size_t grp = bh * n_groups_cap + blk;
+      const size_t grp = bh * n_blocks_cap + blk;            // packed block
+      const size_t kgrp = bh * n_groups_cap + blk / bpg;     // its key group
       // K scale / zero of this group -> LDS
       for (int c = lane; c < TKV_D; c += 64) {
-        ksz[wave][c][0] = __half2float(p.k_scale[grp * TKV_D + c]);
-        ksz[wave][c][1] = __half2float(p.k_zero[grp * TKV_D + c]);
+        ksz[wave][c][0] = __half2float(p.k_scale[kgrp * TKV_D + c]);
+        ksz[wave][c][1] = __half2float(p.k_zero[kgrp * TKV_D + c]);
       }
       for (int w = lane; w < nwords; w += 64) vblk[wave][w] = p.v_codes[grp * nwords + w];
       __builtin_amdgcn_wave_barrier();
@@ -111,7 +115,7 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
         acc1 += qs[2 * hp + 1][c] * kh;
       }
     } else {
-      const int tok = nq + blk * TKV_G + t;
+      const int tok = nq + blk * TKV_BLK + t;
       valid = tok < n;
       if (valid) {
         const __half* krow = p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D;
@@ -148,12 +152,12 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
     }
     // P.V for channels c0, c0+1
     float s0[4] = {0.f, 0.f, 0.f, 0.f}, s1[4] = {0.f, 0.f, 0.f, 0.f}, ls[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int tt = 0; tt < TKV_G; ++tt) {
+    for (int tt = 0; tt < TKV_BLK; ++tt) {
       float v0, v1;
       if (!tail) {
-        const size_t grp = bh * n_groups_cap + blk;
-        const float sc = __half2float(p.v_scale[(grp * 4 + u) * TKV_G + tt]);
-        const float ze = __half2float(p.v_zero[(grp * 4 + u) * TKV_G + tt]);
+        const size_t grp = bh * n_blocks_cap + blk;
+        const float sc = __half2float(p.v_scale[(grp * nu + u) * TKV_BLK + tt]);
+        const float ze = __half2float(p.v_zero[(grp * nu + u) * TKV_BLK + tt]);
         const uint32_t cmask = (1u << p.bits) - 1u;
         int w, f;
         tkv::v_code_pos(p.bits, tt, c0, w, f);
@@ -161,7 +165,7 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
         tkv::v_code_pos(p.bits, tt, c0 + 1, w, f);
         v1 = (float)((vblk[wave][w] >> (p.bits * f)) & cmask) * sc + ze;
       } else {
-        const int tok = nq + blk * TKV_G + tt;
+        const int tok = nq + blk * TKV_BLK + tt;
         if (tok < n) {
           const __half* vrow = p.v_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D;
           v0 = __half2float(vrow[c0]);
@@ -294,9 +298,9 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
     if (n < 0) return TKV_E_INVAL;
     if (n > d->capacity) return TKV_E_CAPACITY;
     p.lens.n[b] = n;
-    const int g = tkv::n_quantized(n, d->residual) / TKV_G;
+    const int g = tkv::n_quantized(n, d->residual, d->group_size) / TKV_BLK;  // in blocks of 32 tokens
     if (g > max_groups) max_groups = g;
-    if (n - g * TKV_G > max_tail) max_tail = n - g * TKV_G;
+    if (n - g * TKV_BLK > max_tail) max_tail = n - g * TKV_BLK;
   }
   // Chunking of the reference kernel: about 1024 workgroups over the whole launch.
   const int bh = d->batch * d->n_kv_heads;
@@ -322,6 +326,7 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   p.hq = d->n_q_heads;
   p.hkv = d->n_kv_heads;
   p.bits = d->bits;
+  p.group = d->group_size;
   p.residual = d->residual;
   p.capacity = d->capacity;
   p.groups_per_chunk = gpc;
@@ -334,12 +339,13 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
     const size_t parts_bytes =
         (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
     uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_bytes + 255) & ~(size_t)255));
-    return tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, g_target_blocks, max_groups,
-                                       max_tail, p.lens, s);
-  } else {
-    p.chunk_offset = 0;
-    quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
+    st = tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, g_target_blocks, max_groups,
+                                     max_tail, p.lens, s);
+    if (st != TKV_E_UNSUPPORTED) return st;
   }
+  // reference kernel: on request, and for the settings the matrix-core kernel is not built for
+  p.chunk_offset = 0;
+  quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
   if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, n_chunks + 1, s);
 }

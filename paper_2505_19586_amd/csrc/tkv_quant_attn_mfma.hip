@@ -1,7 +1,9 @@
 // Matrix-core kernel of tkv_quant_attn_decode (Sec. 2.1 Eq. 3 over the quantized cache
-// of Sec. 4.3) for gfx950, G = Hq/Hkv <= 4, D = 128, g = 32, bits 2 or 4.
+// of Sec. 4.3) for gfx950, G = Hq/Hkv <= 4, D = 128, bits 1, 2 or 4, quantization group 32
+// or 64 (Sec. 5.1 runs 1 and 2 bits with groups of 64).
 //
-// One wave64 owns one 32-token group at a time.  Both contractions run on
+// One wave64 owns one packed block of 32 tokens at a time (half a key group when the
+// quantization group is 64; "group" below means such a block).  Both contractions run on
 // v_mfma_f32_16x16x32_f16 with the packed codes as the A operand:
 //
 //   * a b-bit code c sitting at mantissa bits [bp, bp+b) of an otherwise zero fp16 IS
@@ -97,6 +99,18 @@ __device__ inline uint32_t mix_lo_pair(float a0, float a1, uint32_t s2, uint32_t
                (_Float16)__builtin_fmaf(a1, (float)s[1], -(float)h[1]));
 }
 
+// 1 bit: four MFMA operands out of one word.  Operands 1 and 3 sit four mantissa bits
+// higher than operands 0 and 2: their results carry an extra 2^4.
+__device__ inline void extract1(uint32_t w, uintx4 (&a)[4]) {
+  const uint32_t w8 = w >> 8;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    a[0][j] = w & (0x00010001u << j);
+    a[1][j] = w & (0x00100010u << j);
+    a[2][j] = w8 & (0x00010001u << j);
+    a[3][j] = w8 & (0x00100010u << j);
+  }
+}
 // 2 bit: two MFMA operands (8 registers) out of one 32-bit word of packed codes.
 __device__ inline void extract2(uint32_t w, uintx4& a0, uintx4& a1) {
   const uint32_t w8 = w >> 8;
@@ -156,16 +170,24 @@ struct MergeSmem {
 //   cz     zero-point term of every group of the chunk, [group][4 heads] float
 //   tail   partial results of the waves that share the fp16 tail
 //   q      the 4 query rows as fp16, for the tail
-template <int BITS, int W>
+// GS = quantization group / 32: the K scalers of a slot are those of the block's key group,
+// the V scalers and zero-points [128 / (32 GS)][32 tokens] fp16 each.
+template <int BITS, int GS, int W>
 struct Cfg {
   static constexpr int kThreads = 64 * W;
-  static constexpr int kCode = 512 * BITS;  // bytes of K (or V) codes of one group
+  static constexpr int kCode = 512 * BITS;  // bytes of K (or V) codes of one block
   static constexpr int kKPart = kCode + 256;
   static constexpr int kVPart = kCode + 512;
+  static constexpr int oVs = kCode;                 // V scalers inside a V slot
+  static constexpr int oVz = kCode + 256 / GS;      // V zero-points
   static constexpr int kDepth = 3;
   static constexpr int kWaveRing = kDepth * (kKPart + kVPart);
-  static constexpr int kKLoads = BITS / 2 + 1;  // direct-to-LDS load instructions per part
-  static constexpr int kVLoads = BITS / 2 + 2;
+  // direct-to-LDS load instructions per part: 1 bit = two 4-byte-per-lane loads of codes, else
+  // 16-byte-per-lane loads; GS = 2 fetches V scalers and zero-points with one instruction
+  static constexpr int kCodeLoads = BITS == 1 ? 2 : BITS / 2;
+  static constexpr int kKLoads = kCodeLoads + 1;
+  static constexpr int kVLoads = kCodeLoads + (GS == 1 ? 2 : 1);
+  static constexpr int kCodeWords = BITS == 1 ? 2 : 2 * BITS;  // code words per lane and part
   static constexpr int kBkWave = 2 * 4 * kBkStride * 4;
   static constexpr int oRing = W * kBkWave;
   static constexpr int oCz = oRing + W * kWaveRing;
@@ -181,8 +203,7 @@ struct Cfg {
 // its partial result in `te`.  Lane = (token, channel half) for the logits, lane = channel
 // pair for the weighted sum.
 __device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint32_t* q_h, size_t bh, int nq, int n,
-                                 int wave, int lane) {
-  const int ring = p.residual + TKV_G;
+                                 int ring, int wave, int lane) {
   const int r_total = n - nq;
   const int t = lane / 2, half = lane % 2;
   float M[4], Ls[4], acc[4][2];
@@ -273,9 +294,12 @@ __device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint3
   } while (0)
 #endif
 
-template <int BITS, int W>
+template <int BITS, int GS, int W>
 __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
-  using C = Cfg<BITS, W>;
+  using C = Cfg<BITS, GS, W>;
+  constexpr int KSH = GS - 1;          // key group of a block = block >> KSH
+  constexpr int NU = 4 / GS;           // channel groups of a value row
+  constexpr int GRP = TKV_BLK * GS;    // quantization group
   constexpr int NWORDS = TKV_D * BITS;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_next;
@@ -291,10 +315,11 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);  // wave-uniform: keeps group addresses scalar
   const int G = p.hq / p.hkv;
   const int n = p.lens.n[b];
-  const int nq = tkv::n_quantized(n, p.residual);
-  const int jq = nq / TKV_G;
+  const int nq = tkv::n_quantized(n, p.residual, GRP);
+  const int jq = nq / TKV_BLK;
   const size_t bh = (size_t)b * p.hkv + h;
-  const size_t grp_base = bh * (size_t)(p.capacity / TKV_G);
+  const size_t grp_base = bh * (size_t)(p.capacity / TKV_BLK);   // first packed block of this head
+  const size_t kgrp_base = bh * (size_t)(p.capacity / GRP);      // first key group
   // Work split of this sequence: a 32-token piece of the tail counts as two groups and the
   // tail belongs to the last chunk, which gets correspondingly fewer quantized groups.
   const bool has_tail = chunk == p.n_chunks - 1;
@@ -317,26 +342,38 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   const uint32_t lane16 = 16u * (uint32_t)lane, lane4 = 4u * (uint32_t)lane;  // unsigned: scalar base + 32-bit lane offset
 
   // ---- loads: asynchronous global -> LDS copies of a group's K part / V part ------------
+  auto load_codes = [&](unsigned char* s, const unsigned char* src, uint32_t l16, uint32_t l4) {
+    if (BITS == 1) {
+      lds_load4(src + l4, s);
+      lds_load4(src + 256 + l4, s + 256);
+    } else {
+#pragma unroll
+      for (int x = 0; x < BITS / 2; ++x) lds_load16(src + 1024 * x + l16, s + 1024 * x);
+    }
+  };
+  // GS = 2: lanes 0..31 fetch the block's V scalers, lanes 32..63 its zero-points (128 bytes each)
+  const __half* vmeta_lane = lane < 32 ? p.v_scale + 2 * lane : p.v_zero + 2 * (lane - 32);
   auto load_kpart = [&](uint32_t so, int g) {
-    const size_t grp = grp_base + min(g, last);
+    const int gi = min(g, last);
+    const size_t grp = grp_base + gi;
     unsigned char* s = smem + so;
-    const unsigned char* kc = reinterpret_cast<const unsigned char*>(p.k_codes + grp * NWORDS);
     uint32_t l16 = lane16, l4 = lane4;  // opaque copies: keeps "scalar base + lane offset" addressing
     asm volatile("" : "+v"(l16), "+v"(l4));
-#pragma unroll
-    for (int x = 0; x < BITS / 2; ++x) lds_load16(kc + 1024 * x + l16, s + 1024 * x);
-    lds_load4(reinterpret_cast<const unsigned char*>(p.k_scale + grp * TKV_D) + l4, s + C::kCode);
+    load_codes(s, reinterpret_cast<const unsigned char*>(p.k_codes + grp * NWORDS), l16, l4);
+    lds_load4(reinterpret_cast<const unsigned char*>(p.k_scale + (kgrp_base + (gi >> KSH)) * TKV_D) + l4, s + C::kCode);
   };
   auto load_vpart = [&](uint32_t so, int g) {
     const size_t grp = grp_base + min(g, last);
     unsigned char* s = smem + so;
-    const unsigned char* vc = reinterpret_cast<const unsigned char*>(p.v_codes + grp * NWORDS);
     uint32_t l16 = lane16, l4 = lane4;
     asm volatile("" : "+v"(l16), "+v"(l4));
-#pragma unroll
-    for (int x = 0; x < BITS / 2; ++x) lds_load16(vc + 1024 * x + l16, s + 1024 * x);
-    lds_load4(reinterpret_cast<const unsigned char*>(p.v_scale + grp * TKV_D) + l4, s + C::kCode);
-    lds_load4(reinterpret_cast<const unsigned char*>(p.v_zero + grp * TKV_D) + l4, s + C::kCode + 256);
+    load_codes(s, reinterpret_cast<const unsigned char*>(p.v_codes + grp * NWORDS), l16, l4);
+    if (GS == 1) {
+      lds_load4(reinterpret_cast<const unsigned char*>(p.v_scale + grp * TKV_D) + l4, s + C::oVs);
+      lds_load4(reinterpret_cast<const unsigned char*>(p.v_zero + grp * TKV_D) + l4, s + C::oVz);
+    } else {
+      lds_load4(vmeta_lane + grp * (TKV_D / GS), s + C::oVs);
+    }
   };
 
   // The first three groups of a wave are fixed (wave, wave + W, wave + 2W), the rest come
@@ -362,7 +399,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   for (int m = 0; m < 4; ++m)
     bq[m] = *reinterpret_cast<const uintx4*>(qrow + (size_t)(hs < G ? hs : G - 1) * TKV_D + 32 * m + 8 * rb);
   auto load_az = [&](int t0) {
-    const size_t grp = grp_base + min(blk0 + t0 + slot, last);
+    const size_t grp = kgrp_base + (min(blk0 + t0 + slot, last) >> KSH);
 #pragma unroll
     for (int m = 0; m < 4; ++m) az[m] = *reinterpret_cast<const uintx4*>(p.k_zero + grp * TKV_D + 32 * m + 8 * rb);
   };
@@ -409,11 +446,11 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     }
   }
   // query times the factor that undoes the field position of this lane's channels
-  // (2 bit: 4^(lane%4), 4 bit: 16^(lane%2))
+  // (1 bit: 2^(lane%4), times 2^4 in odd 32-channel blocks; 2 bit: 4^(lane%4); 4 bit: 16^(lane%2))
   float qf[4][2];
   {
-    const int pos = BITS == 2 ? lane % 4 : lane % 2;
-    const float comp = BITS == 2 ? (float)(1 << kEK) / (float)(1 << (2 * pos)) : (float)(1 << kEK) / (float)(1 << (4 * pos));
+    const int shift = BITS == 1 ? lane % 4 + 4 * ((lane / 16) % 2) : BITS == 2 ? 2 * (lane % 4) : 4 * (lane % 2);
+    const float comp = (float)(1 << kEK) / (float)(1 << shift);
 #pragma unroll
     for (int hh = 0; hh < 4; ++hh) {
       const half2_t qq = as_half2(q2[hh]);
@@ -425,7 +462,8 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   __syncthreads();  // cz table, tail slots, query copy and group counter are in place
   TKV_PH();  // 2 set-up done
 
-  if (has_tail && wave < kTailWaves && wave * 32 < n - nq) tail_wave(p, tail_s[wave], q_h, bh, nq, n, wave, lane);
+  if (has_tail && wave < kTailWaves && wave * 32 < n - nq)
+    tail_wave(p, tail_s[wave], q_h, bh, nq, n, p.residual + GRP, wave, lane);
   TKV_PH();  // 3 tail done
 
   // codes carry 2^-24, query side 2^kEK, so S = acc * 2^(24-kEK)
@@ -437,27 +475,28 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   floatx4 acc_z = {0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY;
 
-  // A operand of the z_v / denominator MFMA: rows 0..3 hold z_v[u = row] (loaded per group)
+  // A operand of the z_v / denominator MFMA: rows 0..NU-1 hold z_v[u = row] (loaded per group)
   // times the constant that undoes the weight-side scaling, row 4 holds that constant
-  // alone (denominator), rows 5.. are zero.  Built branch-free as load * zmul + zadd.
-  const int zrow = slot;                    // as A operand this lane holds row `slot`
-  const int zrow_ld = zrow < 4 ? zrow : 3;  // rows >= 4 load a valid row and multiply it by 0
+  // alone (denominator), the other rows are zero.  Built branch-free as load * zmul + zadd.
+  const int zrow = slot;                          // as A operand this lane holds row `slot`
+  const int zrow_ld = zrow < NU ? zrow : NU - 1;  // other rows load a valid row and multiply it by 0
   half2_t zmul[4], zadd[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    // element k = 2j + e of this lane carries 2^-kEP * (4^j | 16^(j%2))
-    const float w = BITS == 2 ? (float)(1 << (2 * j)) / (float)(1 << kEP) : (float)(1 << (4 * (j % 2))) / (float)(1 << kEP);
-    const _Float16 wm = (_Float16)(zrow < 4 ? w : 0.f), wa = (_Float16)(zrow == 4 ? w : 0.f);
+    // element k = 2j + e of this lane carries 2^-kEP * (2^j | 4^j | 16^(j%2))
+    const int fs = BITS == 1 ? j : BITS == 2 ? 2 * j : 4 * (j % 2);
+    const float w = (float)(1 << fs) / (float)(1 << kEP);
+    const _Float16 wm = (_Float16)(zrow < NU ? w : 0.f), wa = (_Float16)(zrow == 4 ? w : 0.f);
     zmul[j] = half2_t{wm, wm};
     zadd[j] = half2_t{wa, wa};
   }
-  // exponent offsets that put 2^kEP / (4^j | 16^(j%2)) into the weights; value i of the
+  // exponent offsets that put 2^kEP / (2^j | 4^j | 16^(j%2)) into the weights; value i of the
   // lane (tile tau = i/4, row x = i%4) is element kappa = 4 tau + x, register j = kappa/2
   float off[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int j = i / 2;
-    off[i] = BITS == 2 ? (float)(kEP - 2 * j) : (float)(kEP - 4 * (j % 2));
+    off[i] = BITS == 1 ? (float)(kEP - j) : BITS == 2 ? (float)(kEP - 2 * j) : (float)(kEP - 4 * (j % 2));
   }
 
   // Next group index from the workgroup's LDS counter.  Written as inline assembly: the
@@ -492,33 +531,50 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   // read the hi rows of the query-side operand, odd ones the lo rows
   const uint32_t* bk_row = &bk_s[us & 1][hs][4 * rb];
   struct QkIn {
-    uint32_t kw[2 * BITS];
+    uint32_t kw[C::kCodeWords];
     uintx4 bk[4];
   };
-  auto read_qk = [&](uint32_t so, QkIn& in) {
-    const unsigned char* s = smem + so;
+  auto read_codes = [&](const unsigned char* s, uint32_t (&cw)[C::kCodeWords]) {
+    if (BITS == 1) {
+      cw[0] = *reinterpret_cast<const uint32_t*>(s + lane4);
+      cw[1] = *reinterpret_cast<const uint32_t*>(s + 256 + lane4);
+    } else {
 #pragma unroll
-    for (int x = 0; x < BITS / 2; ++x) {
-      const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
+      for (int x = 0; x < BITS / 2; ++x) {
+        const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
 #pragma unroll
-      for (int y = 0; y < 4; ++y) in.kw[4 * x + y] = t[y];
+        for (int y = 0; y < 4; ++y) cw[4 * x + y] = t[y];
+      }
     }
+  };
+  auto read_qk = [&](uint32_t so, QkIn& in) {
+    read_codes(smem + so, in.kw);
 #pragma unroll
     for (int m = 0; m < 4; ++m) in.bk[m] = *reinterpret_cast<const uintx4*>(bk_row + 16 * m);
   };
   auto stage_qk = [&](const QkIn& in, floatx4 (&acc_s)[2]) {
     acc_s[0] = floatx4{0.f, 0.f, 0.f, 0.f};
     acc_s[1] = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (BITS == 1) {
+#pragma unroll
+      for (int tau = 0; tau < 2; ++tau) {
+        uintx4 a[4];
+        extract1(in.kw[tau], a);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) acc_s[tau] = mfma(a[m], in.bk[m], acc_s[tau]);
+      }
+      return;
+    }
 #pragma unroll
     for (int m2 = 0; m2 < 2; ++m2) {  // pairs of MFMA steps m = 2*m2, 2*m2+1
 #pragma unroll
       for (int tau = 0; tau < 2; ++tau) {
         uintx4 a[2];
         if (BITS == 2) {
-          extract2(in.kw[2 * tau + m2], a[0], a[1]);
+          extract2(in.kw[(2 * tau + m2) % C::kCodeWords], a[0], a[1]);
         } else {
-          extract4(in.kw[4 * tau + 2 * m2], a[0]);
-          extract4(in.kw[4 * tau + 2 * m2 + 1], a[1]);
+          extract4(in.kw[(4 * tau + 2 * m2) % C::kCodeWords], a[0]);
+          extract4(in.kw[(4 * tau + 2 * m2 + 1) % C::kCodeWords], a[1]);
         }
 #pragma unroll
         for (int y = 0; y < 2; ++y) acc_s[tau] = mfma(a[y], in.bk[2 * m2 + y], acc_s[tau]);
@@ -528,19 +584,14 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   // weights and weight-side operands
   struct PvIn {
     uintx4 sv, zv;
-    uint32_t vw[2 * BITS];
+    uint32_t vw[C::kCodeWords];
     float cz;
   };
   auto read_pv = [&](uint32_t so, int gc, PvIn& in) {
     const unsigned char* s = smem + so;
-    in.sv = *reinterpret_cast<const uintx4*>(s + C::kCode + (us * TKV_G + 8 * rb) * 2);
-    in.zv = *reinterpret_cast<const uintx4*>(s + C::kCode + 256 + (zrow_ld * TKV_G + 8 * rb) * 2);
-#pragma unroll
-    for (int x = 0; x < BITS / 2; ++x) {
-      const uintx4 t = *reinterpret_cast<const uintx4*>(s + 1024 * x + lane16);
-#pragma unroll
-      for (int y = 0; y < 4; ++y) in.vw[4 * x + y] = t[y];
-    }
+    in.sv = *reinterpret_cast<const uintx4*>(s + C::oVs + ((us / GS) * TKV_BLK + 8 * rb) * 2);
+    in.zv = *reinterpret_cast<const uintx4*>(s + C::oVz + (zrow_ld * TKV_BLK + 8 * rb) * 2);
+    read_codes(s, in.vw);
     in.cz = cz_s[(gc - blk0) * 4 + hs];
   };
   struct POps {
@@ -598,14 +649,24 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   // P.V: 8 blocks of 16 channels + the z_v / denominator MFMA
   auto stage_pv = [&](const PvIn& in, const POps& o) {
     acc_z = mfma(o.a_zv, o.bp, acc_z);
+    if (BITS == 1) {
+#pragma unroll
+      for (int wd = 0; wd < 2; ++wd) {
+        uintx4 a[4];
+        extract1(in.vw[wd], a);
+#pragma unroll
+        for (int y = 0; y < 4; ++y) acc_o[4 * wd + y] = mfma(a[y], o.b2, acc_o[4 * wd + y]);
+      }
+      return;
+    }
 #pragma unroll
     for (int wd = 0; wd < 4; ++wd) {
       uintx4 a[2];
       if (BITS == 2) {
-        extract2(in.vw[wd], a[0], a[1]);
+        extract2(in.vw[wd % C::kCodeWords], a[0], a[1]);
       } else {
-        extract4(in.vw[(wd / 2) * 4 + 2 * (wd % 2)], a[0]);
-        extract4(in.vw[(wd / 2) * 4 + 2 * (wd % 2) + 1], a[1]);
+        extract4(in.vw[((wd / 2) * 4 + 2 * (wd % 2)) % C::kCodeWords], a[0]);
+        extract4(in.vw[((wd / 2) * 4 + 2 * (wd % 2) + 1) % C::kCodeWords], a[1]);
       }
 #pragma unroll
       for (int y = 0; y < 2; ++y) acc_o[2 * wd + y] = mfma(a[y], o.b2, acc_o[2 * wd + y]);
@@ -679,16 +740,17 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   if (rb == 0) {
 #pragma unroll
     for (int x = 0; x < 4; ++x)
-      if (x == us) ms.z[wave][hs][us] = acc_z[x];
+      if (x == us / GS) ms.z[wave][hs][us] = acc_z[x];
     if (us == 0) ms.m[wave][hs] = m_run;
   }
   if (rb == 1 && us == 0) ms.l[wave][hs] = acc_z[0];
   __syncthreads();
   {
     const float zt = ms.z[wave][hs][us];
-    const float unscale = (float)(1 << (24 - kEP));
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb) {
+      // 1 bit: the codes of odd 16-channel blocks sit four mantissa bits higher
+      const float unscale = (float)(1 << (24 - kEP - (BITS == 1 && cb % 2 ? 4 : 0)));
       if (cb / 2 == us) {
 #pragma unroll
         for (int x = 0; x < 4; ++x) ms.o[wave][hs][16 * cb + 4 * rb + x] = __builtin_fmaf(acc_o[cb][x], unscale, zt);
@@ -766,14 +828,14 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
 #endif
 }
 
-template <int BITS, int W>
+template <int BITS, int GS, int W>
 int32_t launch_variant(const MfmaParams& p, dim3 grid, hipStream_t s) {
-  using C = Cfg<BITS, W>;
+  using C = Cfg<BITS, GS, W>;
   // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
-  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_attn_mfma_kernel<BITS, W>),
+  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_attn_mfma_kernel<BITS, GS, W>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes) == hipSuccess;
   if (!lds_ok) return TKV_E_HIP;
-  quant_attn_mfma_kernel<BITS, W><<<grid, C::kThreads, C::kLdsBytes, s>>>(p);
+  quant_attn_mfma_kernel<BITS, GS, W><<<grid, C::kThreads, C::kLdsBytes, s>>>(p);
   return tkv::launch_status();
 }
 
@@ -785,14 +847,17 @@ void* g_mfma_prof = nullptr;
 #endif
 
 // Chunks per (sequence, KV head): about `target_blocks` workgroups in total (one per
-// compute unit), at least one 32-token group per wave, and no more groups per chunk than
+// compute unit), at least one 32-token block per wave, and no more blocks per chunk than
 // the zero-point table of a workgroup holds.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
                                float scale2, float* parts, uint32_t* arrivals, int target_blocks, int max_groups,
                                int max_tail, const TkvSeqLens& lens, hipStream_t s) {
-  if (d->head_dim != TKV_D || d->group_size != TKV_G) return TKV_E_UNSUPPORTED;
+  if (d->head_dim != TKV_D) return TKV_E_UNSUPPORTED;
   if (d->n_q_heads / d->n_kv_heads > 4) return TKV_E_UNSUPPORTED;
-  const int waves = d->bits == 2 ? 12 : 8;
+  // built: the benchmark's settings (2 and 4 bit, groups of 32) and the paper's (1 and 2 bit, groups of 64)
+  const int variant = d->bits * 100 + d->group_size;
+  if (variant != 232 && variant != 432 && variant != 164 && variant != 264) return TKV_E_UNSUPPORTED;
+  const int waves = d->bits == 4 ? 8 : 12;
   const int bh = d->batch * d->n_kv_heads;
   const int work = max_groups + 2 * ((max_tail + 31) / 32);  // in groups, as the kernel counts it
   int n_chunks = (target_blocks + bh - 1) / bh;
@@ -828,8 +893,12 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
 #endif
   p.lens = lens;
   const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
-  if (d->bits == 2) return launch_variant<2, 12>(p, grid, s);
-  if (d->bits == 4) return launch_variant<4, 8>(p, grid, s);
+  switch (variant) {
+    case 232: return launch_variant<2, 1, 12>(p, grid, s);
+    case 432: return launch_variant<4, 1, 8>(p, grid, s);
+    case 164: return launch_variant<1, 2, 12>(p, grid, s);
+    case 264: return launch_variant<2, 2, 12>(p, grid, s);
+  }
   return TKV_E_UNSUPPORTED;
 }
 

@@ -168,15 +168,15 @@ class QuantLayer:
     def view(self, name: str) -> torch.Tensor:
         d = self.desc
         bh = (d.batch, d.n_kv_heads)
-        j = d.capacity // 32
+        j = d.capacity // 32   # codes and value scalers / zero-points: blocks of 32 tokens
         buf = self.buffers[name]
         if name in ("k_codes", "v_codes"):
             return buf.view(torch.int32).view(*bh, j, 128 * d.bits)
         if name in ("k_scale", "k_zero"):
-            return buf.view(torch.float16).view(*bh, j, 128)
+            return buf.view(torch.float16).view(*bh, d.capacity // d.group_size, 128)
         if name in ("v_scale", "v_zero"):
-            return buf.view(torch.float16).view(*bh, j, 4, 32)
-        return buf.view(torch.float16).view(*bh, d.residual + 32, 128)
+            return buf.view(torch.float16).view(*bh, j, 128 // d.group_size, 32)
+        return buf.view(torch.float16).view(*bh, d.residual + d.group_size, 128)
 
 
 class SparseLayer:

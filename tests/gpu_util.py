@@ -26,8 +26,9 @@ def check_quant_cache(layer: "tkv.QuantLayer", b: int, k: np.ndarray, v: np.ndar
     d = layer.desc
     n = k.shape[1]
     assert int(layer.seq_len[b]) == n
-    ref = quant.quantize_kv(k, v, bits=d.bits, group=32, residual=d.residual)
-    jq = ref.n_quant // 32
+    g = d.group_size
+    ref = quant.quantize_kv(k, v, bits=d.bits, group=g, residual=d.residual)
+    jq = ref.n_quant // 32   # code blocks
     torch.cuda.synchronize()
     kc = layer.view("k_codes")[b, :, :jq].cpu().numpy().view(np.uint32)
     vc = layer.view("v_codes")[b, :, :jq].cpu().numpy().view(np.uint32)
@@ -36,12 +37,12 @@ def check_quant_cache(layer: "tkv.QuantLayer", b: int, k: np.ndarray, v: np.ndar
     assert np.array_equal(kc, layout.pack_k(ref.k_codes, d.bits)), "k words"
     assert np.array_equal(vc, layout.pack_v(ref.v_codes, d.bits)), "v words"
     for name, want in (("k_scale", ref.k_scale), ("k_zero", ref.k_zero)):
-        got = layer.view(name)[b, :, :jq].cpu().numpy()
+        got = layer.view(name)[b, :, :ref.n_quant // g].cpu().numpy()
         assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), name
     for name, want in (("v_scale", ref.v_scale), ("v_zero", ref.v_zero)):
         got = layout.v_meta_to_logical(layer.view(name)[b, :, :jq].cpu().numpy())
         assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), name
-    ring = d.residual + 32
+    ring = d.residual + g
     slots = np.arange(ref.n_quant, n) % ring
     for name, want in (("k_resid", ref.k_resid), ("v_resid", ref.v_resid)):
         got = layer.view(name)[b].cpu().numpy()[:, slots]

@@ -59,15 +59,15 @@ def _sdesc(**kw):
 
 def test_quant_sizes_follow_table2(L):
     """Sec. 4.4 Table 2: 2*n*h*d_h*(b/16 + 2/g) fp16 elements."""
-    for bits, per_tok_head in ((2, 96), (4, 160)):
-        d = _qdesc(bits=bits, capacity=131072)
+    for bits, g, per_tok_head in ((2, 32, 96), (4, 32, 160), (1, 64, 48), (2, 64, 80)):
+        d = _qdesc(bits=bits, group_size=g, capacity=131072)
         sizes = (C.c_size_t * 8)()
         ws = C.c_size_t()
         assert L.tkv_quant_cache_sizes(C.byref(d), sizes, C.byref(ws)) == 0
         total = sum(sizes[:6])
         assert total == per_tok_head * 131072 * 8
-        assert total == int(2 * 131072 * 8 * 128 * (bits / 16 + 2 / 32) * 2)
-        assert sizes[6] == sizes[7] == 8 * 160 * 128 * 2
+        assert total == int(2 * 131072 * 8 * 128 * (bits / 16 + 2 / g) * 2)
+        assert sizes[6] == sizes[7] == 8 * (128 + g) * 128 * 2
         assert ws.value > 0
 
 
@@ -82,7 +82,9 @@ def test_sparse_sizes(L):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(bits=3), -2), (dict(bits=1), -2), (dict(bits=0), -1), (dict(head_dim=64), -2), (dict(group_size=64), -2),
+    (dict(bits=3), -2), (dict(bits=8), -2), (dict(bits=0), -1), (dict(head_dim=64), -2), (dict(group_size=16), -2),
+    (dict(group_size=128), -2), (dict(group_size=64, residual=96), -1), (dict(group_size=64, capacity=4096 + 32), -1),
+    (dict(residual=1024), -2), (dict(bits=1, group_size=64), 0), (dict(bits=1), 0), (dict(bits=4, group_size=64), 0),
     (dict(n_q_heads=30), -1), (dict(n_q_heads=64), -2), (dict(batch=0), -1), (dict(batch=65), -2),
     (dict(capacity=100), -1), (dict(residual=100), -1), (dict(residual=0), -2), (dict(capacity=0), -1),
 ])

@@ -16,11 +16,11 @@ TOL = 2e-3
 SM = 1.0 / np.sqrt(128.0)
 
 
-@pytest.mark.parametrize("n,bits", [(32768, 2), (32768, 4), (131072, 2)])
-def test_quant_layer_full_size(n, bits):
-    print(f"case full-size quant n={n} bits={bits}", flush=True)
+@pytest.mark.parametrize("n,bits,g", [(32768, 2, 32), (32768, 4, 32), (131072, 2, 32), (131072, 1, 64), (32768, 2, 64)])
+def test_quant_layer_full_size(n, bits, g):
+    print(f"case full-size quant n={n} bits={bits} g={g}", flush=True)
     inp = make_layer(n, config=1, layer=0, seq=bits)
-    layer = tkv.QuantLayer(bits=bits, capacity=n + 32)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=n + 64)
     layer.append(to_new(inp.k), to_new(inp.v))
     ref = check_quant_cache(layer, 0, inp.k, inp.v)          # every code, scaler, zero-point
     out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
@@ -32,7 +32,7 @@ def test_quant_layer_full_size(n, bits):
     layer.append(to_new(new.k), to_new(new.v))
     k2 = np.concatenate([inp.k, new.k], axis=1)
     v2 = np.concatenate([inp.v, new.v], axis=1)
-    layer2 = tkv.QuantLayer(bits=bits, capacity=n + 32)
+    layer2 = tkv.QuantLayer(bits=bits, group_size=g, capacity=n + 64)
     layer2.append(to_new(k2), to_new(v2))
     a = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
     b = layer2.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)

@@ -23,14 +23,18 @@ def kernel_choice(request):
     tkv.debug_quant_attn_config(0)
 
 SM = 1.0 / np.sqrt(128.0)
+# (bits, quantization group): the benchmark's settings, the paper's (Sec. 5.1: 1 and 2 bits,
+# groups of 64), and two that only the reference kernel is built for
+SETTINGS = [(2, 32), (4, 32), (1, 64), (2, 64), (1, 32), (4, 64)]
+MAIN_SETTINGS = SETTINGS[:4]
 
 
-@pytest.mark.parametrize("bits", [2, 4])
-@pytest.mark.parametrize("n", [4096, 1, 127, 128, 159, 160, 161, 1000])
-def test_bulk_append_and_attention(bits, n):
-    print(f"case bulk bits={bits} n={n}", flush=True)
+@pytest.mark.parametrize("bits,g", SETTINGS)
+@pytest.mark.parametrize("n", [4096, 1, 127, 128, 159, 160, 161, 191, 192, 193, 1000])
+def test_bulk_append_and_attention(bits, g, n):
+    print(f"case bulk bits={bits} g={g} n={n}", flush=True)
     inp = make_layer(n, config=0, layer=0, seq=n % 97)
-    layer = tkv.QuantLayer(bits=bits, capacity=4096 + 64)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=4096 + 64)
     layer.append(to_new(inp.k), to_new(inp.v))
     ref = check_quant_cache(layer, 0, inp.k, inp.v)
     out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
@@ -40,15 +44,15 @@ def test_bulk_append_and_attention(bits, n):
     assert err <= TOL
 
 
-@pytest.mark.parametrize("bits", [2, 4])
-def test_incremental_append_equals_bulk(bits):
+@pytest.mark.parametrize("bits,g", MAIN_SETTINGS)
+def test_incremental_append_equals_bulk(bits, g):
     """Decode loop: 8 single-token steps that cross no group boundary, then 40 that
     cross one, then uneven multi-token appends; after each phase the cache must be
     the oracle's cache of the whole prefix."""
-    print(f"case incremental bits={bits}", flush=True)
+    print(f"case incremental bits={bits} g={g}", flush=True)
     n0, total = 4096, 4096 + 8 + 40 + 7 + 90 + 300
     inp = make_layer(total, config=0, layer=0, seq=5)
-    layer = tkv.QuantLayer(bits=bits, capacity=8192)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=8192)
     kd, vd = to_new(inp.k), to_new(inp.v)
     layer.append(kd[:, :n0].contiguous(), vd[:, :n0].contiguous())
     pos = n0
@@ -63,9 +67,10 @@ def test_incremental_append_equals_bulk(bits):
     assert pos == total
 
 
-def test_append_from_empty_in_small_steps():
+@pytest.mark.parametrize("bits,g", [(2, 32), (1, 64)])
+def test_append_from_empty_in_small_steps(bits, g):
     inp = make_layer(400, seq=6)
-    layer = tkv.QuantLayer(bits=2, capacity=512)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=512)
     kd, vd = to_new(inp.k), to_new(inp.v)
     pos = 0
     for s in [1, 1, 30, 96, 31, 1, 1, 200, 39]:
@@ -74,12 +79,12 @@ def test_append_from_empty_in_small_steps():
         check_quant_cache(layer, 0, inp.k[:, :pos], inp.v[:, :pos])
 
 
-@pytest.mark.parametrize("bits", [2, 4])
-def test_ragged_batch(bits):
-    print(f"case ragged bits={bits}", flush=True)
+@pytest.mark.parametrize("bits,g", MAIN_SETTINGS)
+def test_ragged_batch(bits, g):
+    print(f"case ragged bits={bits} g={g}", flush=True)
     lens = [700, 1, 2048, 333, 160]
     inps = [make_layer(n, config=4, layer=0, seq=b) for b, n in enumerate(lens)]
-    layer = tkv.QuantLayer(bits=bits, capacity=2048, batch=len(lens))
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=2048, batch=len(lens))
     layer.append(to_new_batch([i.k for i in inps], 2048), to_new_batch([i.v for i in inps], 2048), n_valid=lens)
     q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
     out = layer.attn_decode(q, SM)

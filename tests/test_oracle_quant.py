@@ -43,17 +43,19 @@ def test_table2_closed_form(golden_dir):
         assert got == float(expect), line
 
 
-@pytest.mark.parametrize("bits", [2, 4])
-def test_table2_matches_actual_buffer_bytes(bits):
-    """Bytes of the arrays the quantizer really produces equal the Table 2 count."""
-    inp = make_layer(32 * 9, seq=3)
-    c = quant.quantize_kv(inp.k, inp.v, bits=bits, group=32, residual=0)
+@pytest.mark.parametrize("bits,g", [(2, 32), (4, 32), (1, 64), (2, 64)])
+def test_table2_matches_actual_buffer_bytes(bits, g):
+    """Bytes of the arrays the quantizer really produces equal the Table 2 count
+    (the table's own setting is 1 bit with groups of 64)."""
+    inp = make_layer(64 * 5, seq=3)
+    c = quant.quantize_kv(inp.k, inp.v, bits=bits, group=g, residual=0)
     hkv, nq, d = c.k_codes.shape
+    assert c.k_scale.shape == (hkv, nq // g, d) and c.v_scale.shape == (hkv, nq, d // g)
     code_bytes = 2 * hkv * nq * d * bits // 8
     meta_bytes = 2 * (c.k_scale.nbytes + c.v_scale.nbytes)
-    elems = quant.table2_quant_elements(nq, hkv, d, 1, bits, 32)
+    elems = quant.table2_quant_elements(nq, hkv, d, 1, bits, g)
     assert code_bytes + meta_bytes == int(elems * 2)
-    assert (code_bytes + meta_bytes) // (hkv * nq) == {2: 96, 4: 160}[bits]
+    assert (code_bytes + meta_bytes) // (hkv * nq) == {(2, 32): 96, (4, 32): 160, (1, 64): 48, (2, 64): 80}[bits, g]
     # packed words have exactly the code bytes
     assert layout.pack_k(c.k_codes, bits).nbytes + layout.pack_v(c.v_codes, bits).nbytes == code_bytes
 
@@ -81,14 +83,14 @@ def test_sixteen_bit_is_identity():
     assert np.array_equal(v.astype(np.float16).view(np.uint16), inp.v.view(np.uint16))
 
 
-@pytest.mark.parametrize("bits", [1, 2, 4, 8])
-def test_error_bound_and_endpoints(bits):
+@pytest.mark.parametrize("bits,g", [(1, 32), (2, 32), (4, 32), (8, 32), (1, 64), (2, 64)])
+def test_error_bound_and_endpoints(bits, g):
     inp = make_layer(32 * 40, seq=2)
-    c = quant.quantize_kv(inp.k, inp.v, bits=bits, group=32, residual=0)
+    c = quant.quantize_kv(inp.k, inp.v, bits=bits, group=g, residual=0)
     qmax = (1 << bits) - 1
     for x, xhat, s, axis in (
-        (inp.k, quant.dequantize_k(c), np.repeat(c.k_scale, 32, axis=1), 1),
-        (inp.v, quant.dequantize_v(c), np.repeat(c.v_scale, 32, axis=2), 2),
+        (inp.k, quant.dequantize_k(c), np.repeat(c.k_scale, g, axis=1), 1),
+        (inp.v, quant.dequantize_v(c), np.repeat(c.v_scale, g, axis=2), 2),
     ):
         x = x.astype(np.float64)
         s = s.astype(np.float64)
@@ -99,18 +101,18 @@ def test_error_bound_and_endpoints(bits):
         # at least one group is close to the bound (a dropped rounding would halve/double it)
         assert (err / s).max() > 0.45
     # code(min) == 0 and code(max) == qmax in every group
-    kg_codes = c.k_codes.reshape(8, -1, 32, 128)
-    kg = inp.k.reshape(8, -1, 32, 128)
+    kg_codes = c.k_codes.reshape(8, -1, g, 128)
+    kg = inp.k.reshape(8, -1, g, 128)
     amin = kg.argmin(axis=2)
     amax = kg.argmax(axis=2)
     assert (np.take_along_axis(kg_codes, amin[:, :, None, :], axis=2) == 0).all()
     assert (np.take_along_axis(kg_codes, amax[:, :, None, :], axis=2) == qmax).all()
-    vg_codes = c.v_codes.reshape(8, -1, 4, 32)
-    vg = inp.v.reshape(8, -1, 4, 32)
+    vg_codes = c.v_codes.reshape(8, -1, 128 // g, g)
+    vg = inp.v.reshape(8, -1, 128 // g, g)
     assert (np.take_along_axis(vg_codes, vg.argmin(axis=3)[..., None], axis=3) == 0).all()
     assert (np.take_along_axis(vg_codes, vg.argmax(axis=3)[..., None], axis=3) == qmax).all()
     # dequantized values stay inside [min, max + s/2]
-    kh = quant.dequantize_k(c).reshape(8, -1, 32, 128)
+    kh = quant.dequantize_k(c).reshape(8, -1, g, 128)
     assert (kh >= kg.min(axis=2, keepdims=True)).all()
     assert (kh <= kg.max(axis=2, keepdims=True).astype(np.float64)
             + c.k_scale.astype(np.float64)[:, :, None, :] / 2 + 1e-12).all()
@@ -155,19 +157,20 @@ def test_flat_and_tiny_range_groups():
             assert (c == 0).all()
 
 
-def test_k_and_v_policies_are_the_same_scalar_quantizer():
-    """Per-channel K quantization of a 32x32 block equals per-token V
+@pytest.mark.parametrize("bits,g", [(2, 32), (1, 64)])
+def test_k_and_v_policies_are_the_same_scalar_quantizer(bits, g):
+    """Per-channel K quantization of a g x g block equals per-token V
     quantization of its transpose (Sec. 4.3: same Eq. 4, different grouping)."""
     rng = np.random.default_rng(11)
-    blk = rng.standard_normal((32, 32)).astype(np.float16)
-    k = np.zeros((1, 32, 128), np.float16)
-    v = np.zeros((1, 32, 128), np.float16)
-    k[0, :, :32] = blk          # tokens x channels
-    v[0, :, :32] = blk.T        # tokens x channels, transposed block
-    c = quant.quantize_kv(k, v, bits=2, group=32, residual=0)
-    assert np.array_equal(c.k_codes[0, :, :32], c.v_codes[0, :, :32].T)
-    assert np.array_equal(c.k_scale[0, 0, :32], c.v_scale[0, :, 0])
-    assert np.array_equal(c.k_zero[0, 0, :32], c.v_zero[0, :, 0])
+    blk = rng.standard_normal((g, g)).astype(np.float16)
+    k = np.zeros((1, g, 128), np.float16)
+    v = np.zeros((1, g, 128), np.float16)
+    k[0, :, :g] = blk          # tokens x channels
+    v[0, :, :g] = blk.T        # tokens x channels, transposed block
+    c = quant.quantize_kv(k, v, bits=bits, group=g, residual=0)
+    assert np.array_equal(c.k_codes[0, :, :g], c.v_codes[0, :, :g].T)
+    assert np.array_equal(c.k_scale[0, 0, :g], c.v_scale[0, :, 0])
+    assert np.array_equal(c.k_zero[0, 0, :g], c.v_zero[0, :, 0])
 
 
 def test_scale_is_float32_division_rounded_to_fp16():
