@@ -30,7 +30,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--context", type=int, default=131072)
-    ap.add_argument("--bits", type=int, default=2)
+    ap.add_argument("--bits", type=int, default=2, help="code width of the quantized layers (1, 2, 4)")
+    ap.add_argument("--group", type=int, default=32, help="quantization group (32, or the paper's 64)")
     ap.add_argument("--top-k", type=int, default=1024)
     ap.add_argument("--host-layers", type=int, default=30,
                     help="distinct pinned host K/V caches (30 = one per sparse layer)")
@@ -97,7 +98,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     N = args.context
-    CAP = N + 32 * ((args.steps * 2 + args.warmup + 64 + 31) // 32)
+    CAP = N + 64 * ((args.steps * 2 + args.warmup + 64 + 63) // 64)
     sm = 1.0 / np.sqrt(128.0)
     t_build = time.time()
 
@@ -125,7 +126,7 @@ def main():
         q, k, v = make_layer_device(N, seed=1000 + l, device=dev)
         qs.append(q[None].contiguous())
         if l in QUANT_LAYERS:
-            L = tkv.QuantLayer(bits=args.bits, capacity=CAP, device=dev)
+            L = tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=CAP, device=dev)
             L.append(k[None], v[None])
             if l == 0:
                 sample["quant"] = (q.cpu().numpy(), k.permute(1, 0, 2).contiguous().cpu().numpy(),
@@ -257,14 +258,15 @@ def main():
     torch.cuda.synchronize()
     dur = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) * 1e3 for k, v in rec.items() if v}  # us
 
-    nq = (N - 128) // 32 * 32
-    per_tok_head = {2: 96, 4: 160}[args.bits]
+    nq = (N - 128) // args.group * args.group
+    # Sec. 4.4, Table 2: b/8 bytes per code, one fp16 scaler and zero-point per group, for K and V
+    per_tok_head = 2 * 128 * args.bits // 8 + 2 * 2 * 2 * 128 // args.group
     quant_bytes = 8 * nq * per_tok_head + 8 * (N - nq) * 512 + 2 * 32 * 128 * 2
     summary_bytes = 8 * N * 32
     gather_bytes = 8 * args.top_k * 512
     roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "traffic": traffic_from_profile("quant_attn_mfma_kernel<%d" % args.bits) if N == 131072 else None,
+            "traffic": traffic_from_profile("quant_attn_mfma_kernel<2") if (N, args.bits, args.group) == (131072, 2, 32) else None,
             "algorithmic_bytes": quant_bytes}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {
@@ -288,7 +290,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"configs[3]: 32-layer hybrid decode step, batch 1, N={N}, layers 0-1 {args.bits}-bit "
-                               f"quantized (g=32, W=128), layers 2-31 sparse (d_s=16, k={args.top_k}, 4 sinks, "
+                               f"quantized (g={args.group}, W=128), layers 2-31 sparse (d_s=16, k={args.top_k}, 4 sinks, "
                                f"64 window)", "schedule": args.schedule, "distinct_host_caches": len(host_pool),
                    "build_s": round(t_build, 1)},
         "roofline": roof, "cpu_baseline": cpu, **extra,
@@ -321,7 +323,7 @@ def cpu_baseline(sample, N, args, sm):
 
     q, k, v = sample["quant"]
     t0 = time.perf_counter()
-    c = quant.quantize_kv(k, v, bits=args.bits, group=32, residual=128)
+    c = quant.quantize_kv(k, v, bits=args.bits, group=args.group, residual=128)
     t_quantize = time.perf_counter() - t0
     reps = 6
     t0 = time.perf_counter()
