@@ -6,9 +6,14 @@ cache, Top-K selection) and the exact attention over n_local + n_topk tokens
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
 Readings where the paper is silent:
-  * The channel list is an input (int32 [Hkv, d_s], ascending).  The paper
-    re-selects it every step from |q_hat_i| * max|K_i| (Eq. 10); that is
-    provided separately as ``critical_channels`` and not part of the scored path.
+  * The channel list is an input of Stage 2 (int32 [Hkv, d_s], ascending).  The
+    paper re-selects it every step from |q_hat_i| * max|K_i| (Eq. 10, Stage 1):
+    ``critical_channels`` is Eq. 10 for one query vector, ``select_channels``
+    its grouped-query form in the pinned float32 order that the library takes.
+  * Grouped-query heads in Stage 1: one channel list per KV head; the
+    contribution of channel i is summed over the group's query heads,
+        s_i = (((|q_0,i| + |q_1,i|) + ...) * max_t |K[t, i]|,
+    each operation one float32 operation, ties to the lower channel.
   * Grouped-query heads: one Top-K index set per KV head; the group's score is
     the sum of its query heads' approximate scores.
   * Tokens resident on the GPU (the first n_sink and the last n_window) are not
@@ -117,3 +122,31 @@ def critical_channels(q_hat: np.ndarray, k: np.ndarray, n_channels: int) -> np.n
     s = np.abs(np.asarray(q_hat, np.float64)) * np.abs(np.asarray(k, np.float64)).max(axis=0)
     order = np.argsort(-s, kind="stable")[:n_channels]
     return np.sort(order).astype(np.int32)
+
+
+def channel_absmax(k: np.ndarray) -> np.ndarray:
+    """max_t |K[t, i]| of Eq. 10 per KV head and channel (exact: a maximum of
+    fp16 magnitudes).  k fp16 [Hkv, N, D] -> float32 [Hkv, D]; zeros for N = 0."""
+    hkv, n, d = k.shape
+    if n == 0:
+        return np.zeros((hkv, d), np.float32)
+    return np.abs(k.astype(np.float32)).max(axis=1)
+
+
+def select_channels(q_hat: np.ndarray, k_absmax: np.ndarray, n_channels: int) -> np.ndarray:
+    """Stage 1 of Sec. 4.2 (Eq. 10) for grouped-query heads, pinned float32 order
+    (module docstring).  q_hat fp16 [Hq, D], k_absmax float32 [Hkv, D]
+    ->  int32 [Hkv, n_channels], ascending."""
+    assert q_hat.dtype == np.float16 and k_absmax.dtype == np.float32
+    hq, d = q_hat.shape
+    hkv = k_absmax.shape[0]
+    g = hq // hkv
+    out = np.zeros((hkv, n_channels), np.int32)
+    for h in range(hkv):
+        a = np.abs(q_hat[h * g].astype(np.float32))
+        for j in range(h * g + 1, (h + 1) * g):
+            a = a + np.abs(q_hat[j].astype(np.float32))          # one RN32 add
+        s = a * k_absmax[h]                                       # one RN32 multiply
+        order = np.argsort(-s.astype(np.float64), kind="stable")[:n_channels]
+        out[h] = np.sort(order)
+    return out

@@ -156,3 +156,58 @@ def test_critical_channels_eq10():
     # s = |q| * max|K| = [0.2, 0.6, 2.0, 1.0]
     assert sparse.critical_channels(q_hat, k, 2).tolist() == [2, 3]
     assert sparse.critical_channels(q_hat, k, 3).tolist() == [1, 2, 3]
+
+
+def test_select_channels_hand_worked_group():
+    """Two query heads share one KV head: s_i = (|q_0,i| + |q_1,i|) * max|K_i|."""
+    q_hat = np.array([[1.0, -2.0, 0.5, 0.0, 3.0, 1.0],
+                      [0.5, 1.0, -0.5, 0.0, -1.0, 1.0]], np.float16)
+    k = np.array([[[4.0, 1.0, -10.0, 100.0, 0.5, 2.0],
+                   [-2.0, 0.5, 1.0, -7.0, 0.25, -2.0]]], np.float16)
+    amax = sparse.channel_absmax(k)
+    assert amax.tolist() == [[4.0, 1.0, 10.0, 100.0, 0.5, 2.0]]
+    # sums of magnitudes [1.5, 3, 1, 0, 4, 2] -> s = [6, 3, 10, 0, 2, 4]
+    assert sparse.select_channels(q_hat, amax, 1).tolist() == [[2]]
+    assert sparse.select_channels(q_hat, amax, 3).tolist() == [[0, 2, 5]]
+    assert sparse.select_channels(q_hat, amax, 4).tolist() == [[0, 1, 2, 5]]
+    # a channel the query does not use is never preferred, however large its keys are
+    assert 3 not in sparse.select_channels(q_hat, amax, 5)[0]
+
+
+def test_select_channels_reduces_to_eq10_for_one_head_and_maximises_the_sum():
+    from itertools import combinations
+    rng = np.random.default_rng(17)
+    for trial in range(20):
+        d, ds = 7, 3
+        q_hat = rng.standard_normal((1, d)).astype(np.float16)
+        k = rng.standard_normal((1, 30, d)).astype(np.float16)
+        got = sparse.select_channels(q_hat, sparse.channel_absmax(k), ds)[0]
+        assert got.tolist() == sparse.critical_channels(q_hat[0], k[0], ds).tolist()
+        s = np.abs(q_hat[0].astype(np.float64)) * np.abs(k[0].astype(np.float64)).max(axis=0)
+        best = max(combinations(range(d), ds), key=lambda c: s[list(c)].sum())
+        assert np.isclose(s[got].sum(), s[list(best)].sum())
+
+
+def test_select_channels_ties_invariances_and_outliers():
+    # all-equal contributions: the lowest channels win
+    q_hat = np.ones((4, 128), np.float16)
+    amax = np.ones((1, 128), np.float32)
+    assert sparse.select_channels(q_hat, amax, 16)[0].tolist() == list(range(16))
+    # positive rescaling of the query does not change the list; permuting channels permutes it
+    rng = np.random.default_rng(23)
+    inp = make_layer(512, seq=3)
+    amax = sparse.channel_absmax(inp.k)
+    base = sparse.select_channels(inp.q, amax, 16)
+    assert np.array_equal(sparse.select_channels(inp.q * np.float16(2), amax, 16), base)
+    perm = rng.permutation(128)
+    permuted = sparse.select_channels(inp.q[:, perm], amax[:, perm], 16)
+    for h in range(8):
+        assert sorted(perm[permuted[h]].tolist()) == base[h].tolist()
+    # a flat query picks the planted outlier channels of the keys (x10 by construction)
+    flat = np.ones_like(inp.q)
+    picked = sparse.select_channels(flat, amax, 16)
+    for h in range(8):
+        assert set(inp.outlier_channels[h]) <= set(picked[h].tolist())
+    # the running maximum over appended pieces equals the maximum over the whole cache
+    a = np.maximum(sparse.channel_absmax(inp.k[:, :100]), sparse.channel_absmax(inp.k[:, 100:]))
+    assert np.array_equal(a, amax)
