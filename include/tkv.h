@@ -242,6 +242,69 @@ int32_t tkv_sparse_attn(const tkv_sparse_desc* desc, const tkv_sparse_cache* cac
                         const int32_t* topk_count, const void* staging, void* out, float sm_scale,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------
+ * Stage 1 of the dynamic retrieval (Sec. 4.2, Fig. 4): critical channels re-estimated
+ * every step (Eq. 10) and the critical key cache fetched for them.  Optional: a layer
+ * whose channel list is fixed only needs the calls above.
+ * ------------------------------------------------------------------------------- */
+
+typedef struct {
+  float* k_absmax; /* device fp32 [B][Hkv][128]: max over cached tokens of |K[t][c]| (the
+                      second factor of Eq. 10); ZERO before the first append               */
+  void* keys_cm;   /* fp16 [B][Hkv][128][capacity], channel-major copy of all keys: pinned
+                      host memory (the paper's CPU pool; fetched per step with
+                      tkv_sparse_prefetch_keys) or device memory (resident; read in place
+                      by tkv_sparse_estimate_topk_cm with rows_per_head = 128)             */
+} tkv_sparse_stage1;
+
+/* Bytes of k_absmax and keys_cm. */
+int32_t tkv_sparse_stage1_sizes(const tkv_sparse_desc* desc, size_t bytes_out[2]);
+
+/*
+ * Cache update of the Stage 1 buffers for the tokens k_new fp16 [B][n_new][Hkv][128]
+ * (device) that tkv_sparse_append[_ragged] is about to append: call it BEFORE that
+ * append, with the same k_new / n_new / n_valid_host (it reads seq_len_host and leaves
+ * it unchanged).  keys_cm receives the transposed rows, k_absmax the running maxima.
+ * capacity must be a multiple of 8.
+ */
+int32_t tkv_sparse_stage1_append(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache,
+                                 const tkv_sparse_stage1* stage1, const void* k_new, int32_t n_new,
+                                 const int32_t* n_valid_host, void* stream);
+
+/*
+ * Eq. 10 per KV head: s_i = (((|q_0,i| + |q_1,i|) + ...) over the group's query heads)
+ * * k_absmax[i], every operation one float32 operation; the d_s channels with the
+ * largest s (ties: lower channel first) are written to channel_idx_out int32
+ * [B][Hkv][d_s] (device) in ASCENDING order.  q_hat: fp16 [B][Hq][128] (device), the
+ * query predicted for this layer one layer early (App. B) or the query itself.
+ */
+int32_t tkv_sparse_select_channels(const tkv_sparse_desc* desc, const tkv_sparse_stage1* stage1,
+                                   const void* q_hat, int32_t* channel_idx_out, void* stream);
+
+/*
+ * Fetch of the critical key cache (Sec. 4.2, "prefetch"): rows channel_idx[b][h][i] of
+ * keys_cm, tokens [0, seq_len), into keys_out fp16 [B][Hkv][d_s][capacity] (device;
+ * the caller alternates two such buffers to overlap the fetch for the next layer with
+ * this layer's compute).  Bound by the host link when keys_cm is host memory:
+ * Hkv * d_s * N * 2 bytes per call.
+ */
+int32_t tkv_sparse_prefetch_keys(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache,
+                                 const tkv_sparse_stage1* stage1, const int32_t* channel_idx, void* keys_out,
+                                 void* stream);
+
+/*
+ * tkv_sparse_estimate_topk over a channel-major critical key cache: same scores, same
+ * selection, same outputs and workspace rules.  keys_cm: device fp16
+ * [B][Hkv][rows_per_head][capacity]; rows_per_head = d_s: row i holds channel
+ * channel_idx[b][h][i] (what tkv_sparse_prefetch_keys wrote); rows_per_head = 128: row c
+ * holds channel c (a resident tkv_sparse_stage1.keys_cm), of which only the listed d_s
+ * rows are read.  cache->key_summary is not used.  capacity must be a multiple of 8.
+ */
+int32_t tkv_sparse_estimate_topk_cm(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,
+                                    const int32_t* channel_idx, const void* keys_cm, int32_t rows_per_head,
+                                    int32_t* topk_idx, int32_t* topk_count, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,7 +35,8 @@ constexpr int kSelectLds = 1024 * 4 + kListCap * 8;
 enum Ctrl { kDone2 = 1, kCtrlWords = 8 };
 
 struct TopkParams {
-  const __half* summary;
+  const __half* summary;       // token-major [B][Hkv][capacity][d_s], or channel-major rows (below)
+  int32_t rows_per_head;       // channel-major: [B][Hkv][rows_per_head][capacity], d_s or 128 rows
   const int32_t* channel_idx;
   const __half* q;
   int32_t* topk_idx;
@@ -123,7 +124,9 @@ __device__ inline void find_bin(const uint32_t* hist, int nbins, uint32_t k, uin
   __syncthreads();
 }
 
-template <int DS>
+// CM: the critical key cache is channel-major (one row of `capacity` tokens per channel):
+// a thread then scores four consecutive tokens, one 8-byte load per channel row.
+template <int DS, bool CM>
 __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
@@ -147,13 +150,24 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   }
   // all of this thread's rows are requested before the first is used (rows past the end
   // re-read the last token)
-  const __half* srow = p.summary + (bh * p.capacity) * DS;
   uint4 rows[kPer][DS / 8];
+  uint2 cols[DS];  // CM: four consecutive tokens of every channel row
+  if (CM) {
+    static_assert(kPer == 4, "four tokens per 8-byte load");
+    const int tq = min(t0 + kPer * tid, (n - 1) & ~3);  // past the end: the last group of four
 #pragma unroll
-  for (int it = 0; it < kPer; ++it) {
-    const int t = min(t0 + it * kThreads + tid, n - 1);
+    for (int i = 0; i < DS; ++i) {
+      const int row = p.rows_per_head == DS ? i : p.channel_idx[bh * DS + i];
+      cols[i] = *reinterpret_cast<const uint2*>(p.summary + (bh * p.rows_per_head + row) * (size_t)p.capacity + tq);
+    }
+  } else {
+    const __half* srow = p.summary + (bh * p.capacity) * DS;
 #pragma unroll
-    for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
+    for (int it = 0; it < kPer; ++it) {
+      const int t = min(t0 + it * kThreads + tid, n - 1);
+#pragma unroll
+      for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
+    }
   }
   __syncthreads();
   // query channels into registers (heads >= G are zero: adding their +0 sums changes nothing)
@@ -166,17 +180,26 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   uint32_t* keys = p.ws.keys + bh * p.capacity;
 #pragma unroll
   for (int it = 0; it < kPer; ++it) {
-    const int t = t0 + it * kThreads + tid;
+    const int t = CM ? t0 + kPer * tid + it : t0 + it * kThreads + tid;
     float kx[DS];
+    if (CM) {
 #pragma unroll
-    for (int x = 0; x < DS / 8; ++x) {
-      const uint32_t w[4] = {rows[it][x].x, rows[it][x].y, rows[it][x].z, rows[it][x].w};
-#pragma unroll
-      for (int y = 0; y < 4; ++y) {
-        const uint32_t wy = w[y];
+      for (int i = 0; i < DS; ++i) {
+        const uint32_t wy = it < 2 ? cols[i].x : cols[i].y;
         const half2_t hh = __builtin_bit_cast(half2_t, wy);
-        kx[8 * x + 2 * y] = (float)hh[0];
-        kx[8 * x + 2 * y + 1] = (float)hh[1];
+        kx[i] = (float)hh[it % 2];
+      }
+    } else {
+#pragma unroll
+      for (int x = 0; x < DS / 8; ++x) {
+        const uint32_t w[4] = {rows[it][x].x, rows[it][x].y, rows[it][x].z, rows[it][x].w};
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+          const uint32_t wy = w[y];
+          const half2_t hh = __builtin_bit_cast(half2_t, wy);
+          kx[8 * x + 2 * y] = (float)hh[0];
+          kx[8 * x + 2 * y + 1] = (float)hh[1];
+        }
       }
     }
     float total = 0.f;
@@ -416,13 +439,19 @@ static void* g_topk_prof = nullptr;
 extern "C" void tkv_debug_set_dump_topk(void* ptr) { g_topk_prof = ptr; }
 #endif
 
-extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
-                                            int32_t* topk_idx, int32_t* topk_count, void* workspace,
-                                            size_t workspace_bytes, void* stream) {
+namespace {
+// Both entry points: validation, parameters, the two launches.  keys: token-major key summary
+// (rows_per_head == 0) or channel-major rows.
+int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q, const void* keys,
+                             int32_t rows_per_head, const int32_t* channel_idx, int32_t* topk_idx,
+                             int32_t* topk_count, void* workspace, size_t workspace_bytes, void* stream) {
   int32_t st = tkv::check_sparse_desc(d);
   if (st != TKV_OK) return st;
-  if (!c || !c->seq_len_host || !c->key_summary || !c->channel_idx || !q || !topk_idx || !topk_count || !workspace)
+  if (!c || !c->seq_len_host || !keys || !channel_idx || !q || !topk_idx || !topk_count || !workspace)
     return TKV_E_INVAL;
+  const bool cm = rows_per_head != 0;
+  if (cm && rows_per_head != d->n_channels && rows_per_head != TKV_D) return TKV_E_INVAL;
+  if (cm && d->capacity % 8 != 0) return TKV_E_INVAL;
   size_t need = 0;
   tkv_sparse_cache_sizes(d, nullptr, &need);
   if (workspace_bytes < need) return TKV_E_WORKSPACE;
@@ -435,8 +464,9 @@ extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_
     p.lens.n[b] = n;
     if (n > max_n) max_n = n;
   }
-  p.summary = (const __half*)c->key_summary;
-  p.channel_idx = c->channel_idx;
+  p.summary = (const __half*)keys;
+  p.rows_per_head = rows_per_head;
+  p.channel_idx = channel_idx;
   p.q = (const __half*)q;
   p.topk_idx = topk_idx;
   p.topk_count = topk_count;
@@ -460,10 +490,35 @@ extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
   if (!lds_ok) return TKV_E_HIP;
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;  // 4 Mi tokens per sequence
-  if (d->n_channels == 16)
-    score_kernel<16><<<grid, kThreads, kScoreLds, s>>>(p);
-  else
-    score_kernel<8><<<grid, kThreads, kScoreLds, s>>>(p);
+  if (d->n_channels == 16) {
+    if (cm)
+      score_kernel<16, true><<<grid, kThreads, kScoreLds, s>>>(p);
+    else
+      score_kernel<16, false><<<grid, kThreads, kScoreLds, s>>>(p);
+  } else {
+    if (cm)
+      score_kernel<8, true><<<grid, kThreads, kScoreLds, s>>>(p);
+    else
+      score_kernel<8, false><<<grid, kThreads, kScoreLds, s>>>(p);
+  }
   select_kernel<<<grid, kThreads, kSelectLds, s>>>(p);
   return tkv::launch_status();
+}
+}  // namespace
+
+extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
+                                            int32_t* topk_idx, int32_t* topk_count, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+  if (!c) return tkv::check_sparse_desc(d) != TKV_OK ? tkv::check_sparse_desc(d) : TKV_E_INVAL;
+  return estimate_topk_launch(d, c, q, c->key_summary, 0, c->channel_idx, topk_idx, topk_count, workspace,
+                              workspace_bytes, stream);
+}
+
+extern "C" int32_t tkv_sparse_estimate_topk_cm(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
+                                               const int32_t* channel_idx, const void* keys_cm,
+                                               int32_t rows_per_head, int32_t* topk_idx, int32_t* topk_count,
+                                               void* workspace, size_t workspace_bytes, void* stream) {
+  if (rows_per_head == 0) return tkv::check_sparse_desc(d) != TKV_OK ? tkv::check_sparse_desc(d) : TKV_E_INVAL;
+  return estimate_topk_launch(d, c, q, keys_cm, rows_per_head, channel_idx, topk_idx, topk_count, workspace,
+                              workspace_bytes, stream);
 }

@@ -48,6 +48,10 @@ class SparseCache(C.Structure):
                 ("kv_local", C.c_void_p), ("seq_len_host", C.POINTER(C.c_int32))]
 
 
+class SparseStage1(C.Structure):
+    _fields_ = [("k_absmax", C.c_void_p), ("keys_cm", C.c_void_p)]
+
+
 def lib() -> C.CDLL:
     """Loads libtkv.so (built by paper_2505_19586_amd/build.py); raises if absent."""
     global _LIB
@@ -74,12 +78,22 @@ def lib() -> C.CDLL:
         L.tkv_sparse_gather.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp]
         L.tkv_sparse_attn.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp, C.c_float,
                                       vp, sz, vp]
+        L.tkv_sparse_stage1_sizes.argtypes = [C.POINTER(SparseDesc), C.POINTER(sz)]
+        L.tkv_sparse_stage1_append.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), C.POINTER(SparseStage1),
+                                               vp, i32, C.POINTER(i32), vp]
+        L.tkv_sparse_select_channels.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseStage1), vp, vp, vp]
+        L.tkv_sparse_prefetch_keys.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), C.POINTER(SparseStage1),
+                                               vp, vp, vp]
+        L.tkv_sparse_estimate_topk_cm.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, i32,
+                                                  vp, vp, vp, sz, vp]
         L.tkv_debug_quant_attn_config.argtypes = [i32, i32]
         L.tkv_debug_quant_attn_config.restype = i32
         for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
                      "tkv_quantize_append_ragged", "tkv_sparse_append_ragged",
                      "tkv_sparse_cache_sizes", "tkv_sparse_append", "tkv_sparse_estimate_topk",
-                     "tkv_sparse_gather_attn", "tkv_sparse_gather", "tkv_sparse_attn"):
+                     "tkv_sparse_gather_attn", "tkv_sparse_gather", "tkv_sparse_attn",
+                     "tkv_sparse_stage1_sizes", "tkv_sparse_stage1_append", "tkv_sparse_select_channels",
+                     "tkv_sparse_prefetch_keys", "tkv_sparse_estimate_topk_cm"):
             getattr(L, name).restype = C.c_int32
         _LIB = L
     return _LIB
@@ -269,3 +283,76 @@ class SparseLayer:
                                      float(sm_scale), self.workspace.data_ptr(), self.workspace_bytes,
                                      _stream(stream)), "tkv_sparse_attn")
         return out
+
+
+class Stage1:
+    """Stage 1 buffers of one sparsity-friendly layer (tkv_sparse_stage1): running
+    channel maxima, a channel-major copy of the keys (pinned host memory, or device
+    memory with resident=True) and two buffers for the fetched critical key cache."""
+
+    def __init__(self, layer: SparseLayer, resident: bool = False, keys_cm: torch.Tensor | None = None):
+        self.layer = layer
+        d = layer.desc
+        sizes = (C.c_size_t * 2)()
+        _check(lib().tkv_sparse_stage1_sizes(C.byref(d), sizes), "tkv_sparse_stage1_sizes")
+        self.k_absmax = torch.zeros(d.batch, d.n_kv_heads, d.head_dim, dtype=torch.float32, device=layer.device)
+        if keys_cm is None:
+            if resident:
+                keys_cm = torch.zeros(int(sizes[1]) // 2, dtype=torch.float16, device=layer.device)
+            else:
+                keys_cm = torch.zeros(int(sizes[1]) // 2, dtype=torch.float16, pin_memory=True)
+        assert keys_cm.numel() * 2 >= int(sizes[1])
+        self.resident = keys_cm.is_cuda
+        self.keys_cm = keys_cm.view(-1)[: int(sizes[1]) // 2].view(d.batch, d.n_kv_heads, d.head_dim, d.capacity)
+        self.channel_idx = torch.zeros(d.batch, d.n_kv_heads, d.n_channels, dtype=torch.int32, device=layer.device)
+        self.fetched = [torch.zeros(d.batch, d.n_kv_heads, d.n_channels, d.capacity, dtype=torch.float16,
+                                    device=layer.device) for _ in range(2)]   # double buffer (Sec. 4.2)
+        self.s1 = SparseStage1(self.k_absmax.data_ptr(), self.keys_cm.data_ptr())
+
+    def append(self, k_new: torch.Tensor, n_valid=None, stream=None) -> None:
+        """Call before layer.append with the same rows."""
+        d = self.layer.desc
+        assert k_new.dtype == torch.float16 and k_new.is_cuda and k_new.is_contiguous()
+        assert k_new.shape[0] == d.batch and tuple(k_new.shape[2:]) == (d.n_kv_heads, d.head_dim)
+        nv = None
+        if n_valid is not None:
+            nv = np.ascontiguousarray(n_valid, dtype=np.int32)
+            assert nv.shape == (d.batch,)
+        _check(lib().tkv_sparse_stage1_append(C.byref(d), C.byref(self.layer.cache), C.byref(self.s1),
+                                              k_new.data_ptr(), int(k_new.shape[1]),
+                                              None if nv is None else nv.ctypes.data_as(C.POINTER(C.c_int32)),
+                                              _stream(stream)), "tkv_sparse_stage1_append")
+
+    def select_channels(self, q_hat: torch.Tensor, stream=None) -> torch.Tensor:
+        d = self.layer.desc
+        assert q_hat.dtype == torch.float16 and q_hat.is_cuda and q_hat.is_contiguous()
+        assert tuple(q_hat.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        _check(lib().tkv_sparse_select_channels(C.byref(d), C.byref(self.s1), q_hat.data_ptr(),
+                                                self.channel_idx.data_ptr(), _stream(stream)),
+               "tkv_sparse_select_channels")
+        return self.channel_idx
+
+    def prefetch(self, buf: int = 0, stream=None) -> torch.Tensor:
+        """Fetch the rows of the current channel list into double-buffer half `buf`."""
+        _check(lib().tkv_sparse_prefetch_keys(C.byref(self.layer.desc), C.byref(self.layer.cache), C.byref(self.s1),
+                                              self.channel_idx.data_ptr(), self.fetched[buf].data_ptr(),
+                                              _stream(stream)), "tkv_sparse_prefetch_keys")
+        return self.fetched[buf]
+
+    def estimate_topk(self, q: torch.Tensor, buf: int | None = 0, stream=None):
+        """Stage 2 over the fetched buffer `buf`, or (buf=None, resident keys only) in place
+        over the channel-major keys."""
+        L = self.layer
+        d = L.desc
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        if buf is None:
+            assert self.resident, "in-place scoring needs device-resident channel-major keys"
+            keys, rows = self.keys_cm, d.head_dim
+        else:
+            keys, rows = self.fetched[buf], d.n_channels
+        _check(lib().tkv_sparse_estimate_topk_cm(C.byref(d), C.byref(L.cache), q.data_ptr(),
+                                                 self.channel_idx.data_ptr(), keys.data_ptr(), int(rows),
+                                                 L.topk_idx.data_ptr(), L.topk_count.data_ptr(),
+                                                 L.workspace.data_ptr(), L.workspace_bytes, _stream(stream)),
+               "tkv_sparse_estimate_topk_cm")
+        return L.topk_idx, L.topk_count

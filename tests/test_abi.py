@@ -23,7 +23,7 @@ def L():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "tkv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tkv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(tkv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(L):

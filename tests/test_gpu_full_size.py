@@ -64,6 +64,34 @@ def test_sparse_layer_full_size():
     assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
 
 
+def test_stage1_full_size():
+    """Dynamic channels at the full context: maxima, Eq. 10 list, fetched critical key cache
+    (pinned-host channel-major keys), Stage 2 over it."""
+    n, top_k = 131072, 1024
+    print(f"case full-size stage 1 n={n}", flush=True)
+    inp = make_layer(n, config=2, layer=1, seq=1)
+    layer = tkv.SparseLayer(top_k=top_k, capacity=n)
+    s1 = tkv.Stage1(layer)
+    kd, vd = to_new(inp.k), to_new(inp.v)
+    s1.append(kd)
+    layer.append(kd, vd)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    ch_dev = s1.select_channels(q)
+    keys = s1.prefetch(1)
+    s1.estimate_topk(q, 1)
+    torch.cuda.synchronize()
+    amax = sparse.channel_absmax(inp.k)
+    assert np.array_equal(s1.k_absmax[0].cpu().numpy(), amax)
+    ch = sparse.select_channels(inp.q, amax, 16)
+    assert np.array_equal(ch_dev[0].cpu().numpy(), ch)
+    summ = sparse.key_summary(inp.k, ch)
+    assert np.array_equal(keys[0].cpu().numpy().view(np.uint16),
+                          np.ascontiguousarray(summ.transpose(0, 2, 1)).view(np.uint16))
+    idx, cnt = sparse.estimate_topk(inp.q, summ, ch, n, top_k=top_k, n_sink=4, n_window=64)
+    assert np.array_equal(layer.topk_count[0].cpu().numpy(), cnt)
+    assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
+
+
 def test_batched_ragged_hybrid():
     """Batch 8, ragged lengths (scaled-down version of the batched configuration)."""
     lens = ragged_lengths(8, 4096, 8192).tolist()
