@@ -35,6 +35,10 @@ def parse():
     ap.add_argument("--top-k", type=int, default=1024)
     ap.add_argument("--host-layers", type=int, default=30,
                     help="distinct pinned host K/V caches (30 = one per sparse layer)")
+    ap.add_argument("--dynamic-channels", choices=["off", "resident", "host"], default="off",
+                    help="re-select the critical channels every step (Eq. 10): 'resident' scores in place over "
+                         "channel-major keys kept on the GPU, 'host' fetches the critical key cache from a "
+                         "pinned-host channel-major copy one layer ahead (the paper's design)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["chained", "overlapped"], default="chained")
     ap.add_argument("--one-schedule", action="store_true", help="time only --schedule (profiling runs)")
@@ -97,6 +101,8 @@ def main():
         b.build_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.dynamic_channels != "off":
+        args.schedule = "chained"
     N = args.context
     CAP = N + 64 * ((args.steps * 2 + args.warmup + 64 + 63) // 64)
     sm = 1.0 / np.sqrt(128.0)
@@ -120,6 +126,7 @@ def main():
     # ---- build the caches
     layers = []
     qs = []
+    stage1 = {}
     host_pool = []
     sample = {}
     for l in range(N_LAYERS):
@@ -137,6 +144,10 @@ def main():
             if si >= args.host_layers:
                 kv_host = host_pool[si % args.host_layers]
             L = tkv.SparseLayer(top_k=args.top_k, capacity=CAP, device=dev, kv_host=kv_host)
+            if args.dynamic_channels != "off":   # Stage 1 buffers see the keys before the layer's own append
+                shared = next(iter(stage1.values())).fetched if stage1 else None   # one double buffer for all layers
+                stage1[l] = tkv.Stage1(L, resident=args.dynamic_channels == "resident", fetched=shared)
+                stage1[l].append(k[None])
             if kv_host is None:
                 host_pool.append(L.kv_host)
             L.set_channels(static_channels_device(k, 16)[None])
@@ -190,8 +201,51 @@ def main():
             compute.wait_event(pe)
             layers[pl].attn(qs[pl], sm, out=outs[pl])
 
+    sparse_ids = [l for l in range(N_LAYERS) if l not in QUANT_LAYERS]
+    fetch_stream = torch.cuda.Stream() if args.dynamic_channels == "host" else None
+
+    def step_dynamic():
+        """Chained step with the critical channels re-selected per layer and step (Eq. 10).
+        'resident': Stage 2 reads the listed rows of the GPU-resident channel-major keys.
+        'host': Stage 1 of the next sparse layer (append, channel selection, fetch of its
+        critical key cache into the other half of the double buffer) is enqueued one layer
+        ahead, the fetch on its own stream (legal here because the synthetic queries of
+        different layers are independent; a model would use the predicted query)."""
+        compute = torch.cuda.current_stream()
+        fetched = {}
+
+        def start_fetch(j):
+            l = sparse_ids[j]
+            stage1[l].append_both(new_k[l], new_v[l])
+            stage1[l].select_channels(qs[l])
+            a = torch.cuda.Event(); a.record(compute)
+            fetch_stream.wait_event(a)
+            stage1[l].prefetch(j % 2, stream=fetch_stream)
+            b = torch.cuda.Event(); b.record(fetch_stream)
+            fetched[l] = b
+
+        if fetch_stream is not None:
+            start_fetch(0)
+        for l, L in enumerate(layers):
+            if l in QUANT_LAYERS:
+                L.append(new_k[l], new_v[l])
+                L.attn_decode(qs[l], sm, out=outs[l])
+                continue
+            j = sparse_ids.index(l)
+            if fetch_stream is None:
+                stage1[l].append_both(new_k[l], new_v[l])
+                stage1[l].select_estimate_topk(qs[l], qs[l])
+            else:
+                if j + 1 < len(sparse_ids):
+                    start_fetch(j + 1)
+                compute.wait_event(fetched[l])
+                stage1[l].estimate_topk(qs[l], j % 2)
+            L.gather_attn(qs[l], sm, out=outs[l])
+
     def step_chained(rec=None):
         """Every call of a layer waits for the previous one: what a real model allows."""
+        if rec is None and args.dynamic_channels != "off":
+            return step_dynamic()
         for l, L in enumerate(layers):
             L.append(new_k[l], new_v[l])      # Eq. 2: the step's new token joins the cache first
             if l in QUANT_LAYERS:
@@ -248,7 +302,7 @@ def main():
 
     ms_per_step = timed(args.schedule)
     other = "overlapped" if args.schedule == "chained" else "chained"
-    ms_other = None if args.one_schedule else timed(other)
+    ms_other = None if args.one_schedule or args.dynamic_channels != "off" else timed(other)
 
     # per-kernel durations with events on the launching stream (separate passes so the
     # events do not perturb the step time above)
@@ -291,7 +345,9 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"configs[3]: 32-layer hybrid decode step, batch 1, N={N}, layers 0-1 {args.bits}-bit "
                                f"quantized (g={args.group}, W=128), layers 2-31 sparse (d_s=16, k={args.top_k}, 4 sinks, "
-                               f"64 window)", "schedule": args.schedule, "distinct_host_caches": len(host_pool),
+                               f"64 window)" + ("" if args.dynamic_channels == "off" else
+                                               f", critical channels re-selected every step ({args.dynamic_channels})"),
+                   "schedule": args.schedule, "distinct_host_caches": len(host_pool),
                    "build_s": round(t_build, 1)},
         "roofline": roof, "cpu_baseline": cpu, **extra,
     }

@@ -305,6 +305,26 @@ int32_t tkv_sparse_estimate_topk_cm(const tkv_sparse_desc* desc, const tkv_spars
                                     int32_t* topk_idx, int32_t* topk_count, void* workspace,
                                     size_t workspace_bytes, void* stream);
 
+/*
+ * Stage 1 and Stage 2 in one call for RESIDENT channel-major keys (stage1->keys_cm in device
+ * memory): Eq. 10 as in tkv_sparse_select_channels (list also written to channel_idx_out),
+ * then scoring and Top-K as in tkv_sparse_estimate_topk_cm with rows_per_head = 128.  Nothing
+ * crosses the host link.  TKV_E_INVAL if keys_cm is not device memory.
+ */
+int32_t tkv_sparse_select_estimate_topk(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache,
+                                        const tkv_sparse_stage1* stage1, const void* q_hat, const void* q,
+                                        int32_t* channel_idx_out, int32_t* topk_idx, int32_t* topk_count,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * tkv_sparse_append_ragged that also keeps the Stage 1 buffers up to date (stage1 may be
+ * NULL: then it is tkv_sparse_append_ragged).  Replaces the pair tkv_sparse_stage1_append +
+ * tkv_sparse_append_ragged; a decode step's single token costs one launch.
+ */
+int32_t tkv_sparse_append_dynamic(const tkv_sparse_desc* desc, tkv_sparse_cache* cache,
+                                  const tkv_sparse_stage1* stage1, const void* k_new, const void* v_new,
+                                  int32_t n_new, const int32_t* n_valid_host, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -132,10 +132,49 @@ __device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __h
   }
 }
 
+// Eq. 10 (Sec. 4.2, Stage 1) for one (sequence, KV head), by a whole workgroup of at least
+// TKV_D threads (thread c < TKV_D owns channel c; contains barriers):
+//   s_c = (((|q_0,c| + |q_1,c|) + ...) over the G query heads) * kmax[c],
+// every operation one float32 operation; the ds channels with the largest s (ties: lower
+// channel first) go to out[0..ds) in ascending order (and to out2 unless null).
+// q0: the G query rows [G][TKV_D]; s_s, s_sel: TKV_D words of LDS scratch each.
+__device__ inline void select_channels_block(const __half* q0, int G, const float* kmax, int ds, float* s_s,
+                                             uint32_t* s_sel, int32_t* out, int32_t* out2) {
+#pragma clang fp contract(off)
+  const int c = threadIdx.x;
+  float s = 0.f;
+  if (c < TKV_D) {
+    float a = fabsf(__half2float(q0[c]));
+    for (int j = 1; j < G; ++j) a = a + fabsf(__half2float(q0[(size_t)j * TKV_D + c]));
+    s = a * kmax[c];
+    s_s[c] = s;
+  }
+  __syncthreads();
+  bool sel = false;
+  if (c < TKV_D) {
+    int rank = 0;  // channels that come before this one: larger s, or equal s and lower index
+    for (int j = 0; j < TKV_D; ++j) {
+      const float sj = s_s[j];
+      rank += (sj > s || (sj == s && j < c)) ? 1 : 0;
+    }
+    sel = rank < ds;
+    s_sel[c] = sel ? 1u : 0u;
+  }
+  __syncthreads();
+  if (sel) {
+    int pos = 0;  // ascending output: selected channels below this one
+    for (int j = 0; j < c; ++j) pos += (int)s_sel[j];
+    out[pos] = c;
+    if (out2) out2[pos] = c;
+  }
+  __syncthreads();
+}
+
 // Carve-up of the sparse-layer workspace (per bh = (sequence, KV head)):
 //   keys  uint32 [BH][capacity]   order-preserving image of the approximate scores
-//   cand  uint2  [BH][capacity]   (key, token) pairs in or above the threshold bin; the workgroup
-//                                 that owns tokens [4096 x, 4096 x + 4096) lists them from entry 4096 x
+//   cand  uint2  [BH][capacity + 4096]  (key, token) pairs in or above the threshold bin; the
+//                                 workgroup that owns tokens [T x, T x + T) lists them from entry T x
+//                                 (T = tokens per workgroup of the launch, rounded up to 4)
 //   hist  uint32 [BH][8192]       histogram of the 13-bit key prefix
 //   ctrl  uint32 [BH][8]          1: arrival counter of the Top-K selection; 4: arrival counter of
 //                                 the attention
@@ -144,6 +183,7 @@ __device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __h
 struct SparseWs {
   uint32_t* keys;
   uint2* cand;
+  size_t cand_stride;  // entries per (sequence, KV head)
   uint32_t* hist;
   uint32_t* ctrl;
   uint32_t* blk;
@@ -156,7 +196,7 @@ inline size_t sparse_ws_layout(const tkv_sparse_desc* d, size_t off[6], int32_t*
   const int32_t nb = (int32_t)((cap + 1023) / 1024 + 1);
   size_t o = 0;
   off[0] = o; o = align16(o + bh * cap * 4);
-  off[1] = o; o = align16(o + bh * cap * 8);
+  off[1] = o; o = align16(o + bh * (cap + 4096) * 8);
   off[2] = o; o += bh * 8192 * 4;
   off[3] = o; o = align16(o + bh * 8 * 4);
   off[4] = o; o = align16(o + bh * (size_t)nb * 4);
@@ -171,6 +211,7 @@ inline SparseWs carve_sparse_ws(const tkv_sparse_desc* d, void* workspace) {
   char* base = (char*)workspace;
   ws.keys = (uint32_t*)(base + off[0]);
   ws.cand = (uint2*)(base + off[1]);
+  ws.cand_stride = (size_t)d->capacity + 4096;
   ws.hist = (uint32_t*)(base + off[2]);
   ws.ctrl = (uint32_t*)(base + off[3]);
   ws.blk = (uint32_t*)(base + off[4]);

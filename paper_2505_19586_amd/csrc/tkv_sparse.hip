@@ -14,6 +14,8 @@ struct AppendParams {
   __half* kv_local;
   const __half* k_new;
   const __half* v_new;
+  float* k_absmax;   // Stage 1 buffers updated by the same launch (short appends), or null
+  __half* keys_cm;
   int32_t hkv, ds, n_sink, n_window, capacity;
   int32_t n_stride;  // rows per sequence in k_new / v_new
   TkvSeqLens n_old;
@@ -42,6 +44,17 @@ __global__ __launch_bounds__(256) void sparse_append_kernel(AppendParams p) {
     const size_t bh = (size_t)b * p.hkv + h;
     const int c = p.channel_idx[bh * p.ds + ci];
     p.summary[(bh * p.capacity + tok) * p.ds + ci] = p.k_new[(((size_t)b * p.n_stride + i) * p.hkv + h) * TKV_D + c];
+  }
+  if (p.keys_cm != nullptr) {
+    // Stage 1 (Sec. 4.2): the token's column of the channel-major keys and the running maxima
+    // of Eq. 10 (bit patterns of non-negative floats order like integers)
+    for (int x = tid; x < p.hkv * TKV_D; x += 256) {
+      const int h = x / TKV_D, c = x % TKV_D;
+      const size_t bh = (size_t)b * p.hkv + h;
+      const __half v = p.k_new[(((size_t)b * p.n_stride + i) * p.hkv + h) * TKV_D + c];
+      p.keys_cm[(bh * TKV_D + c) * (size_t)p.capacity + tok] = v;
+      atomicMax(reinterpret_cast<uint32_t*>(p.k_absmax + bh * TKV_D + c), __float_as_uint(fabsf(__half2float(v))));
+    }
   }
 }
 
@@ -294,6 +307,23 @@ int32_t fill_lens(const tkv_sparse_desc* d, const tkv_sparse_cache* c, TkvSeqLen
   return TKV_OK;
 }
 
+// Device-visible address of pinned host memory or of device memory.
+int32_t device_view_of_any(const void* ptr, const void** dev) {
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, ptr);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
+  }
+  if (attr.type == hipMemoryTypeDevice) {
+    *dev = ptr;
+    return TKV_OK;
+  }
+  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
+  *dev = attr.devicePointer;
+  return TKV_OK;
+}
+
 // Device-visible address of a pinned host allocation; TKV_E_NOTPINNED otherwise.
 int32_t device_view_of_host(const void* host, const void** dev) {
   hipPointerAttribute_t attr;
@@ -309,9 +339,19 @@ int32_t device_view_of_host(const void* host, const void** dev) {
 
 }  // namespace
 
-extern "C" int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* d, tkv_sparse_cache* c, const void* k_new,
-                                            const void* v_new, int32_t n_new, const int32_t* n_valid_host,
-                                            void* stream) {
+namespace {
+constexpr int kFusedStage1Rows = 8;  // appends up to this long update the Stage 1 buffers in the same launch
+}
+
+extern "C" int32_t tkv_sparse_append_dynamic(const tkv_sparse_desc* d, tkv_sparse_cache* c,
+                                             const tkv_sparse_stage1* s1, const void* k_new, const void* v_new,
+                                             int32_t n_new, const int32_t* n_valid_host, void* stream) {
+  if (s1 != nullptr && n_new > kFusedStage1Rows) {
+    // long appends: the tiled transpose kernel first, then the plain append
+    const int32_t st1 = tkv_sparse_stage1_append(d, c, s1, k_new, n_new, n_valid_host, stream);
+    if (st1 != TKV_OK) return st1;
+    s1 = nullptr;
+  }
   int32_t st = tkv::check_sparse_desc(d);
   if (st != TKV_OK) return st;
   if (!c || !c->seq_len_host || n_new < 0) return TKV_E_INVAL;
@@ -335,6 +375,16 @@ extern "C" int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* d, tkv_sparse
   p.kv_local = (__half*)c->kv_local;
   p.k_new = (const __half*)k_new;
   p.v_new = (const __half*)v_new;
+  p.k_absmax = nullptr;
+  p.keys_cm = nullptr;
+  if (s1 != nullptr) {
+    if (!s1->k_absmax || !s1->keys_cm) return TKV_E_INVAL;
+    const void* cm = nullptr;
+    st = device_view_of_any(s1->keys_cm, &cm);
+    if (st != TKV_OK) return st;
+    p.k_absmax = s1->k_absmax;
+    p.keys_cm = (__half*)cm;
+  }
   p.hkv = d->n_kv_heads;
   p.ds = d->n_channels;
   p.n_sink = d->n_sink;
@@ -345,6 +395,12 @@ extern "C" int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* d, tkv_sparse
   if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += p.n_add.n[b];
   return TKV_OK;
+}
+
+extern "C" int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* d, tkv_sparse_cache* c, const void* k_new,
+                                            const void* v_new, int32_t n_new, const int32_t* n_valid_host,
+                                            void* stream) {
+  return tkv_sparse_append_dynamic(d, c, nullptr, k_new, v_new, n_new, n_valid_host, stream);
 }
 
 extern "C" int32_t tkv_sparse_append(const tkv_sparse_desc* d, tkv_sparse_cache* c, const void* k_new,

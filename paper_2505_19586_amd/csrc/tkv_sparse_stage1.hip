@@ -4,10 +4,6 @@
 // tkv_sparse_estimate_topk_cm (tkv_sparse_topk.hip).
 #include "tkv_common.h"
 
-// Eq. 10's float32 operations decide integers (the channel list): keep each a single
-// rounded operation.
-#pragma clang fp contract(off)
-
 namespace {
 
 constexpr int kTile = 64;  // tokens per workgroup of the append kernel
@@ -64,28 +60,11 @@ struct SelectParams {
 __global__ __launch_bounds__(TKV_D) void select_channels_kernel(SelectParams p) {
   __shared__ float s_s[TKV_D];
   __shared__ uint32_t s_sel[TKV_D];
-  const int b = blockIdx.y, h = blockIdx.x, c = threadIdx.x;
+  const int b = blockIdx.y, h = blockIdx.x;
   const int G = p.hq / p.hkv;
   const size_t bh = (size_t)b * p.hkv + h;
-  const __half* q0 = p.q_hat + ((size_t)b * p.hq + (size_t)h * G) * TKV_D;
-  float a = fabsf(__half2float(q0[c]));
-  for (int j = 1; j < G; ++j) a = a + fabsf(__half2float(q0[(size_t)j * TKV_D + c]));
-  const float s = a * p.k_absmax[bh * TKV_D + c];
-  s_s[c] = s;
-  __syncthreads();
-  int rank = 0;  // channels that come before this one: larger s, or equal s and lower index
-  for (int j = 0; j < TKV_D; ++j) {
-    const float sj = s_s[j];
-    rank += (sj > s || (sj == s && j < c)) ? 1 : 0;
-  }
-  const bool sel = rank < p.ds;
-  s_sel[c] = sel ? 1u : 0u;
-  __syncthreads();
-  if (sel) {
-    int pos = 0;  // ascending output: selected channels below this one
-    for (int j = 0; j < c; ++j) pos += (int)s_sel[j];
-    p.channel_idx[bh * p.ds + pos] = c;
-  }
+  tkv::select_channels_block(p.q_hat + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, G, p.k_absmax + bh * TKV_D, p.ds,
+                             s_s, s_sel, p.channel_idx + bh * p.ds, nullptr);
 }
 
 struct PrefetchParams {

@@ -23,7 +23,8 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 constexpr int kThreads = 1024;
 constexpr int kWavesPerBlock = kThreads / 64;
 constexpr int kPer = 4;                // tokens per thread in the scoring phase
-constexpr int kTok = kThreads * kPer;  // tokens per workgroup
+constexpr int kTok = kThreads * kPer;  // tokens per workgroup and pass
+constexpr int kMaxPass = 2;            // a workgroup owns up to kMaxPass * kTok tokens (see the entry point)
 constexpr int kPrefixBits = 13;
 constexpr int kBins = 1 << kPrefixBits;  // 8192
 constexpr int kLowBits = 32 - kPrefixBits;  // 19
@@ -38,11 +39,15 @@ struct TopkParams {
   const __half* summary;       // token-major [B][Hkv][capacity][d_s], or channel-major rows (below)
   int32_t rows_per_head;       // channel-major: [B][Hkv][rows_per_head][capacity], d_s or 128 rows
   const int32_t* channel_idx;
+  const float* k_absmax;       // non-null: Stage 1 in the same launch (Eq. 10 from q_hat and these maxima);
+  const __half* q_hat;         //   the list is also written to channel_out
+  int32_t* channel_out;
   const __half* q;
   int32_t* topk_idx;
   int32_t* topk_count;
   tkv::SparseWs ws;
   int32_t hq, hkv, top_k, n_sink, n_window, capacity;
+  int32_t tpw;  // tokens per workgroup: a multiple of 4, at most kMaxPass * kTok
   TkvSeqLens lens;
 #ifdef TKV_PHASE
   long long* prof;
@@ -135,40 +140,54 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int n = p.lens.n[b];
   const size_t bh = (size_t)b * p.hkv + h;
-  const int t0 = blockIdx.x * kTok;
+  const int t0 = blockIdx.x * p.tpw;
   if (t0 >= n) return;
+  const int t_end = min(n, t0 + p.tpw);  // this workgroup's tokens: [t0, t_end), kTok per pass
   TKV_PH(0);
   int lo, hi;
   candidate_range(p, n, lo, hi);
   const uint32_t k = (uint32_t)min(p.top_k, hi - lo);
   const int G = p.hq / p.hkv;
   for (int i = tid; i < kBins; i += kThreads) hist[i] = 0u;
+  // Stage 1 fused in (resident channel-major keys only): every workgroup derives the head's
+  // channel list for itself, the first one also reports it
+  __shared__ int32_t s_chan[DS];
+  const bool dyn = CM && p.k_absmax != nullptr;
+  if (dyn) {
+    __shared__ float s_s[TKV_D];
+    __shared__ uint32_t s_sel[TKV_D];
+    tkv::select_channels_block(p.q_hat + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, G, p.k_absmax + bh * TKV_D, DS,
+                               s_s, s_sel, s_chan, blockIdx.x == 0 ? p.channel_out + bh * DS : nullptr);
+  }
   if (tid < 4 * DS) {
     const int j = tid / DS, i = tid % DS;
-    const int c = p.channel_idx[bh * DS + i];
+    const int c = dyn ? s_chan[i] : p.channel_idx[bh * DS + i];
     qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
   }
   // all of this thread's rows are requested before the first is used (rows past the end
   // re-read the last token)
   uint4 rows[kPer][DS / 8];
   uint2 cols[DS];  // CM: four consecutive tokens of every channel row
-  if (CM) {
-    static_assert(kPer == 4, "four tokens per 8-byte load");
-    const int tq = min(t0 + kPer * tid, (n - 1) & ~3);  // past the end: the last group of four
+  auto load_pass = [&](int tb) {
+    if (CM) {
+      static_assert(kPer == 4, "four tokens per 8-byte load");
+      const int tq = min(tb + kPer * tid, (n - 1) & ~3);  // past the end: the last group of four
 #pragma unroll
-    for (int i = 0; i < DS; ++i) {
-      const int row = p.rows_per_head == DS ? i : p.channel_idx[bh * DS + i];
-      cols[i] = *reinterpret_cast<const uint2*>(p.summary + (bh * p.rows_per_head + row) * (size_t)p.capacity + tq);
+      for (int i = 0; i < DS; ++i) {
+        const int row = dyn ? s_chan[i] : p.rows_per_head == DS ? i : p.channel_idx[bh * DS + i];
+        cols[i] = *reinterpret_cast<const uint2*>(p.summary + (bh * p.rows_per_head + row) * (size_t)p.capacity + tq);
+      }
+    } else {
+      const __half* srow = p.summary + (bh * p.capacity) * DS;
+#pragma unroll
+      for (int it = 0; it < kPer; ++it) {
+        const int t = min(tb + it * kThreads + tid, n - 1);
+#pragma unroll
+        for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
+      }
     }
-  } else {
-    const __half* srow = p.summary + (bh * p.capacity) * DS;
-#pragma unroll
-    for (int it = 0; it < kPer; ++it) {
-      const int t = min(t0 + it * kThreads + tid, n - 1);
-#pragma unroll
-      for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
-    }
-  }
+  };
+  load_pass(t0);
   __syncthreads();
   // query channels into registers (heads >= G are zero: adding their +0 sums changes nothing)
   float qr[4][DS];
@@ -178,9 +197,11 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
     for (int i = 0; i < DS; ++i) qr[j][i] = qc[j][i];
 
   uint32_t* keys = p.ws.keys + bh * p.capacity;
+  for (int tb = t0; tb < t_end; tb += kTok) {
+  if (tb != t0) load_pass(tb);
 #pragma unroll
   for (int it = 0; it < kPer; ++it) {
-    const int t = CM ? t0 + kPer * tid + it : t0 + it * kThreads + tid;
+    const int t = CM ? tb + kPer * tid + it : tb + it * kThreads + tid;
     float kx[DS];
     if (CM) {
 #pragma unroll
@@ -212,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
       total = j == 0 ? a : total + a;
     }
     total = total + 0.0f;
-    if (t < n) {
+    if (t < t_end) {
       uint32_t key = 0u;  // non-candidates: below every score
       if (t >= lo && t < hi) {
         key = score_key(total);
@@ -221,6 +242,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
       keys[t] = key;  // read by the next launch
     }
   }
+  }
   __syncthreads();
   TKV_PH(1);
   // Only bins that can hold the head's k-th key go to the global histogram: the k-th key of
@@ -228,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   // block's own k-th bin are irrelevant (and skipping them spares most global atomics).
   uint32_t first_bin = 0;
   {
-    const int c_lo = max(lo, t0), c_hi = min(hi, min(n, t0 + kTok));
+    const int c_lo = max(lo, t0), c_hi = min(hi, t_end);
     if (c_hi - c_lo >= (int)k && k > 0) {
       uint32_t above_unused;
       find_bin(hist, kBins, k, scratch, first_bin, above_unused);
@@ -245,7 +267,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                // 1024 words
   uint2* list_s = reinterpret_cast<uint2*>(smem + 1024 * 4);         // kListCap entries
   __shared__ uint32_t scratch[kWavesPerBlock + 4];
-  __shared__ uint32_t s_cnt[kPer][kWavesPerBlock];
+  constexpr int kSub = kMaxPass * kPer;  // sub-tiles of kThreads tokens per workgroup
+  __shared__ uint32_t s_cnt[kSub][kWavesPerBlock];
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int lane = tid % 64, wave = tid / 64;
   const int n = p.lens.n[b];
@@ -261,23 +284,25 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
     }
     return;
   }
-  const int t0 = blockIdx.x * kTok;
+  const int t0 = blockIdx.x * p.tpw;
   if (t0 >= n) return;
+  const int t_end = min(n, t0 + p.tpw);
+  const int nsub = (t_end - t0 + kThreads - 1) / kThreads;  // <= kSub
   uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
   uint32_t* gh = p.ws.hist + bh * kBins;
   const uint32_t* keys = p.ws.keys + bh * p.capacity;
-  uint2* list_g = p.ws.cand + bh * (size_t)p.capacity;  // workgroup x owns entries [x * kTok, +kTok)
+  uint2* list_g = p.ws.cand + bh * p.ws.cand_stride;  // workgroup x owns entries [x * tpw, +tpw)
   uint32_t* cnt_g = p.ws.blk + bh * p.ws.nblk_cap;
-  const int nblk = (n + kTok - 1) / kTok;
+  const int nblk = (n + p.tpw - 1) / p.tpw;
 
   // ---- bin of the head's k-th key, found by every workgroup for itself from the head's
   // histogram (complete for every bin that can matter: see the scoring kernel); the keys of
   // this workgroup are requested in the same round
-  uint32_t kb[kPer];
+  uint32_t kb[kSub];
 #pragma unroll
-  for (int j = 0; j < kPer; ++j) {  // sub-tile j, element tid: token order = (j, tid)
+  for (int j = 0; j < kSub; ++j) {  // sub-tile j, element tid: token order = (j, tid)
     const int t = t0 + j * kThreads + tid;
-    kb[j] = t < n ? keys[t] : 0u;
+    kb[j] = (j < nsub && t < t_end) ? keys[t] : 0u;
   }
   uint32_t bin, above;
   {
@@ -293,16 +318,17 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
 
   // ---- this workgroup's tokens in or above the bin, in token order
   {
-    unsigned long long mask[kPer];
+    unsigned long long mask[kSub];
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) {
+    for (int j = 0; j < kSub; ++j) {
       mask[j] = __builtin_amdgcn_ballot_w64(kb[j] != 0u && (kb[j] >> kLowBits) >= bin);
       if (lane == 0) s_cnt[j][wave] = (uint32_t)__builtin_popcountll(mask[j]);
     }
     __syncthreads();
     uint32_t run = 0;  // entries of earlier sub-tiles
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) {
+    for (int j = 0; j < kSub; ++j) {
+      if (j >= nsub) break;
       uint32_t before = 0, all = 0;
       for (int w = 0; w < kWavesPerBlock; ++w) {
         const uint32_t c = s_cnt[j][w];
@@ -357,7 +383,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
     const uint32_t o = offs[x], c = offs[x + 1] - o;
     for (uint32_t i = lane; i < c; i += 64) {
       if (o + i < (uint32_t)kListCap) {
-        const uint2* e = &list_g[(size_t)x * kTok + i];
+        const uint2* e = &list_g[(size_t)x * p.tpw + i];
         list_s[o + i] = make_uint2(ld_agent(&e->x), ld_agent(&e->y));
       }
     }
@@ -369,7 +395,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
       const int mid = (x0 + x1) / 2;
       if (offs[mid] <= i) x0 = mid; else x1 = mid;
     }
-    const uint2* e = &list_g[(size_t)x0 * kTok + (i - offs[x0])];
+    const uint2* e = &list_g[(size_t)x0 * p.tpw + (i - offs[x0])];
     return make_uint2(ld_agent(&e->x), ld_agent(&e->y));
   };
   __syncthreads();
@@ -444,11 +470,14 @@ namespace {
 // (rows_per_head == 0) or channel-major rows.
 int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q, const void* keys,
                              int32_t rows_per_head, const int32_t* channel_idx, int32_t* topk_idx,
-                             int32_t* topk_count, void* workspace, size_t workspace_bytes, void* stream) {
+                             int32_t* topk_count, void* workspace, size_t workspace_bytes, void* stream,
+                             const float* k_absmax = nullptr, const void* q_hat = nullptr,
+                             int32_t* channel_out = nullptr) {
   int32_t st = tkv::check_sparse_desc(d);
   if (st != TKV_OK) return st;
-  if (!c || !c->seq_len_host || !keys || !channel_idx || !q || !topk_idx || !topk_count || !workspace)
-    return TKV_E_INVAL;
+  if (!c || !c->seq_len_host || !keys || !q || !topk_idx || !topk_count || !workspace) return TKV_E_INVAL;
+  if (k_absmax ? (!q_hat || !channel_out) : !channel_idx) return TKV_E_INVAL;
+  if ((uintptr_t)keys % 8 != 0) return TKV_E_INVAL;
   const bool cm = rows_per_head != 0;
   if (cm && rows_per_head != d->n_channels && rows_per_head != TKV_D) return TKV_E_INVAL;
   if (cm && d->capacity % 8 != 0) return TKV_E_INVAL;
@@ -467,6 +496,9 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   p.summary = (const __half*)keys;
   p.rows_per_head = rows_per_head;
   p.channel_idx = channel_idx;
+  p.k_absmax = k_absmax;
+  p.q_hat = (const __half*)q_hat;
+  p.channel_out = channel_out;
   p.q = (const __half*)q;
   p.topk_idx = topk_idx;
   p.topk_count = topk_count;
@@ -482,8 +514,39 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
 #endif
 
   hipStream_t s = (hipStream_t)stream;
-  int nblk = (max_n + kTok - 1) / kTok;
+  // Tokens per workgroup.  The kernels keep one 1024-thread workgroup per compute unit, so
+  // the launch takes ceil(workgroups / compute units) rounds: with 4096 tokens each, a
+  // context just past a multiple of 4096 * (compute units / heads) would pay a whole extra
+  // round for a few tokens.  Instead the heads' tokens are split evenly over as many
+  // workgroups as fill the machine a whole number of times (each owning up to 8192 tokens),
+  // or, when even one round is not filled, over more and smaller workgroups.
+  static const int n_cus = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      v = 0;
+    return v > 0 ? v : 256;
+  }();
+  const int bh_count = d->batch * d->n_kv_heads;
+  const int full = (max_n + kTok - 1) / kTok;
+  int nblk = full > 0 ? full : 1;
+  const int per_head = n_cus / bh_count;  // workgroups per head that fill the machine once
+  if (per_head >= 1) {
+    if (full * bh_count <= n_cus) {
+      nblk = (max_n + kThreads - 1) / kThreads;  // at least one token per thread
+      if (nblk > per_head) nblk = per_head;
+      if (nblk < 1) nblk = 1;
+    } else {
+      nblk = (full * bh_count / n_cus) * per_head;  // whole rounds, rounded down
+    }
+  }
+  int tpw = ((max_n + nblk - 1) / nblk + 3) & ~3;
+  if (tpw < 4) tpw = 4;
+  if (tpw > kMaxPass * kTok) {  // (only if the head count does not divide the compute units evenly)
+    tpw = kMaxPass * kTok;
+  }
+  nblk = (max_n + tpw - 1) / tpw;
   if (nblk < 1) nblk = 1;
+  p.tpw = tpw;
   const dim3 grid(nblk, d->n_kv_heads, d->batch);
   // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
   static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
@@ -521,4 +584,21 @@ extern "C" int32_t tkv_sparse_estimate_topk_cm(const tkv_sparse_desc* d, const t
   if (rows_per_head == 0) return tkv::check_sparse_desc(d) != TKV_OK ? tkv::check_sparse_desc(d) : TKV_E_INVAL;
   return estimate_topk_launch(d, c, q, keys_cm, rows_per_head, channel_idx, topk_idx, topk_count, workspace,
                               workspace_bytes, stream);
+}
+
+extern "C" int32_t tkv_sparse_select_estimate_topk(const tkv_sparse_desc* d, const tkv_sparse_cache* c,
+                                                   const tkv_sparse_stage1* s1, const void* q_hat, const void* q,
+                                                   int32_t* channel_idx_out, int32_t* topk_idx, int32_t* topk_count,
+                                                   void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!s1 || !s1->k_absmax || !s1->keys_cm || !q_hat || !channel_idx_out) return TKV_E_INVAL;
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, s1->keys_cm) != hipSuccess) {
+    (void)hipGetLastError();
+    return TKV_E_INVAL;
+  }
+  if (attr.type != hipMemoryTypeDevice) return TKV_E_INVAL;  // scored in place: the keys must be resident
+  return estimate_topk_launch(d, c, q, s1->keys_cm, TKV_D, nullptr, topk_idx, topk_count, workspace, workspace_bytes,
+                              stream, s1->k_absmax, q_hat, channel_idx_out);
 }

@@ -86,6 +86,10 @@ def lib() -> C.CDLL:
                                                vp, vp, vp]
         L.tkv_sparse_estimate_topk_cm.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, i32,
                                                   vp, vp, vp, sz, vp]
+        L.tkv_sparse_select_estimate_topk.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache),
+                                                      C.POINTER(SparseStage1), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tkv_sparse_append_dynamic.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), C.POINTER(SparseStage1),
+                                                vp, vp, i32, C.POINTER(i32), vp]
         L.tkv_debug_quant_attn_config.argtypes = [i32, i32]
         L.tkv_debug_quant_attn_config.restype = i32
         for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
@@ -93,7 +97,8 @@ def lib() -> C.CDLL:
                      "tkv_sparse_cache_sizes", "tkv_sparse_append", "tkv_sparse_estimate_topk",
                      "tkv_sparse_gather_attn", "tkv_sparse_gather", "tkv_sparse_attn",
                      "tkv_sparse_stage1_sizes", "tkv_sparse_stage1_append", "tkv_sparse_select_channels",
-                     "tkv_sparse_prefetch_keys", "tkv_sparse_estimate_topk_cm"):
+                     "tkv_sparse_prefetch_keys", "tkv_sparse_estimate_topk_cm",
+                     "tkv_sparse_select_estimate_topk", "tkv_sparse_append_dynamic"):
             getattr(L, name).restype = C.c_int32
         _LIB = L
     return _LIB
@@ -290,7 +295,8 @@ class Stage1:
     channel maxima, a channel-major copy of the keys (pinned host memory, or device
     memory with resident=True) and two buffers for the fetched critical key cache."""
 
-    def __init__(self, layer: SparseLayer, resident: bool = False, keys_cm: torch.Tensor | None = None):
+    def __init__(self, layer: SparseLayer, resident: bool = False, keys_cm: torch.Tensor | None = None,
+                 fetched: list | None = None):
         self.layer = layer
         d = layer.desc
         sizes = (C.c_size_t * 2)()
@@ -305,8 +311,12 @@ class Stage1:
         self.resident = keys_cm.is_cuda
         self.keys_cm = keys_cm.view(-1)[: int(sizes[1]) // 2].view(d.batch, d.n_kv_heads, d.head_dim, d.capacity)
         self.channel_idx = torch.zeros(d.batch, d.n_kv_heads, d.n_channels, dtype=torch.int32, device=layer.device)
-        self.fetched = [torch.zeros(d.batch, d.n_kv_heads, d.n_channels, d.capacity, dtype=torch.float16,
-                                    device=layer.device) for _ in range(2)]   # double buffer (Sec. 4.2)
+        if fetched is None:   # double buffer (Sec. 4.2); layers of the same shape may share one pair
+            fetched = [torch.zeros(d.batch, d.n_kv_heads, d.n_channels, d.capacity, dtype=torch.float16,
+                                   device=layer.device) for _ in range(2)]
+        assert len(fetched) == 2 and all(tuple(f.shape) == (d.batch, d.n_kv_heads, d.n_channels, d.capacity)
+                                         for f in fetched)
+        self.fetched = fetched
         self.s1 = SparseStage1(self.k_absmax.data_ptr(), self.keys_cm.data_ptr())
 
     def append(self, k_new: torch.Tensor, n_valid=None, stream=None) -> None:
@@ -322,6 +332,36 @@ class Stage1:
                                               k_new.data_ptr(), int(k_new.shape[1]),
                                               None if nv is None else nv.ctypes.data_as(C.POINTER(C.c_int32)),
                                               _stream(stream)), "tkv_sparse_stage1_append")
+
+    def append_both(self, k_new: torch.Tensor, v_new: torch.Tensor, n_valid=None, stream=None) -> None:
+        """Stage 1 buffers and the layer's own cache in one call (tkv_sparse_append_dynamic)."""
+        L = self.layer
+        d = L.desc
+        assert k_new.dtype == torch.float16 and k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous()
+        assert tuple(k_new.shape) == tuple(v_new.shape) and k_new.shape[0] == d.batch
+        assert tuple(k_new.shape[2:]) == (d.n_kv_heads, d.head_dim)
+        nv = None
+        if n_valid is not None:
+            nv = np.ascontiguousarray(n_valid, dtype=np.int32)
+            assert nv.shape == (d.batch,)
+        _check(lib().tkv_sparse_append_dynamic(C.byref(d), C.byref(L.cache), C.byref(self.s1), k_new.data_ptr(),
+                                               v_new.data_ptr(), int(k_new.shape[1]),
+                                               None if nv is None else nv.ctypes.data_as(C.POINTER(C.c_int32)),
+                                               _stream(stream)), "tkv_sparse_append_dynamic")
+
+    def select_estimate_topk(self, q_hat: torch.Tensor, q: torch.Tensor, stream=None):
+        """Eq. 10 and Stage 2 in one call over the resident channel-major keys."""
+        L = self.layer
+        d = L.desc
+        for t in (q_hat, q):
+            assert t.dtype == torch.float16 and t.is_cuda and t.is_contiguous()
+            assert tuple(t.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        _check(lib().tkv_sparse_select_estimate_topk(C.byref(d), C.byref(L.cache), C.byref(self.s1), q_hat.data_ptr(),
+                                                     q.data_ptr(), self.channel_idx.data_ptr(), L.topk_idx.data_ptr(),
+                                                     L.topk_count.data_ptr(), L.workspace.data_ptr(),
+                                                     L.workspace_bytes, _stream(stream)),
+               "tkv_sparse_select_estimate_topk")
+        return L.topk_idx, L.topk_count
 
     def select_channels(self, q_hat: torch.Tensor, stream=None) -> torch.Tensor:
         d = self.layer.desc

@@ -24,14 +24,18 @@ def _layer(inp, *, top_k, capacity, n_channels=16, resident=False, shape=None):
     return layer, tkv.Stage1(layer, resident=resident)
 
 
-def _append(layer, s1, k, v, pieces):
-    """Append in the given piece sizes: Stage 1 buffers first, then the layer's own."""
+def _append(layer, s1, k, v, pieces, both=False):
+    """Append in the given piece sizes: Stage 1 buffers first, then the layer's own; or both
+    through the combined entry point (short pieces then take its single-launch path)."""
     kd, vd = to_new(k), to_new(v)
     pos = 0
     for s in pieces:
         kn, vn = kd[:, pos:pos + s].contiguous(), vd[:, pos:pos + s].contiguous()
-        s1.append(kn)
-        layer.append(kn, vn)
+        if both:
+            s1.append_both(kn, vn)
+        else:
+            s1.append(kn)
+            layer.append(kn, vn)
         pos += s
     assert pos == k.shape[1]
 
@@ -47,13 +51,17 @@ def _check_stage1_buffers(s1, b, k):
 @pytest.mark.parametrize("resident", [False, True])
 @pytest.mark.parametrize("n,top_k,pieces", [
     (4096, 128, [4096]), (1, 16, [1]), (70, 16, [70]), (1000, 128, [1, 63, 64, 65, 7, 800]),
-    (5000, 1024, [4999, 1]), (4100, 1024, [3, 4097]),
+    (5000, 1024, [4999, 1]), (4100, 1024, [3, 4097]), (300, 128, [200, 8, 9, 1, 1, 1, 2, 70, 8]),
 ])
 def test_select_fetch_score_attend(resident, n, top_k, pieces):
     print(f"case stage1 n={n} k={top_k} resident={resident}", flush=True)
     inp = make_layer(n, config=0, layer=1, seq=n % 83)
     layer, s1 = _layer(inp, top_k=top_k, capacity=(max(n, 64) + 37 + 7) // 8 * 8, resident=resident)
-    _append(layer, s1, inp.k, inp.v, pieces)
+    _append(layer, s1, inp.k, inp.v, pieces, both=(n % 2 == 0))
+    torch.cuda.synchronize()
+    host = layer.kv_host[0, :, :n].numpy()     # the layer's own cache, whichever entry point filled it
+    assert np.array_equal(host[:, :, 0].view(np.uint16), inp.k.view(np.uint16))
+    assert np.array_equal(host[:, :, 1].view(np.uint16), inp.v.view(np.uint16))
     _check_stage1_buffers(s1, 0, inp.k)
     # the query itself stands in for the predicted query of App. B
     q = torch.from_numpy(inp.q)[None].cuda()
@@ -80,6 +88,17 @@ def test_select_fetch_score_attend(resident, n, top_k, pieces):
         torch.cuda.synchronize()
         assert np.array_equal(layer.topk_count[0].cpu().numpy(), cnt)
         assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
+        # Stage 1 and Stage 2 in one call
+        layer.topk_idx.fill_(-7)
+        s1.channel_idx.fill_(-7)
+        s1.select_estimate_topk(q, q)
+        torch.cuda.synchronize()
+        assert np.array_equal(s1.channel_idx[0].cpu().numpy(), ch)
+        assert np.array_equal(layer.topk_count[0].cpu().numpy(), cnt)
+        assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
+    else:
+        with pytest.raises(tkv.TkvError):   # in-place scoring needs resident keys
+            s1.select_estimate_topk(q, q)
     out = layer.gather_attn(q, SM)
     want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, n, SM, n_sink=4, n_window=64)
     assert attn_err(out[0], want) <= TOL
