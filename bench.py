@@ -247,7 +247,8 @@ def main():
         if rec is None and args.dynamic_channels != "off":
             return step_dynamic()
         for l, L in enumerate(layers):
-            L.append(new_k[l], new_v[l])      # Eq. 2: the step's new token joins the cache first
+            if l in QUANT_LAYERS or rec is not None:
+                L.append(new_k[l], new_v[l])      # Eq. 2: the step's new token joins the cache first
             if l in QUANT_LAYERS:
                 if rec is not None:
                     a, b = ev(), ev(); a.record()
@@ -257,9 +258,10 @@ def main():
             else:
                 if rec is not None:
                     a, b = ev(), ev(); a.record()
-                L.estimate_topk(qs[l])
-                if rec is not None:
+                    L.estimate_topk(qs[l])
                     b.record(); rec["topk"].append((a, b))
+                else:                 # the scoring launch also appends the step's new token
+                    L.append_estimate_topk(new_k[l], new_v[l], qs[l])
                 if rec is not None:   # per-call timing pass: the transfer on its own
                     g0, g1 = ev(), ev(); g0.record()
                     L.gather()

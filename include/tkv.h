@@ -217,6 +217,17 @@ int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* desc, const tkv_sparse_c
                                  size_t workspace_bytes, void* stream);
 
 /*
+ * A decode step's tkv_sparse_append_ragged and tkv_sparse_estimate_topk in one call (and
+ * one launch fewer): the n_new <= min(8, n_window) new tokens are appended by the scoring
+ * launch itself (they are newer than every Top-K candidate, so the scores do not depend on
+ * them).  Same results as the two calls.  seq_len_host[b] += n_valid on success.
+ */
+int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* desc, tkv_sparse_cache* cache, const void* k_new,
+                                        const void* v_new, int32_t n_new, const int32_t* n_valid_host,
+                                        const void* q, int32_t* topk_idx, int32_t* topk_count, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+
+/*
  * Fetch of the Top-K tokens from the host cache (Sec. 4.2; the one transfer that
  * cannot be hidden) and exact attention (Eq. 3) of every query head over
  * sinks [0, n_sink) U selected U window [N - n_window, N) (Sec. 5.1: n_local + n_topk).

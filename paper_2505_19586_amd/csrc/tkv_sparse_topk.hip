@@ -49,6 +49,15 @@ struct TopkParams {
   int32_t hq, hkv, top_k, n_sink, n_window, capacity;
   int32_t tpw;  // tokens per workgroup: a multiple of 4, at most kMaxPass * kTok
   TkvSeqLens lens;
+  // Eq. 2 in the same launch (app_k non-null): the last workgroup of every (sequence, KV head)
+  // appends the step's new tokens; lens already counts them
+  const __half* app_k;
+  const __half* app_v;
+  __half* app_host;     // device-visible view of the pinned host cache
+  __half* app_local;
+  __half* app_summary;
+  int32_t app_stride;   // rows per sequence in app_k / app_v
+  TkvSeqLens app_add;
 #ifdef TKV_PHASE
   long long* prof;
 #endif
@@ -129,6 +138,31 @@ __device__ inline void find_bin(const uint32_t* hist, int nbins, uint32_t k, uin
   __syncthreads();
 }
 
+// Cache update (Eq. 2) of one KV head by one workgroup: host rows, resident sink / window rows,
+// critical channels of the key summary.
+template <int DS>
+__device__ inline void append_tokens(const TopkParams& p, int b, int h, int tid) {
+  const size_t bh = (size_t)b * p.hkv + h;
+  const int add = p.app_add.n[b], n1 = p.lens.n[b], n0 = n1 - add;
+  for (int x = tid; x < add * 32; x += kThreads) {
+    const int i = x / 32, kv = (x % 32) / 16, part = x % 16;
+    const int tok = n0 + i;
+    const uint4 v = reinterpret_cast<const uint4*>((kv ? p.app_v : p.app_k) +
+                                                   (((size_t)b * p.app_stride + i) * p.hkv + h) * TKV_D)[part];
+    reinterpret_cast<uint4*>(p.app_host + ((bh * p.capacity + tok) * 2 + kv) * TKV_D)[part] = v;
+    const bool local = tok < p.n_sink || tok >= n1 - p.n_window;
+    const int slot = tok < p.n_sink ? tok : p.n_sink + tok % p.n_window;
+    if (local)
+      reinterpret_cast<uint4*>(p.app_local + ((bh * (p.n_sink + p.n_window) + slot) * 2 + kv) * TKV_D)[part] = v;
+  }
+  for (int x = tid; x < add * DS; x += kThreads) {
+    const int i = x / DS, ci = x % DS;
+    const int c = p.channel_idx[bh * DS + ci];
+    p.app_summary[(bh * p.capacity + (size_t)(n0 + i)) * DS + ci] =
+        p.app_k[(((size_t)b * p.app_stride + i) * p.hkv + h) * TKV_D + c];
+  }
+}
+
 // CM: the critical key cache is channel-major (one row of `capacity` tokens per channel):
 // a thread then scores four consecutive tokens, one 8-byte load per channel row.
 template <int DS, bool CM>
@@ -140,6 +174,12 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int n = p.lens.n[b];
   const size_t bh = (size_t)b * p.hkv + h;
+  if (p.app_k != nullptr && blockIdx.x == gridDim.x - 1) {
+    // The new tokens are newer than every Top-K candidate (at most n_window of them): the
+    // scoring workgroups read their summary rows at most to discard the result.
+    append_tokens<DS>(p, b, h, tid);
+    return;
+  }
   const int t0 = blockIdx.x * p.tpw;
   if (t0 >= n) return;
   const int t_end = min(n, t0 + p.tpw);  // this workgroup's tokens: [t0, t_end), kTok per pass
@@ -472,7 +512,7 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
                              int32_t rows_per_head, const int32_t* channel_idx, int32_t* topk_idx,
                              int32_t* topk_count, void* workspace, size_t workspace_bytes, void* stream,
                              const float* k_absmax = nullptr, const void* q_hat = nullptr,
-                             int32_t* channel_out = nullptr) {
+                             int32_t* channel_out = nullptr, const TopkParams* app = nullptr) {
   int32_t st = tkv::check_sparse_desc(d);
   if (st != TKV_OK) return st;
   if (!c || !c->seq_len_host || !keys || !q || !topk_idx || !topk_count || !workspace) return TKV_E_INVAL;
@@ -547,7 +587,18 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   nblk = (max_n + tpw - 1) / tpw;
   if (nblk < 1) nblk = 1;
   p.tpw = tpw;
+  p.app_k = nullptr;
+  if (app != nullptr) {
+    p.app_k = app->app_k;
+    p.app_v = app->app_v;
+    p.app_host = app->app_host;
+    p.app_local = app->app_local;
+    p.app_summary = app->app_summary;
+    p.app_stride = app->app_stride;
+    p.app_add = app->app_add;
+  }
   const dim3 grid(nblk, d->n_kv_heads, d->batch);
+  const dim3 grid_score(nblk + (app != nullptr ? 1 : 0), d->n_kv_heads, d->batch);
   // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
   static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
@@ -555,14 +606,14 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;  // 4 Mi tokens per sequence
   if (d->n_channels == 16) {
     if (cm)
-      score_kernel<16, true><<<grid, kThreads, kScoreLds, s>>>(p);
+      score_kernel<16, true><<<grid_score, kThreads, kScoreLds, s>>>(p);
     else
-      score_kernel<16, false><<<grid, kThreads, kScoreLds, s>>>(p);
+      score_kernel<16, false><<<grid_score, kThreads, kScoreLds, s>>>(p);
   } else {
     if (cm)
-      score_kernel<8, true><<<grid, kThreads, kScoreLds, s>>>(p);
+      score_kernel<8, true><<<grid_score, kThreads, kScoreLds, s>>>(p);
     else
-      score_kernel<8, false><<<grid, kThreads, kScoreLds, s>>>(p);
+      score_kernel<8, false><<<grid_score, kThreads, kScoreLds, s>>>(p);
   }
   select_kernel<<<grid, kThreads, kSelectLds, s>>>(p);
   return tkv::launch_status();
@@ -601,4 +652,43 @@ extern "C" int32_t tkv_sparse_select_estimate_topk(const tkv_sparse_desc* d, con
   if (attr.type != hipMemoryTypeDevice) return TKV_E_INVAL;  // scored in place: the keys must be resident
   return estimate_topk_launch(d, c, q, s1->keys_cm, TKV_D, nullptr, topk_idx, topk_count, workspace, workspace_bytes,
                               stream, s1->k_absmax, q_hat, channel_idx_out);
+}
+
+extern "C" int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* d, tkv_sparse_cache* c, const void* k_new,
+                                                   const void* v_new, int32_t n_new, const int32_t* n_valid_host,
+                                                   const void* q, int32_t* topk_idx, int32_t* topk_count,
+                                                   void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->seq_len_host || !c->key_summary || !c->channel_idx || !c->kv_host || !c->kv_local || !k_new || !v_new)
+    return TKV_E_INVAL;
+  if (n_new < 1 || n_new > 8 || n_new > d->n_window) return TKV_E_INVAL;
+  TopkParams app;
+  for (int b = 0; b < d->batch; ++b) {
+    const int64_t n0 = c->seq_len_host[b];
+    const int32_t add = n_valid_host ? n_valid_host[b] : n_new;
+    if (n0 < 0 || add < 0 || add > n_new) return TKV_E_INVAL;
+    if (n0 + add > d->capacity) return TKV_E_CAPACITY;
+    app.app_add.n[b] = add;
+  }
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, c->kv_host);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
+  }
+  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
+  app.app_k = (const __half*)k_new;
+  app.app_v = (const __half*)v_new;
+  app.app_host = (__half*)attr.devicePointer;
+  app.app_local = (__half*)c->kv_local;
+  app.app_summary = (__half*)c->key_summary;
+  app.app_stride = n_new;
+  // the kernels see the lengths after the append
+  for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += app.app_add.n[b];
+  st = estimate_topk_launch(d, c, q, c->key_summary, 0, c->channel_idx, topk_idx, topk_count, workspace,
+                            workspace_bytes, stream, nullptr, nullptr, nullptr, &app);
+  if (st != TKV_OK)
+    for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] -= app.app_add.n[b];
+  return st;
 }

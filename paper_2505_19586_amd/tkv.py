@@ -90,6 +90,8 @@ def lib() -> C.CDLL:
                                                       C.POINTER(SparseStage1), vp, vp, vp, vp, vp, vp, sz, vp]
         L.tkv_sparse_append_dynamic.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), C.POINTER(SparseStage1),
                                                 vp, vp, i32, C.POINTER(i32), vp]
+        L.tkv_sparse_append_estimate_topk.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32,
+                                                      C.POINTER(i32), vp, vp, vp, vp, sz, vp]
         L.tkv_debug_quant_attn_config.argtypes = [i32, i32]
         L.tkv_debug_quant_attn_config.restype = i32
         for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
@@ -98,7 +100,8 @@ def lib() -> C.CDLL:
                      "tkv_sparse_gather_attn", "tkv_sparse_gather", "tkv_sparse_attn",
                      "tkv_sparse_stage1_sizes", "tkv_sparse_stage1_append", "tkv_sparse_select_channels",
                      "tkv_sparse_prefetch_keys", "tkv_sparse_estimate_topk_cm",
-                     "tkv_sparse_select_estimate_topk", "tkv_sparse_append_dynamic"):
+                     "tkv_sparse_select_estimate_topk", "tkv_sparse_append_dynamic",
+                     "tkv_sparse_append_estimate_topk"):
             getattr(L, name).restype = C.c_int32
         _LIB = L
     return _LIB
@@ -259,6 +262,26 @@ class SparseLayer:
                                               self.topk_idx.data_ptr(), self.topk_count.data_ptr(),
                                               self.workspace.data_ptr(), self.workspace_bytes, _stream(stream)),
                "tkv_sparse_estimate_topk")
+        return self.topk_idx, self.topk_count
+
+    def append_estimate_topk(self, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, n_valid=None,
+                             stream=None):
+        """A decode step's append and estimate_topk in one call (at most 8 new tokens)."""
+        d = self.desc
+        assert k_new.dtype == torch.float16 and k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous()
+        assert tuple(k_new.shape) == tuple(v_new.shape) and k_new.shape[0] == d.batch
+        assert tuple(k_new.shape[2:]) == (d.n_kv_heads, d.head_dim)
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        nv = None
+        if n_valid is not None:
+            nv = np.ascontiguousarray(n_valid, dtype=np.int32)
+            assert nv.shape == (d.batch,)
+        _check(lib().tkv_sparse_append_estimate_topk(
+            C.byref(d), C.byref(self.cache), k_new.data_ptr(), v_new.data_ptr(), int(k_new.shape[1]),
+            None if nv is None else nv.ctypes.data_as(C.POINTER(C.c_int32)), q.data_ptr(),
+            self.topk_idx.data_ptr(), self.topk_count.data_ptr(), self.workspace.data_ptr(), self.workspace_bytes,
+            _stream(stream)), "tkv_sparse_append_estimate_topk")
         return self.topk_idx, self.topk_count
 
     def gather_attn(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor | None = None,

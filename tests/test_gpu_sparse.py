@@ -168,3 +168,38 @@ def test_ties_beyond_the_on_chip_list():
     assert np.array_equal(cnt[0].cpu().numpy(), want_cnt)
     assert np.array_equal(idx[0].cpu().numpy(), want_idx)
     assert np.array_equal(want_idx[0, :top_k], np.arange(4, 4 + top_k))
+
+
+@pytest.mark.parametrize("n0,steps", [(3000, [1] * 70 + [3, 8, 1]), (0, [1, 1, 2, 8, 1] * 15), (60, [1] * 12)])
+def test_decode_steps_with_append_inside_the_scoring_launch(n0, steps):
+    """tkv_sparse_append_estimate_topk: a decode loop that crosses the sink and window
+    boundaries; after every step the selection and the attention are the oracle's for the
+    whole prefix, and at the end the host cache and the summary hold every token."""
+    print(f"case sparse fused append n0={n0}", flush=True)
+    total = n0 + sum(steps)
+    inp = make_layer(total, config=0, layer=1, seq=11)
+    layer = tkv.SparseLayer(top_k=128, capacity=total + 5)
+    ch = static_channels(inp.k, 16)
+    layer.set_channels(ch[None])
+    kd, vd = to_new(inp.k), to_new(inp.v)
+    if n0:
+        layer.append(kd[:, :n0].contiguous(), vd[:, :n0].contiguous())
+    q = torch.from_numpy(inp.q)[None].cuda()
+    pos = n0
+    for i, s in enumerate(steps):
+        layer.append_estimate_topk(kd[:, pos:pos + s].contiguous(), vd[:, pos:pos + s].contiguous(), q)
+        pos += s
+        assert int(layer.seq_len[0]) == pos
+        out = layer.gather_attn(q, SM)
+        if i % 7 == 0 or i >= len(steps) - 3:
+            sub = LayerInputs(inp.q, inp.k[:, :pos], inp.v[:, :pos], inp.outlier_channels, inp.dominant_tokens)
+            _check_layer(layer, 0, sub, ch, q, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.key_summary[0, :, :total].cpu().numpy().view(np.uint16),
+                          sparse.key_summary(inp.k, ch).view(np.uint16))
+    host = layer.kv_host[0, :, :total].numpy()
+    assert np.array_equal(host[:, :, 0].view(np.uint16), inp.k.view(np.uint16))
+    assert np.array_equal(host[:, :, 1].view(np.uint16), inp.v.view(np.uint16))
+    # too many rows for the fused form
+    with pytest.raises(tkv.TkvError):
+        layer.append_estimate_topk(kd[:, :9].contiguous(), vd[:, :9].contiguous(), q)
