@@ -180,11 +180,11 @@ def main():
         because the synthetic queries of different layers are independent."""
         pending = None   # (layer, event after which its staged rows are complete)
         for l, L in enumerate(layers):
-            L.append(new_k[l], new_v[l])
             if l in QUANT_LAYERS:
+                L.append(new_k[l], new_v[l])
                 L.attn_decode(qs[l], sm, out=outs[l])
                 continue
-            L.estimate_topk(qs[l])
+            L.append_estimate_topk(new_k[l], new_v[l], qs[l])
             ready = torch.cuda.Event()
             ready.record(compute)
             side.wait_event(ready)

@@ -204,14 +204,14 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
     const int c = dyn ? s_chan[i] : p.channel_idx[bh * DS + i];
     qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
   }
-  // all of this thread's rows are requested before the first is used (rows past the end
-  // re-read the last token)
+  // all of this thread's rows of a pass are requested before the first is used (threads past
+  // the workgroup's last token re-read that token: no traffic beyond the workgroup's share)
   uint4 rows[kPer][DS / 8];
   uint2 cols[DS];  // CM: four consecutive tokens of every channel row
   auto load_pass = [&](int tb) {
     if (CM) {
       static_assert(kPer == 4, "four tokens per 8-byte load");
-      const int tq = min(tb + kPer * tid, (n - 1) & ~3);  // past the end: the last group of four
+      const int tq = min(tb + kPer * tid, (t_end - 1) & ~3);  // past the end: the workgroup's last group of four
 #pragma unroll
       for (int i = 0; i < DS; ++i) {
         const int row = dyn ? s_chan[i] : p.rows_per_head == DS ? i : p.channel_idx[bh * DS + i];
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
       const __half* srow = p.summary + (bh * p.capacity) * DS;
 #pragma unroll
       for (int it = 0; it < kPer; ++it) {
-        const int t = min(tb + it * kThreads + tid, n - 1);
+        const int t = min(tb + it * kThreads + tid, t_end - 1);  // past the end: the workgroup's last row again
 #pragma unroll
         for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
       }
