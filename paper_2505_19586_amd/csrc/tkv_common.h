@@ -45,6 +45,29 @@ int32_t check_quant_desc(const tkv_quant_desc* d);
 int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, int n_parts, hipStream_t s);
 int32_t check_sparse_desc(const tkv_sparse_desc* d);
 
+// Device-visible address of a caller's buffer.  kDevHostOnly: pinned host memory only
+// (TKV_E_NOTPINNED otherwise); kDevAny: pinned host memory or device memory; kDevDeviceOnly:
+// device memory only (TKV_E_INVAL otherwise).
+enum DevView { kDevHostOnly, kDevAny, kDevDeviceOnly };
+inline int32_t device_view(const void* ptr, DevView mode, const void** dev) {
+  hipPointerAttribute_t attr;
+  const hipError_t e = hipPointerGetAttributes(&attr, ptr);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    if (mode == kDevDeviceOnly) return TKV_E_INVAL;
+    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
+  }
+  if (attr.type == hipMemoryTypeDevice) {
+    if (mode == kDevHostOnly) return TKV_E_NOTPINNED;
+    *dev = ptr;
+    return TKV_OK;
+  }
+  if (mode == kDevDeviceOnly) return TKV_E_INVAL;
+  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
+  *dev = attr.devicePointer;
+  return TKV_OK;
+}
+
 // ---- cross-chunk merge by the last workgroup of a (sequence, KV head) --------------------
 // Partials cross workgroups through device-scope stores and loads (they bypass the caches
 // that are not coherent between workgroups).  Such loads are served slowly, one load

@@ -307,36 +307,6 @@ int32_t fill_lens(const tkv_sparse_desc* d, const tkv_sparse_cache* c, TkvSeqLen
   return TKV_OK;
 }
 
-// Device-visible address of pinned host memory or of device memory.
-int32_t device_view_of_any(const void* ptr, const void** dev) {
-  hipPointerAttribute_t attr;
-  hipError_t e = hipPointerGetAttributes(&attr, ptr);
-  if (e != hipSuccess) {
-    (void)hipGetLastError();
-    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
-  }
-  if (attr.type == hipMemoryTypeDevice) {
-    *dev = ptr;
-    return TKV_OK;
-  }
-  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
-  *dev = attr.devicePointer;
-  return TKV_OK;
-}
-
-// Device-visible address of a pinned host allocation; TKV_E_NOTPINNED otherwise.
-int32_t device_view_of_host(const void* host, const void** dev) {
-  hipPointerAttribute_t attr;
-  hipError_t e = hipPointerGetAttributes(&attr, host);
-  if (e != hipSuccess) {
-    (void)hipGetLastError();
-    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
-  }
-  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
-  *dev = attr.devicePointer;
-  return TKV_OK;
-}
-
 }  // namespace
 
 namespace {
@@ -367,7 +337,7 @@ extern "C" int32_t tkv_sparse_append_dynamic(const tkv_sparse_desc* d, tkv_spars
     p.n_add.n[b] = add;
   }
   const void* host_dev = nullptr;
-  st = device_view_of_host(c->kv_host, &host_dev);
+  st = tkv::device_view(c->kv_host, tkv::kDevHostOnly, &host_dev);
   if (st != TKV_OK) return st;
   p.summary = (__half*)c->key_summary;
   p.channel_idx = c->channel_idx;
@@ -380,7 +350,7 @@ extern "C" int32_t tkv_sparse_append_dynamic(const tkv_sparse_desc* d, tkv_spars
   if (s1 != nullptr) {
     if (!s1->k_absmax || !s1->keys_cm) return TKV_E_INVAL;
     const void* cm = nullptr;
-    st = device_view_of_any(s1->keys_cm, &cm);
+    st = tkv::device_view(s1->keys_cm, tkv::kDevAny, &cm);
     if (st != TKV_OK) return st;
     p.k_absmax = s1->k_absmax;
     p.keys_cm = (__half*)cm;
@@ -414,7 +384,7 @@ extern "C" int32_t tkv_sparse_gather(const tkv_sparse_desc* d, const tkv_sparse_
   if (st != TKV_OK) return st;
   if (!c || !c->kv_host || !topk_idx || !topk_count || !staging) return TKV_E_INVAL;
   const void* host_dev = nullptr;
-  st = device_view_of_host(c->kv_host, &host_dev);
+  st = tkv::device_view(c->kv_host, tkv::kDevHostOnly, &host_dev);
   if (st != TKV_OK) return st;
   GatherParams p;
   p.kv_host = (const __half*)host_dev;
@@ -478,7 +448,7 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
   p.out = (__half*)out;
   if (topk_idx_fused) {
     const void* host_dev = nullptr;
-    st = device_view_of_host(c->kv_host, &host_dev);
+    st = tkv::device_view(c->kv_host, tkv::kDevHostOnly, &host_dev);
     if (st != TKV_OK) return st;
     p.kv_host = (const __half*)host_dev;
     p.topk_idx = topk_idx_fused;

@@ -104,23 +104,6 @@ __global__ __launch_bounds__(256) void prefetch_rows_kernel(PrefetchParams p) {
   }
 }
 
-// Device-visible address of pinned host memory or of device memory.
-int32_t device_view(const void* ptr, const void** dev) {
-  hipPointerAttribute_t attr;
-  hipError_t e = hipPointerGetAttributes(&attr, ptr);
-  if (e != hipSuccess) {
-    (void)hipGetLastError();
-    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
-  }
-  if (attr.type == hipMemoryTypeDevice) {
-    *dev = ptr;
-    return TKV_OK;
-  }
-  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
-  *dev = attr.devicePointer;
-  return TKV_OK;
-}
-
 }  // namespace
 
 extern "C" int32_t tkv_sparse_stage1_sizes(const tkv_sparse_desc* d, size_t bytes_out[2]) {
@@ -152,7 +135,7 @@ extern "C" int32_t tkv_sparse_stage1_append(const tkv_sparse_desc* d, const tkv_
     p.n_add.n[b] = add;
   }
   const void* cm = nullptr;
-  st = device_view(s1->keys_cm, &cm);
+  st = tkv::device_view(s1->keys_cm, tkv::kDevAny, &cm);
   if (st != TKV_OK) return st;
   p.k_absmax = s1->k_absmax;
   p.keys_cm = (__half*)cm;
@@ -199,7 +182,7 @@ extern "C" int32_t tkv_sparse_prefetch_keys(const tkv_sparse_desc* d, const tkv_
   }
   if (max_n == 0) return TKV_OK;
   const void* cm = nullptr;
-  st = device_view(s1->keys_cm, &cm);
+  st = tkv::device_view(s1->keys_cm, tkv::kDevAny, &cm);
   if (st != TKV_OK) return st;
   p.keys_cm = (const __half*)cm;
   p.channel_idx = channel_idx;

@@ -644,12 +644,9 @@ extern "C" int32_t tkv_sparse_select_estimate_topk(const tkv_sparse_desc* d, con
   int32_t st = tkv::check_sparse_desc(d);
   if (st != TKV_OK) return st;
   if (!s1 || !s1->k_absmax || !s1->keys_cm || !q_hat || !channel_idx_out) return TKV_E_INVAL;
-  hipPointerAttribute_t attr;
-  if (hipPointerGetAttributes(&attr, s1->keys_cm) != hipSuccess) {
-    (void)hipGetLastError();
-    return TKV_E_INVAL;
-  }
-  if (attr.type != hipMemoryTypeDevice) return TKV_E_INVAL;  // scored in place: the keys must be resident
+  const void* cm = nullptr;  // scored in place: the keys must be resident
+  st = tkv::device_view(s1->keys_cm, tkv::kDevDeviceOnly, &cm);
+  if (st != TKV_OK) return st;
   return estimate_topk_launch(d, c, q, s1->keys_cm, TKV_D, nullptr, topk_idx, topk_count, workspace, workspace_bytes,
                               stream, s1->k_absmax, q_hat, channel_idx_out);
 }
@@ -671,16 +668,12 @@ extern "C" int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* d, tkv
     if (n0 + add > d->capacity) return TKV_E_CAPACITY;
     app.app_add.n[b] = add;
   }
-  hipPointerAttribute_t attr;
-  hipError_t e = hipPointerGetAttributes(&attr, c->kv_host);
-  if (e != hipSuccess) {
-    (void)hipGetLastError();
-    return e == hipErrorInvalidValue ? TKV_E_NOTPINNED : TKV_E_HIP;
-  }
-  if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) return TKV_E_NOTPINNED;
+  const void* host_dev = nullptr;
+  st = tkv::device_view(c->kv_host, tkv::kDevHostOnly, &host_dev);
+  if (st != TKV_OK) return st;
   app.app_k = (const __half*)k_new;
   app.app_v = (const __half*)v_new;
-  app.app_host = (__half*)attr.devicePointer;
+  app.app_host = (__half*)host_dev;
   app.app_local = (__half*)c->kv_local;
   app.app_summary = (__half*)c->key_summary;
   app.app_stride = n_new;

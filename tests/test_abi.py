@@ -152,6 +152,39 @@ def test_call_errors_before_any_gpu_work(L):
     assert L.tkv_sparse_gather(C.byref(s), C.byref(sc2), fake, fake, fake, None) in (-5, -6)
 
 
+def test_stage1_and_fused_entry_points_validate_before_any_gpu_work(L):
+    from paper_2505_19586_amd.tkv import SparseCache, SparseStage1
+    fake = C.c_void_p(0x1000)
+    s = _sdesc()                                   # capacity 4096
+    lens = (C.c_int32 * 1)(4090)
+    sc = SparseCache(fake, fake, fake, fake, lens)
+    s1 = SparseStage1(fake, fake)
+    sizes = (C.c_size_t * 2)()
+    assert L.tkv_sparse_stage1_sizes(C.byref(s), sizes) == 0
+    assert sizes[0] == 8 * 128 * 4 and sizes[1] == 8 * 128 * 4096 * 2
+    assert L.tkv_sparse_stage1_sizes(C.byref(s), None) == -1
+    # capacity
+    assert L.tkv_sparse_stage1_append(C.byref(s), C.byref(sc), C.byref(s1), fake, 10, None, None) == -3
+    assert L.tkv_sparse_append_dynamic(C.byref(s), C.byref(sc), C.byref(s1), fake, fake, 10, None, None) == -3
+    assert L.tkv_sparse_append_estimate_topk(C.byref(s), C.byref(sc), fake, fake, 7, None, fake, fake, fake, fake,
+                                             1 << 30, None) == -3
+    assert lens[0] == 4090                         # nothing was appended
+    # too many rows for the fused decode-step form, NULL arguments, channel-major shape rules
+    assert L.tkv_sparse_append_estimate_topk(C.byref(s), C.byref(sc), fake, fake, 9, None, fake, fake, fake, fake,
+                                             1 << 30, None) == -1
+    assert L.tkv_sparse_select_channels(C.byref(s), C.byref(s1), None, fake, None) == -1
+    assert L.tkv_sparse_select_channels(C.byref(s), None, fake, fake, None) == -1
+    assert L.tkv_sparse_prefetch_keys(C.byref(s), C.byref(sc), C.byref(s1), None, fake, None) == -1
+    assert L.tkv_sparse_estimate_topk_cm(C.byref(s), C.byref(sc), fake, fake, fake, 7, fake, fake, fake, 1 << 30,
+                                         None) == -1          # rows_per_head must be d_s or 128
+    assert L.tkv_sparse_estimate_topk_cm(C.byref(s), C.byref(sc), fake, fake, fake, 16, fake, fake, fake, 8,
+                                         None) == -4          # workspace too small
+    odd = _sdesc(capacity=4100)                                # channel-major rows need capacity % 8 == 0
+    assert L.tkv_sparse_estimate_topk_cm(C.byref(odd), C.byref(sc), fake, fake, fake, 16, fake, fake, fake,
+                                         1 << 30, None) == -1
+    assert L.tkv_sparse_stage1_append(C.byref(odd), C.byref(sc), C.byref(s1), fake, 1, None, None) == -1
+
+
 def test_binding_refuses_to_run_without_gpu():
     import torch
     if torch.cuda.is_available():
