@@ -92,18 +92,20 @@ def test_stage1_full_size():
     assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
 
 
-def test_batched_ragged_hybrid():
-    """Batch 8, ragged lengths (scaled-down version of the batched configuration)."""
-    lens = ragged_lengths(8, 4096, 8192).tolist()
+@pytest.mark.parametrize("lo,hi", [(4096, 8192), (16384, 32768)])
+def test_batched_ragged_hybrid(lo, hi):
+    """Batch 8, ragged lengths: the batched configuration at its own sizes (16384..32768
+    tokens per sequence) and a scaled-down version."""
+    lens = ragged_lengths(8, lo, hi).tolist()
     print(f"case batched ragged lens={lens}", flush=True)
     nmax = max(lens)
     inps = [make_layer(n, config=4, layer=0, seq=b) for b, n in enumerate(lens)]
     q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
     kb, vb = to_new_batch([i.k for i in inps], nmax), to_new_batch([i.v for i in inps], nmax)
-    ql = tkv.QuantLayer(bits=2, capacity=8192, batch=8)
+    ql = tkv.QuantLayer(bits=2, capacity=hi, batch=8)
     ql.append(kb, vb, n_valid=lens)
     out = ql.attn_decode(q, SM)
-    sl = tkv.SparseLayer(top_k=1024, capacity=8192, batch=8)
+    sl = tkv.SparseLayer(top_k=1024, capacity=hi, batch=8)
     chs = [static_channels(i.k, 16) for i in inps]
     sl.set_channels(np.stack(chs))
     sl.append(kb, vb, n_valid=lens)
