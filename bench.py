@@ -309,10 +309,47 @@ def main():
     # per-kernel durations with events on the launching stream (separate passes so the
     # events do not perturb the step time above)
     rec = {"quant": [], "topk": [], "gather": []}
-    for _ in range(max(3, args.steps // 2)):
+    for _ in range(max(25, args.steps // 2)):   # >= 50 samples of every call
         step_chained(rec)
     torch.cuda.synchronize()
-    dur = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) * 1e3 for k, v in rec.items() if v}  # us
+    samples = {k: np.array([a.elapsed_time(b) for a, b in v]) * 1e3 for k, v in rec.items() if v}  # us
+    dur = {k: float(v.mean()) for k, v in samples.items()}
+    spread = {k: {"n": int(v.size), "p10": float(np.percentile(v, 10)), "p50": float(np.percentile(v, 50)),
+                  "p90": float(np.percentile(v, 90))} for k, v in samples.items()}
+
+    # The dominant kernel on its own: launches back to back between ONE pair of events (an event
+    # pair around a single launch adds 3-4 us of its own), over four distinct caches (> 256 MB
+    # in total, so every sweep comes from HBM as it does inside the step).
+    pool = [layers[l] for l in QUANT_LAYERS]
+    for x in range(max(0, 4 - len(pool))):
+        _, k, v = make_layer_device(N, seed=5000 + x, device=dev)
+        L = tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=CAP, device=dev)
+        L.append(k[None], v[None])
+        pool.append(L)
+        del k, v
+    for L in pool:
+        L.attn_decode(qs[0], sm, out=outs[0])
+    e0, e1 = ev(), ev()
+    rounds = 13   # 52 launches
+    e0.record()
+    for _ in range(rounds):
+        for L in pool:
+            L.attn_decode(qs[0], sm, out=outs[0])
+    e1.record()
+    torch.cuda.synchronize()
+    dur["quant_in_step"] = dur["quant"]
+    dur["quant"] = e0.elapsed_time(e1) * 1e3 / (rounds * len(pool))
+    del pool
+    # the gather alone, the same way: every sparse layer's rows (distinct host caches), twice
+    g0, g1 = ev(), ev()
+    g0.record()
+    for _ in range(2):
+        for l in sparse_ids:
+            layers[l].gather()
+    g1.record()
+    torch.cuda.synchronize()
+    dur["gather_in_step"] = dur["gather"]
+    dur["gather"] = g0.elapsed_time(g1) * 1e3 / (2 * len(sparse_ids))
 
     nq = (N - 128) // args.group * args.group
     # Sec. 4.4, Table 2: b/8 bytes per code, one fp16 scaler and zero-point per group, for K and V
@@ -326,8 +363,9 @@ def main():
             "algorithmic_bytes": quant_bytes}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {
-        "quant_attn_us": dur["quant"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"],
+        "quant_attn_us": dur["quant"], "quant_attn_in_step_us": dur["quant_in_step"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"], "gather_in_step_us": dur["gather_in_step"],
         "estimate_topk_GBs": summary_bytes / dur["topk"] / 1e3,
+        "per_call_us": {"quant_attn": spread["quant"], "estimate_topk": spread["topk"], "gather": spread["gather"]},
         "other_schedule": None if ms_other is None else {
             "schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS,
             "gather_compute_units": args.gather_cus},
