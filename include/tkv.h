@@ -166,7 +166,8 @@ typedef struct {
   int32_t n_q_heads;
   int32_t n_kv_heads;
   int32_t head_dim;     /* 128                                                            */
-  int32_t n_channels;   /* d_s: critical channels kept on the GPU; 16 (or 8)              */
+  int32_t n_channels;   /* d_s: critical channels kept on the GPU; 16, 12 or 8 (Sec. 5.1
+                           runs 8 and 12)                                                 */
   int32_t top_k;        /* n_topk: tokens fetched per KV head, 1..4096                    */
   int32_t n_sink;       /* first tokens always resident; with n_window this is n_local    */
   int32_t n_window;     /* newest tokens always resident; 1..1024                         */

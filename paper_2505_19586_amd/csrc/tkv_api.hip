@@ -44,7 +44,7 @@ int32_t check_sparse_desc(const tkv_sparse_desc* d) {
   if (st != TKV_OK) return st;
   if (d->n_channels <= 0 || d->top_k <= 0 || d->n_sink < 0 || d->n_window <= 0 || d->capacity <= 0)
     return TKV_E_INVAL;
-  if (d->n_channels != 16 && d->n_channels != 8) return TKV_E_UNSUPPORTED;
+  if (d->n_channels != 16 && d->n_channels != 12 && d->n_channels != 8) return TKV_E_UNSUPPORTED;
   if (d->top_k > 4096 || d->n_window > 1024 || d->n_sink > 1024) return TKV_E_UNSUPPORTED;
   return TKV_OK;
 }

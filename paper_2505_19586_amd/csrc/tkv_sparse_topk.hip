@@ -206,7 +206,8 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   }
   // all of this thread's rows of a pass are requested before the first is used (threads past
   // the workgroup's last token re-read that token: no traffic beyond the workgroup's share)
-  uint4 rows[kPer][DS / 8];
+  static_assert(DS % 4 == 0, "summary rows are read in 8-byte pieces");
+  uint2 rows[kPer][DS / 4];  // (pairs of pieces merge into 16-byte loads where the row allows it)
   uint2 cols[DS];  // CM: four consecutive tokens of every channel row
   auto load_pass = [&](int tb) {
     if (CM) {
@@ -222,8 +223,17 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
 #pragma unroll
       for (int it = 0; it < kPer; ++it) {
         const int t = min(tb + it * kThreads + tid, t_end - 1);  // past the end: the workgroup's last row again
+        if (DS % 8 == 0) {
 #pragma unroll
-        for (int x = 0; x < DS / 8; ++x) rows[it][x] = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
+          for (int x = 0; x < DS / 8; ++x) {
+            const uint4 v = reinterpret_cast<const uint4*>(srow + (size_t)t * DS)[x];
+            rows[it][2 * x] = make_uint2(v.x, v.y);
+            rows[it][2 * x + 1] = make_uint2(v.z, v.w);
+          }
+        } else {
+#pragma unroll
+          for (int x = 0; x < DS / 4; ++x) rows[it][x] = reinterpret_cast<const uint2*>(srow + (size_t)t * DS)[x];
+        }
       }
     }
   };
@@ -252,14 +262,14 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
       }
     } else {
 #pragma unroll
-      for (int x = 0; x < DS / 8; ++x) {
-        const uint32_t w[4] = {rows[it][x].x, rows[it][x].y, rows[it][x].z, rows[it][x].w};
+      for (int x = 0; x < DS / 4; ++x) {
+        const uint32_t w[2] = {rows[it][x].x, rows[it][x].y};
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
+        for (int y = 0; y < 2; ++y) {
           const uint32_t wy = w[y];
           const half2_t hh = __builtin_bit_cast(half2_t, wy);
-          kx[8 * x + 2 * y] = (float)hh[0];
-          kx[8 * x + 2 * y + 1] = (float)hh[1];
+          kx[4 * x + 2 * y] = (float)hh[0];
+          kx[4 * x + 2 * y + 1] = (float)hh[1];
         }
       }
     }
@@ -609,6 +619,11 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
       score_kernel<16, true><<<grid_score, kThreads, kScoreLds, s>>>(p);
     else
       score_kernel<16, false><<<grid_score, kThreads, kScoreLds, s>>>(p);
+  } else if (d->n_channels == 12) {
+    if (cm)
+      score_kernel<12, true><<<grid_score, kThreads, kScoreLds, s>>>(p);
+    else
+      score_kernel<12, false><<<grid_score, kThreads, kScoreLds, s>>>(p);
   } else {
     if (cm)
       score_kernel<8, true><<<grid_score, kThreads, kScoreLds, s>>>(p);

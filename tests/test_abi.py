@@ -104,7 +104,7 @@ def test_bad_struct_size_and_null(L):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(n_channels=12), -2), (dict(n_channels=0), -1), (dict(top_k=0), -1), (dict(top_k=5000), -2),
+    (dict(n_channels=10), -2), (dict(n_channels=12), 0), (dict(n_channels=0), -1), (dict(top_k=0), -1), (dict(top_k=5000), -2),
     (dict(n_window=0), -1), (dict(n_sink=-1), -1), (dict(head_dim=96), -2),
 ])
 def test_sparse_desc_errors(L, kw, status):

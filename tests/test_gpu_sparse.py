@@ -139,7 +139,7 @@ def test_ragged_batch():
         _check_layer(layer, b, inp, chs[b], q, out)
 
 
-@pytest.mark.parametrize("shape,n_channels", [(HeadShape(8, 8, 128), 16), (HeadShape(16, 8, 128), 8)])
+@pytest.mark.parametrize("shape,n_channels", [(HeadShape(8, 8, 128), 16), (HeadShape(16, 8, 128), 8), (HeadShape(32, 8, 128), 12)])
 def test_other_shapes(shape, n_channels):
     inp = make_layer(2500, shape=shape, seq=11)
     layer, ch = _build(inp, top_k=200, capacity=2500, n_channels=n_channels, shape=shape)

@@ -153,6 +153,36 @@ def test_ragged_batch_other_grouping_and_eight_channels():
         assert attn_err(out[b], want) <= TOL
 
 
+def test_the_papers_long_context_setting():
+    """Sec. 5.1 / App. D: 12 critical channels, n_local = 128 (no separate sinks), n_topk = 896,
+    channels re-selected from the query, keys fetched from the host copy."""
+    n = 6000
+    inp = make_layer(n, config=0, layer=1, seq=21)
+    layer = tkv.SparseLayer(n_channels=12, top_k=896, n_sink=0, n_window=128, capacity=6000)
+    s1 = tkv.Stage1(layer)
+    _append(layer, s1, inp.k, inp.v, [5990, 8, 2], both=True)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    ch_dev = s1.select_channels(q)
+    s1.prefetch(0)
+    s1.estimate_topk(q, 0)
+    out = layer.gather_attn(q, SM)
+    torch.cuda.synchronize()
+    ch = sparse.select_channels(inp.q, sparse.channel_absmax(inp.k), 12)
+    assert np.array_equal(ch_dev[0].cpu().numpy(), ch)
+    idx, cnt = sparse.estimate_topk(inp.q, sparse.key_summary(inp.k, ch), ch, n, top_k=896, n_sink=0, n_window=128)
+    assert np.array_equal(layer.topk_count[0].cpu().numpy(), cnt)
+    assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
+    want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, n, SM, n_sink=0, n_window=128)
+    assert attn_err(out[0], want) <= TOL
+    # the same list through the token-major summary (static path with 12 channels)
+    layer2 = tkv.SparseLayer(n_channels=12, top_k=896, n_sink=0, n_window=128, capacity=6000)
+    layer2.set_channels(ch[None])
+    layer2.append(to_new(inp.k), to_new(inp.v))
+    layer2.estimate_topk(q)
+    torch.cuda.synchronize()
+    assert np.array_equal(layer2.topk_idx[0].cpu().numpy(), idx)
+
+
 def test_argument_errors():
     inp = make_layer(100, seq=1)
     layer = tkv.SparseLayer(top_k=16, capacity=100)          # capacity not a multiple of 8
