@@ -33,6 +33,13 @@ def parse():
     ap.add_argument("--bits", type=int, default=2, help="code width of the quantized layers (1, 2, 4)")
     ap.add_argument("--group", type=int, default=32, help="quantization group (32, or the paper's 64)")
     ap.add_argument("--top-k", type=int, default=1024)
+    ap.add_argument("--channels", type=int, default=16, help="critical channels d_s (8, 12, 16)")
+    ap.add_argument("--n-sink", type=int, default=4)
+    ap.add_argument("--n-window", type=int, default=64)
+    ap.add_argument("--paper-setting", action="store_true",
+                    help="the paper's long-context configuration (Sec. 5.1, App. D): 1 bit, groups of 64, "
+                         "n_local 128, n_topk 896, 12 critical channels re-selected every step and fetched "
+                         "from host memory")
     ap.add_argument("--host-layers", type=int, default=30,
                     help="distinct pinned host K/V caches (30 = one per sparse layer)")
     ap.add_argument("--dynamic-channels", choices=["off", "resident", "host"], default="off",
@@ -101,8 +108,13 @@ def main():
         b.build_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.paper_setting:
+        args.bits, args.group, args.top_k, args.channels, args.n_sink, args.n_window = 1, 64, 896, 12, 0, 128
+        if args.dynamic_channels == "off":
+            args.dynamic_channels = "host"
     if args.dynamic_channels != "off":
         args.schedule = "chained"
+    sparse_kw = dict(top_k=args.top_k, n_channels=args.channels, n_sink=args.n_sink, n_window=args.n_window)
     N = args.context
     CAP = N + 64 * ((args.steps * 2 + args.warmup + 64 + 63) // 64)
     sm = 1.0 / np.sqrt(128.0)
@@ -143,18 +155,18 @@ def main():
             kv_host = None
             if si >= args.host_layers:
                 kv_host = host_pool[si % args.host_layers]
-            L = tkv.SparseLayer(top_k=args.top_k, capacity=CAP, device=dev, kv_host=kv_host)
+            L = tkv.SparseLayer(capacity=CAP, device=dev, kv_host=kv_host, **sparse_kw)
             if args.dynamic_channels != "off":   # Stage 1 buffers see the keys before the layer's own append
                 shared = next(iter(stage1.values())).fetched if stage1 else None   # one double buffer for all layers
                 stage1[l] = tkv.Stage1(L, resident=args.dynamic_channels == "resident", fetched=shared)
                 stage1[l].append(k[None])
             if kv_host is None:
                 host_pool.append(L.kv_host)
-            L.set_channels(static_channels_device(k, 16)[None])
+            L.set_channels(static_channels_device(k, args.channels)[None])
             if kv_host is None:
                 L.append(k[None], v[None])
             else:  # aliased host cache: keep its rows, refresh only the GPU-side state
-                tmp = tkv.SparseLayer(top_k=args.top_k, capacity=CAP, device=dev)
+                tmp = tkv.SparseLayer(capacity=CAP, device=dev, **sparse_kw)
                 tmp.set_channels(L.channel_idx)
                 tmp.append(k[None], v[None])
                 L.key_summary.copy_(tmp.key_summary); L.kv_local.copy_(tmp.kv_local); L.seq_len[:] = tmp.seq_len
@@ -355,7 +367,7 @@ def main():
     # Sec. 4.4, Table 2: b/8 bytes per code, one fp16 scaler and zero-point per group, for K and V
     per_tok_head = 2 * 128 * args.bits // 8 + 2 * 2 * 2 * 128 // args.group
     quant_bytes = 8 * nq * per_tok_head + 8 * (N - nq) * 512 + 2 * 32 * 128 * 2
-    summary_bytes = 8 * N * 32
+    summary_bytes = 8 * N * args.channels * 2
     gather_bytes = 8 * args.top_k * 512
     roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -384,8 +396,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"configs[3]: 32-layer hybrid decode step, batch 1, N={N}, layers 0-1 {args.bits}-bit "
-                               f"quantized (g={args.group}, W=128), layers 2-31 sparse (d_s=16, k={args.top_k}, 4 sinks, "
-                               f"64 window)" + ("" if args.dynamic_channels == "off" else
+                               f"quantized (g={args.group}, W=128), layers 2-31 sparse (d_s={args.channels}, k={args.top_k}, "
+                               f"{args.n_sink} sinks, {args.n_window} window)" + ("" if args.dynamic_channels == "off" else
                                                f", critical channels re-selected every step ({args.dynamic_channels})"),
                    "schedule": args.schedule, "distinct_host_caches": len(host_pool),
                    "build_s": round(t_build, 1)},
@@ -430,8 +442,8 @@ def cpu_baseline(sample, N, args, sm):
     summ = sparse.key_summary(k, ch)
     t0 = time.perf_counter()
     for _ in range(reps):
-        idx, cnt = sparse.estimate_topk(q, summ, ch, N, top_k=args.top_k, n_sink=4, n_window=64)
-        sparse.sparse_attention(q, k, v, idx, cnt, N, sm, n_sink=4, n_window=64)
+        idx, cnt = sparse.estimate_topk(q, summ, ch, N, top_k=args.top_k, n_sink=args.n_sink, n_window=args.n_window)
+        sparse.sparse_attention(q, k, v, idx, cnt, N, sm, n_sink=args.n_sink, n_window=args.n_window)
     t_sparse = (time.perf_counter() - t0) / reps
     per_layer_token_us = (2 * t_quant + 30 * t_sparse) / 32 * 1e6
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
