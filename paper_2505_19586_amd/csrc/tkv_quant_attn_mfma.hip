@@ -144,6 +144,7 @@ __device__ inline void lds_load4(const void* g, void* l) {
 constexpr int kEK = 4;            // query-side operands carry 2^kEK
 constexpr int kEP = 6;            // weight-side operands carry 2^kEP
 constexpr int kHeadroomLog2 = 4;  // lazy rescale: weights may reach 2^kHeadroomLog2
+constexpr int kRefBelowMax = 3;   // a rescale puts the reference this far under the largest logit (< headroom)
 constexpr int kBkStride = 80;     // words per head row of the query-side operand in LDS
 constexpr int kMaxGpc = 512;      // groups per chunk that the zero-point table holds
 constexpr int kTailWaves = 4;     // waves of the last chunk that share the fp16 tail
@@ -622,11 +623,15 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
       constexpr uint32_t kLimit = (uint32_t)(127 + kEP + kHeadroomLog2) << 23;  // 2^(kEP + headroom)
       if (__builtin_amdgcn_ballot_w64(mm >= kLimit) != 0ull) {
         const float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
-        float mn = fmaxf(m_run, __builtin_fmaf(mx, K1, cz));  // largest logit among this lane's 8 tokens
+        float mn = __builtin_fmaf(mx, K1, cz);  // largest logit among this lane's 8 tokens
         mn = fmaxf(mn, __shfl_xor(mn, 4, 64));
         mn = fmaxf(mn, __shfl_xor(mn, 8, 64));
         mn = fmaxf(mn, __shfl_xor(mn, 16, 64));
         mn = fmaxf(mn, __shfl_xor(mn, 32, 64));
+        // New reference: kRefBelowMax under the head's largest logit (never lower than before).
+        // The largest weight is then 2^kRefBelowMax and the many small ones, which carry most of
+        // the mass in a long context, sit that much further inside fp16's normal range.
+        mn = fmaxf(m_run, mn - (float)kRefBelowMax);
         const float alpha = exp2f(m_run - mn);  // 0 on the first group
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc_o[i] *= alpha;
