@@ -122,6 +122,21 @@ def test_peaked_attention_and_extreme_values():
     assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
 
 
+@pytest.mark.parametrize("bits,g", MAIN_SETTINGS)
+@pytest.mark.parametrize("scale", [64.0, 250.0])
+def test_large_value_magnitudes(bits, g, scale):
+    """Values of magnitude up to about 1000 (scalers of a few hundred): the fp16 operands of
+    the matrix-core kernel must not overflow."""
+    inp = make_layer(3000, seq=9)
+    v = (inp.v.astype(np.float32) * scale).astype(np.float16)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=3008 + 64)
+    layer.append(to_new(inp.k), to_new(v))
+    ref = check_quant_cache(layer, 0, inp.k, v)
+    out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
+    assert torch.isfinite(out).all()
+    assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
+
+
 def test_many_chunks(kernel_choice):
     """More split-K chunks than the usual cap of 64 (forced through the tuning hook): the
     cross-chunk merge then runs in several rounds."""
