@@ -141,10 +141,11 @@ int32_t tkv_quantize_append_ragged(const tkv_quant_desc* desc, tkv_quant_cache* 
  * logits = sm_scale * q . (code*s + z) over the quantized tokens and sm_scale * q . k
  * over the fp16 tail, one softmax over all N tokens, out = weights . V-hat.
  * q, out: fp16 [B][Hq][128].  A sequence with 0 tokens yields zeros.
- * Value range: the matrix-core kernel feeds fp16 products of softmax weights and value
- * scalers to the matrix cores; cached values of magnitude up to about 1000 are safe at
- * every bit width, far larger ones overflow fp16 and give non-finite outputs (the reference
- * kernel of tkv_debug_quant_attn_config has no such limit).
+ * Input range: the matrix-core kernel feeds fp16 products to the matrix cores: softmax
+ * weight x value scaler, and query element x key scaler.  Cached values of magnitude up
+ * to about 1000 and query-times-key-scaler products up to 65504 are safe at every bit
+ * width; far larger ones overflow fp16 and give wrong or non-finite outputs (the
+ * reference kernel of tkv_debug_quant_attn_config has no such limit).
  * The work is split over token chunks whose partial (max, sum, weighted V) results
  * go through `workspace` and are merged with a log-sum-exp merge.  The workspace must be
  * ZERO-FILLED by the caller before its first use (it ends in arrival counters that every

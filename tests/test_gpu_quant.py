@@ -137,6 +137,22 @@ def test_large_value_magnitudes(bits, g, scale):
     assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
 
 
+@pytest.mark.parametrize("bits,g", MAIN_SETTINGS)
+@pytest.mark.parametrize("k_scale,q_scale", [(64.0, 1.0), (1.0, 64.0), (16.0, 16.0)])
+def test_large_key_and_query_magnitudes(bits, g, k_scale, q_scale):
+    """Keys in the thousands (outlier channels x 64) and large queries: the product of a query
+    element and a key scaler must stay inside fp16 on its way to the matrix cores."""
+    inp = make_layer(3000, seq=9)
+    k = (inp.k.astype(np.float32) * k_scale).astype(np.float16)
+    q = (inp.q.astype(np.float32) * q_scale).astype(np.float16)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=3008 + 64)
+    layer.append(to_new(k), to_new(inp.v))
+    ref = check_quant_cache(layer, 0, k, inp.v)
+    out = layer.attn_decode(torch.from_numpy(q)[None].cuda(), SM)
+    assert torch.isfinite(out).all()
+    assert attn_err(out[0], attention.quant_attention(q, ref, SM)) <= TOL
+
+
 def test_many_chunks(kernel_choice):
     """More split-K chunks than the usual cap of 64 (forced through the tuning hook): the
     cross-chunk merge then runs in several rounds."""
