@@ -2,11 +2,16 @@
 // scores of every cached token from the critical query channels and the critical key
 // cache, then exact Top-K (ties to the lower token index, output ascending).
 //
-// Two launches over the same grid of 4096-token workgroups (the histogram and counters in
-// the workspace must be zero before the first call; every call leaves them zero):
-//   score    reads the key summary once, computes S(t) in the pinned float32 order, writes
-//            an order-preserving 32-bit key per token and adds its 13-bit-prefix histogram
-//            to the head's;
+// Two launches over the same grid; a workgroup owns a contiguous share of a head's tokens
+// (the entry point sizes the shares so that the workgroups fill the machine a whole number
+// of times) and works through it in passes of 4096 tokens.  The histogram and counters in
+// the workspace must be zero before the first call; every call leaves them zero.
+//   score    reads the critical key cache once (token-major summary, or channel-major rows),
+//            computes S(t) in the pinned float32 order, writes an order-preserving 32-bit
+//            key per token and adds its 13-bit-prefix histogram to the head's.  Optional
+//            riders: Eq. 10's channel selection at the start of every workgroup (resident
+//            channel-major keys), and the decode step's cache update (Eq. 2) by one more
+//            workgroup per head;
 //   select   every workgroup locates the bin of the k-th key in the head's histogram and
 //            lists its own tokens in or above that bin, in token order; the
 //            last workgroup of a head concatenates the lists (a few thousand entries, in
