@@ -341,6 +341,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   }
   const int t0 = blockIdx.x * p.tpw;
   if (t0 >= n) return;
+  TKV_PH(3);
   const int t_end = min(n, t0 + p.tpw);
   const int nsub = (t_end - t0 + kThreads - 1) / kThreads;  // <= kSub
   uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
@@ -370,6 +371,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
     __syncthreads();
     find_bin(h8, kBins, k, scratch, bin, above);
   }
+  TKV_PH(4);
 
   // ---- this workgroup's tokens in or above the bin, in token order
   {
@@ -403,6 +405,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   __syncthreads();
   if (tid == 0) scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone2], 1u) == (uint32_t)nblk - 1u;
   __syncthreads();
+  TKV_PH(5);
   if (!scratch[kWavesPerBlock + 2]) return;
   // every workgroup has read the histogram: leave it and the counter zero for the next call
   if (tid == 0) st_agent(&ctrl[kDone2], 0u);
@@ -454,6 +457,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
     return make_uint2(ld_agent(&e->x), ld_agent(&e->y));
   };
   __syncthreads();
+  TKV_PH(6);
   uint32_t k_rem = k - above;  // 1 <= k_rem <= keys in the bin
 
   // ---- exact threshold inside the bin: radix select on the low 19 key bits (10 + 9)
@@ -511,6 +515,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
     eq_run += te;
     __syncthreads();
   }
+  TKV_PH(7);
 }
 
 }  // namespace
