@@ -92,7 +92,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
-              "(the path shards by KV head, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by KV head, one host link per GPU)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
