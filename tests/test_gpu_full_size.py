@@ -145,3 +145,39 @@ def test_limits_of_the_descriptor():
     check_quant_cache(ql, 0, inp.k, inp.v)
     out = ql.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
     assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL
+
+
+def test_sixty_four_sequences():
+    """The largest batch the ABI takes (64): more (sequence, head) problems than compute units."""
+    rng = np.random.default_rng(64)
+    lens = rng.integers(1, 1500, size=64).tolist()
+    lens[3], lens[40] = 1500, 0
+    print(f"case batch 64 lens={lens[:8]}...", flush=True)
+    nmax = max(lens)
+    inps = [make_layer(max(n, 1), config=4, layer=1, seq=100 + b) for b, n in enumerate(lens)]
+    q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
+    kb, vb = to_new_batch([i.k for i in inps], nmax), to_new_batch([i.v for i in inps], nmax)
+    ql = tkv.QuantLayer(bits=2, capacity=1536, batch=64)
+    ql.append(kb, vb, n_valid=lens)
+    out = ql.attn_decode(q, SM)
+    sl = tkv.SparseLayer(top_k=128, capacity=1536, batch=64)
+    chs = [static_channels(i.k, 16) for i in inps]
+    sl.set_channels(np.stack(chs))
+    sl.append(kb, vb, n_valid=lens)
+    sl.estimate_topk(q)
+    out_s = sl.gather_attn(q, SM)
+    torch.cuda.synchronize()
+    for b, inp in enumerate(inps):
+        n = lens[b]
+        if n == 0:
+            assert (out[b] == 0).all() and (out_s[b] == 0).all()
+            assert int(sl.topk_count[b].sum()) == 0
+            continue
+        ref = check_quant_cache(ql, b, inp.k[:, :n], inp.v[:, :n])
+        assert attn_err(out[b], attention.quant_attention(inp.q, ref, SM)) <= TOL
+        idx, cnt = sparse.estimate_topk(inp.q, sparse.key_summary(inp.k[:, :n], chs[b]), chs[b], n,
+                                        top_k=128, n_sink=4, n_window=64)
+        assert np.array_equal(sl.topk_count[b].cpu().numpy(), cnt)
+        assert np.array_equal(sl.topk_idx[b].cpu().numpy(), idx)
+        want = sparse.sparse_attention(inp.q, inp.k[:, :n], inp.v[:, :n], idx, cnt, n, SM, n_sink=4, n_window=64)
+        assert attn_err(out_s[b], want) <= TOL
