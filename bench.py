@@ -51,18 +51,25 @@ def parse():
                     help="overlapped (the benchmark's configuration): sparse-layer gathers on a side stream under "
                          "the other layers' compute; chained: every call waits for the previous one")
     ap.add_argument("--one-schedule", action="store_true", help="time only --schedule (profiling runs)")
+    ap.add_argument("--lookahead", type=int, default=2,
+                    help="overlapped schedule: sparse layers whose scoring runs ahead of the attention")
+    ap.add_argument("--gather-streams", type=int, default=2,
+                    help="overlapped schedule: side streams the gathers alternate between")
     ap.add_argument("--gather-cus", type=int, default=16,
-                    help="overlapped schedule: compute units reserved for the gather stream (0 = no masks)")
+                    help="overlapped schedule: compute units reserved for the gather streams, split evenly (0 = no masks)")
     return ap.parse_args()
 
 
-def cu_masked_streams(n_gather_cus, n_cus=256):
-    """Two HIP streams with disjoint compute-unit masks: (gather stream on the first
-    n_gather_cus units, compute stream on the others), wrapped for torch.  None if the
-    runtime refuses."""
+def cu_masked_streams(n_gather_cus, n_streams=1, n_cus=256):
+    """HIP streams with disjoint compute-unit masks, wrapped for torch: n_streams gather
+    streams that split the first n_gather_cus units evenly (consecutive unit numbers sit in
+    different dies, so a mask of 8 has one unit in every die) and a compute stream on all
+    the others.  Returns ([gather streams], compute stream, destroy) or None if the runtime
+    refuses."""
     import ctypes as C
     import torch
-    if n_gather_cus <= 0 or n_gather_cus >= n_cus:
+    per = n_gather_cus // max(n_streams, 1)
+    if n_streams < 1 or per < 8 or n_gather_cus >= n_cus:
         return None
     try:
         hip = C.CDLL("libamdhip64.so")
@@ -72,10 +79,12 @@ def cu_masked_streams(n_gather_cus, n_cus=256):
     fn.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_uint32)]
     fn.restype = C.c_int
     words = n_cus // 32
-    bits_g = (1 << n_gather_cus) - 1
-    bits_c = ((1 << n_cus) - 1) ^ bits_g
+    gather_bits = [((1 << per) - 1) << (per * i) for i in range(n_streams)]
+    all_gather = 0
+    for b in gather_bits:
+        all_gather |= b
     out, handles = [], []
-    for bits in (bits_g, bits_c):
+    for bits in gather_bits + [((1 << n_cus) - 1) ^ all_gather]:
         mask = (C.c_uint32 * words)(*[(bits >> (32 * i)) & 0xFFFFFFFF for i in range(words)])
         h = C.c_void_p()
         if fn(C.byref(h), words, mask) != 0 or not h.value:
@@ -87,7 +96,7 @@ def cu_masked_streams(n_gather_cus, n_cus=256):
         hip.hipStreamDestroy.argtypes = [C.c_void_p]
         for h in handles:
             hip.hipStreamDestroy(h)
-    return out[0], out[1], destroy
+    return out[:-1], out[-1], destroy
 
 
 def main():
@@ -188,31 +197,36 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def step_overlapped(compute, side):
-        """Software-pipelined enqueue: while layer l's rows cross the host link on the side
-        stream, layer l+1's append and scoring run on the compute stream.  Legal only
-        because the synthetic queries of different layers are independent."""
-        pending = None   # (layer, event after which its staged rows are complete)
+    def step_overlapped(compute, sides):
+        """Software-pipelined enqueue.  The gathers alternate between the side streams, so the
+        link already serves layer l+1's rows while layer l's gather drains and the next launch
+        is set up (one stream alone leaves the link idle for ~10 us between two gathers); the
+        compute stream runs append + scoring + selection `lookahead` sparse layers ahead of the
+        attention, so that no gather ever waits for its indices.  Legal only because the
+        synthetic queries of different layers are independent."""
+        lookahead = args.lookahead
+        done = {}      # layer -> event after which its staged rows are complete
+        order = []     # sparse layers in flight, oldest first
         for l, L in enumerate(layers):
             if l in QUANT_LAYERS:
                 L.append(new_k[l], new_v[l])
                 L.attn_decode(qs[l], sm, out=outs[l])
                 continue
             L.append_estimate_topk(new_k[l], new_v[l], qs[l])
+            side = sides[l % len(sides)]
             ready = torch.cuda.Event()
             ready.record(compute)
             side.wait_event(ready)
             L.gather(stream=side)
-            done = torch.cuda.Event()
-            done.record(side)
-            if pending is not None:
-                pl, pe = pending
-                compute.wait_event(pe)
+            done[l] = torch.cuda.Event()
+            done[l].record(side)
+            order.append(l)
+            if len(order) > lookahead:
+                pl = order.pop(0)
+                compute.wait_event(done.pop(pl))
                 layers[pl].attn(qs[pl], sm, out=outs[pl])
-            pending = (l, done)
-        if pending is not None:
-            pl, pe = pending
-            compute.wait_event(pe)
+        for pl in order:
+            compute.wait_event(done.pop(pl))
             layers[pl].attn(qs[pl], sm, out=outs[pl])
 
     sparse_ids = [l for l in range(N_LAYERS) if l not in QUANT_LAYERS]
@@ -295,14 +309,14 @@ def main():
             # A kernel that shares compute units with the gather is slowed to the pace of the
             # host link (its memory instructions queue behind the gather's): the gather gets
             # compute units of its own and everything else the rest.
-            masked = cu_masked_streams(args.gather_cus)
+            masked = cu_masked_streams(args.gather_cus, args.gather_streams)
             if masked is None:
-                side, compute = torch.cuda.Stream(), torch.cuda.current_stream()
+                sides, compute = [torch.cuda.Stream() for _ in range(args.gather_streams)], torch.cuda.current_stream()
                 ctx = contextlib.nullcontext()
             else:
-                side, compute, destroy = masked
+                sides, compute, destroy = masked
                 ctx = torch.cuda.stream(compute)
-            step = lambda: step_overlapped(compute, side)
+            step = lambda: step_overlapped(compute, sides)
         with ctx:
             for _ in range(args.warmup):
                 step()
@@ -401,7 +415,8 @@ def main():
                                f"{args.n_sink} sinks, {args.n_window} window)" + ("" if args.dynamic_channels == "off" else
                                                f", critical channels re-selected every step ({args.dynamic_channels})"),
                    "schedule": args.schedule,
-                   **({"gather_compute_units": args.gather_cus} if args.schedule == "overlapped" else {}),
+                   **({"gather_compute_units": args.gather_cus, "gather_streams": args.gather_streams}
+                      if args.schedule == "overlapped" else {}),
                    "distinct_host_caches": len(host_pool),
                    "build_s": round(t_build, 1)},
         "roofline": roof, "cpu_baseline": cpu, **extra,
