@@ -197,6 +197,8 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
+    sparse_ids = [l for l in range(N_LAYERS) if l not in QUANT_LAYERS]
+
     def step_overlapped(compute, sides):
         """Software-pipelined enqueue.  The gathers alternate between the side streams, so the
         link already serves layer l+1's rows while layer l's gather drains and the next launch
@@ -207,7 +209,12 @@ def main():
         lookahead = args.lookahead
         done = {}      # layer -> event after which its staged rows are complete
         order = []     # sparse layers in flight, oldest first
-        for l, L in enumerate(layers):
+        # the first sparse layers are scored before the quantized layers' attention, so that the
+        # link is busy from the start of the step (gathers under quantized-layer compute)
+        first = sparse_ids[:lookahead]
+        sequence = first + [l for l in range(N_LAYERS) if l not in first]
+        for l in sequence:
+            L = layers[l]
             if l in QUANT_LAYERS:
                 L.append(new_k[l], new_v[l])
                 L.attn_decode(qs[l], sm, out=outs[l])
@@ -229,7 +236,6 @@ def main():
             compute.wait_event(done.pop(pl))
             layers[pl].attn(qs[pl], sm, out=outs[pl])
 
-    sparse_ids = [l for l in range(N_LAYERS) if l not in QUANT_LAYERS]
     fetch_stream = torch.cuda.Stream() if args.dynamic_channels == "host" else None
 
     def step_dynamic():
