@@ -342,6 +342,50 @@ int32_t tkv_sparse_append_dynamic(const tkv_sparse_desc* desc, tkv_sparse_cache*
                                   const tkv_sparse_stage1* stage1, const void* k_new, const void* v_new,
                                   int32_t n_new, const int32_t* n_valid_host, void* stream);
 
+/* ---------------------------------------------------------------------------------
+ * Offline identification (Sec. 4.1): which layers are quantization-friendly
+ * ------------------------------------------------------------------------------- */
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(tkv_pref_desc)                                          */
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;     /* 128                                                            */
+  int32_t n_q;          /* most recent query vectors of the prompt used per head (Eq. 6);
+                           a multiple of 16, at most 256                                  */
+  int32_t top_k;        /* k of Eq. 7, 1..4096                                            */
+  int32_t capacity;     /* largest prompt length n                                        */
+  int32_t batch;
+} tkv_pref_desc;
+
+/* Workspace bytes of tkv_dense_preference (grows with capacity * n_q * Hq / Hkv). */
+int32_t tkv_dense_preference_sizes(const tkv_pref_desc* desc, size_t* workspace_bytes);
+
+/*
+ * Dense preference score of one layer, Eq. 6-8, per query head:
+ *     A = softmax(q_last K^T * sm_scale) row by row over all n keys (Eq. 6 as printed: no
+ *     mask), P = n_q - sum over the rows of their top_k largest entries (Eq. 7, 8).
+ * q_last: fp16 [B][n_q][Hq][128] (device), the n_q most recent query vectors of the prompt;
+ * k: fp16 [B][n][Hkv][128] (device), the prompt's keys (the layout of the append calls);
+ * query head j reads KV head j / (Hq/Hkv).  p_out: float32 [B][Hq] (device).
+ * Logits are float32 (fp16 products accumulated in float32); the Top-K of a row is exact on
+ * those logits (ties: lower index).  workspace: ZERO-FILLED before its first use, left
+ * consistent by every call; concurrent calls need separate workspaces.
+ */
+int32_t tkv_dense_preference(const tkv_pref_desc* desc, const void* q_last, const void* k, int32_t n,
+                             float sm_scale, float* p_out, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
+ * Eq. 9 on the host.  The layer's score is read as the mean over its heads of P / n_q (the
+ * average attention mass outside the top_k keys; Sec. 5.1 uses tau = 0.2); p_heads_host:
+ * HOST float32 [n_heads].  Returns 1 (quantization-friendly: score > tau), 0
+ * (sparsity-friendly) or a negative tkv_status; the score itself goes to *layer_score_out
+ * unless that is NULL.
+ */
+int32_t tkv_classify_layer(const float* p_heads_host, int32_t n_heads, int32_t n_q, float tau,
+                           float* layer_score_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtkv.so")
 
 SOURCES = ["tkv_api.hip", "tkv_quant.hip", "tkv_quant_attn.hip", "tkv_quant_attn_mfma.hip", "tkv_sparse.hip", "tkv_sparse_topk.hip",
-           "tkv_sparse_stage1.hip"]
+           "tkv_sparse_stage1.hip", "tkv_pref.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

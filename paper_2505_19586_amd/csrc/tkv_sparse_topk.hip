@@ -317,6 +317,48 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   TKV_PH(2);
 }
 
+// The scoring launch for scores that already exist (float32 [rows][pre_stride], row = blockIdx.y):
+// keys, histogram and local bound exactly as in score_kernel.  Used by the dense preference
+// score (Sec. 4.1), whose rows are attention logits.
+__global__ __launch_bounds__(kThreads) void prescored_kernel(TopkParams p, const float* pre, size_t pre_stride) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+  __shared__ uint32_t scratch[kWavesPerBlock + 4];
+  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const int n = p.lens.n[b];
+  const size_t bh = (size_t)b * p.hkv + h;
+  const int t0 = blockIdx.x * p.tpw;
+  if (t0 >= n) return;
+  const int t_end = min(n, t0 + p.tpw);
+  int lo, hi;
+  candidate_range(p, n, lo, hi);
+  const uint32_t k = (uint32_t)min(p.top_k, hi - lo);
+  for (int i = tid; i < kBins; i += kThreads) hist[i] = 0u;
+  __syncthreads();
+  const float* row = pre + bh * pre_stride;
+  uint32_t* keys = p.ws.keys + bh * p.capacity;
+  for (int t = t0 + tid; t < t_end; t += kThreads) {
+    uint32_t key = 0u;
+    if (t >= lo && t < hi) {
+      key = score_key(row[t] + 0.0f);
+      atomicAdd(&hist[key >> kLowBits], 1u);
+    }
+    keys[t] = key;
+  }
+  __syncthreads();
+  uint32_t first_bin = 0;
+  {
+    const int c_lo = max(lo, t0), c_hi = min(hi, t_end);
+    if (c_hi - c_lo >= (int)k && k > 0) {
+      uint32_t above_unused;
+      find_bin(hist, kBins, k, scratch, first_bin, above_unused);
+    }
+  }
+  uint32_t* gh = p.ws.hist + bh * kBins;
+  for (int i = tid; i < kBins; i += kThreads)
+    if (i >= (int)first_bin && hist[i]) atomicAdd(&gh[i], hist[i]);
+}
+
 __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                // 1024 words
@@ -710,3 +752,41 @@ extern "C" int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* d, tkv
     for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] -= app.app_add.n[b];
   return st;
 }
+
+namespace tkv {
+// Exact Top-K (ties to the lower index, ascending output, -1 padding) of every row of a float32
+// score matrix [n_rows][stride] over columns [0, n): the selection machinery of
+// tkv_sparse_estimate_topk on scores that already exist.  ws: carve_sparse_ws of a descriptor
+// with batch 1, n_rows KV heads and capacity >= n; zero-filled before first use.
+int32_t topk_of_scores(const float* scores, size_t stride, int n_rows, int n, int top_k, int capacity, SparseWs ws,
+                       int32_t* topk_idx, int32_t* topk_count, hipStream_t s) {
+  if (n_rows < 1 || n_rows > 65535 || n < 0 || n > capacity || top_k < 1 || top_k > 4096) return TKV_E_INVAL;
+  TopkParams p = {};
+  p.summary = nullptr;
+  p.rows_per_head = 0;
+  p.channel_idx = nullptr;
+  p.q = nullptr;
+  p.topk_idx = topk_idx;
+  p.topk_count = topk_count;
+  p.ws = ws;
+  p.hq = n_rows;
+  p.hkv = n_rows;
+  p.top_k = top_k;
+  p.n_sink = 0;
+  p.n_window = 0;
+  p.capacity = capacity;
+  p.lens.n[0] = n;
+  p.app_k = nullptr;
+  int nblk = (n + kTok - 1) / kTok;
+  if (nblk < 1) nblk = 1;
+  if (nblk >= 1024) return TKV_E_UNSUPPORTED;
+  p.tpw = kTok;
+  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
+  if (!lds_ok) return TKV_E_HIP;
+  const dim3 grid(nblk, n_rows, 1);
+  prescored_kernel<<<grid, kThreads, kScoreLds, s>>>(p, scores, stride);
+  select_kernel<<<grid, kThreads, kSelectLds, s>>>(p);
+  return launch_status();
+}
+}  // namespace tkv

@@ -48,6 +48,12 @@ class SparseCache(C.Structure):
                 ("kv_local", C.c_void_p), ("seq_len_host", C.POINTER(C.c_int32))]
 
 
+class PrefDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("n_q", C.c_int32), ("top_k", C.c_int32), ("capacity", C.c_int32),
+                ("batch", C.c_int32)]
+
+
 class SparseStage1(C.Structure):
     _fields_ = [("k_absmax", C.c_void_p), ("keys_cm", C.c_void_p)]
 
@@ -92,6 +98,9 @@ def lib() -> C.CDLL:
                                                 vp, vp, i32, C.POINTER(i32), vp]
         L.tkv_sparse_append_estimate_topk.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32,
                                                       C.POINTER(i32), vp, vp, vp, vp, sz, vp]
+        L.tkv_dense_preference_sizes.argtypes = [C.POINTER(PrefDesc), C.POINTER(sz)]
+        L.tkv_dense_preference.argtypes = [C.POINTER(PrefDesc), vp, vp, i32, C.c_float, vp, vp, sz, vp]
+        L.tkv_classify_layer.argtypes = [C.POINTER(C.c_float), i32, i32, C.c_float, C.POINTER(C.c_float)]
         L.tkv_debug_quant_attn_config.argtypes = [i32, i32]
         L.tkv_debug_quant_attn_config.restype = i32
         for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
@@ -101,7 +110,8 @@ def lib() -> C.CDLL:
                      "tkv_sparse_stage1_sizes", "tkv_sparse_stage1_append", "tkv_sparse_select_channels",
                      "tkv_sparse_prefetch_keys", "tkv_sparse_estimate_topk_cm",
                      "tkv_sparse_select_estimate_topk", "tkv_sparse_append_dynamic",
-                     "tkv_sparse_append_estimate_topk"):
+                     "tkv_sparse_append_estimate_topk", "tkv_dense_preference_sizes", "tkv_dense_preference",
+                     "tkv_classify_layer"):
             getattr(L, name).restype = C.c_int32
         _LIB = L
     return _LIB
@@ -419,3 +429,40 @@ class Stage1:
                                                  L.workspace.data_ptr(), L.workspace_bytes, _stream(stream)),
                "tkv_sparse_estimate_topk_cm")
         return L.topk_idx, L.topk_count
+
+
+class DensePreference:
+    """Offline identification of a layer (tkv_dense_preference, tkv_classify_layer)."""
+
+    def __init__(self, *, n_q_heads=32, n_kv_heads=8, head_dim=128, n_q=64, top_k=1024, capacity, batch=1,
+                 device="cuda:0"):
+        dev = _require_gpu(device)
+        self.desc = PrefDesc(C.sizeof(PrefDesc), n_q_heads, n_kv_heads, head_dim, n_q, top_k, capacity, batch)
+        ws = C.c_size_t()
+        _check(lib().tkv_dense_preference_sizes(C.byref(self.desc), C.byref(ws)), "tkv_dense_preference_sizes")
+        self.workspace_bytes = int(ws.value)
+        self.workspace = torch.zeros(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        self.device = dev
+
+    def score(self, q_last: torch.Tensor, k: torch.Tensor, sm_scale: float, stream=None) -> torch.Tensor:
+        """q_last fp16 [B, n_q, Hq, D], k fp16 [B, n, Hkv, D] -> float32 [B, Hq] (Eq. 8 per head)."""
+        d = self.desc
+        for t in (q_last, k):
+            assert t.dtype == torch.float16 and t.is_cuda and t.is_contiguous()
+        assert tuple(q_last.shape) == (d.batch, d.n_q, d.n_q_heads, d.head_dim)
+        assert k.shape[0] == d.batch and tuple(k.shape[2:]) == (d.n_kv_heads, d.head_dim)
+        out = torch.empty(d.batch, d.n_q_heads, dtype=torch.float32, device=self.device)
+        _check(lib().tkv_dense_preference(C.byref(d), q_last.data_ptr(), k.data_ptr(), int(k.shape[1]),
+                                          float(sm_scale), out.data_ptr(), self.workspace.data_ptr(),
+                                          self.workspace_bytes, _stream(stream)), "tkv_dense_preference")
+        return out
+
+    def classify(self, p_heads: torch.Tensor, tau: float = 0.2):
+        """Eq. 9 for one sequence: (True if quantization-friendly, layer score)."""
+        p = np.ascontiguousarray(p_heads.detach().float().cpu().numpy().reshape(-1), dtype=np.float32)
+        score = C.c_float()
+        r = lib().tkv_classify_layer(p.ctypes.data_as(C.POINTER(C.c_float)), int(p.size), int(self.desc.n_q),
+                                     float(tau), C.byref(score))
+        if r < 0:
+            raise TkvError(r, "tkv_classify_layer")
+        return bool(r), float(score.value)

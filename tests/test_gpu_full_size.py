@@ -181,3 +181,21 @@ def test_sixty_four_sequences():
         assert np.array_equal(sl.topk_idx[b].cpu().numpy(), idx)
         want = sparse.sparse_attention(inp.q, inp.k[:, :n], inp.v[:, :n], idx, cnt, n, SM, n_sink=4, n_window=64)
         assert attn_err(out_s[b], want) <= TOL
+
+
+def test_dense_preference_full_size():
+    """Offline identification at the full context: 64 query rows per head against 131072 keys."""
+    from oracle import preference
+    n, n_q, top_k = 131072, 64, 1024
+    print(f"case full-size dense preference n={n}", flush=True)
+    inp = make_layer(n, config=2, layer=3, seq=2)
+    rng = np.random.default_rng(8)
+    q_last = (inp.q[None].astype(np.float32) + 0.5 * rng.standard_normal((n_q, 32, 128))).astype(np.float16)
+    dp = tkv.DensePreference(n_q=n_q, top_k=top_k, capacity=n)
+    kd = torch.from_numpy(np.ascontiguousarray(inp.k.transpose(1, 0, 2)))[None].contiguous().cuda()
+    out = dp.score(torch.from_numpy(q_last)[None].contiguous().cuda(), kd, SM)
+    torch.cuda.synchronize()
+    want = preference.dense_preference(q_last[:, :8], inp.k[:2], top_k, SM)     # two KV heads' worth of the oracle
+    got = out[0, :8].cpu().numpy()
+    print(f"   max |P - P_oracle| = {np.abs(got - want).max():.2e}", flush=True)
+    assert np.abs(got - want).max() <= 1e-4 * n_q
