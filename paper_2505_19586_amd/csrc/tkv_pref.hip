@@ -25,6 +25,7 @@ struct PrefParams {
   float* ml;             // [R][ntb][2]: per token block, row maximum and sum of 2^(x - max)
   const int32_t* topk_idx;
   const int32_t* topk_count;
+  float* row_p;          // [R]: 1 - top-k mass of every row
   float* p_out;          // [B][Hq]
   float scale2;          // sm_scale * log2(e)
   int32_t hq, hkv, n_q, n, b, h, ntb, top_k;
@@ -108,42 +109,43 @@ __device__ inline float block_sum(float v, float* scratch) {
   return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
-// One workgroup per query head of the group: Eq. 8 from the rows' softmax statistics and the
-// logits of the selected keys.
-__global__ __launch_bounds__(256) void pref_finish_kernel(PrefParams p) {
+// One workgroup per query row: its share of Eq. 8 (1 - mass of the selected keys) from the
+// row's softmax statistics and the logits of the selected keys.
+__global__ __launch_bounds__(256) void pref_row_kernel(PrefParams p) {
   __shared__ float scratch[4];
   __shared__ float s_m[4], s_l[4];
-  const int j = blockIdx.x, tid = threadIdx.x;
-  const int G = p.hq / p.hkv;
-  float total = 0.f;
-  for (int i = 0; i < p.n_q; ++i) {
-    const int r = j * p.n_q + i;
-    // row maximum and denominator
-    float m = -INFINITY, l = 0.f;
-    for (int tb = tid; tb < p.ntb; tb += 256) {
-      const float* src = p.ml + ((size_t)r * p.ntb + tb) * 2;
-      ml_merge(m, l, src[0], src[1]);
-    }
-    for (int d = 32; d >= 1; d >>= 1) {
-      const float m2 = __shfl_xor(m, d, 64), l2 = __shfl_xor(l, d, 64);
-      ml_merge(m, l, m2, l2);
-    }
-    __syncthreads();
-    if (tid % 64 == 0) s_m[tid / 64] = m, s_l[tid / 64] = l;
-    __syncthreads();
-    m = s_m[0], l = s_l[0];
-    for (int w = 1; w < 4; ++w) ml_merge(m, l, s_m[w], s_l[w]);
-    // mass of the selected keys (Eq. 7)
-    const int cnt = p.topk_count[r];
-    float tsum = 0.f;
-    for (int e = tid; e < cnt; e += 256) {
-      const int t = p.topk_idx[(size_t)r * p.top_k + e];
-      tsum += exp2f(p.scores[(size_t)r * p.stride + t] - m);
-    }
-    tsum = block_sum(tsum, scratch);
-    total += l > 0.f ? 1.0f - tsum / l : 0.f;
+  const int r = blockIdx.x, tid = threadIdx.x;
+  float m = -INFINITY, l = 0.f;
+  for (int tb = tid; tb < p.ntb; tb += 256) {
+    const float* src = p.ml + ((size_t)r * p.ntb + tb) * 2;
+    ml_merge(m, l, src[0], src[1]);
   }
-  if (tid == 0) p.p_out[(size_t)p.b * p.hq + (size_t)p.h * G + j] = total;
+  for (int d = 32; d >= 1; d >>= 1) {
+    const float m2 = __shfl_xor(m, d, 64), l2 = __shfl_xor(l, d, 64);
+    ml_merge(m, l, m2, l2);
+  }
+  if (tid % 64 == 0) s_m[tid / 64] = m, s_l[tid / 64] = l;
+  __syncthreads();
+  m = s_m[0], l = s_l[0];
+  for (int w = 1; w < 4; ++w) ml_merge(m, l, s_m[w], s_l[w]);
+  const int cnt = p.topk_count[r];
+  float tsum = 0.f;
+  for (int e = tid; e < cnt; e += 256) {
+    const int t = p.topk_idx[(size_t)r * p.top_k + e];
+    tsum += exp2f(p.scores[(size_t)r * p.stride + t] - m);
+  }
+  tsum = block_sum(tsum, scratch);
+  if (tid == 0) p.row_p[r] = l > 0.f ? 1.0f - tsum / l : 0.f;
+}
+
+// Eq. 8 per query head: the sum of its rows' shares, in row order (one thread per head).
+__global__ void pref_sum_kernel(PrefParams p) {
+  const int j = threadIdx.x;
+  const int G = p.hq / p.hkv;
+  if (j >= G) return;
+  float total = 0.f;
+  for (int i = 0; i < p.n_q; ++i) total += p.row_p[j * p.n_q + i];
+  p.p_out[(size_t)p.b * p.hq + (size_t)p.h * G + j] = total;
 }
 
 int32_t check_pref_desc(const tkv_pref_desc* d) {
@@ -165,6 +167,7 @@ struct PrefWs {
   float* ml;
   int32_t* topk_idx;
   int32_t* topk_count;
+  float* row_p;
   void* select_ws;
   size_t stride;
   int32_t ntb;
@@ -193,12 +196,14 @@ size_t pref_ws_layout(const tkv_pref_desc* d, char* base, PrefWs* out) {
   const size_t o_ml = o;       o = tkv::align16(o + R * (size_t)ntb * 8);
   const size_t o_idx = o;      o = tkv::align16(o + R * (size_t)d->top_k * 4);
   const size_t o_cnt = o;      o = tkv::align16(o + R * 4);
+  const size_t o_rowp = o;     o = tkv::align16(o + R * 4);
   if (out) {
     out->select_ws = base + o_sel;
     out->scores = (float*)(base + o_scores);
     out->ml = (float*)(base + o_ml);
     out->topk_idx = (int32_t*)(base + o_idx);
     out->topk_count = (int32_t*)(base + o_cnt);
+    out->row_p = (float*)(base + o_rowp);
     out->stride = stride;
     out->ntb = ntb;
     out->sel = sel;
@@ -236,6 +241,7 @@ extern "C" int32_t tkv_dense_preference(const tkv_pref_desc* d, const void* q_la
   p.ml = ws.ml;
   p.topk_idx = ws.topk_idx;
   p.topk_count = ws.topk_count;
+  p.row_p = ws.row_p;
   p.p_out = p_out;
   p.scale2 = sm_scale * 1.44269504088896340736f;
   p.hq = d->n_q_heads;
@@ -254,7 +260,8 @@ extern "C" int32_t tkv_dense_preference(const tkv_pref_desc* d, const void* q_la
       if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
       st = tkv::topk_of_scores(ws.scores, ws.stride, R, n, d->top_k, (int)ws.stride, sws, ws.topk_idx, ws.topk_count, s);
       if (st != TKV_OK) return st;
-      pref_finish_kernel<<<dim3(G), 256, 0, s>>>(p);
+      pref_row_kernel<<<dim3(R), 256, 0, s>>>(p);
+      pref_sum_kernel<<<1, 64, 0, s>>>(p);
       if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
     }
   }

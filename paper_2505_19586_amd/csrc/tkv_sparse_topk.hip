@@ -777,10 +777,11 @@ int32_t topk_of_scores(const float* scores, size_t stride, int n_rows, int n, in
   p.capacity = capacity;
   p.lens.n[0] = n;
   p.app_k = nullptr;
-  int nblk = (n + kTok - 1) / kTok;
+  // many rows: as few workgroups per row as the kernels allow (their fixed cost dominates)
+  p.tpw = kMaxPass * kTok;
+  int nblk = (n + p.tpw - 1) / p.tpw;
   if (nblk < 1) nblk = 1;
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;
-  p.tpw = kTok;
   static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
   if (!lds_ok) return TKV_E_HIP;
