@@ -185,6 +185,34 @@ def test_stage1_and_fused_entry_points_validate_before_any_gpu_work(L):
     assert L.tkv_sparse_stage1_append(C.byref(odd), C.byref(sc), C.byref(s1), fake, 1, None, None) == -1
 
 
+def test_dense_preference_validation_and_host_classification(L):
+    from paper_2505_19586_amd.tkv import PrefDesc
+    fake = C.c_void_p(0x1000)
+
+    def desc(**kw):
+        d = dict(n_q_heads=32, n_kv_heads=8, head_dim=128, n_q=64, top_k=1024, capacity=4096, batch=1)
+        d.update(kw)
+        return PrefDesc(C.sizeof(PrefDesc), d["n_q_heads"], d["n_kv_heads"], d["head_dim"], d["n_q"], d["top_k"],
+                        d["capacity"], d["batch"])
+    ws = C.c_size_t()
+    assert L.tkv_dense_preference_sizes(C.byref(desc()), C.byref(ws)) == 0 and ws.value > 4 * 256 * 4096
+    for kw, status in ((dict(n_q=20), -2), (dict(n_q=0), -1), (dict(top_k=5000), -2), (dict(head_dim=64), -2),
+                       (dict(n_q_heads=30), -1), (dict(capacity=0), -1)):
+        assert L.tkv_dense_preference_sizes(C.byref(desc(**kw)), C.byref(ws)) == status
+    assert L.tkv_dense_preference_sizes(C.byref(desc()), None) == -1
+    d = desc()
+    assert L.tkv_dense_preference(C.byref(d), fake, fake, 5000, 0.1, fake, fake, 1 << 40, None) == -3   # n > capacity
+    assert L.tkv_dense_preference(C.byref(d), fake, fake, 100, 0.1, fake, fake, 8, None) == -4          # workspace
+    assert L.tkv_dense_preference(C.byref(d), None, fake, 100, 0.1, fake, fake, 1 << 40, None) == -1
+    # Eq. 9 on the host: mean over heads of P / n_q against tau
+    p = (C.c_float * 4)(8.0, 16.0, 24.0, 32.0)            # n_q = 64 -> shares 0.125 .. 0.5, mean 0.3125
+    score = C.c_float()
+    assert L.tkv_classify_layer(p, 4, 64, 0.2, C.byref(score)) == 1 and abs(score.value - 0.3125) < 1e-7
+    assert L.tkv_classify_layer(p, 4, 64, 0.4, None) == 0
+    assert L.tkv_classify_layer(None, 4, 64, 0.2, None) == -1
+    assert L.tkv_classify_layer(p, 0, 64, 0.2, None) == -1
+
+
 def test_binding_refuses_to_run_without_gpu():
     import torch
     if torch.cuda.is_available():
