@@ -46,6 +46,9 @@ def parse():
                     help="re-select the critical channels every step (Eq. 10): 'resident' scores in place over "
                          "channel-major keys kept on the GPU, 'host' fetches the critical key cache from a "
                          "pinned-host channel-major copy one layer ahead (the paper's design)")
+    ap.add_argument("--identify", action="store_true",
+                    help="instead of the decode step, time the offline identification of one layer (dense "
+                         "preference score, Sec. 4.1) at --context with 64 query rows per head and k = --top-k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["chained", "overlapped"], default="overlapped",
                     help="overlapped (the benchmark's configuration): sparse-layer gathers on a side stream under "
@@ -119,6 +122,8 @@ def main():
         b.build_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.identify:
+        return identify(args, tkv, torch, dev)
     if args.paper_setting:
         args.bits, args.group, args.top_k, args.channels, args.n_sink, args.n_window = 1, 64, 896, 12, 0, 128
         if args.dynamic_channels == "off":
@@ -428,6 +433,38 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, **extra,
     }
     print(json.dumps(line))
+
+
+def identify(args, tkv, torch, dev):
+    """Offline identification of one layer (not the headline): dense preference score of
+    synthetic Gaussian queries and keys, timed over a few calls."""
+    n, n_q = args.context, 64
+    g = torch.Generator(device=dev)
+    g.manual_seed(11)
+    q_last = torch.randn(1, n_q, 32, 128, generator=g, device=dev).half()
+    keys = torch.randn(1, n, 8, 128, generator=g, device=dev).half()
+    dp = tkv.DensePreference(n_q=n_q, top_k=args.top_k, capacity=n, device=dev)
+    sm = 128 ** -0.5
+    for _ in range(max(1, args.warmup)):
+        out = dp.score(q_last, keys, sm)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(3, args.steps // 4)
+    e0.record()
+    for _ in range(reps):
+        out = dp.score(q_last, keys, sm)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    friendly, score = dp.classify(out[0], 0.2)
+    flops = 2.0 * 32 * n_q * n * 128
+    print(json.dumps({
+        "metric": "offline identification ms per layer", "value": ms, "unit": "ms/layer", "n_gpus": 1,
+        "higher_is_better": False, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"dense preference score, 32 query / 8 KV heads, n={n}, n_q={n_q}, k={args.top_k}"},
+        "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": flops / ms / 1e9 / 2500.0, "traffic": None},
+        "layer_score": score, "quantization_friendly": friendly, "workspace_MiB": dp.workspace_bytes / 2 ** 20}))
 
 
 def traffic_from_profile(kernel: str):
