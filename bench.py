@@ -241,7 +241,7 @@ def main():
             compute.wait_event(done.pop(pl))
             layers[pl].attn(qs[pl], sm, out=outs[pl])
 
-    fetch_stream = torch.cuda.Stream() if args.dynamic_channels == "host" else None
+    fetch = {"stream": torch.cuda.Stream() if args.dynamic_channels == "host" else None}
 
     def step_dynamic():
         """Chained step with the critical channels re-selected per layer and step (Eq. 10).
@@ -251,6 +251,7 @@ def main():
         ahead, the fetch on its own stream (legal here because the synthetic queries of
         different layers are independent; a model would use the predicted query)."""
         compute = torch.cuda.current_stream()
+        fetch_stream = fetch["stream"]
         fetched = {}
 
         def start_fetch(j):
@@ -316,6 +317,13 @@ def main():
         destroy = None
         if schedule == "chained":
             ctx, step = contextlib.nullcontext(), step_chained
+            if args.dynamic_channels == "host":
+                # the fetch of the critical key cache gets compute units of its own, like the gather
+                masked = cu_masked_streams(args.gather_cus, 1)
+                if masked is not None:
+                    sides, compute, destroy = masked
+                    fetch["stream"] = sides[0]
+                    ctx = torch.cuda.stream(compute)
         else:
             # A kernel that shares compute units with the gather is slowed to the pace of the
             # host link (its memory instructions queue behind the gather's): the gather gets
