@@ -201,12 +201,21 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   if (dyn) {
     __shared__ float s_s[TKV_D];
     __shared__ uint32_t s_sel[TKV_D];
+    __shared__ __half q_all[4][TKV_D];  // whole query rows, fetched while the list is being made
+    if (tid >= kThreads - 4 * TKV_D / 2) {
+      const int x = tid - (kThreads - 4 * TKV_D / 2), j = x / (TKV_D / 2), w = x % (TKV_D / 2);
+      const uint32_t v = j < G ? reinterpret_cast<const uint32_t*>(p.q + ((size_t)b * p.hq + (size_t)h * G + j) * TKV_D)[w] : 0u;
+      reinterpret_cast<uint32_t*>(&q_all[j][0])[w] = v;
+    }
     tkv::select_channels_block(p.q_hat + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, G, p.k_absmax + bh * TKV_D, DS,
                                s_s, s_sel, s_chan, blockIdx.x == 0 ? p.channel_out + bh * DS : nullptr);
-  }
-  if (tid < 4 * DS) {
+    if (tid < 4 * DS) {
+      const int j = tid / DS, i = tid % DS;
+      qc[j][i] = __half2float(q_all[j][s_chan[i]]);  // rows of heads >= G are zero
+    }
+  } else if (tid < 4 * DS) {
     const int j = tid / DS, i = tid % DS;
-    const int c = dyn ? s_chan[i] : p.channel_idx[bh * DS + i];
+    const int c = p.channel_idx[bh * DS + i];
     qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
   }
   // all of this thread's rows of a pass are requested before the first is used (threads past
