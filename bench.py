@@ -128,8 +128,8 @@ def main():
         args.bits, args.group, args.top_k, args.channels, args.n_sink, args.n_window = 1, 64, 896, 12, 0, 128
         if args.dynamic_channels == "off":
             args.dynamic_channels = "host"
-    if args.dynamic_channels != "off":
-        args.schedule = "chained"
+    if args.dynamic_channels == "host":
+        args.schedule = "chained"   # its own pipeline: the fetch of layer l+1 under layer l
     sparse_kw = dict(top_k=args.top_k, n_channels=args.channels, n_sink=args.n_sink, n_window=args.n_window)
     N = args.context
     CAP = N + 64 * ((args.steps * 2 + args.warmup + 64 + 63) // 64)
@@ -224,7 +224,11 @@ def main():
                 L.append(new_k[l], new_v[l])
                 L.attn_decode(qs[l], sm, out=outs[l])
                 continue
-            L.append_estimate_topk(new_k[l], new_v[l], qs[l])
+            if l in stage1:   # resident channel-major keys: Eq. 10 and the scoring in one call
+                stage1[l].append_both(new_k[l], new_v[l])
+                stage1[l].select_estimate_topk(qs[l], qs[l])
+            else:
+                L.append_estimate_topk(new_k[l], new_v[l], qs[l])
             side = sides[l % len(sides)]
             ready = torch.cuda.Event()
             ready.record(compute)
@@ -351,7 +355,7 @@ def main():
 
     ms_per_step = timed(args.schedule)
     other = "overlapped" if args.schedule == "chained" else "chained"
-    ms_other = None if args.one_schedule or args.dynamic_channels != "off" else timed(other)
+    ms_other = None if args.one_schedule or args.dynamic_channels == "host" else timed(other)
 
     # per-kernel durations with events on the launching stream (separate passes so the
     # events do not perturb the step time above)
