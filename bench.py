@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--context", type=int, default=131072)
+    ap.add_argument("--batch", type=int, default=1, help="sequences decoded together (configs[4]: 8)")
+    ap.add_argument("--ragged", action="store_true",
+                    help="sequence lengths uniform in [context/2, context] (configs[4]: --batch 8 --context 32768 --ragged)")
     ap.add_argument("--bits", type=int, default=2, help="code width of the quantized layers (1, 2, 4)")
     ap.add_argument("--group", type=int, default=32, help="quantization group (32, or the paper's 64)")
     ap.add_argument("--top-k", type=int, default=1024)
@@ -130,8 +133,21 @@ def main():
             args.dynamic_channels = "host"
     if args.dynamic_channels == "host":
         args.schedule = "chained"   # its own pipeline: the fetch of layer l+1 under layer l
-    sparse_kw = dict(top_k=args.top_k, n_channels=args.channels, n_sink=args.n_sink, n_window=args.n_window)
+    B = args.batch
+    if B < 1 or B > 64:
+        print("bench.py: --batch must be between 1 and 64", file=sys.stderr)
+        sys.exit(2)
+    if B > 1 and args.dynamic_channels != "off":
+        print("bench.py: the dynamic-channel modes are timed at batch 1", file=sys.stderr)
+        sys.exit(2)
+    sparse_kw = dict(top_k=args.top_k, n_channels=args.channels, n_sink=args.n_sink, n_window=args.n_window, batch=B)
     N = args.context
+    if args.ragged:
+        from synth import ragged_lengths
+        lens = [int(x) for x in ragged_lengths(B, N // 2, N)]
+    else:
+        lens = [N] * B
+    tot = sum(lens)
     CAP = N + 64 * ((args.steps * 2 + args.warmup + 64 + 63) // 64)
     sm = 1.0 / np.sqrt(128.0)
     t_build = time.time()
@@ -157,15 +173,30 @@ def main():
     stage1 = {}
     host_pool = []
     sample = {}
+    def make_batch(seed):
+        """q [B][Hq][D], k and v [B][max len][Hkv][D] (rows past a sequence's length are not
+        appended), channel lists [B][Hkv][d_s]"""
+        qq, kk, vv, cc = [], [], [], []
+        for b in range(B):
+            q, k, v = make_layer_device(max(lens), seed=seed + 100000 * b, device=dev)
+            qq.append(q); kk.append(k); vv.append(v)
+            cc.append(static_channels_device(k[:lens[b]], args.channels))
+        if B == 1:
+            return qq[0][None].contiguous(), kk[0][None], vv[0][None], cc[0][None]
+        return torch.stack(qq), torch.stack(kk), torch.stack(vv), torch.stack(cc)
+
+    def host_sample(q, k, v):   # sequence 0 as the oracle takes it: [Hkv][n][D]
+        return (q[0].cpu().numpy(), k[0, :lens[0]].permute(1, 0, 2).contiguous().cpu().numpy(),
+                v[0, :lens[0]].permute(1, 0, 2).contiguous().cpu().numpy())
+
     for l in range(N_LAYERS):
-        q, k, v = make_layer_device(N, seed=1000 + l, device=dev)
-        qs.append(q[None].contiguous())
+        q, k, v, ch = make_batch(1000 + l)
+        qs.append(q)
         if l in QUANT_LAYERS:
-            L = tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=CAP, device=dev)
-            L.append(k[None], v[None])
+            L = tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=CAP, batch=B, device=dev)
+            L.append(k, v, n_valid=lens)
             if l == 0:
-                sample["quant"] = (q.cpu().numpy(), k.permute(1, 0, 2).contiguous().cpu().numpy(),
-                                   v.permute(1, 0, 2).contiguous().cpu().numpy())
+                sample["quant"] = host_sample(q, k, v)
         else:
             si = l - len(QUANT_LAYERS)
             kv_host = None
@@ -175,30 +206,29 @@ def main():
             if args.dynamic_channels != "off":   # Stage 1 buffers see the keys before the layer's own append
                 shared = next(iter(stage1.values())).fetched if stage1 else None   # one double buffer for all layers
                 stage1[l] = tkv.Stage1(L, resident=args.dynamic_channels == "resident", fetched=shared)
-                stage1[l].append(k[None])
+                stage1[l].append(k)
             if kv_host is None:
                 host_pool.append(L.kv_host)
-            L.set_channels(static_channels_device(k, args.channels)[None])
+            L.set_channels(ch)
             if kv_host is None:
-                L.append(k[None], v[None])
+                L.append(k, v, n_valid=lens)
             else:  # aliased host cache: keep its rows, refresh only the GPU-side state
                 tmp = tkv.SparseLayer(capacity=CAP, device=dev, **sparse_kw)
                 tmp.set_channels(L.channel_idx)
-                tmp.append(k[None], v[None])
+                tmp.append(k, v, n_valid=lens)
                 L.key_summary.copy_(tmp.key_summary); L.kv_local.copy_(tmp.kv_local); L.seq_len[:] = tmp.seq_len
                 del tmp
             if l == len(QUANT_LAYERS):
-                sample["sparse"] = (q.cpu().numpy(), k.permute(1, 0, 2).contiguous().cpu().numpy(),
-                                    v.permute(1, 0, 2).contiguous().cpu().numpy(), L.channel_idx[0].cpu().numpy())
+                sample["sparse"] = host_sample(q, k, v) + (L.channel_idx[0].cpu().numpy(),)
         layers.append(L)
         del k, v
     torch.cuda.synchronize()
     t_build = time.time() - t_build
 
-    outs = [torch.empty(1, 32, 128, dtype=torch.float16, device=dev) for _ in range(N_LAYERS)]
+    outs = [torch.empty(B, 32, 128, dtype=torch.float16, device=dev) for _ in range(N_LAYERS)]
     g = torch.Generator(device=dev); g.manual_seed(7)
-    new_k = [torch.randn(1, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
-    new_v = [torch.randn(1, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
+    new_k = [torch.randn(B, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
+    new_v = [torch.randn(B, 1, 8, 128, generator=g, device=dev).half() for _ in range(N_LAYERS)]
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
@@ -373,9 +403,9 @@ def main():
     # in total, so every sweep comes from HBM as it does inside the step).
     pool = [layers[l] for l in QUANT_LAYERS]
     for x in range(max(0, 4 - len(pool))):
-        _, k, v = make_layer_device(N, seed=5000 + x, device=dev)
-        L = tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=CAP, device=dev)
-        L.append(k[None], v[None])
+        _, k, v, _ = make_batch(5000 + x)
+        L = tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=CAP, batch=B, device=dev)
+        L.append(k, v, n_valid=lens)
         pool.append(L)
         del k, v
     for L in pool:
@@ -402,15 +432,15 @@ def main():
     dur["gather_in_step"] = dur["gather"]
     dur["gather"] = g0.elapsed_time(g1) * 1e3 / (2 * len(sparse_ids))
 
-    nq = (N - 128) // args.group * args.group
+    nq = sum((n - 128) // args.group * args.group for n in lens)
     # Sec. 4.4, Table 2: b/8 bytes per code, one fp16 scaler and zero-point per group, for K and V
     per_tok_head = 2 * 128 * args.bits // 8 + 2 * 2 * 2 * 128 // args.group
-    quant_bytes = 8 * nq * per_tok_head + 8 * (N - nq) * 512 + 2 * 32 * 128 * 2
-    summary_bytes = 8 * N * args.channels * 2
-    gather_bytes = 8 * args.top_k * 512
+    quant_bytes = 8 * nq * per_tok_head + 8 * (tot - nq) * 512 + B * 2 * 32 * 128 * 2
+    summary_bytes = 8 * tot * args.channels * 2
+    gather_bytes = B * 8 * args.top_k * 512
     roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "traffic": traffic_from_profile("quant_attn_mfma_kernel<2") if (N, args.bits, args.group) == (131072, 2, 32) else None,
+            "traffic": traffic_from_profile("quant_attn_mfma_kernel<2") if (N, B, args.bits, args.group) == (131072, 1, 2, 32) else None,
             "algorithmic_bytes": quant_bytes}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {
@@ -418,7 +448,7 @@ def main():
         "estimate_topk_GBs": summary_bytes / dur["topk"] / 1e3,
         "per_call_us": {"quant_attn": spread["quant"], "estimate_topk": spread["topk"], "gather": spread["gather"]},
         "other_schedule": None if ms_other is None else {
-            "schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS},
+            "schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS / B},
         "host_link": {"bound": "host_link", "kernel": "tkv_sparse_gather", "achieved": gather_bytes / dur["gather"] / 1e3,
                       "peak": h2d, "unit": "GB/s", "frac": gather_bytes / dur["gather"] / 1e3 / h2d,
                       "peak_source": "pinned 1 GiB hipMemcpy H2D measured in this run"},
@@ -426,14 +456,21 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(sample, N, args, sm)
+        cpu = cpu_baseline(sample, lens[0], tot, args, sm)
 
+    if B == 1:
+        metric = "decode attention us per layer-token at %dk ctx" % (N // 1024)
+        shape = f"configs[3]: 32-layer hybrid decode step, batch 1, N={N}"
+    else:   # one step decodes one token of every sequence: B layer-tokens per layer
+        metric = "decode attention us per layer-token, batch %d" % B
+        shape = (f"configs[4]: 32-layer hybrid decode step, batch {B}, lengths "
+                 + (f"uniform in [{N // 2}, {N}] ({tot} tokens in all)" if args.ragged else f"{N} each"))
     line = {
-        "metric": "decode attention us per layer-token at 128k ctx", "value": ms_per_step * 1e3 / N_LAYERS,
+        "metric": metric, "value": ms_per_step * 1e3 / N_LAYERS / B,
         "unit": "us/layer-token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"configs[3]: 32-layer hybrid decode step, batch 1, N={N}, layers 0-1 {args.bits}-bit "
+        "config": {"workload": f"{shape}, layers 0-1 {args.bits}-bit "
                                f"quantized (g={args.group}, W=128), layers 2-31 sparse (d_s={args.channels}, k={args.top_k}, "
                                f"{args.n_sink} sinks, {args.n_window} window)" + ("" if args.dynamic_channels == "off" else
                                                f", critical channels re-selected every step ({args.dynamic_channels})"),
@@ -493,10 +530,11 @@ def traffic_from_profile(kernel: str):
     return None
 
 
-def cpu_baseline(sample, N, args, sm):
+def cpu_baseline(sample, N, tot, args, sm):
     """The oracle as it stands on the host cores, on a bounded sample: one whole
-    quantized layer and one whole sparse layer at the full context, a few repetitions
-    each, weighted 2 : 30 over the 32 layers."""
+    quantized layer and one whole sparse layer of one sequence (N tokens), a few repetitions
+    each, weighted 2 : 30 over the 32 layers.  A batch is priced by its token count `tot`
+    (the oracle's work is proportional to it) and reported per layer-token like `value`."""
     import numpy as np
     from threadpoolctl import threadpool_info
 
@@ -518,10 +556,11 @@ def cpu_baseline(sample, N, args, sm):
         idx, cnt = sparse.estimate_topk(q, summ, ch, N, top_k=args.top_k, n_sink=args.n_sink, n_window=args.n_window)
         sparse.sparse_attention(q, k, v, idx, cnt, N, sm, n_sink=args.n_sink, n_window=args.n_window)
     t_sparse = (time.perf_counter() - t0) / reps
-    per_layer_token_us = (2 * t_quant + 30 * t_sparse) / 32 * 1e6
+    per_layer_token_us = (2 * t_quant + 30 * t_sparse) / 32 * 1e6 * (tot / N) / args.batch
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": per_layer_token_us, "unit": "us/layer-token", "cores": threads, "kind": "oracle",
-            "sample": "one whole quantized layer and one whole sparse layer (8 KV heads, 32 query heads) at N=%d, "
+            "sample": ("" if args.batch == 1 else "sequence 0 of the batch, scaled by the batch's token count: ") +
+                      "one whole quantized layer and one whole sparse layer (8 KV heads, 32 query heads) at N=%d, "
                       "%d repetitions each, weighted 2:30 over the 32 layers; quant attention %.2fs, sparse "
                       "estimate+topk+attention %.2fs per layer-token (quantizing the layer once: %.1fs, "
                       "not counted)" % (N, reps, t_quant, t_sparse, t_quantize)}
