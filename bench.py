@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--identify", action="store_true",
                     help="instead of the decode step, time the offline identification of one layer (dense "
                          "preference score, Sec. 4.1) at --context with 64 query rows per head and k = --top-k")
+    ap.add_argument("--per-call", choices=["quant", "sparse"], default=None,
+                    help="instead of the decode step, time the entry points of ONE layer kind on their own over "
+                         "many distinct caches (configs[1]: --per-call quant --context 32768 [--bits 4]; "
+                         "configs[2]: --per-call sparse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["chained", "overlapped"], default="overlapped",
                     help="overlapped (the benchmark's configuration): sparse-layer gathers on a side stream under "
@@ -127,6 +131,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.identify:
         return identify(args, tkv, torch, dev)
+    if args.per_call:
+        return per_call(args, tkv, torch, dev)
     if args.paper_setting:
         args.bits, args.group, args.top_k, args.channels, args.n_sink, args.n_window = 1, 64, 896, 12, 0, 128
         if args.dynamic_channels == "off":
@@ -514,6 +520,117 @@ def identify(args, tkv, torch, dev):
         "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": flops / ms / 1e9 / 2500.0, "traffic": None},
         "layer_score": score, "quantization_friendly": friendly, "workspace_MiB": dp.workspace_bytes / 2 ** 20}))
+
+
+def per_call(args, tkv, torch, dev):
+    """The entry points of one layer kind on their own (not the headline).  Launches go back
+    to back between one pair of events, round-robin over enough distinct caches that every
+    sweep comes from HBM (more than three times the 256 MB Infinity Cache where the layer's
+    GPU-resident data is what is read); 'hot' repeats one cache instead."""
+    from synth.device import make_layer_device, static_channels_device
+    N, sm = args.context, 128 ** -0.5
+    reps = max(3, args.steps // 4)
+
+    def timed(fn, n_calls):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * n_calls)
+
+    out = torch.empty(1, 32, 128, dtype=torch.float16, device=dev)
+    g = torch.Generator(device=dev); g.manual_seed(7)
+    k1 = torch.randn(1, 1, 8, 128, generator=g, device=dev).half()
+    v1 = torch.randn(1, 1, 8, 128, generator=g, device=dev).half()
+    calls = {}
+    if args.per_call == "quant":
+        nq = (N - 128) // args.group * args.group
+        per_tok_head = 2 * 128 * args.bits // 8 + 2 * 2 * 2 * 128 // args.group
+        qbytes = 8 * nq * per_tok_head + 8 * (N - nq) * 512 + 2 * 32 * 128 * 2
+        n_caches = max(4, -(-3 * 256 * 2 ** 20 // qbytes))      # > 3 x 256 MB in all
+        layers, qs, t_bulk = [], [], []
+        for l in range(n_caches):
+            q, k, v = make_layer_device(N, seed=1000 + l, device=dev)
+            L = tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=N + 128, device=dev)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); L.append(k[None], v[None]); e1.record(); e1.synchronize()
+            t_bulk.append(e0.elapsed_time(e1) * 1e3)
+            layers.append(L); qs.append(q[None].contiguous())
+            del k, v
+        calls["quantize_append_bulk_us"] = float(sorted(t_bulk)[len(t_bulk) // 2])   # median; the first call pays for set-up
+        calls["quantize_append_bulk_GBs"] = (8 * N * 512 + qbytes) / calls["quantize_append_bulk_us"] / 1e3
+        cold = timed(lambda: [L.attn_decode(q, sm, out=out) for L, q in zip(layers, qs)], n_caches)
+        hot = timed(lambda: [layers[0].attn_decode(qs[0], sm, out=out) for _ in range(n_caches)], n_caches)
+        # 64 single-token appends on one cache: two of them complete a group and quantize it
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        layers[1].append(k1, v1); torch.cuda.synchronize()
+        e0.record()
+        for _ in range(64):
+            layers[1].append(k1, v1)
+        e1.record(); torch.cuda.synchronize()
+        calls["quantize_append_1_token_us"] = e0.elapsed_time(e1) * 1e3 / 64
+        calls["quant_attn_hot_in_cache_us"] = hot
+        calls["distinct_caches"] = n_caches
+        value, roof = cold, {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": qbytes / cold / 1e3,
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": qbytes / cold / 1e3 / HBM_PEAK_GBS,
+                             "traffic": None, "algorithmic_bytes": qbytes}
+        workload = (f"configs[1]: single quantized layer, batch 1, N={N}, {args.bits} bit, g={args.group}, W=128; "
+                    f"{n_caches} distinct caches round-robin")
+        metric = "tkv_quant_attn_decode us per call"
+    else:
+        pin = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        h2d = 0.0
+        for _ in range(3):
+            e0.record(); dst.copy_(pin, non_blocking=True); e1.record(); e1.synchronize()
+            h2d = max(h2d, (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        del pin, dst
+        sbytes = 8 * N * args.channels * 2
+        n_caches = max(8, -(-3 * 256 * 2 ** 20 // sbytes))
+        kw = dict(top_k=args.top_k, n_channels=args.channels, n_sink=args.n_sink, n_window=args.n_window)
+        layers, qs, spare_host = [], [], None
+        for l in range(n_caches):
+            q, k, v = make_layer_device(N, seed=2000 + l, device=dev)
+            # eight distinct host K/V caches (4 GiB: only the selected rows are read), then aliased;
+            # the GPU-resident summaries are all distinct
+            L = tkv.SparseLayer(capacity=N + 128, device=dev, kv_host=layers[l % 8].kv_host if l >= 8 else None, **kw)
+            L.set_channels(static_channels_device(k, args.channels)[None])
+            if l < 8:
+                L.append(k[None], v[None])
+            else:   # build the GPU-side state through a throw-away layer whose host rows are not kept
+                tmp = tkv.SparseLayer(capacity=N + 128, device=dev, kv_host=spare_host, **kw)
+                spare_host = tmp.kv_host
+                tmp.set_channels(L.channel_idx)
+                tmp.append(k[None], v[None])
+                L.key_summary.copy_(tmp.key_summary); L.kv_local.copy_(layers[l % 8].kv_local); L.seq_len[:] = tmp.seq_len
+                del tmp
+            layers.append(L); qs.append(q[None].contiguous())
+            del k, v
+        torch.cuda.synchronize()
+        pairs = list(zip(layers, qs))
+        t_topk = timed(lambda: [L.estimate_topk(q) for L, q in pairs], n_caches)
+        t_fused = timed(lambda: [L.gather_attn(q, sm, out=out) for L, q in pairs], n_caches)
+        t_gather = timed(lambda: [L.gather() for L, _ in pairs], n_caches)
+        t_attn = timed(lambda: [L.attn(q, sm, out=out) for L, q in pairs], n_caches)
+        t_app = timed(lambda: [L.append_estimate_topk(k1, v1, q) for L, q in pairs[:8]], 8)
+        gbytes = 8 * args.top_k * 512
+        calls = {"estimate_topk_us": t_topk, "estimate_topk_GBs": sbytes / t_topk / 1e3,
+                 "estimate_topk_frac_of_hbm": sbytes / t_topk / 1e3 / HBM_PEAK_GBS,
+                 "gather_attn_fused_us": t_fused, "gather_alone_us": t_gather, "attention_over_staged_rows_us": t_attn,
+                 "append_estimate_topk_us": t_app, "distinct_summaries": n_caches, "distinct_host_caches": 8,
+                 "h2d_memcpy_GBs": h2d}
+        value, roof = t_gather, {"bound": "host_link", "kernel": "tkv_sparse_gather", "achieved": gbytes / t_gather / 1e3,
+                                 "peak": h2d, "unit": "GB/s", "frac": gbytes / t_gather / 1e3 / h2d, "traffic": None,
+                                 "peak_source": "pinned 1 GiB hipMemcpy H2D measured in this run"}
+        workload = (f"configs[2]: single sparse layer, batch 1, N={N}, d_s={args.channels}, k={args.top_k}, "
+                    f"{args.n_sink} sinks, {args.n_window} window; {n_caches} distinct summaries, 8 distinct host caches")
+        metric = "sparse gather us per call"
+    print(json.dumps({"metric": metric, "value": value, "unit": "us/call", "n_gpus": 1, "higher_is_better": False,
+                      "dtype": "f16", "data": "synthetic", "config": {"workload": workload}, "roofline": roof,
+                      "calls": calls}))
 
 
 def traffic_from_profile(kernel: str):
