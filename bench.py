@@ -427,6 +427,7 @@ def main():
     dur["quant_in_step"] = dur["quant"]
     dur["quant"] = e0.elapsed_time(e1) * 1e3 / (rounds * len(pool))
     del pool
+    dur["read_sweep"] = read_sweep_us(tkv, torch, dev, quant_bytes_of(args, lens), rounds)
     # the gather alone, the same way: every sparse layer's rows (distinct host caches), twice
     g0, g1 = ev(), ev()
     g0.record()
@@ -438,16 +439,16 @@ def main():
     dur["gather_in_step"] = dur["gather"]
     dur["gather"] = g0.elapsed_time(g1) * 1e3 / (2 * len(sparse_ids))
 
-    nq = sum((n - 128) // args.group * args.group for n in lens)
-    # Sec. 4.4, Table 2: b/8 bytes per code, one fp16 scaler and zero-point per group, for K and V
-    per_tok_head = 2 * 128 * args.bits // 8 + 2 * 2 * 2 * 128 // args.group
-    quant_bytes = 8 * nq * per_tok_head + 8 * (tot - nq) * 512 + B * 2 * 32 * 128 * 2
+    quant_bytes = quant_bytes_of(args, lens)
     summary_bytes = 8 * tot * args.channels * 2
     gather_bytes = B * 8 * args.top_k * 512
     roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "traffic": traffic_from_profile("quant_attn_mfma_kernel<2") if (N, B, args.bits, args.group) == (131072, 1, 2, 32) else None,
-            "algorithmic_bytes": quant_bytes}
+            "algorithmic_bytes": quant_bytes,
+            # a kernel that only streams the same number of bytes (tkv_debug_read_sweep), timed the same way
+            "read_sweep_us": dur["read_sweep"], "read_sweep_GBs": quant_bytes / dur["read_sweep"] / 1e3,
+            "time_vs_read_sweep": dur["quant"] / dur["read_sweep"]}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {
         "quant_attn_us": dur["quant"], "quant_attn_in_step_us": dur["quant_in_step"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"], "gather_in_step_us": dur["gather_in_step"],
@@ -522,6 +523,36 @@ def identify(args, tkv, torch, dev):
         "layer_score": score, "quantization_friendly": friendly, "workspace_MiB": dp.workspace_bytes / 2 ** 20}))
 
 
+def quant_bytes_of(args, lens):
+    """Algorithmic bytes of one tkv_quant_attn_decode call (Sec. 4.4, Table 2: b/8 bytes per
+    code, one fp16 scaler and zero-point per group, for K and V; fp16 rows for the tail;
+    query in, output out)."""
+    nq = sum((n - 128) // args.group * args.group for n in lens)
+    per_tok_head = 2 * 128 * args.bits // 8 + 2 * 2 * 2 * 128 // args.group
+    return 8 * nq * per_tok_head + 8 * (sum(lens) - nq) * 512 + len(lens) * 2 * 32 * 128 * 2
+
+
+def read_sweep_us(tkv, torch, dev, n_bytes, rounds):
+    """Microseconds per launch of a kernel that only reads n_bytes, back to back between one
+    pair of events, round-robin over four distinct buffers (every sweep from HBM)."""
+    n16 = (n_bytes + 15) // 16 * 16
+    bufs = [torch.empty(n16, dtype=torch.uint8, device=dev).fill_(x + 1) for x in range(4)]
+    best = None
+    for wgs in (256, 4096, 8192):     # the fastest of a few grid sizes is the reference
+        for b in bufs:
+            tkv.debug_read_sweep(b, wgs)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(rounds):
+            for b in bufs:
+                tkv.debug_read_sweep(b, wgs)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (rounds * len(bufs))
+        best = us if best is None else min(best, us)
+    return best
+
+
 def per_call(args, tkv, torch, dev):
     """The entry points of one layer kind on their own (not the headline).  Launches go back
     to back between one pair of events, round-robin over enough distinct caches that every
@@ -572,6 +603,7 @@ def per_call(args, tkv, torch, dev):
         e1.record(); torch.cuda.synchronize()
         calls["quantize_append_1_token_us"] = e0.elapsed_time(e1) * 1e3 / 64
         calls["quant_attn_hot_in_cache_us"] = hot
+        calls["read_sweep_same_bytes_us"] = read_sweep_us(tkv, torch, dev, qbytes, 13)
         calls["distinct_caches"] = n_caches
         value, roof = cold, {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": qbytes / cold / 1e3,
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": qbytes / cold / 1e3 / HBM_PEAK_GBS,

@@ -162,6 +162,14 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
  * chunks per (sequence, KV head) unless target_blocks asks for more than that). */
 int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks);
 
+/* Measurement aid (not part of the method): one plain read sweep over `bytes` bytes of
+ * device memory at `src` (both multiples of 16), 16-byte loads, n_workgroups workgroups of
+ * 256 lanes (1 to 65536).  `sink`: NULL or a device buffer of n_workgroups 32-bit words
+ * (almost never written; it only keeps the loads alive).  The benchmark times it over as
+ * many bytes as a tkv_quant_attn_decode call reads: what a kernel that does nothing but
+ * stream that volume takes on the same machine, launch included. */
+int32_t tkv_debug_read_sweep(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream);
+
 /* ---------------------------------------------------------------------------------
  * Sparsity-friendly layers
  * ------------------------------------------------------------------------------- */

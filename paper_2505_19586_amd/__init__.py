@@ -4,5 +4,5 @@ Thin ctypes binding over libtkv.so (hand-written HIP for gfx950).  PyTorch is us
 only for device memory and streams.
 """
 from .tkv import (  # noqa: F401
-    DensePreference, QuantDesc, QuantLayer, SparseDesc, SparseLayer, Stage1, TkvError, debug_quant_attn_config, lib, library_path,
+    DensePreference, QuantDesc, QuantLayer, SparseDesc, SparseLayer, Stage1, TkvError, debug_quant_attn_config, debug_read_sweep, lib, library_path,
 )

@@ -98,3 +98,35 @@ extern "C" int32_t tkv_sparse_cache_sizes(const tkv_sparse_desc* d, size_t bytes
   }
   return TKV_OK;
 }
+
+namespace {
+
+// Measurement aid: a plain read sweep of a device buffer, 16 bytes per lane and load, eight
+// loads in flight per lane.  The loaded words are folded into one value that is stored only
+// if it equals a constant no fold produces in practice, so the loads cannot be dropped.
+__global__ __launch_bounds__(256) void read_sweep_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* sink) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  uint32_t acc = 0u;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 v = src[i];
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == 0x9E3779B9u && sink) sink[blockIdx.x] = acc;
+}
+
+}  // namespace
+
+extern "C" int32_t tkv_debug_read_sweep(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream) {
+  if (!src || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)src & 15) != 0) return TKV_E_INVAL;
+  if (n_workgroups <= 0 || n_workgroups > 65536) return TKV_E_INVAL;
+  read_sweep_kernel<<<dim3(n_workgroups), 256, 0, (hipStream_t)stream>>>((const uint4*)src, bytes / 16, (uint32_t*)sink);
+  return tkv::launch_status();
+}

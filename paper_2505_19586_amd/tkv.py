@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
         L.tkv_classify_layer.argtypes = [C.POINTER(C.c_float), i32, i32, C.c_float, C.POINTER(C.c_float)]
         L.tkv_debug_quant_attn_config.argtypes = [i32, i32]
         L.tkv_debug_quant_attn_config.restype = i32
+        L.tkv_debug_read_sweep.argtypes = [vp, C.c_size_t, vp, i32, vp]
+        L.tkv_debug_read_sweep.restype = i32
         for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
                      "tkv_quantize_append_ragged", "tkv_sparse_append_ragged",
                      "tkv_sparse_cache_sizes", "tkv_sparse_append", "tkv_sparse_estimate_topk",
@@ -120,6 +122,13 @@ def lib() -> C.CDLL:
 def debug_quant_attn_config(kernel_choice: int = 0, target_blocks: int = 0) -> None:
     """0 = matrix-core kernel (default), 1 = reference kernel; see tkv.h."""
     _check(lib().tkv_debug_quant_attn_config(int(kernel_choice), int(target_blocks)), "tkv_debug_quant_attn_config")
+
+
+def debug_read_sweep(buf: torch.Tensor, n_workgroups: int = 2048, stream=None) -> None:
+    """Measurement aid: one plain read sweep over a device tensor (size a multiple of 16 bytes)."""
+    assert buf.is_cuda and buf.is_contiguous()
+    _check(lib().tkv_debug_read_sweep(buf.data_ptr(), buf.numel() * buf.element_size(), None, int(n_workgroups),
+                                      _stream(stream)), "tkv_debug_read_sweep")
 
 
 def _check(status: int, where: str) -> None:

@@ -152,6 +152,16 @@ def test_call_errors_before_any_gpu_work(L):
     assert L.tkv_sparse_gather(C.byref(s), C.byref(sc2), fake, fake, fake, None) in (-5, -6)
 
 
+def test_read_sweep_argument_errors(L):
+    fake = 0x1000
+    assert L.tkv_debug_read_sweep(None, 1024, None, 256, None) == -1
+    assert L.tkv_debug_read_sweep(fake, 0, None, 256, None) == -1
+    assert L.tkv_debug_read_sweep(fake, 1000, None, 256, None) == -1        # not a multiple of 16
+    assert L.tkv_debug_read_sweep(fake + 4, 1024, None, 256, None) == -1    # misaligned
+    assert L.tkv_debug_read_sweep(fake, 1024, None, 0, None) == -1
+    assert L.tkv_debug_read_sweep(fake, 1024, None, 1 << 20, None) == -1
+
+
 def test_stage1_and_fused_entry_points_validate_before_any_gpu_work(L):
     from paper_2505_19586_amd.tkv import SparseCache, SparseStage1
     fake = C.c_void_p(0x1000)

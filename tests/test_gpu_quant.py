@@ -172,3 +172,14 @@ def test_many_chunks(kernel_choice):
             assert attn_err(out[0], want) <= TOL
     finally:
         tkv.debug_quant_attn_config(0, 256)
+
+
+def test_read_sweep_runs_and_leaves_the_buffer_alone():
+    """The measurement kernel of the benchmark: reads only."""
+    buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    before = buf.clone()
+    for wgs in (1, 256, 2048):
+        tkv.debug_read_sweep(buf, wgs)
+    tkv.debug_read_sweep(buf[: 4 * 13])          # shorter than one pass of the grid
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
