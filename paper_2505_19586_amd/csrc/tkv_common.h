@@ -93,7 +93,7 @@ __device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __h
   float* red = cw + G * n_chunks;        // [4 heads][4 classes][128]
   float* Ls = red + 4 * 4 * TKV_D;       // [4]
   const int lane = tid % 64, wave = tid / 64;
-  // round 1: maxima and sums of all chunks, and (for up to 64 chunks) this thread's channels
+  // first pass: maxima and sums of all chunks, and (for up to 64 chunks) this thread's channels
   for (int i = tid; i < G * n_chunks; i += nthr) {
     const float* pk = head0 + (size_t)i * TKV_PART_STRIDE;
     ml[2 * i] = __hip_atomic_load(pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
