@@ -707,7 +707,16 @@ def cpu_baseline(sample, N, tot, args, sm):
     t_sparse = (time.perf_counter() - t0) / reps
     per_layer_token_us = (2 * t_quant + 30 * t_sparse) / 32 * 1e6 * (tot / N) / args.batch
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    cpu_model = ""
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                cpu_model = ln.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     return {"value": per_layer_token_us, "unit": "us/layer-token", "cores": threads, "kind": "oracle",
+            "cpu_model": cpu_model, "host_cpus": os.cpu_count(),
             "sample": ("" if args.batch == 1 else "sequence 0 of the batch, scaled by the batch's token count: ") +
                       "one whole quantized layer and one whole sparse layer (8 KV heads, 32 query heads) at N=%d, "
                       "%d repetitions each, weighted 2:30 over the 32 layers; quant attention %.2fs, sparse "
