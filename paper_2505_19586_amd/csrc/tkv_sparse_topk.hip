@@ -95,52 +95,86 @@ __device__ inline uint32_t rank_in(unsigned long long mask) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Inclusive suffix sums over the threads of a workgroup: returns sum of v over threads
-// >= tid.  scratch holds one word per wave.
-__device__ inline uint32_t block_suffix_sum(uint32_t v, uint32_t* scratch) {
-  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
-  uint32_t s = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t o = __shfl_down(s, d, 64);
-    if (lane + d < 64) s += o;
-  }
-  if (lane == 0) scratch[wave] = s;  // wave totals
-  __syncthreads();
-  for (int w = wave + 1; w < kWavesPerBlock; ++w) s += scratch[w];
-  __syncthreads();
-  return s;
-}
-
-// Finds, in a histogram of `nbins` counts (a multiple of the workgroup size, or smaller
-// than it) where larger bin = larger key, the bin that holds the k-th largest key:
-// `above` keys lie in higher bins, above < k <= above + count[bin].  Result valid in every
-// thread.  scratch holds kWavesPerBlock + 2 words.
-__device__ inline void find_bin(const uint32_t* hist, int nbins, uint32_t k, uint32_t* scratch, uint32_t& bin,
+// Finds, in a histogram of kBins counts where larger bin = larger key, the bin that holds the
+// k-th largest key: `above` keys lie in higher bins, above < k <= above + count[bin].  Two
+// levels: every thread sums its kBins / kThreads bins into `part` (kThreads words of LDS), the
+// first wave scans those sums (16 per lane) and walks down into the one thread's bins.
+// Result valid in every thread.  scratch holds kWavesPerBlock + 2 words.
+__device__ inline void find_bin(const uint32_t* hist, uint32_t k, uint32_t* part, uint32_t* scratch, uint32_t& bin,
                                 uint32_t& above) {
   const int tid = threadIdx.x;
-  const int per = nbins >= kThreads ? nbins / kThreads : 1;
-  const bool on = tid * per < nbins;
+  constexpr int per = kBins / kThreads;       // bins per thread
+  constexpr int per_lane = kThreads / 64;     // thread sums per lane of the first wave
   uint32_t local = 0;
-  if (on)
-    for (int i = 0; i < per; ++i) local += hist[tid * per + i];
-  const uint32_t incl = block_suffix_sum(local, scratch);  // keys in this thread's bins and higher
-  const uint32_t excl = incl - local;
-  if (on && excl < k && k <= incl) {  // exactly one thread
-    uint32_t run = excl;
-    int bsel = tid * per + per - 1;
-    for (; bsel > tid * per; --bsel) {
-      const uint32_t c = hist[bsel];
-      if (run + c >= k) break;
-      run += c;
+#pragma unroll
+  for (int i = 0; i < per; ++i) local += hist[tid * per + i];
+  part[tid] = local;
+  __syncthreads();
+  if (tid < 64) {
+    uint32_t mine = 0;
+    for (int i = 0; i < per_lane; ++i) mine += part[tid * per_lane + i];
+    uint32_t incl = mine;  // keys in this lane's bins and in those of higher lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_down(incl, d, 64);
+      if (tid + d < 64) incl += o;
     }
-    scratch[kWavesPerBlock] = (uint32_t)bsel;
-    scratch[kWavesPerBlock + 1] = run;
+    const uint32_t excl = incl - mine;
+    if (excl < k && k <= incl) {  // exactly one lane
+      uint32_t run = excl;
+      int t = tid * per_lane + per_lane - 1;  // thread whose bins hold the k-th key
+      for (; t > tid * per_lane; --t) {
+        const uint32_t c = part[t];
+        if (run + c >= k) break;
+        run += c;
+      }
+      int bsel = t * per + per - 1;
+      for (; bsel > t * per; --bsel) {
+        const uint32_t c = hist[bsel];
+        if (run + c >= k) break;
+        run += c;
+      }
+      scratch[kWavesPerBlock] = (uint32_t)bsel;
+      scratch[kWavesPerBlock + 1] = run;
+    }
   }
   __syncthreads();
   bin = scratch[kWavesPerBlock];
   above = scratch[kWavesPerBlock + 1];
+}
+
+// find_bin for at most 1024 bins by the first wave alone (lane l owns the bins [l * per,
+// (l + 1) * per), per = nbins / 64): one barrier instead of four.  The histogram must be
+// complete (barrier before the call); the result is valid in every thread after the call.
+__device__ inline void find_bin_wave(const uint32_t* hist, int nbins, uint32_t k, uint32_t* scratch, uint32_t& bin,
+                                     uint32_t& above) {
+  const int tid = threadIdx.x;
+  if (tid < 64) {
+    const int per = nbins / 64;  // 8 or 16
+    uint32_t local = 0;
+    for (int i = 0; i < per; ++i) local += hist[tid * per + i];
+    uint32_t incl = local;  // keys in this lane's bins and in those of higher lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_down(incl, d, 64);
+      if (tid + d < 64) incl += o;
+    }
+    const uint32_t excl = incl - local;
+    if (excl < k && k <= incl) {  // exactly one lane
+      uint32_t run = excl;
+      int bsel = tid * per + per - 1;
+      for (; bsel > tid * per; --bsel) {
+        const uint32_t c = hist[bsel];
+        if (run + c >= k) break;
+        run += c;
+      }
+      scratch[kWavesPerBlock] = (uint32_t)bsel;
+      scratch[kWavesPerBlock + 1] = run;
+    }
+  }
   __syncthreads();
+  bin = scratch[kWavesPerBlock];
+  above = scratch[kWavesPerBlock + 1];
 }
 
 // Cache update (Eq. 2) of one KV head by one workgroup: host rows, resident sink / window rows,
@@ -176,6 +210,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
   __shared__ float qc[4][DS];
   __shared__ uint32_t scratch[kWavesPerBlock + 4];
+  __shared__ uint32_t part[kThreads];  // per-thread bin sums of find_bin
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int n = p.lens.n[b];
   const size_t bh = (size_t)b * p.hkv + h;
@@ -317,7 +352,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
     const int c_lo = max(lo, t0), c_hi = min(hi, t_end);
     if (c_hi - c_lo >= (int)k && k > 0) {
       uint32_t above_unused;
-      find_bin(hist, kBins, k, scratch, first_bin, above_unused);
+      find_bin(hist, k, part, scratch, first_bin, above_unused);
     }
   }
   uint32_t* gh = p.ws.hist + bh * kBins;
@@ -333,6 +368,7 @@ __global__ __launch_bounds__(kThreads) void prescored_kernel(TopkParams p, const
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
   __shared__ uint32_t scratch[kWavesPerBlock + 4];
+  __shared__ uint32_t part[kThreads];  // per-thread bin sums of find_bin
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int n = p.lens.n[b];
   const size_t bh = (size_t)b * p.hkv + h;
@@ -360,7 +396,7 @@ __global__ __launch_bounds__(kThreads) void prescored_kernel(TopkParams p, const
     const int c_lo = max(lo, t0), c_hi = min(hi, t_end);
     if (c_hi - c_lo >= (int)k && k > 0) {
       uint32_t above_unused;
-      find_bin(hist, kBins, k, scratch, first_bin, above_unused);
+      find_bin(hist, k, part, scratch, first_bin, above_unused);
     }
   }
   uint32_t* gh = p.ws.hist + bh * kBins;
@@ -420,7 +456,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
 #pragma unroll
     for (int x = 0; x < kBins / kThreads; ++x) h8[x * kThreads + tid] = hv[x];
     __syncthreads();
-    find_bin(h8, kBins, k, scratch, bin, above);
+    find_bin(h8, k, hist, scratch, bin, above);  // hist: not in use yet
   }
   TKV_PH(4);
 
@@ -469,6 +505,9 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   // read from its workgroup's list in the workspace.
   uint32_t* offs = hist;  // list offsets of the workgroups (the entry point launches < 1024), then the total
   for (int x = tid; x <= nblk; x += kThreads) offs[x] = 0u;
+  __shared__ uint32_t h2[1024], h3[512];  // radix-select histograms (below)
+  for (int i = tid; i < 1024; i += kThreads) h2[i] = 0u;
+  for (int i = tid; i < 512; i += kThreads) h3[i] = 0u;
   __syncthreads();
   if (tid < 64) {  // exclusive scan of the counts by one wave
     uint32_t carry = 0;
@@ -511,27 +550,23 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   TKV_PH(6);
   uint32_t k_rem = k - above;  // 1 <= k_rem <= keys in the bin
 
-  // ---- exact threshold inside the bin: radix select on the low 19 key bits (10 + 9)
-  __shared__ uint32_t h2[1024];
-  for (int i = tid; i < 1024; i += kThreads) h2[i] = 0u;
-  __syncthreads();
+  // ---- exact threshold inside the bin: radix select on the low 19 key bits (10 + 9).  The two
+  // histograms were cleared before the concatenation; each search is done by one wave.
   for (uint32_t i = tid; i < M; i += kThreads) {
     const uint32_t key = get(i).x;
     if ((key >> kLowBits) == bin) atomicAdd(&h2[(key & kLowMask) >> 9], 1u);
   }
   __syncthreads();
   uint32_t d1, a1;
-  find_bin(h2, 1024, k_rem, scratch, d1, a1);
+  find_bin_wave(h2, 1024, k_rem, scratch, d1, a1);
   k_rem -= a1;
-  for (int i = tid; i < 512; i += kThreads) h2[i] = 0u;
-  __syncthreads();
   for (uint32_t i = tid; i < M; i += kThreads) {
     const uint32_t key = get(i).x;
-    if ((key >> kLowBits) == bin && ((key & kLowMask) >> 9) == d1) atomicAdd(&h2[key & 0x1FFu], 1u);
+    if ((key >> kLowBits) == bin && ((key & kLowMask) >> 9) == d1) atomicAdd(&h3[key & 0x1FFu], 1u);
   }
   __syncthreads();
   uint32_t d2, a2;
-  find_bin(h2, 512, k_rem, scratch, d2, a2);
+  find_bin_wave(h3, 512, k_rem, scratch, d2, a2);
   const uint32_t take = k_rem - a2;                       // keys equal to T that are selected (lowest indices)
   const uint32_t T = (bin << kLowBits) | (d1 << 9) | d2;  // threshold key
 
@@ -543,14 +578,15 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
     if (i < M) e = get(i);
     const bool gt = e.x > T, eq = e.x == T;  // T != 0: every real key has a non-zero prefix
     const unsigned long long mg = __builtin_amdgcn_ballot_w64(gt), me = __builtin_amdgcn_ballot_w64(eq);
+    const int set = (int)((base / kThreads) & 1u) * 2;  // alternate the count rows: one barrier per tile
     if (lane == 0) {
-      s_cnt[0][wave] = (uint32_t)__builtin_popcountll(mg);
-      s_cnt[1][wave] = (uint32_t)__builtin_popcountll(me);
+      s_cnt[set][wave] = (uint32_t)__builtin_popcountll(mg);
+      s_cnt[set + 1][wave] = (uint32_t)__builtin_popcountll(me);
     }
     __syncthreads();
     uint32_t pg = 0, pe = 0, tg = 0, te = 0;
     for (int w = 0; w < kWavesPerBlock; ++w) {
-      const uint32_t cg = s_cnt[0][w], ce = s_cnt[1][w];
+      const uint32_t cg = s_cnt[set][w], ce = s_cnt[set + 1][w];
       pg += w < wave ? cg : 0u;
       pe += w < wave ? ce : 0u;
       tg += cg;
@@ -564,7 +600,6 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
     }
     gt_run += tg;
     eq_run += te;
-    __syncthreads();
   }
   TKV_PH(7);
 }
