@@ -757,8 +757,8 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     if (us == 0) ms.m[wave][hs] = m_run;
   }
   if (rb == 1 && us == 0) ms.l[wave][hs] = acc_z[0];
-  __syncthreads();
   {
+    // written by lanes of this same wave just above: a wave's LDS operations execute in order
     const float zt = ms.z[wave][hs][us];
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb) {
@@ -771,13 +771,16 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     }
   }
   __syncthreads();
-  // merge weights of the W wave entries and the tail entries, once per (entry, head)
+  // merge weights of the W wave entries and the tail entries: every wave works them out for
+  // itself (lane = (entry, head)) into arrays of its own, which spares the workgroup a barrier
   constexpr int NE = W + kTailWaves;
-  __shared__ float s_w[NE][4];
-  __shared__ float s_ml[2][4];
+  __shared__ float s_w_all[W][NE][4];
+  __shared__ float s_ml_all[W][2][4];
   static_assert(NE <= 16, "one wave covers all (entry, head) pairs");
-  if (tid < 64) {  // lane = (entry, head)
-    const int e = tid / 4, hh = tid % 4;
+  float(*s_w)[4] = s_w_all[wave];
+  float(*s_ml)[4] = s_ml_all[wave];
+  {
+    const int e = lane / 4, hh = lane % 4;
     float me = -INFINITY, le = 0.f;
     if (e < W) {
       me = ms.m[e][hh];
@@ -797,7 +800,6 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
       s_ml[1][hh] = Lsum;
     }
   }
-  __syncthreads();
   for (int i = tid; i < G * TKV_D; i += C::kThreads) {
     const int hh = i / TKV_D, c = i % TKV_D;
     float O = 0.f;
