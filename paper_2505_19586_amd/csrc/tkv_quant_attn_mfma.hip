@@ -162,12 +162,13 @@ struct TailEntry {
   float l[4];
   float o[4][TKV_D];
 };
-template <int W>
-struct MergeSmem {
-  float m[W][4];
-  float l[W][4];
-  float z[W][4][4];
-  float o[W][4][TKV_D];
+// Results of one wave for the merge inside the workgroup; it takes the place of the start of
+// the wave's own load ring once the wave has left the group loop.
+struct MergeWave {
+  float m[4];
+  float l[4];
+  float z[4][4];
+  float o[4][TKV_D];
 };
 
 // ---- LDS plan (dynamic shared memory) ---------------------------------------------------
@@ -175,7 +176,7 @@ struct MergeSmem {
 //   ring   per wave 3 K slots (codes, scalers) then 3 V slots (codes, scalers, zero-points);
 //          the direct global->LDS loads put lane l's bytes at slot + 16*l (codes) or
 //          slot + 4*l (fp16 rows), i.e. a slot is a copy of the group's packed block.  After
-//          the main loop the same bytes hold the per-wave results for the workgroup merge.
+//          the main loop the start of a wave's ring holds its results for the workgroup merge.
 //   cz     zero-point term of every group of the chunk, [group][4 heads] float
 //   tail   partial results of the waves that share the fp16 tail
 //   q      the 4 query rows as fp16, for the tail
@@ -203,7 +204,8 @@ struct Cfg {
   static constexpr int oTail = oCz + kMaxGpc * 16;
   static constexpr int oQ = oTail + kTailWaves * (int)sizeof(TailEntry);
   static constexpr int kLdsBytes = oQ + 4 * TKV_D * 2;
-  static_assert(sizeof(MergeSmem<W>) + (3 * 4 * TKV_MAX_CHUNKS + 4 * 4 * TKV_D + 4) * 4 <= (size_t)W * kWaveRing, "merge scratch must fit in the ring");
+  static_assert(sizeof(MergeWave) <= (size_t)kWaveRing, "a wave's results fit in its own ring");
+  static_assert((3 * 4 * TKV_MAX_CHUNKS + 4 * 4 * TKV_D + 4) * 4 <= (size_t)W * kWaveRing, "merge scratch must fit in the ring");
   static_assert(kLdsBytes + 64 <= 160 * 1024, "LDS budget of one compute unit");
 };
 
@@ -744,33 +746,34 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
 #undef TKV_WAIT_VMCNT
   TKV_PH();  // 4 this wave's groups done
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct-to-LDS load may land after the ring is reused
-  __syncthreads();
-  TKV_PH();  // 5 all waves done
 
-  // ---- per-wave results -> LDS.  acc_z rows: lanes 0..15 (rb 0) hold rows 0..3 = z-terms
-  // for u = row; lanes 16..31 register 0 hold row 4 = denominator.
-  MergeSmem<W>& ms = *reinterpret_cast<MergeSmem<W>*>(smem + C::oRing);
+  // ---- per-wave results -> LDS, each wave into its own (now idle) ring, so no wave waits for
+  // another before writing.  acc_z rows: lanes 0..15 (rb 0) hold rows 0..3 = z-terms for
+  // u = row; lanes 16..31 register 0 hold row 4 = denominator.
+  auto merge_of = [&](int w) -> MergeWave& { return *reinterpret_cast<MergeWave*>(smem + C::oRing + w * C::kWaveRing); };
+  MergeWave& mw = merge_of(wave);
   if (rb == 0) {
 #pragma unroll
     for (int x = 0; x < 4; ++x)
-      if (x == us / GS) ms.z[wave][hs][us] = acc_z[x];
-    if (us == 0) ms.m[wave][hs] = m_run;
+      if (x == us / GS) mw.z[hs][us] = acc_z[x];
+    if (us == 0) mw.m[hs] = m_run;
   }
-  if (rb == 1 && us == 0) ms.l[wave][hs] = acc_z[0];
+  if (rb == 1 && us == 0) mw.l[hs] = acc_z[0];
   {
     // written by lanes of this same wave just above: a wave's LDS operations execute in order
-    const float zt = ms.z[wave][hs][us];
+    const float zt = mw.z[hs][us];
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb) {
       // 1 bit: the codes of odd 16-channel blocks sit four mantissa bits higher
       const float unscale = (float)(1 << (24 - kEP - (BITS == 1 && cb % 2 ? 4 : 0)));
       if (cb / 2 == us) {
 #pragma unroll
-        for (int x = 0; x < 4; ++x) ms.o[wave][hs][16 * cb + 4 * rb + x] = __builtin_fmaf(acc_o[cb][x], unscale, zt);
+        for (int x = 0; x < 4; ++x) mw.o[hs][16 * cb + 4 * rb + x] = __builtin_fmaf(acc_o[cb][x], unscale, zt);
       }
     }
   }
   __syncthreads();
+  TKV_PH();  // 5 all waves done, results in LDS
   // merge weights of the W wave entries and the tail entries: every wave works them out for
   // itself (lane = (entry, head)) into arrays of its own, which spares the workgroup a barrier
   constexpr int NE = W + kTailWaves;
@@ -783,8 +786,8 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     const int e = lane / 4, hh = lane % 4;
     float me = -INFINITY, le = 0.f;
     if (e < W) {
-      me = ms.m[e][hh];
-      le = ms.l[e][hh];
+      me = merge_of(e).m[hh];
+      le = merge_of(e).l[hh];
     } else if (e < NE) {
       me = tail_s[e - W].m[hh];
       le = tail_s[e - W].l[hh];
@@ -804,7 +807,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     const int hh = i / TKV_D, c = i % TKV_D;
     float O = 0.f;
 #pragma unroll
-    for (int w = 0; w < W; ++w) O = __builtin_fmaf(ms.o[w][hh][c], s_w[w][hh], O);
+    for (int w = 0; w < W; ++w) O = __builtin_fmaf(merge_of(w).o[hh][c], s_w[w][hh], O);
 #pragma unroll
     for (int w = 0; w < kTailWaves; ++w) {  // unused tail slots hold no data, only a zero weight
       const float wgt = s_w[W + w][hh];
@@ -831,7 +834,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   if (s_flag != 0u) {
     if (tid == 0) p.arrivals[bh] = 0u;
     const float* head0 = p.parts + ((size_t)b * p.hq + (size_t)h * G) * p.n_chunks * TKV_PART_STRIDE;
-    float* scratch = reinterpret_cast<float*>(smem + C::oRing + sizeof(MergeSmem<W>));
+    float* scratch = reinterpret_cast<float*>(smem + C::oRing);  // the waves' results have been consumed
     tkv::merge_chunks(head0, G, p.n_chunks, p.out + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, scratch, tid, C::kThreads);
   }
   TKV_PH();  // 7 end
