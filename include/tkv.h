@@ -157,9 +157,11 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
 
 /* Test and tuning hook (process-wide, not thread-safe): kernel_choice 0 = matrix-core
  * kernel, which also covers the fp16 tail (default), 1 = shape-generic
- * reference kernel for everything; target_blocks > 0 sets the number of workgroups
- * the split-K launch aims at (0 keeps the current value; the launch uses at most 64
- * chunks per (sequence, KV head) unless target_blocks asks for more than that). */
+ * reference kernel for everything.  By default the split-K launch aims at one workgroup per
+ * compute unit that the stream may use (all of them, or those of its compute-unit mask);
+ * target_blocks > 0 fixes the number of workgroups instead, -1 returns to the default, 0
+ * keeps the current setting (the launch uses at most 64 chunks per (sequence, KV head)
+ * unless target_blocks asks for more than that). */
 int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks);
 
 /* Measurement aid (not part of the method): one plain read sweep over `bytes` bytes of

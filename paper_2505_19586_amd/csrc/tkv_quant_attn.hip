@@ -15,7 +15,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
 namespace {
 
 int g_kernel_choice = 0;      // 0: matrix-core kernel (+ reference kernel for the tail), 1: reference kernel only
-int g_target_blocks = 256;    // workgroups the split-K launch aims at (one per compute unit)
+int g_target_blocks = 0;      // workgroups the split-K launch aims at; 0 = one per compute unit of the stream
 
 struct QuantAttnParams {
   const uint32_t* k_codes;
@@ -272,9 +272,10 @@ int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, in
 }  // namespace tkv
 
 extern "C" int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks) {
-  if (kernel_choice < 0 || kernel_choice > 1 || target_blocks < 0) return TKV_E_INVAL;
+  if (kernel_choice < 0 || kernel_choice > 1 || target_blocks < -1) return TKV_E_INVAL;
   g_kernel_choice = kernel_choice;
   if (target_blocks > 0) g_target_blocks = target_blocks;
+  if (target_blocks == -1) g_target_blocks = 0;  // back to one workgroup per compute unit of the stream
   return TKV_OK;
 }
 
@@ -339,7 +340,21 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
     const size_t parts_bytes =
         (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
     uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_bytes + 255) & ~(size_t)255));
-    st = tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, g_target_blocks, max_groups,
+    int target_blocks = g_target_blocks;
+    if (target_blocks == 0) {
+      // One workgroup per compute unit that the stream may use: on a stream with a compute-unit
+      // mask a launch sized for the whole machine would leave a few workgroups for a second round.
+      uint32_t mask[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      target_blocks = 256;
+      if (hipExtStreamGetCUMask(s, 8, mask) == hipSuccess) {
+        int cus = 0;
+        for (uint32_t m : mask) cus += __builtin_popcount(m);
+        if (cus > 0 && cus <= 256) target_blocks = cus;
+      } else {
+        (void)hipGetLastError();
+      }
+    }
+    st = tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, target_blocks, max_groups,
                                      max_tail, p.lens, s);
     if (st != TKV_E_UNSUPPORTED) return st;
   }

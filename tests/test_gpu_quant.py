@@ -171,7 +171,7 @@ def test_many_chunks(kernel_choice):
             out = layer.attn_decode(q, SM)
             assert attn_err(out[0], want) <= TOL
     finally:
-        tkv.debug_quant_attn_config(0, 256)
+        tkv.debug_quant_attn_config(0, -1)
 
 
 def test_read_sweep_runs_and_leaves_the_buffer_alone():
@@ -183,3 +183,36 @@ def test_read_sweep_runs_and_leaves_the_buffer_alone():
     tkv.debug_read_sweep(buf[: 4 * 13])          # shorter than one pass of the grid
     torch.cuda.synchronize()
     assert torch.equal(buf, before)
+
+
+def test_stream_with_compute_unit_mask():
+    """On a stream that may use only part of the machine the split-K launch sizes itself to
+    that part; the result does not depend on it."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    create = hip.hipExtStreamCreateWithCUMask
+    create.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_uint32)]
+    create.restype = C.c_int
+    mask = (C.c_uint32 * 8)(0xFFFF0000, 0xFFFFFFFF, 0xFFFFFFFF, 0x0000FFFF, 0, 0, 0, 0)   # 96 units
+    handle = C.c_void_p()
+    if create(C.byref(handle), 8, mask) != 0 or not handle.value:
+        pytest.skip("streams with a compute-unit mask are not available")
+    stream = torch.cuda.ExternalStream(handle.value)
+    try:
+        inp = make_layer(5000, seq=12)
+        layer = tkv.QuantLayer(bits=2, capacity=5056)
+        layer.append(to_new(inp.k), to_new(inp.v))
+        ref = check_quant_cache(layer, 0, inp.k, inp.v)
+        q = torch.from_numpy(inp.q)[None].cuda()
+        want = attention.quant_attention(inp.q, ref, SM)
+        torch.cuda.synchronize()
+        out_masked = layer.attn_decode(q, SM, stream=stream)
+        stream.synchronize()
+        out_masked = out_masked.clone()
+        out_plain = layer.attn_decode(q, SM)
+        torch.cuda.synchronize()
+        assert attn_err(out_masked[0], want) <= TOL and attn_err(out_plain[0], want) <= TOL
+    finally:
+        torch.cuda.synchronize()
+        hip.hipStreamDestroy.argtypes = [C.c_void_p]
+        hip.hipStreamDestroy(handle)
