@@ -61,7 +61,7 @@ def parse():
                     help="overlapped (the benchmark's configuration): sparse-layer gathers on a side stream under "
                          "the other layers' compute; chained: every call waits for the previous one")
     ap.add_argument("--one-schedule", action="store_true", help="time only --schedule (profiling runs)")
-    ap.add_argument("--lookahead", type=int, default=2,
+    ap.add_argument("--lookahead", type=int, default=4,
                     help="overlapped schedule: sparse layers whose scoring runs ahead of the attention")
     ap.add_argument("--gather-streams", type=int, default=2,
                     help="overlapped schedule: side streams the gathers alternate between")
@@ -72,14 +72,19 @@ def parse():
 
 def cu_masked_streams(n_gather_cus, n_streams=1, n_cus=256):
     """HIP streams with disjoint compute-unit masks, wrapped for torch: n_streams gather
-    streams that split the first n_gather_cus units evenly (consecutive unit numbers sit in
-    different dies, so a mask of 8 has one unit in every die) and a compute stream on all
-    the others.  Returns ([gather streams], compute stream, destroy) or None if the runtime
-    refuses."""
+    streams that split the first n_gather_cus mask bits evenly, and a compute stream on
+    everything above the next multiple of 32 bits.  Mask bit i is a unit of shader engine
+    i mod 32 (four engines per die), and a launch hands every engine the same share of its
+    workgroups: only a mask that takes the same number of units from every engine (whole
+    groups of 32 bits) leaves the compute stream a machine on which one-workgroup-per-unit
+    launches still finish in one round; with 16 units taken from half of the engines every
+    kernel of the compute stream ran about 1.5 times longer.  Returns ([gather streams],
+    compute stream, destroy) or None if the runtime refuses."""
     import ctypes as C
     import torch
     per = n_gather_cus // max(n_streams, 1)
-    if n_streams < 1 or per < 8 or n_gather_cus >= n_cus:
+    reserved = -(-n_gather_cus // 32) * 32
+    if n_streams < 1 or per < 8 or reserved >= n_cus:
         return None
     try:
         hip = C.CDLL("libamdhip64.so")
@@ -90,14 +95,13 @@ def cu_masked_streams(n_gather_cus, n_streams=1, n_cus=256):
     fn.restype = C.c_int
     words = n_cus // 32
     gather_bits = [((1 << per) - 1) << (per * i) for i in range(n_streams)]
-    all_gather = 0
-    for b in gather_bits:
-        all_gather |= b
+    compute_bits = ((1 << n_cus) - 1) ^ ((1 << reserved) - 1)
     out, handles = [], []
-    for bits in gather_bits + [((1 << n_cus) - 1) ^ all_gather]:
+    for bits in gather_bits + [compute_bits]:
         mask = (C.c_uint32 * words)(*[(bits >> (32 * i)) & 0xFFFFFFFF for i in range(words)])
         h = C.c_void_p()
         if fn(C.byref(h), words, mask) != 0 or not h.value:
+            hip.hipGetLastError()   # the refusal must not surface in a later launch check
             return None
         handles.append(h)
         out.append(torch.cuda.ExternalStream(h.value))

@@ -39,6 +39,27 @@ __host__ __device__ inline int32_t n_quantized(int32_t n, int32_t w, int32_t g) 
 
 inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? TKV_OK : TKV_E_HIP; }
 
+// Compute units that kernels of this stream may use: those of its compute-unit mask
+// (hipExtStreamCreateWithCUMask), all of the device's for an ordinary stream.  Launches that
+// aim at one workgroup per compute unit size themselves with it.
+inline int stream_compute_units(hipStream_t s) {
+  static const int device_cus = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      v = 0;
+    return v > 0 ? v : 256;
+  }();
+  uint32_t mask[16] = {0};
+  if (hipExtStreamGetCUMask(s, 16, mask) != hipSuccess) {
+    (void)hipGetLastError();
+    return device_cus;
+  }
+  int cus = 0;
+  for (uint32_t m : mask) cus += __builtin_popcount(m);
+  return cus > 0 && cus <= device_cus ? cus : device_cus;
+}
+
 int32_t check_quant_desc(const tkv_quant_desc* d);
 // Merges [n_heads_total][n_parts][TKV_PART_STRIDE] float partials (max in log2 units, sum,
 // weighted V) into fp16 [n_heads_total][D].

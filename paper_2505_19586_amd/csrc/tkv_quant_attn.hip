@@ -341,19 +341,9 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
         (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
     uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_bytes + 255) & ~(size_t)255));
     int target_blocks = g_target_blocks;
-    if (target_blocks == 0) {
-      // One workgroup per compute unit that the stream may use: on a stream with a compute-unit
-      // mask a launch sized for the whole machine would leave a few workgroups for a second round.
-      uint32_t mask[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      target_blocks = 256;
-      if (hipExtStreamGetCUMask(s, 8, mask) == hipSuccess) {
-        int cus = 0;
-        for (uint32_t m : mask) cus += __builtin_popcount(m);
-        if (cus > 0 && cus <= 256) target_blocks = cus;
-      } else {
-        (void)hipGetLastError();
-      }
-    }
+    // one workgroup per compute unit that the stream may use: on a stream with a compute-unit
+    // mask a launch sized for the whole machine would leave a few workgroups for a second round
+    if (target_blocks == 0) target_blocks = tkv::stream_compute_units(s);
     st = tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, target_blocks, max_groups,
                                      max_tail, p.lens, s);
     if (st != TKV_E_UNSUPPORTED) return st;

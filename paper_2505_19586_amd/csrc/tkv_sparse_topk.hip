@@ -665,13 +665,9 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   // context just past a multiple of 4096 * (compute units / heads) would pay a whole extra
   // round for a few tokens.  Instead the heads' tokens are split evenly over as many
   // workgroups as fill the machine a whole number of times (each owning up to 8192 tokens),
-  // or, when even one round is not filled, over more and smaller workgroups.
-  static const int n_cus = [] {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-      v = 0;
-    return v > 0 ? v : 256;
-  }();
+  // or, when even one round is not filled, over more and smaller workgroups.  "The machine" is
+  // what the stream may use of it.
+  const int n_cus = tkv::stream_compute_units(s);  // of the stream's compute-unit mask, if it has one
   const int bh_count = d->batch * d->n_kv_heads;
   const int full = (max_n + kTok - 1) / kTok;
   int nblk = full > 0 ? full : 1;
