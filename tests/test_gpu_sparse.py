@@ -203,3 +203,36 @@ def test_decode_steps_with_append_inside_the_scoring_launch(n0, steps):
     # too many rows for the fused form
     with pytest.raises(tkv.TkvError):
         layer.append_estimate_topk(kd[:, :9].contiguous(), vd[:, :9].contiguous(), q)
+
+
+@pytest.mark.parametrize("units", [224, 96, 8])
+def test_streams_with_compute_unit_masks(units):
+    """Scoring, Top-K, gather and attention on a stream that may use only part of the machine:
+    the token split follows the stream's mask, the results do not depend on it."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    create = hip.hipExtStreamCreateWithCUMask
+    create.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_uint32)]
+    create.restype = C.c_int
+    bits = ((1 << 256) - 1) ^ ((1 << (256 - units)) - 1) if units >= 32 else (1 << units) - 1
+    mask = (C.c_uint32 * 8)(*[(bits >> (32 * i)) & 0xFFFFFFFF for i in range(8)])
+    handle = C.c_void_p()
+    if create(C.byref(handle), 8, mask) != 0 or not handle.value:
+        hip.hipGetLastError()
+        pytest.skip("streams with a compute-unit mask are not available")
+    stream = torch.cuda.ExternalStream(handle.value)
+    try:
+        n = 9000
+        inp = make_layer(n, config=0, layer=1, seq=5)
+        layer, ch = _build(inp, top_k=1024, capacity=n + 40)
+        q = torch.from_numpy(inp.q)[None].cuda()
+        out = torch.empty(1, inp.q.shape[0], 128, dtype=torch.float16, device="cuda")
+        torch.cuda.synchronize()
+        layer.estimate_topk(q, stream=stream)
+        layer.gather_attn(q, SM, out=out, gather_stream=stream, compute_stream=stream)
+        stream.synchronize()
+        _check_layer(layer, 0, inp, ch, q, out)
+    finally:
+        torch.cuda.synchronize()
+        hip.hipStreamDestroy.argtypes = [C.c_void_p]
+        hip.hipStreamDestroy(handle)
