@@ -66,7 +66,8 @@ def parse():
     ap.add_argument("--gather-streams", type=int, default=2,
                     help="overlapped schedule: side streams the gathers alternate between")
     ap.add_argument("--gather-cus", type=int, default=16,
-                    help="overlapped schedule: compute units reserved for the gather streams, split evenly (0 = no masks)")
+                    help="overlapped schedule: compute units of the gather streams, split evenly (0 = no masks); the "
+                         "compute stream gets what lies above the next multiple of 32 mask bits")
     return ap.parse_args()
 
 
