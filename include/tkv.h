@@ -227,6 +227,8 @@ int32_t tkv_sparse_append_ragged(const tkv_sparse_desc* desc, tkv_sparse_cache* 
  * workspace: at least the size tkv_sparse_cache_sizes reports, ZERO-FILLED by the caller
  * before its first use (it holds histograms and counters that every call leaves zero
  * again); concurrent calls need separate workspaces.
+ * The tokens are split over about one workgroup per compute unit that `stream` may use
+ * (all of them, or those of its compute-unit mask); the result does not depend on it.
  */
 int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* desc, const tkv_sparse_cache* cache, const void* q,
                                  int32_t* topk_idx, int32_t* topk_count, void* workspace,
