@@ -374,6 +374,8 @@ def main():
             # host link (its memory instructions queue behind the gather's): the gather gets
             # compute units of its own and everything else the rest.
             masked = cu_masked_streams(args.gather_cus, args.gather_streams)
+            if masked is None and args.gather_cus > 0:
+                return None   # no streams with compute-unit masks here: plain overlap is slower than chaining
             if masked is None:
                 sides, compute = [torch.cuda.Stream() for _ in range(args.gather_streams)], torch.cuda.current_stream()
                 ctx = contextlib.nullcontext()
@@ -395,6 +397,9 @@ def main():
         return ms
 
     ms_per_step = timed(args.schedule)
+    if ms_per_step is None:   # the overlapped schedule could not be set up
+        args.schedule = "chained"
+        ms_per_step = timed("chained")
     other = "overlapped" if args.schedule == "chained" else "chained"
     ms_other = None if args.one_schedule or args.dynamic_channels == "host" else timed(other)
 
