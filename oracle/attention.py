@@ -84,3 +84,16 @@ def max_rel_err(out: np.ndarray, ref: np.ndarray) -> float:
     den = np.abs(ref).max(axis=-1)
     den = np.where(den == 0, 1.0, den)
     return float((num / den).max())
+
+
+def elementwise_rel_err(out: np.ndarray, ref: np.ndarray, floor: float = 2e-3) -> float:
+    """Reported beside max_rel_err (never asserted): per query-head vector,
+    max_c |out - ref| / max(|ref_c|, floor * rms_c(ref)); the maximum over heads is
+    returned.  The floor keeps channels whose reference value is nearly zero from
+    dominating; a head whose reference is all zero uses a denominator of 1."""
+    out = np.asarray(out, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = np.sqrt((ref * ref).mean(axis=-1, keepdims=True))
+    den = np.maximum(np.abs(ref), float(floor) * rms)
+    den = np.where(den == 0, 1.0, den)
+    return float((np.abs(out - ref) / den).max())

@@ -52,3 +52,9 @@ def check_quant_cache(layer: "tkv.QuantLayer", b: int, k: np.ndarray, v: np.ndar
 
 def attn_err(out: torch.Tensor, ref: np.ndarray) -> float:
     return attention.max_rel_err(out.float().cpu().numpy().astype(np.float64), ref)
+
+
+def attn_err_elementwise(out: torch.Tensor, ref: np.ndarray) -> float:
+    """Reported beside attn_err, never asserted: element-wise relative error with a floor of
+    2e-3 * rms(ref) under every denominator."""
+    return attention.elementwise_rel_err(out.float().cpu().numpy().astype(np.float64), ref)

@@ -9,7 +9,7 @@ import paper_2505_19586_amd as tkv
 from oracle import attention, quant, sparse
 from synth import make_layer, ragged_lengths, static_channels
 
-from gpu_util import attn_err, check_quant_cache, to_new, to_new_batch
+from gpu_util import attn_err, attn_err_elementwise, check_quant_cache, to_new, to_new_batch
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
@@ -24,8 +24,9 @@ def test_quant_layer_full_size(n, bits, g):
     layer.append(to_new(inp.k), to_new(inp.v))
     ref = check_quant_cache(layer, 0, inp.k, inp.v)          # every code, scaler, zero-point
     out = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
-    err = attn_err(out[0], attention.quant_attention(inp.q, ref, SM))
-    print(f"   err {err:.3e}", flush=True)
+    want = attention.quant_attention(inp.q, ref, SM)
+    err = attn_err(out[0], want)
+    print(f"   err {err:.3e} (element-wise with 2e-3 rms floor: {attn_err_elementwise(out[0], want):.3e})", flush=True)
     assert err <= TOL
     # one decoded token more: the single-token append path at full size
     new = make_layer(1, config=1, layer=1, seq=bits)
@@ -56,7 +57,7 @@ def test_sparse_layer_full_size():
     assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
     want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, n, SM, n_sink=4, n_window=64)
     err = attn_err(out[0], want)
-    print(f"   err {err:.3e}", flush=True)
+    print(f"   err {err:.3e} (element-wise with 2e-3 rms floor: {attn_err_elementwise(out[0], want):.3e})", flush=True)
     assert err <= TOL
     # a second call on the same workspace (self-cleaning counters) gives the same indices
     layer.estimate_topk(q)

@@ -126,3 +126,54 @@ def test_dequant_group_mapping_is_not_transposed():
     tv, cv = np.nonzero(dv[0])
     assert set(tv) == {45} and cv.min() >= 96 and cv.max() < 128
     assert not dk[0].any() and not dv[1].any()
+
+
+def test_error_metric_hand_worked():
+    """Pins the metric behind every attention parity assertion: per query-head vector,
+    max_c |out - ref| / max_c |ref|, then the maximum over heads.  All values are binary
+    fractions, so the expected numbers are exact.
+
+    head 0: ref (8, 1, -2, 0), errors (1/64, 0, 0, 1/16): the largest error sits on the
+            channel whose reference is 0, the largest |ref| on another -> (1/16) / 8 = 2^-7
+    head 1: ref (1/2, -1/4, 1/8, 1/4), errors (0, 1/64, 0, 0) -> (1/64) / (1/2) = 2^-5
+    The worst head (1) is not the head with the largest reference or the largest absolute
+    error (0).  Variants that must NOT come out: whole-tensor denominator 2^-7, minimum over
+    heads 2^-7, mean over heads 5 * 2^-8, error and reference taken on the same channel (inf)."""
+    ref = np.array([[8.0, 1.0, -2.0, 0.0], [0.5, -0.25, 0.125, 0.25]])
+    out = ref + np.array([[1 / 64, 0.0, 0.0, 1 / 16], [0.0, -1 / 64, 0.0, 0.0]])
+    assert attention.max_rel_err(out, ref) == 2.0 ** -5
+    # each head on its own, and symmetric in the sign of the error
+    assert attention.max_rel_err(out[0], ref[0]) == 2.0 ** -7
+    assert attention.max_rel_err(out[1], ref[1]) == 2.0 ** -5
+    assert attention.max_rel_err(2 * ref - out, ref) == 2.0 ** -5
+    # heads swapped: the same value (maximum over heads, not the first or the last head)
+    assert attention.max_rel_err(out[::-1], ref[::-1]) == 2.0 ** -5
+    # a leading batch axis is just more heads
+    assert attention.max_rel_err(out[None], ref[None]) == 2.0 ** -5
+    # all-zero reference head: denominator 1, the error itself is reported
+    z = np.zeros((1, 4))
+    assert attention.max_rel_err(z + np.array([0.0, 2.0 ** -9, 0.0, 0.0]), z) == 2.0 ** -9
+    assert attention.max_rel_err(ref, ref) == 0.0
+    # scaling both by a constant leaves the metric unchanged (it is relative)
+    assert attention.max_rel_err(4 * out, 4 * ref) == 2.0 ** -5
+
+
+def test_elementwise_error_hand_worked():
+    """The reported-only companion: max_c |out - ref| / max(|ref_c|, floor * rms(ref)) per head.
+    Same example.  head 0: rms = sqrt((64 + 1 + 4 + 0) / 4) = sqrt(17.25); channel 3 has
+    ref 0, so its denominator is the floor 2e-3 * sqrt(17.25) -> (1/16) / that; channel 0
+    gives (1/64) / 8.  head 1: floor = 2e-3 * sqrt(0.390625 / 4) is below every |ref_c| ->
+    (1/64) / (1/4) = 1/16."""
+    ref = np.array([[8.0, 1.0, -2.0, 0.0], [0.5, -0.25, 0.125, 0.25]])
+    out = ref + np.array([[1 / 64, 0.0, 0.0, 1 / 16], [0.0, -1 / 64, 0.0, 0.0]])
+    h0 = (1 / 16) / (2e-3 * np.sqrt(17.25))
+    assert attention.elementwise_rel_err(out[0], ref[0]) == pytest.approx(h0, rel=1e-12)
+    assert attention.elementwise_rel_err(out[1], ref[1]) == 1 / 16
+    assert attention.elementwise_rel_err(out, ref) == pytest.approx(h0, rel=1e-12)
+    # a larger floor takes over the denominators of small channels
+    assert attention.elementwise_rel_err(out[1], ref[1], floor=1.0) == pytest.approx(
+        (1 / 64) / np.sqrt(0.390625 / 4), rel=1e-12)
+    # all-zero reference: denominator 1
+    z = np.zeros((2, 4))
+    assert attention.elementwise_rel_err(z + 0.25, z) == 0.25
+    assert attention.elementwise_rel_err(ref, ref) == 0.0
