@@ -15,8 +15,13 @@
  *   - Every function returns a tkv_status (0 = ok, negative = error).  Argument
  *     errors are reported before anything is enqueued and never touch the GPU.
  *   - The caller owns every buffer.  Unless an argument says "host", pointers are
- *     device pointers.  The library allocates nothing and keeps no state between
- *     calls (a few process-wide device queries are cached).
+ *     device pointers.  The library allocates no memory.  What it keeps between calls:
+ *     a few cached device queries (process-wide), and per HOST THREAD two events that
+ *     tkv_sparse_gather_attn uses to order its two streams (created at that thread's
+ *     first two-stream call, never destroyed).  Calls from different host threads are
+ *     independent as long as they use different workspaces and streams.
+ *   - A returned TKV_E_HIP comes from a HIP call the library made itself; the
+ *     library neither reads nor clears the runtime's process-wide "last error".
  *   - Calls enqueue work on the given hipStream_t (passed as void*) and return
  *     without synchronizing.  Sequence lengths live in caller-owned HOST int32
  *     arrays; kernels receive them by value, so the arrays may be changed as soon as
@@ -145,7 +150,7 @@ int32_t tkv_quantize_append_ragged(const tkv_quant_desc* desc, tkv_quant_cache* 
  * weight x value scaler, and query element x key scaler.  Cached values of magnitude up
  * to about 1000 and query-times-key-scaler products up to 65504 are safe at every bit
  * width; far larger ones overflow fp16 and give wrong or non-finite outputs (the
- * reference kernel of tkv_debug_quant_attn_config has no such limit).
+ * reference kernel that tkv_debug.h can switch to has no such limit).
  * The work is split over token chunks whose partial (max, sum, weighted V) results
  * go through `workspace` and are merged with a log-sum-exp merge.  The workspace must be
  * ZERO-FILLED by the caller before its first use (it ends in arrival counters that every
@@ -154,23 +159,6 @@ int32_t tkv_quantize_append_ragged(const tkv_quant_desc* desc, tkv_quant_cache* 
 int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache* cache, const void* q,
                               void* out, float sm_scale, void* workspace, size_t workspace_bytes,
                               void* stream);
-
-/* Test and tuning hook (process-wide, not thread-safe): kernel_choice 0 = matrix-core
- * kernel, which also covers the fp16 tail (default), 1 = shape-generic
- * reference kernel for everything.  By default the split-K launch aims at one workgroup per
- * compute unit that the stream may use (all of them, or those of its compute-unit mask);
- * target_blocks > 0 fixes the number of workgroups instead, -1 returns to the default, 0
- * keeps the current setting (the launch uses at most 64 chunks per (sequence, KV head)
- * unless target_blocks asks for more than that). */
-int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks);
-
-/* Measurement aid (not part of the method): one plain read sweep over `bytes` bytes of
- * device memory at `src` (both multiples of 16), 16-byte loads, n_workgroups workgroups of
- * 256 lanes (1 to 65536).  `sink`: NULL or a device buffer of n_workgroups 32-bit words
- * (almost never written; it only keeps the loads alive).  The benchmark times it over as
- * many bytes as a tkv_quant_attn_decode call reads: what a kernel that does nothing but
- * stream that volume takes on the same machine, launch included. */
-int32_t tkv_debug_read_sweep(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream);
 
 /* ---------------------------------------------------------------------------------
  * Sparsity-friendly layers

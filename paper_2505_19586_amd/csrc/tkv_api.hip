@@ -127,6 +127,6 @@ __global__ __launch_bounds__(256) void read_sweep_kernel(const uint4* __restrict
 extern "C" int32_t tkv_debug_read_sweep(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream) {
   if (!src || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)src & 15) != 0) return TKV_E_INVAL;
   if (n_workgroups <= 0 || n_workgroups > 65536) return TKV_E_INVAL;
-  read_sweep_kernel<<<dim3(n_workgroups), 256, 0, (hipStream_t)stream>>>((const uint4*)src, bytes / 16, (uint32_t*)sink);
-  return tkv::launch_status();
+  TKV_LAUNCH(read_sweep_kernel, dim3(n_workgroups), 256, 0, (hipStream_t)stream, (const uint4*)src, bytes / 16, (uint32_t*)sink);
+  return TKV_OK;
 }

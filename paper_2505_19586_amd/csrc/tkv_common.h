@@ -5,7 +5,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "tkv.h"
+#include "tkv_debug.h"
 
 #define TKV_D 128      // head_dim
 #define TKV_BLK 32     // tokens per block of packed codes (the quantization group is 32 or 64)
@@ -37,7 +41,24 @@ __host__ __device__ inline int32_t n_quantized(int32_t n, int32_t w, int32_t g) 
   return n >= w ? ((n - w) / g) * g : 0;
 }
 
-inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? TKV_OK : TKV_E_HIP; }
+// Kernel launch whose status is the launch's own return value: the process-wide "last error" of
+// the HIP runtime is neither read nor cleared, so an earlier error of the calling program is
+// never reported as the library's and never erased.
+template <typename... KArgs, typename... Args>
+inline int32_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s,
+                      Args&&... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "kernel argument count");
+  std::tuple<KArgs...> vals{static_cast<KArgs>(std::forward<Args>(args))...};
+  void* ptrs[sizeof...(KArgs)];
+  std::apply([&](auto&... v) { int i = 0; ((ptrs[i++] = (void*)&v), ...); }, vals);
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, s) == hipSuccess
+             ? TKV_OK
+             : TKV_E_HIP;
+}
+#define TKV_LAUNCH(kernel, grid, block, lds, stream, ...)                                                  \
+  do {                                                                                                     \
+    if (tkv::launch(kernel, grid, block, lds, stream, __VA_ARGS__) != TKV_OK) return TKV_E_HIP;            \
+  } while (0)
 
 // Compute units that kernels of this stream may use: those of its compute-unit mask
 // (hipExtStreamCreateWithCUMask), all of the device's for an ordinary stream.  Launches that

@@ -256,13 +256,11 @@ extern "C" int32_t tkv_dense_preference(const tkv_pref_desc* d, const void* q_la
     for (int h = 0; h < d->n_kv_heads; ++h) {
       p.b = b;
       p.h = h;
-      pref_logits_kernel<<<dim3(p.ntb, (R / 16 + 3) / 4), 256, 0, s>>>(p);
-      if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+      TKV_LAUNCH(pref_logits_kernel, dim3(p.ntb, (R / 16 + 3) / 4), 256, 0, s, p);
       st = tkv::topk_of_scores(ws.scores, ws.stride, R, n, d->top_k, (int)ws.stride, sws, ws.topk_idx, ws.topk_count, s);
       if (st != TKV_OK) return st;
-      pref_row_kernel<<<dim3(R), 256, 0, s>>>(p);
-      pref_sum_kernel<<<1, 64, 0, s>>>(p);
-      if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+      TKV_LAUNCH(pref_row_kernel, dim3(R), 256, 0, s, p);
+      TKV_LAUNCH(pref_sum_kernel, 1, 64, 0, s, p);
     }
   }
   return TKV_OK;

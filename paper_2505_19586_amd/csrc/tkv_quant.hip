@@ -219,19 +219,17 @@ extern "C" int32_t tkv_quantize_append_ragged(const tkv_quant_desc* d, tkv_quant
     const dim3 grid(max_groups, d->n_kv_heads, d->batch);
     const int variant = d->bits * 100 + d->group_size;
     switch (variant) {
-      case 132: quantize_group_kernel<1, 32><<<grid, 256, 0, s>>>(p); break;
-      case 232: quantize_group_kernel<2, 32><<<grid, 256, 0, s>>>(p); break;
-      case 432: quantize_group_kernel<4, 32><<<grid, 256, 0, s>>>(p); break;
-      case 164: quantize_group_kernel<1, 64><<<grid, 256, 0, s>>>(p); break;
-      case 264: quantize_group_kernel<2, 64><<<grid, 256, 0, s>>>(p); break;
-      case 464: quantize_group_kernel<4, 64><<<grid, 256, 0, s>>>(p); break;
+      case 132: TKV_LAUNCH((quantize_group_kernel<1, 32>), grid, 256, 0, s, p); break;
+      case 232: TKV_LAUNCH((quantize_group_kernel<2, 32>), grid, 256, 0, s, p); break;
+      case 432: TKV_LAUNCH((quantize_group_kernel<4, 32>), grid, 256, 0, s, p); break;
+      case 164: TKV_LAUNCH((quantize_group_kernel<1, 64>), grid, 256, 0, s, p); break;
+      case 264: TKV_LAUNCH((quantize_group_kernel<2, 64>), grid, 256, 0, s, p); break;
+      case 464: TKV_LAUNCH((quantize_group_kernel<4, 64>), grid, 256, 0, s, p); break;
       default: return TKV_E_UNSUPPORTED;
     }
-    if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
   }
   if (max_copy > 0) {
-    ring_update_kernel<<<dim3(max_copy, d->batch), 256, 0, s>>>(p);
-    if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+    TKV_LAUNCH(ring_update_kernel, dim3(max_copy, d->batch), 256, 0, s, p);
   }
   for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += p.n_add.n[b];
   return TKV_OK;

@@ -1,6 +1,8 @@
 // tkv_quant_attn_decode: Eq. 3 (Sec. 2.1) over the dequantized cache of a
 // quantization-friendly layer (Sec. 4.3), split over token chunks with a
 // log-sum-exp merge.
+#include <atomic>
+
 #include "tkv_common.h"
 
 namespace tkv {
@@ -14,8 +16,8 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
 
 namespace {
 
-int g_kernel_choice = 0;      // 0: matrix-core kernel (+ reference kernel for the tail), 1: reference kernel only
-int g_target_blocks = 0;      // workgroups the split-K launch aims at; 0 = one per compute unit of the stream
+std::atomic<int> g_kernel_choice{0};      // 0: matrix-core kernel (+ reference kernel for the tail), 1: reference kernel only
+std::atomic<int> g_target_blocks{0};      // workgroups the split-K launch aims at; 0 = one per compute unit of the stream
 
 struct QuantAttnParams {
   const uint32_t* k_codes;
@@ -266,8 +268,8 @@ __global__ __launch_bounds__(TKV_D) void attn_merge_kernel(const float* parts, _
 
 namespace tkv {
 int32_t launch_attn_merge(const float* parts, __half* out, int n_heads_total, int n_parts, hipStream_t s) {
-  attn_merge_kernel<<<dim3(n_heads_total), TKV_D, 0, s>>>(parts, out, n_parts);
-  return launch_status();
+  TKV_LAUNCH(attn_merge_kernel, dim3(n_heads_total), TKV_D, 0, s, parts, out, n_parts);
+  return TKV_OK;
 }
 }  // namespace tkv
 
@@ -334,13 +336,13 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   p.n_chunks = n_chunks;
 
   hipStream_t s = (hipStream_t)stream;
-  if (g_kernel_choice == 0) {
+  if (g_kernel_choice.load() == 0) {
     // matrix-core kernel: one launch covers the quantized groups and the fp16 tail
     // arrival counters sit behind the partials (zero before first use, left zero by every call)
     const size_t parts_bytes =
         (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
     uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_bytes + 255) & ~(size_t)255));
-    int target_blocks = g_target_blocks;
+    int target_blocks = g_target_blocks.load();
     // one workgroup per compute unit that the stream may use: on a stream with a compute-unit
     // mask a launch sized for the whole machine would leave a few workgroups for a second round
     if (target_blocks == 0) target_blocks = tkv::stream_compute_units(s);
@@ -350,7 +352,6 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   }
   // reference kernel: on request, and for the settings the matrix-core kernel is not built for
   p.chunk_offset = 0;
-  quant_attn_generic_kernel<<<dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s>>>(p);
-  if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+  TKV_LAUNCH(quant_attn_generic_kernel, dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s, p);
   return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, n_chunks + 1, s);
 }

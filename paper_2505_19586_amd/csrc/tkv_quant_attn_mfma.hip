@@ -853,8 +853,8 @@ int32_t launch_variant(const MfmaParams& p, dim3 grid, hipStream_t s) {
   static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_attn_mfma_kernel<BITS, GS, W>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes) == hipSuccess;
   if (!lds_ok) return TKV_E_HIP;
-  quant_attn_mfma_kernel<BITS, GS, W><<<grid, C::kThreads, C::kLdsBytes, s>>>(p);
-  return tkv::launch_status();
+  TKV_LAUNCH((quant_attn_mfma_kernel<BITS, GS, W>), grid, C::kThreads, C::kLdsBytes, s, p);
+  return TKV_OK;
 }
 
 }  // namespace

@@ -361,8 +361,7 @@ extern "C" int32_t tkv_sparse_append_dynamic(const tkv_sparse_desc* d, tkv_spars
   p.n_window = d->n_window;
   p.capacity = d->capacity;
   p.n_stride = n_new;
-  sparse_append_kernel<<<dim3(n_new, d->batch), 256, 0, (hipStream_t)stream>>>(p);
-  if (tkv::launch_status() != TKV_OK) return TKV_E_HIP;
+  TKV_LAUNCH(sparse_append_kernel, dim3(n_new, d->batch), 256, 0, (hipStream_t)stream, p);
   for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += p.n_add.n[b];
   return TKV_OK;
 }
@@ -399,8 +398,8 @@ extern "C" int32_t tkv_sparse_gather(const tkv_sparse_desc* d, const tkv_sparse_
   const int gmax = (d->top_k + 4 * kGatherRows - 1) / (4 * kGatherRows);
   if (gx > gmax) gx = gmax;
   if (gx < 1) gx = 1;
-  gather_rows_kernel<<<dim3(gx, d->n_kv_heads, d->batch), 256, 0, (hipStream_t)stream>>>(p);
-  return tkv::launch_status();
+  TKV_LAUNCH(gather_rows_kernel, dim3(gx, d->n_kv_heads, d->batch), 256, 0, (hipStream_t)stream, p);
+  return TKV_OK;
 }
 
 namespace {
@@ -456,11 +455,11 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                                    kAttnMaxWaves * 32 * kRowPitch) == hipSuccess;
     if (!lds_ok) return TKV_E_HIP;
-    sparse_attn_kernel<true><<<dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, W * 32 * kRowPitch, s>>>(p);
+    TKV_LAUNCH(sparse_attn_kernel<true>, dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, W * 32 * kRowPitch, s, p);
   } else {
-    sparse_attn_kernel<false><<<dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s>>>(p);
+    TKV_LAUNCH(sparse_attn_kernel<false>, dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s, p);
   }
-  return tkv::launch_status();
+  return TKV_OK;
 }
 }  // namespace
 
@@ -472,8 +471,10 @@ extern "C" int32_t tkv_sparse_attn(const tkv_sparse_desc* d, const tkv_sparse_ca
 }
 
 namespace {
-// Two process-wide events order the gather stream against the compute stream.
-// They carry no data; re-recording an event only affects waits enqueued later.
+// Two events per host thread order the gather stream against the compute stream.  They carry
+// no data; re-recording an event only affects waits enqueued later, and a thread enqueues its
+// record / wait pairs in program order, so calls of different threads (on their own streams)
+// cannot pick up each other's records.
 struct StreamLink {
   hipEvent_t topk_ready = nullptr, rows_ready = nullptr;
   int32_t init() {
@@ -483,7 +484,7 @@ struct StreamLink {
     return TKV_OK;
   }
 };
-StreamLink g_link;
+thread_local StreamLink g_link;
 }  // namespace
 
 extern "C" int32_t tkv_sparse_gather_attn(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,

@@ -144,8 +144,8 @@ extern "C" int32_t tkv_sparse_stage1_append(const tkv_sparse_desc* d, const tkv_
   p.capacity = d->capacity;
   p.n_stride = n_new;
   const dim3 grid((n_new + kTile - 1) / kTile, d->n_kv_heads, d->batch);
-  stage1_append_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(p);
-  return tkv::launch_status();
+  TKV_LAUNCH(stage1_append_kernel, grid, 256, 0, (hipStream_t)stream, p);
+  return TKV_OK;
 }
 
 extern "C" int32_t tkv_sparse_select_channels(const tkv_sparse_desc* d, const tkv_sparse_stage1* s1,
@@ -160,8 +160,8 @@ extern "C" int32_t tkv_sparse_select_channels(const tkv_sparse_desc* d, const tk
   p.hq = d->n_q_heads;
   p.hkv = d->n_kv_heads;
   p.ds = d->n_channels;
-  select_channels_kernel<<<dim3(d->n_kv_heads, d->batch), TKV_D, 0, (hipStream_t)stream>>>(p);
-  return tkv::launch_status();
+  TKV_LAUNCH(select_channels_kernel, dim3(d->n_kv_heads, d->batch), TKV_D, 0, (hipStream_t)stream, p);
+  return TKV_OK;
 }
 
 extern "C" int32_t tkv_sparse_prefetch_keys(const tkv_sparse_desc* d, const tkv_sparse_cache* c,
@@ -197,6 +197,6 @@ extern "C" int32_t tkv_sparse_prefetch_keys(const tkv_sparse_desc* d, const tkv_
   const int gx_max = (pieces + 15) / 16;
   if (gx > gx_max) gx = gx_max;
   if (gx < 1) gx = 1;
-  prefetch_rows_kernel<<<dim3(gx, d->n_kv_heads * d->n_channels, d->batch), 256, 0, (hipStream_t)stream>>>(p);
-  return tkv::launch_status();
+  TKV_LAUNCH(prefetch_rows_kernel, dim3(gx, d->n_kv_heads * d->n_channels, d->batch), 256, 0, (hipStream_t)stream, p);
+  return TKV_OK;
 }

@@ -708,22 +708,22 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;  // 4 Mi tokens per sequence
   if (d->n_channels == 16) {
     if (cm)
-      score_kernel<16, true><<<grid_score, kThreads, kScoreLds, s>>>(p);
+      TKV_LAUNCH((score_kernel<16, true>), grid_score, kThreads, kScoreLds, s, p);
     else
-      score_kernel<16, false><<<grid_score, kThreads, kScoreLds, s>>>(p);
+      TKV_LAUNCH((score_kernel<16, false>), grid_score, kThreads, kScoreLds, s, p);
   } else if (d->n_channels == 12) {
     if (cm)
-      score_kernel<12, true><<<grid_score, kThreads, kScoreLds, s>>>(p);
+      TKV_LAUNCH((score_kernel<12, true>), grid_score, kThreads, kScoreLds, s, p);
     else
-      score_kernel<12, false><<<grid_score, kThreads, kScoreLds, s>>>(p);
+      TKV_LAUNCH((score_kernel<12, false>), grid_score, kThreads, kScoreLds, s, p);
   } else {
     if (cm)
-      score_kernel<8, true><<<grid_score, kThreads, kScoreLds, s>>>(p);
+      TKV_LAUNCH((score_kernel<8, true>), grid_score, kThreads, kScoreLds, s, p);
     else
-      score_kernel<8, false><<<grid_score, kThreads, kScoreLds, s>>>(p);
+      TKV_LAUNCH((score_kernel<8, false>), grid_score, kThreads, kScoreLds, s, p);
   }
-  select_kernel<<<grid, kThreads, kSelectLds, s>>>(p);
-  return tkv::launch_status();
+  TKV_LAUNCH(select_kernel, grid, kThreads, kSelectLds, s, p);
+  return TKV_OK;
 }
 }  // namespace
 
@@ -826,8 +826,8 @@ int32_t topk_of_scores(const float* scores, size_t stride, int n_rows, int n, in
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
   if (!lds_ok) return TKV_E_HIP;
   const dim3 grid(nblk, n_rows, 1);
-  prescored_kernel<<<grid, kThreads, kScoreLds, s>>>(p, scores, stride);
-  select_kernel<<<grid, kThreads, kSelectLds, s>>>(p);
-  return launch_status();
+  TKV_LAUNCH(prescored_kernel, grid, kThreads, kScoreLds, s, p, scores, stride);
+  TKV_LAUNCH(select_kernel, grid, kThreads, kSelectLds, s, p);
+  return TKV_OK;
 }
 }  // namespace tkv

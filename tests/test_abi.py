@@ -1,4 +1,4 @@
-"""The C-ABI library loads, exports every symbol include/tkv.h declares, and reports
+"""The C-ABI library loads, exports every symbol include/*.h declares, and reports
 argument errors without touching a GPU."""
 import ctypes as C
 import os
@@ -21,9 +21,20 @@ def L():
 
 
 def _declared_functions():
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(tkv_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_debug_hooks_are_not_in_the_product_header():
     text = open(os.path.join(ROOT, "include", "tkv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tkv_[a-z0-9_]+)\s*\(", text)))
+    assert "tkv_debug_" not in text
+    assert "tkv_debug_read_sweep" in open(os.path.join(ROOT, "include", "tkv_debug.h")).read()
 
 
 def test_every_declared_symbol_is_exported(L):
@@ -231,3 +242,18 @@ def test_binding_refuses_to_run_without_gpu():
         tkv.QuantLayer(capacity=4096)
     with pytest.raises(RuntimeError):
         tkv.SparseLayer(capacity=4096)
+
+
+def test_library_leaves_the_callers_last_error_alone(L):
+    """An earlier HIP error of the calling program is neither reported as the library's nor
+    erased by it: argument checks and size helpers make no HIP call that could do either."""
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipSetDevice.argtypes = [C.c_int]
+    assert hip.hipSetDevice(12345) != 0                 # the caller's own error
+    d = _qdesc()
+    sizes = (C.c_size_t * 8)()
+    assert L.tkv_quant_cache_sizes(C.byref(d), sizes, None) == 0
+    assert L.tkv_quant_attn_decode(C.byref(d), None, None, None, C.c_float(1.0), None, 0, None) == -1
+    sd = _sdesc()
+    assert L.tkv_sparse_estimate_topk(C.byref(sd), None, None, None, None, None, 0, None) == -1
+    assert hip.hipGetLastError() != 0                   # still there for the caller to read
