@@ -160,6 +160,27 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
                               void* out, float sm_scale, void* workspace, size_t workspace_bytes,
                               void* stream);
 
+/*
+ * tkv_quant_attn_decode for callers that cannot allocate or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as tkv_quant_attn_decode, but the split-K partials and arrival
+ * counters live in a fixed device array inside the library image
+ * (TKV_STATIC_MAX_HEADS * 4 + TKV_STATIC_PARTS_BYTES bytes on every GPU the library runs on,
+ * held until the process ends).  The call allocates nothing and frees nothing.
+ * Limits: batch * n_kv_heads <= TKV_STATIC_MAX_HEADS and the launch's partials
+ * (batch * n_q_heads * chunks * 528 bytes; chunks is about compute units / (batch * n_kv_heads),
+ * at most 64) must fit in TKV_STATIC_PARTS_BYTES, else TKV_E_WORKSPACE and nothing is enqueued.
+ * Batch 1 to 64 with 32 query heads fits at every context length.
+ * The device that owns `stream` and the buffers must be the calling thread's current device.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or host threads) race with each other and give wrong results; calls on one stream
+ * are safe.  The first call on a device looks the array up (no allocation).
+ */
+#define TKV_STATIC_MAX_HEADS 4096
+#define TKV_STATIC_PARTS_BYTES (4u << 20)
+int32_t tkv_quant_attn_decode_static(const tkv_quant_desc* desc, const tkv_quant_cache* cache, const void* q,
+                                     void* out, float sm_scale, void* stream);
+
 /* ---------------------------------------------------------------------------------
  * Sparsity-friendly layers
  * ------------------------------------------------------------------------------- */

@@ -2,6 +2,7 @@
 // quantization-friendly layer (Sec. 4.3), split over token chunks with a
 // log-sum-exp merge.
 #include <atomic>
+#include <mutex>
 
 #include "tkv_common.h"
 
@@ -9,9 +10,8 @@ namespace tkv {
 // matrix-core path (tkv_quant_attn_mfma.hip); returns TKV_E_UNSUPPORTED when the
 // shape is not one it is built for.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
-                               float scale2, float* parts, uint32_t* arrivals, int target_blocks, int max_groups,
-                               int max_tail,
-                               const TkvSeqLens& lens, hipStream_t s);
+                               float scale2, float* parts, size_t parts_floats, uint32_t* arrivals, int target_blocks,
+                               int max_groups, int max_tail, const TkvSeqLens& lens, hipStream_t s);
 }  // namespace tkv
 
 namespace {
@@ -281,19 +281,13 @@ extern "C" int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t ta
   return TKV_OK;
 }
 
-extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q,
-                                         void* out, float sm_scale, void* workspace, size_t workspace_bytes,
-                                         void* stream) {
-  int32_t st = tkv::check_quant_desc(d);
-  if (st != TKV_OK) return st;
-  if (!c || !c->seq_len_host || !q || !out || !workspace) return TKV_E_INVAL;
-  if (!c->k_codes || !c->k_scale || !c->k_zero || !c->v_codes || !c->v_scale || !c->v_zero || !c->k_resid ||
-      !c->v_resid)
-    return TKV_E_INVAL;
-  size_t need = 0;
-  tkv_quant_cache_sizes(d, nullptr, &need);
-  if (workspace_bytes < need) return TKV_E_WORKSPACE;
+namespace {
 
+// Body of both entry points.  parts: room for parts_floats floats of split-K partials; arrivals:
+// one zero word per (sequence, KV head).  TKV_E_WORKSPACE if the launch's partials do not fit.
+int32_t quant_attn_decode_impl(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q, void* out,
+                               float sm_scale, float* parts, size_t parts_floats, uint32_t* arrivals,
+                               hipStream_t s) {
   QuantAttnParams p;
   int max_groups = 0, max_tail = 0;
   for (int b = 0; b < d->batch; ++b) {
@@ -324,7 +318,7 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   p.k_resid = (const __half*)c->k_resid;
   p.v_resid = (const __half*)c->v_resid;
   p.q = (const __half*)q;
-  p.parts = (float*)workspace;
+  p.parts = parts;
   p.scale2 = sm_scale * 1.44269504088896340736f;
   p.hq = d->n_q_heads;
   p.hkv = d->n_kv_heads;
@@ -335,23 +329,101 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   p.groups_per_chunk = gpc;
   p.n_chunks = n_chunks;
 
-  hipStream_t s = (hipStream_t)stream;
   if (g_kernel_choice.load() == 0) {
     // matrix-core kernel: one launch covers the quantized groups and the fp16 tail
-    // arrival counters sit behind the partials (zero before first use, left zero by every call)
-    const size_t parts_bytes =
-        (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
-    uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_bytes + 255) & ~(size_t)255));
     int target_blocks = g_target_blocks.load();
     // one workgroup per compute unit that the stream may use: on a stream with a compute-unit
     // mask a launch sized for the whole machine would leave a few workgroups for a second round
     if (target_blocks == 0) target_blocks = tkv::stream_compute_units(s);
-    st = tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, arrivals, target_blocks, max_groups,
-                                     max_tail, p.lens, s);
+    const int32_t st = tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, parts_floats, arrivals,
+                                                   target_blocks, max_groups, max_tail, p.lens, s);
     if (st != TKV_E_UNSUPPORTED) return st;
   }
   // reference kernel: on request, and for the settings the matrix-core kernel is not built for
+  if ((size_t)d->batch * d->n_q_heads * (n_chunks + 1) * TKV_PART_STRIDE > parts_floats) return TKV_E_WORKSPACE;
   p.chunk_offset = 0;
   TKV_LAUNCH(quant_attn_generic_kernel, dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s, p);
   return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, n_chunks + 1, s);
+}
+
+int32_t check_decode_args(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q, const void* out) {
+  const int32_t st = tkv::check_quant_desc(d);
+  if (st != TKV_OK) return st;
+  if (!c || !c->seq_len_host || !q || !out) return TKV_E_INVAL;
+  if (!c->k_codes || !c->k_scale || !c->k_zero || !c->v_codes || !c->v_scale || !c->v_zero || !c->k_resid ||
+      !c->v_resid)
+    return TKV_E_INVAL;
+  return TKV_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q,
+                                         void* out, float sm_scale, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+  int32_t st = check_decode_args(d, c, q, out);
+  if (st != TKV_OK) return st;
+  if (!workspace) return TKV_E_INVAL;
+  size_t need = 0;
+  tkv_quant_cache_sizes(d, nullptr, &need);
+  if (workspace_bytes < need) return TKV_E_WORKSPACE;
+  // arrival counters sit behind the partials (zero before first use, left zero by every call)
+  const size_t parts_floats = (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE;
+  uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_floats * sizeof(float) + 255) & ~(size_t)255));
+  return quant_attn_decode_impl(d, c, q, out, sm_scale, (float*)workspace, parts_floats, arrivals, (hipStream_t)stream);
+}
+
+// ---- tkv_quant_attn_decode for callers that cannot hand over a workspace -----------------
+// The split-K partials and arrival counters live in a fixed array in device memory that is part
+// of the library image (every GPU the library runs on holds its own copy until the process
+// ends).  In host code the array's name is only a stand-in for the symbol: the address that
+// kernels may use is looked up once per device with that device current.
+namespace {
+
+constexpr size_t kStaticCounterWords = TKV_STATIC_MAX_HEADS;   // one per (sequence, KV head)
+constexpr size_t kStaticPartsBytes = TKV_STATIC_PARTS_BYTES;
+constexpr size_t kStaticBytes = kStaticCounterWords * sizeof(uint32_t) + kStaticPartsBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_ptr[kMaxDevices] = {};  // device address of `scratch` on each device
+
+int32_t static_scratch(unsigned char** ptr_out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TKV_E_HIP;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return TKV_E_HIP;
+    g_static_ptr[dev] = (unsigned char*)ptr;
+  }
+  *ptr_out = g_static_ptr[dev];
+  return TKV_OK;
+}
+
+// Clears the arrival counters (a fill kernel, not a memset node: the call may be recorded
+// into a graph by its caller).
+__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t* dst, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = 0u;
+}
+
+}  // namespace
+
+extern "C" int32_t tkv_quant_attn_decode_static(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q,
+                                                void* out, float sm_scale, void* stream) {
+  int32_t st = check_decode_args(d, c, q, out);
+  if (st != TKV_OK) return st;
+  const int bh = d->batch * d->n_kv_heads;
+  if ((size_t)bh > kStaticCounterWords) return TKV_E_WORKSPACE;
+  unsigned char* base = nullptr;
+  st = static_scratch(&base);
+  if (st != TKV_OK) return st;
+  uint32_t* arrivals = (uint32_t*)base;
+  float* parts = (float*)(base + kStaticCounterWords * sizeof(uint32_t));
+  hipStream_t s = (hipStream_t)stream;
+  // the array keeps whatever the previous call left: the counters must start at zero
+  TKV_LAUNCH(clear_words_kernel, dim3((bh + 255) / 256), 256, 0, s, arrivals, bh);
+  return quant_attn_decode_impl(d, c, q, out, sm_scale, parts, kStaticPartsBytes / sizeof(float), arrivals, s);
 }

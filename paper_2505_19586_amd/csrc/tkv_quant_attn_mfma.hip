@@ -868,8 +868,8 @@ void* g_mfma_prof = nullptr;
 // compute unit), at least one 32-token block per wave, and no more blocks per chunk than
 // the zero-point table of a workgroup holds.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
-                               float scale2, float* parts, uint32_t* arrivals, int target_blocks, int max_groups,
-                               int max_tail, const TkvSeqLens& lens, hipStream_t s) {
+                               float scale2, float* parts, size_t parts_floats, uint32_t* arrivals, int target_blocks,
+                               int max_groups, int max_tail, const TkvSeqLens& lens, hipStream_t s) {
   if (d->head_dim != TKV_D) return TKV_E_UNSUPPORTED;
   if (d->n_q_heads / d->n_kv_heads > 4) return TKV_E_UNSUPPORTED;
   // built: the benchmark's settings (2 and 4 bit, groups of 32) and the paper's (1 and 2 bit, groups of 64)
@@ -887,6 +887,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   if (n_chunks < 1) n_chunks = 1;
   if ((work + n_chunks - 1) / n_chunks > kMaxGpc) n_chunks = (work + kMaxGpc - 1) / kMaxGpc;
   if (n_chunks > TKV_MAX_CHUNKS) return TKV_E_UNSUPPORTED;
+  if ((size_t)d->batch * d->n_q_heads * n_chunks * TKV_PART_STRIDE > parts_floats) return TKV_E_WORKSPACE;
   MfmaParams p;
   p.k_codes = (const uint32_t*)c->k_codes;
   p.v_codes = (const uint32_t*)c->v_codes;

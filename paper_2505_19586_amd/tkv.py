@@ -76,6 +76,7 @@ def lib() -> C.CDLL:
         L.tkv_sparse_append_ragged.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32,
                                                C.POINTER(i32), vp]
         L.tkv_quant_attn_decode.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, C.c_float, vp, sz, vp]
+        L.tkv_quant_attn_decode_static.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, C.c_float, vp]
         L.tkv_sparse_cache_sizes.argtypes = [C.POINTER(SparseDesc), C.POINTER(sz), C.POINTER(sz)]
         L.tkv_sparse_append.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32, vp]
         L.tkv_sparse_estimate_topk.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, vp, vp, sz, vp]
@@ -106,6 +107,7 @@ def lib() -> C.CDLL:
         L.tkv_debug_read_sweep.argtypes = [vp, C.c_size_t, vp, i32, vp]
         L.tkv_debug_read_sweep.restype = i32
         for name in ("tkv_quant_cache_sizes", "tkv_quantize_append", "tkv_quant_attn_decode",
+                     "tkv_quant_attn_decode_static",
                      "tkv_quantize_append_ragged", "tkv_sparse_append_ragged",
                      "tkv_sparse_cache_sizes", "tkv_sparse_append", "tkv_sparse_estimate_topk",
                      "tkv_sparse_gather_attn", "tkv_sparse_gather", "tkv_sparse_attn",
@@ -203,6 +205,16 @@ class QuantLayer:
         _check(lib().tkv_quant_attn_decode(C.byref(d), C.byref(self.cache), q.data_ptr(), out.data_ptr(),
                                            float(sm_scale), self.workspace.data_ptr(), self.workspace_bytes,
                                            _stream(stream)), "tkv_quant_attn_decode")
+        return out
+
+    def attn_decode_static(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor, stream=None):
+        """tkv_quant_attn_decode_static: no workspace, nothing allocated (the caller passes `out`)."""
+        d = self.desc
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        assert out.dtype == torch.float16 and out.is_cuda and out.is_contiguous() and out.shape == q.shape
+        assert tuple(q.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        _check(lib().tkv_quant_attn_decode_static(C.byref(d), C.byref(self.cache), q.data_ptr(), out.data_ptr(),
+                                                  float(sm_scale), _stream(stream)), "tkv_quant_attn_decode_static")
         return out
 
     # typed views of the raw buffers (for tests)
