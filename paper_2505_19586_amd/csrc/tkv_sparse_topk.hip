@@ -2,21 +2,32 @@
 // scores of every cached token from the critical query channels and the critical key
 // cache, then exact Top-K (ties to the lower token index, output ascending).
 //
-// Two launches over the same grid; a workgroup owns a contiguous share of a head's tokens
-// (the entry point sizes the shares so that the workgroups fill the machine a whole number
-// of times) and works through it in passes of 4096 tokens.  The histogram and counters in
-// the workspace must be zero before the first call; every call leaves them zero.
-//   score    reads the critical key cache once (token-major summary, or channel-major rows),
-//            computes S(t) in the pinned float32 order, writes an order-preserving 32-bit
-//            key per token and adds its 13-bit-prefix histogram to the head's.  Optional
-//            riders: Eq. 10's channel selection at the start of every workgroup (resident
-//            channel-major keys), and the decode step's cache update (Eq. 2) by one more
-//            workgroup per head;
-//   select   every workgroup locates the bin of the k-th key in the head's histogram and
-//            lists its own tokens in or above that bin, in token order; the
-//            last workgroup of a head concatenates the lists (a few thousand entries, in
-//            LDS), finds the exact threshold by radix select on the remaining 19 key bits
-//            and writes the selected tokens in token order.
+// One launch.  A workgroup owns a contiguous share of a head's tokens (the entry point sizes
+// the shares so that the workgroups fill the machine a whole number of times) and scores it
+// in passes of 4096 tokens: the critical key cache is read once (token-major summary, or
+// channel-major rows), S(t) is computed in the pinned float32 order and kept in registers as
+// an order-preserving 32-bit key, together with an LDS histogram of the keys' 13-bit prefix.
+// No key is ever written to memory.  Then
+//   * the workgroup adds the part of its histogram that can matter to the head's histogram
+//     (bins at or above the bin of its own k-th key: the head's k-th key cannot be lower);
+//   * it lists, in token order, its tokens at or above a bin L of its own choice: the bin of
+//     its r-th largest key, r = 1.5 x its fair share of k plus 16.  If the head's Top-K were
+//     spread evenly, every workgroup would hold its fair share of it, so L almost always
+//     lies at or below the bin B of the head's k-th key and the list holds every token of
+//     this workgroup that can be selected;
+//   * the last workgroup of the head to arrive (arrival counter) reads the head's histogram,
+//     finds B exactly, and checks every workgroup's L <= B.  A workgroup whose list stops
+//     short of B (its tokens hold far more than their share of the Top-K) is re-scored by the
+//     last workgroup and its list rebuilt down to B: the result never depends on the guess,
+//     only the time does.  It then concatenates the lists (a few thousand entries, in LDS),
+//     finds the exact threshold by radix select on the remaining 19 key bits and writes the
+//     selected tokens in token order.
+// Optional riders of the launch: Eq. 10's channel selection at the start of every workgroup
+// (resident channel-major keys), and the decode step's cache update (Eq. 2) by one more
+// workgroup per head.  The histogram and counters in the workspace must be zero before the
+// first call; every call leaves them zero.
+// prescored + select: the same selection in two launches for scores that already exist (rows
+// of attention logits for the dense preference score): keys go through the workspace there.
 // Inside a launch, data crosses workgroups only through device-scope stores, loads and
 // atomics, ordered by waiting for them to complete before an arrival counter is bumped.
 #include "tkv_common.h"
@@ -37,6 +48,12 @@ constexpr uint32_t kLowMask = (1u << kLowBits) - 1u;
 constexpr int kListCap = 8192;  // candidate entries kept in LDS; further ones go to the workspace
 constexpr int kScoreLds = kBins * 4;
 constexpr int kSelectLds = 1024 * 4 + kListCap * 8;
+constexpr int kSub = kMaxPass * kPer;  // sub-tiles of kThreads tokens per workgroup
+// fused kernel: local / head histogram, list offsets, list (the channel-major variant also
+// stages its keys there to put them into token order)
+constexpr int kFusedLds = kBins * 4 + 1024 * 4 + kListCap * 8;
+constexpr int kCountBits = 14;  // a workgroup's list length (<= kMaxPass * kTok) in its control word, L above it
+static_assert(kMaxPass * kTok < (1 << kCountBits), "list length field");
 
 enum Ctrl { kDone2 = 1, kCtrlWords = 8 };
 
@@ -143,6 +160,54 @@ __device__ inline void find_bin(const uint32_t* hist, uint32_t k, uint32_t* part
   above = scratch[kWavesPerBlock + 1];
 }
 
+// find_bin for two ranks at once (k1, k2 >= 1, both at most the number of keys in the
+// histogram): same two barriers.
+__device__ inline void find_bin2(const uint32_t* hist, uint32_t k1, uint32_t k2, uint32_t* part, uint32_t* scratch,
+                                 uint32_t& bin1, uint32_t& bin2) {
+  const int tid = threadIdx.x;
+  constexpr int per = kBins / kThreads;
+  constexpr int per_lane = kThreads / 64;
+  uint32_t local = 0;
+#pragma unroll
+  for (int i = 0; i < per; ++i) local += hist[tid * per + i];
+  part[tid] = local;
+  __syncthreads();
+  if (tid < 64) {
+    uint32_t mine = 0;
+    for (int i = 0; i < per_lane; ++i) mine += part[tid * per_lane + i];
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_down(incl, d, 64);
+      if (tid + d < 64) incl += o;
+    }
+    const uint32_t excl = incl - mine;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      const uint32_t k = which ? k2 : k1;
+      if (excl < k && k <= incl) {  // exactly one lane per rank
+        uint32_t run = excl;
+        int t = tid * per_lane + per_lane - 1;
+        for (; t > tid * per_lane; --t) {
+          const uint32_t c = part[t];
+          if (run + c >= k) break;
+          run += c;
+        }
+        int bsel = t * per + per - 1;
+        for (; bsel > t * per; --bsel) {
+          const uint32_t c = hist[bsel];
+          if (run + c >= k) break;
+          run += c;
+        }
+        scratch[kWavesPerBlock + 4 + which] = (uint32_t)bsel;
+      }
+    }
+  }
+  __syncthreads();
+  bin1 = scratch[kWavesPerBlock + 4];
+  bin2 = scratch[kWavesPerBlock + 5];
+}
+
 // find_bin for at most 1024 bins by the first wave alone (lane l owns the bins [l * per,
 // (l + 1) * per), per = nbins / 64): one barrier instead of four.  The histogram must be
 // complete (barrier before the call); the result is valid in every thread after the call.
@@ -205,13 +270,20 @@ __device__ inline void append_tokens(const TopkParams& p, int b, int h, int tid)
 // CM: the critical key cache is channel-major (one row of `capacity` tokens per channel):
 // a thread then scores four consecutive tokens, one 8-byte load per channel row.
 template <int DS, bool CM>
-__global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
+__global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                            // kBins words
+  uint32_t* offs = reinterpret_cast<uint32_t*>(smem + kBins * 4);                // 1024 words
+  uint2* list_s = reinterpret_cast<uint2*>(smem + kBins * 4 + 1024 * 4);         // kListCap entries
+  uint32_t* stage = reinterpret_cast<uint32_t*>(list_s);                         // CM: kMaxPass * kTok keys
   __shared__ float qc[4][DS];
-  __shared__ uint32_t scratch[kWavesPerBlock + 4];
+  __shared__ uint32_t scratch[kWavesPerBlock + 8];
   __shared__ uint32_t part[kThreads];  // per-thread bin sums of find_bin
+  __shared__ uint32_t s_cnt[kSub][kWavesPerBlock];
+  __shared__ uint32_t s_nrep;
+  __shared__ uint16_t s_rep[kThreads];
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid % 64, wave = tid / 64;
   const int n = p.lens.n[b];
   const size_t bh = (size_t)b * p.hkv + h;
   if (p.app_k != nullptr && blockIdx.x == gridDim.x - 1) {
@@ -220,13 +292,19 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
     append_tokens<DS>(p, b, h, tid);
     return;
   }
-  const int t0 = blockIdx.x * p.tpw;
-  if (t0 >= n) return;
-  const int t_end = min(n, t0 + p.tpw);  // this workgroup's tokens: [t0, t_end), kTok per pass
-  TKV_PH(0);
+  int32_t* out = p.topk_idx + bh * p.top_k;
   int lo, hi;
   candidate_range(p, n, lo, hi);
   const uint32_t k = (uint32_t)min(p.top_k, hi - lo);
+  if (k == 0 && blockIdx.x == 0) {  // nothing to select: the first workgroup reports the empty result
+    for (int i = tid; i < p.top_k; i += kThreads) out[i] = -1;
+    if (tid == 0) p.topk_count[bh] = 0;
+  }
+  const int t0 = blockIdx.x * p.tpw;
+  if (t0 >= n) return;
+  const int t_end = min(n, t0 + p.tpw);  // this workgroup's tokens: [t0, t_end), kTok per pass
+  const int nblk = (n + p.tpw - 1) / p.tpw;
+  TKV_PH(0);
   const int G = p.hq / p.hkv;
   for (int i = tid; i < kBins; i += kThreads) hist[i] = 0u;
   // Stage 1 fused in (resident channel-major keys only): every workgroup derives the head's
@@ -253,15 +331,15 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
     const int c = p.channel_idx[bh * DS + i];
     qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
   }
-  // all of this thread's rows of a pass are requested before the first is used (threads past
-  // the workgroup's last token re-read that token: no traffic beyond the workgroup's share)
+  // all of a thread's rows of a pass are requested before the first is used (threads past
+  // the share's last token re-read that token: no traffic beyond the share)
   static_assert(DS % 4 == 0, "summary rows are read in 8-byte pieces");
   uint2 rows[kPer][DS / 4];  // (pairs of pieces merge into 16-byte loads where the row allows it)
   uint2 cols[DS];  // CM: four consecutive tokens of every channel row
-  auto load_pass = [&](int tb) {
+  auto load_pass = [&](int tb, int te) {
     if (CM) {
       static_assert(kPer == 4, "four tokens per 8-byte load");
-      const int tq = min(tb + kPer * tid, (t_end - 1) & ~3);  // past the end: the workgroup's last group of four
+      const int tq = min(tb + kPer * tid, (te - 1) & ~3);  // past the end: the share's last group of four
 #pragma unroll
       for (int i = 0; i < DS; ++i) {
         const int row = dyn ? s_chan[i] : p.rows_per_head == DS ? i : p.channel_idx[bh * DS + i];
@@ -271,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
       const __half* srow = p.summary + (bh * p.capacity) * DS;
 #pragma unroll
       for (int it = 0; it < kPer; ++it) {
-        const int t = min(tb + it * kThreads + tid, t_end - 1);  // past the end: the workgroup's last row again
+        const int t = min(tb + it * kThreads + tid, te - 1);  // past the end: the share's last row again
         if (DS % 8 == 0) {
 #pragma unroll
           for (int x = 0; x < DS / 8; ++x) {
@@ -286,7 +364,8 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
       }
     }
   };
-  load_pass(t0);
+  if (k == 0) return;  // (after Stage 1: the channel list is reported even when no token is a candidate)
+  load_pass(t0, t_end);
   __syncthreads();
   // query channels into registers (heads >= G are zero: adding their +0 sums changes nothing)
   float qr[4][DS];
@@ -295,70 +374,279 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
 #pragma unroll
     for (int i = 0; i < DS; ++i) qr[j][i] = qc[j][i];
 
-  uint32_t* keys = p.ws.keys + bh * p.capacity;
-  for (int tb = t0; tb < t_end; tb += kTok) {
-  if (tb != t0) load_pass(tb);
+  // Keys of the loaded pass `ps` of the share [ts, te): kb[kPer * ps + j] is the key of token
+  // ts + ps * kTok + j * kThreads + tid (0 for a non-candidate or past the share).  Token-major
+  // keys are produced in that order; channel-major ones (token ts + ps * kTok + 4 tid + it) go
+  // through `stage` and are put in order by collect_keys.
+  uint32_t kb[kSub];
+  auto score_pass = [&](int ts, int te, int ps, bool count) {
+    const int tb = ts + ps * kTok;
 #pragma unroll
-  for (int it = 0; it < kPer; ++it) {
-    const int t = CM ? tb + kPer * tid + it : tb + it * kThreads + tid;
-    float kx[DS];
-    if (CM) {
+    for (int it = 0; it < kPer; ++it) {
+      const int t = CM ? tb + kPer * tid + it : tb + it * kThreads + tid;
+      float kx[DS];
+      if (CM) {
 #pragma unroll
-      for (int i = 0; i < DS; ++i) {
-        const uint32_t wy = it < 2 ? cols[i].x : cols[i].y;
-        const half2_t hh = __builtin_bit_cast(half2_t, wy);
-        kx[i] = (float)hh[it % 2];
-      }
-    } else {
-#pragma unroll
-      for (int x = 0; x < DS / 4; ++x) {
-        const uint32_t w[2] = {rows[it][x].x, rows[it][x].y};
-#pragma unroll
-        for (int y = 0; y < 2; ++y) {
-          const uint32_t wy = w[y];
+        for (int i = 0; i < DS; ++i) {
+          const uint32_t wy = it < 2 ? cols[i].x : cols[i].y;
           const half2_t hh = __builtin_bit_cast(half2_t, wy);
-          kx[4 * x + 2 * y] = (float)hh[0];
-          kx[4 * x + 2 * y + 1] = (float)hh[1];
+          kx[i] = (float)hh[it % 2];
+        }
+      } else {
+#pragma unroll
+        for (int x = 0; x < DS / 4; ++x) {
+          const uint32_t w[2] = {rows[it][x].x, rows[it][x].y};
+#pragma unroll
+          for (int y = 0; y < 2; ++y) {
+            const uint32_t wy = w[y];
+            const half2_t hh = __builtin_bit_cast(half2_t, wy);
+            kx[4 * x + 2 * y] = (float)hh[0];
+            kx[4 * x + 2 * y + 1] = (float)hh[1];
+          }
         }
       }
-    }
-    float total = 0.f;
+      float total = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k
-      float a = qr[j][0] * kx[0];
+      for (int j = 0; j < 4; ++j) {
+        // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k
+        float a = qr[j][0] * kx[0];
 #pragma unroll
-      for (int i = 1; i < DS; ++i) a = __builtin_fmaf(qr[j][i], kx[i], a);
-      total = j == 0 ? a : total + a;
-    }
-    total = total + 0.0f;
-    if (t < t_end) {
-      uint32_t key = 0u;  // non-candidates: below every score
-      if (t >= lo && t < hi) {
-        key = score_key(total);
-        atomicAdd(&hist[key >> kLowBits], 1u);
+        for (int i = 1; i < DS; ++i) a = __builtin_fmaf(qr[j][i], kx[i], a);
+        total = j == 0 ? a : total + a;
       }
-      keys[t] = key;  // read by the next launch
+      total = total + 0.0f;
+      uint32_t key = 0u;  // non-candidates: below every score
+      if (t < te && t >= lo && t < hi) {
+        key = score_key(total);
+        if (count) atomicAdd(&hist[key >> kLowBits], 1u);
+      }
+      if (CM)
+        stage[ps * kTok + kPer * tid + it] = key;
+      else
+        kb[kPer * ps + it] = key;
     }
-  }
-  }
+  };
+  // scores the whole share [ts, te) (the first pass already loaded if `loaded`)
+  auto score_share = [&](int ts, int te, bool loaded, bool count) {
+#pragma unroll
+    for (int ps = 0; ps < kMaxPass; ++ps) {
+      const int tb = ts + ps * kTok;
+      if (tb < te) {
+        if (ps != 0 || !loaded) load_pass(tb, te);
+        score_pass(ts, te, ps, count);
+      } else if (!CM) {
+#pragma unroll
+        for (int it = 0; it < kPer; ++it) kb[kPer * ps + it] = 0u;
+      }
+    }
+    if (CM) {
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < kSub; ++j) kb[j] = ts + j * kThreads + tid < te ? stage[j * kThreads + tid] : 0u;
+    }
+  };
+  // Lists the keys kb of the share starting at token ts that lie in or above `bin`, in token
+  // order, from entry ts of the head's list area; returns the list length (in every thread).
+  uint2* list_g = p.ws.cand + bh * p.ws.cand_stride;  // the workgroup of share x owns entries [x * tpw, +tpw)
+  auto list_share = [&](int ts, uint32_t bin) -> uint32_t {
+    unsigned long long mask[kSub];
+    __syncthreads();  // s_cnt may still be read by the previous use
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) {
+      mask[j] = __builtin_amdgcn_ballot_w64(kb[j] != 0u && (kb[j] >> kLowBits) >= bin);
+      if (lane == 0) s_cnt[j][wave] = (uint32_t)__builtin_popcountll(mask[j]);
+    }
+    __syncthreads();
+    uint32_t run = 0;  // entries of earlier sub-tiles
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) {
+      uint32_t before = 0, all = 0;
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        const uint32_t c = s_cnt[j][w];
+        before += w < wave ? c : 0u;
+        all += c;
+      }
+      if ((mask[j] >> lane) & 1ull) {
+        uint2* e = &list_g[(size_t)ts + run + before + rank_in(mask[j])];
+        st_agent(&e->x, kb[j]);
+        st_agent(&e->y, (uint32_t)(ts + j * kThreads + tid));
+      }
+      run += all;
+    }
+    return run;
+  };
+
+  score_share(t0, t_end, true, true);
   __syncthreads();
   TKV_PH(1);
-  // Only bins that can hold the head's k-th key go to the global histogram: the k-th key of
-  // the whole head is never below the k-th key of this block alone, so bins under the
-  // block's own k-th bin are irrelevant (and skipping them spares most global atomics).
-  uint32_t first_bin = 0;
+  // ---- this workgroup's two bins: `first_bin`, the bin of its own k-th key (lower bins cannot
+  // hold the head's k-th key and stay out of the head's histogram, which spares most global
+  // atomics), and `my_bin`, the bin of its r-th key, down to which it lists its tokens
+  uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
+  uint32_t* gh = p.ws.hist + bh * kBins;
+  uint32_t* cnt_g = p.ws.blk + bh * p.ws.nblk_cap;
+  uint32_t first_bin = 0, my_bin = 0;
   {
-    const int c_lo = max(lo, t0), c_hi = min(hi, t_end);
-    if (c_hi - c_lo >= (int)k && k > 0) {
-      uint32_t above_unused;
-      find_bin(hist, k, part, scratch, first_bin, above_unused);
+    const uint32_t mine = (uint32_t)max(0, min(hi, t_end) - max(lo, t0));  // candidates in this share
+    // fair share of k, times 1.5, plus 16
+    const uint32_t r = (uint32_t)(((unsigned long long)k * mine * 3ull) / (2ull * (unsigned long long)(hi - lo))) + 16u;
+    const uint32_t k1 = mine >= k ? k : 0u, k2 = r < mine ? r : 0u;
+    if (k1 != 0u && k2 != 0u) {
+      find_bin2(hist, k1, k2, part, scratch, first_bin, my_bin);
+    } else if (k1 != 0u || k2 != 0u) {
+      uint32_t above_unused, bsel;
+      find_bin(hist, k1 != 0u ? k1 : k2, part, scratch, bsel, above_unused);
+      if (k1 != 0u) first_bin = bsel; else my_bin = bsel;
     }
   }
-  uint32_t* gh = p.ws.hist + bh * kBins;
+  const uint32_t my_len = list_share(t0, my_bin);
+  if (tid == 0) st_agent(&cnt_g[blockIdx.x], (my_bin << kCountBits) | my_len);
   for (int i = tid; i < kBins; i += kThreads)
     if (i >= (int)first_bin && hist[i]) atomicAdd(&gh[i], hist[i]);
   TKV_PH(2);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0) scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone2], 1u) == (uint32_t)nblk - 1u;
+  __syncthreads();
+  TKV_PH(3);
+  if (!scratch[kWavesPerBlock + 2]) return;
+
+  // ---- the head's last workgroup.  Head histogram and the workgroups' control words in one
+  // round of device-scope loads; histogram and counter are left zero for the next call.
+  if (tid == 0) st_agent(&ctrl[kDone2], 0u);
+  for (int i = (int)k + tid; i < p.top_k; i += kThreads) out[i] = -1;
+  if (tid == 0) p.topk_count[bh] = (int32_t)k;
+  uint32_t bin, above;
+  {
+    uint32_t hv[kBins / kThreads];
+#pragma unroll
+    for (int x = 0; x < kBins / kThreads; ++x) hv[x] = ld_agent(&gh[x * kThreads + tid]);
+    const uint32_t cw = tid < nblk ? ld_agent(&cnt_g[tid]) : 0u;  // the entry point launches < 1024 workgroups per head
+#pragma unroll
+    for (int x = 0; x < kBins / kThreads; ++x) {
+      hist[x * kThreads + tid] = hv[x];
+      if (hv[x] != 0u) st_agent(&gh[x * kThreads + tid], 0u);
+    }
+    if (tid == 0) s_nrep = 0u;
+    __syncthreads();
+    find_bin(hist, k, part, scratch, bin, above);
+    TKV_PH(4);
+    // shares whose list stops above the head's bin: rebuilt here, down to that bin
+    offs[tid] = cw & ((1u << kCountBits) - 1u);  // list lengths for now
+    if (tid < nblk && (cw >> kCountBits) > bin) s_rep[atomicAdd(&s_nrep, 1u)] = (uint16_t)tid;
+    __syncthreads();
+    const uint32_t nrep = s_nrep;
+    for (uint32_t r = 0; r < nrep; ++r) {
+      const int x = s_rep[r];
+      const int ts = x * p.tpw, te = min(n, ts + p.tpw);
+      score_share(ts, te, false, false);
+      const uint32_t len = list_share(ts, bin);
+      if (tid == 0) offs[x] = len;
+    }
+    if (nrep != 0u) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the rebuilt lists are read back below
+    __syncthreads();
+  }
+
+  // ---- concatenate the lists (wave w copies those of workgroups w, w + 16, ...).  Entry i of
+  // the concatenation lives in LDS if i < kListCap, else it is read from its workgroup's list
+  // in the workspace.
+  __shared__ uint32_t h2[1024], h3[512];  // radix-select histograms (below)
+  for (int i = tid; i < 1024; i += kThreads) h2[i] = 0u;
+  for (int i = tid; i < 512; i += kThreads) h3[i] = 0u;
+  if (tid < 64) {  // exclusive scan of the list lengths by one wave (in place)
+    uint32_t carry = 0;
+    for (int x0 = 0; x0 < nblk; x0 += 64) {
+      const int x = x0 + tid;
+      const uint32_t c = x < nblk ? offs[x] : 0u;
+      uint32_t incl = c;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (tid >= d) incl += o;
+      }
+      if (x < nblk) offs[x] = carry + incl - c;
+      carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    }
+    if (tid == 0) offs[nblk] = carry;
+  }
+  __syncthreads();
+  const uint32_t M = offs[nblk];
+  for (int x = wave; x < nblk; x += kWavesPerBlock) {
+    const uint32_t o = offs[x], c = offs[x + 1] - o;
+    for (uint32_t i = lane; i < c; i += 64) {
+      if (o + i < (uint32_t)kListCap) {
+        const uint2* e = &list_g[(size_t)x * p.tpw + i];
+        list_s[o + i] = make_uint2(ld_agent(&e->x), ld_agent(&e->y));
+      }
+    }
+  }
+  auto get = [&](uint32_t i) -> uint2 {
+    if (i < (uint32_t)kListCap) return list_s[i];
+    int x0 = 0, x1 = nblk;  // workgroup whose list holds entry i: offs[x0] <= i < offs[x0 + 1]
+    while (x1 - x0 > 1) {
+      const int mid = (x0 + x1) / 2;
+      if (offs[mid] <= i) x0 = mid; else x1 = mid;
+    }
+    const uint2* e = &list_g[(size_t)x0 * p.tpw + (i - offs[x0])];
+    return make_uint2(ld_agent(&e->x), ld_agent(&e->y));
+  };
+  __syncthreads();
+  TKV_PH(5);
+  uint32_t k_rem = k - above;  // 1 <= k_rem <= keys in the bin
+
+  // ---- exact threshold inside the bin: radix select on the low 19 key bits (10 + 9), each
+  // search done by one wave
+  for (uint32_t i = tid; i < M; i += kThreads) {
+    const uint32_t key = get(i).x;
+    if ((key >> kLowBits) == bin) atomicAdd(&h2[(key & kLowMask) >> 9], 1u);
+  }
+  __syncthreads();
+  uint32_t d1, a1;
+  find_bin_wave(h2, 1024, k_rem, scratch, d1, a1);
+  k_rem -= a1;
+  for (uint32_t i = tid; i < M; i += kThreads) {
+    const uint32_t key = get(i).x;
+    if ((key >> kLowBits) == bin && ((key & kLowMask) >> 9) == d1) atomicAdd(&h3[key & 0x1FFu], 1u);
+  }
+  __syncthreads();
+  uint32_t d2, a2;
+  find_bin_wave(h3, 512, k_rem, scratch, d2, a2);
+  const uint32_t take = k_rem - a2;                       // keys equal to T that are selected (lowest indices)
+  const uint32_t T = (bin << kLowBits) | (d1 << 9) | d2;  // threshold key
+  TKV_PH(6);
+
+  // ---- ordered compaction of the list: every key above T, and the first `take` equal to T
+  uint32_t gt_run = 0, eq_run = 0;
+  for (uint32_t base = 0; base < M; base += kThreads) {
+    const uint32_t i = base + tid;
+    uint2 e = make_uint2(0u, 0u);
+    if (i < M) e = get(i);
+    const bool gt = e.x > T, eq = e.x == T;  // T != 0: every real key has a non-zero prefix
+    const unsigned long long mg = __builtin_amdgcn_ballot_w64(gt), me = __builtin_amdgcn_ballot_w64(eq);
+    const int set = (int)((base / kThreads) & 1u) * 2;  // alternate the count rows: one barrier per tile
+    if (lane == 0) {
+      s_cnt[set][wave] = (uint32_t)__builtin_popcountll(mg);
+      s_cnt[set + 1][wave] = (uint32_t)__builtin_popcountll(me);
+    }
+    __syncthreads();
+    uint32_t pg = 0, pe = 0, tg = 0, te = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+      const uint32_t cg = s_cnt[set][w], ce = s_cnt[set + 1][w];
+      pg += w < wave ? cg : 0u;
+      pe += w < wave ? ce : 0u;
+      tg += cg;
+      te += ce;
+    }
+    const uint32_t my_gt = gt_run + pg + rank_in(mg), my_eq = eq_run + pe + rank_in(me);
+    if (gt) {
+      out[my_gt + min(my_eq, take)] = (int32_t)e.y;
+    } else if (eq && my_eq < take) {
+      out[my_gt + my_eq] = (int32_t)e.y;
+    }
+    gt_run += tg;
+    eq_run += te;
+  }
+  TKV_PH(7);
 }
 
 // The scoring launch for scores that already exist (float32 [rows][pre_stride], row = blockIdx.y):
@@ -367,7 +655,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(TopkParams p) {
 __global__ __launch_bounds__(kThreads) void prescored_kernel(TopkParams p, const float* pre, size_t pre_stride) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
-  __shared__ uint32_t scratch[kWavesPerBlock + 4];
+  __shared__ uint32_t scratch[kWavesPerBlock + 8];
   __shared__ uint32_t part[kThreads];  // per-thread bin sums of find_bin
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int n = p.lens.n[b];
@@ -408,8 +696,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                // 1024 words
   uint2* list_s = reinterpret_cast<uint2*>(smem + 1024 * 4);         // kListCap entries
-  __shared__ uint32_t scratch[kWavesPerBlock + 4];
-  constexpr int kSub = kMaxPass * kPer;  // sub-tiles of kThreads tokens per workgroup
+  __shared__ uint32_t scratch[kWavesPerBlock + 8];
   __shared__ uint32_t s_cnt[kSub][kWavesPerBlock];
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
   const int lane = tid % 64, wave = tid / 64;
@@ -612,7 +899,17 @@ extern "C" void tkv_debug_set_dump_topk(void* ptr) { g_topk_prof = ptr; }
 #endif
 
 namespace {
-// Both entry points: validation, parameters, the two launches.  keys: token-major key summary
+template <int DS, bool CM>
+int32_t launch_fused(const TopkParams& p, dim3 grid, hipStream_t s) {
+  // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
+  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_select_kernel<DS, CM>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds) == hipSuccess;
+  if (!lds_ok) return TKV_E_HIP;
+  TKV_LAUNCH((score_select_kernel<DS, CM>), grid, kThreads, kFusedLds, s, p);
+  return TKV_OK;
+}
+
+// All entry points: validation, parameters, the launch.  keys: token-major key summary
 // (rows_per_head == 0) or channel-major rows.
 int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q, const void* keys,
                              int32_t rows_per_head, const int32_t* channel_idx, int32_t* topk_idx,
@@ -699,31 +996,13 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
     p.app_stride = app->app_stride;
     p.app_add = app->app_add;
   }
-  const dim3 grid(nblk, d->n_kv_heads, d->batch);
-  const dim3 grid_score(nblk + (app != nullptr ? 1 : 0), d->n_kv_heads, d->batch);
-  // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
-  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
-  if (!lds_ok) return TKV_E_HIP;
+  const dim3 grid(nblk + (app != nullptr ? 1 : 0), d->n_kv_heads, d->batch);
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;  // 4 Mi tokens per sequence
-  if (d->n_channels == 16) {
-    if (cm)
-      TKV_LAUNCH((score_kernel<16, true>), grid_score, kThreads, kScoreLds, s, p);
-    else
-      TKV_LAUNCH((score_kernel<16, false>), grid_score, kThreads, kScoreLds, s, p);
-  } else if (d->n_channels == 12) {
-    if (cm)
-      TKV_LAUNCH((score_kernel<12, true>), grid_score, kThreads, kScoreLds, s, p);
-    else
-      TKV_LAUNCH((score_kernel<12, false>), grid_score, kThreads, kScoreLds, s, p);
-  } else {
-    if (cm)
-      TKV_LAUNCH((score_kernel<8, true>), grid_score, kThreads, kScoreLds, s, p);
-    else
-      TKV_LAUNCH((score_kernel<8, false>), grid_score, kThreads, kScoreLds, s, p);
-  }
-  TKV_LAUNCH(select_kernel, grid, kThreads, kSelectLds, s, p);
-  return TKV_OK;
+  if (d->n_channels == 16)
+    return cm ? launch_fused<16, true>(p, grid, s) : launch_fused<16, false>(p, grid, s);
+  if (d->n_channels == 12)
+    return cm ? launch_fused<12, true>(p, grid, s) : launch_fused<12, false>(p, grid, s);
+  return cm ? launch_fused<8, true>(p, grid, s) : launch_fused<8, false>(p, grid, s);
 }
 }  // namespace
 

@@ -236,3 +236,65 @@ def test_streams_with_compute_unit_masks(units):
         torch.cuda.synchronize()
         hip.hipStreamDestroy.argtypes = [C.c_void_p]
         hip.hipStreamDestroy(handle)
+
+
+def _only_topk(inp, k_mod, ch, top_k):
+    n = inp.k.shape[1]
+    layer = tkv.SparseLayer(top_k=top_k, capacity=n)
+    layer.set_channels(ch[None])
+    layer.append(to_new(k_mod), to_new(inp.v))
+    q = torch.from_numpy(inp.q)[None].cuda()
+    idx, cnt = layer.estimate_topk(q)
+    torch.cuda.synchronize()
+    want_idx, want_cnt = sparse.estimate_topk(inp.q, sparse.key_summary(k_mod, ch), ch, n, top_k=top_k,
+                                              n_sink=4, n_window=64)
+    assert np.array_equal(cnt[0].cpu().numpy(), want_cnt)
+    assert np.array_equal(idx[0].cpu().numpy(), want_idx)
+    # the same call again on the same workspace: histogram and counters were left clean
+    idx, cnt = layer.estimate_topk(q)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx[0].cpu().numpy(), want_idx)
+    return want_idx
+
+
+@pytest.mark.parametrize("n,top_k,spans", [
+    (20000, 1024, [(2100, 2900)]),                 # one workgroup's share holds most of the Top-K
+    (20000, 1024, [(0, 700), (19000, 20000)]),     # first and last share (sinks / window cut into them)
+    (131072, 1024, [(70000, 70600), (4096, 4500)]),
+    (131072, 4096, [(100000, 104000)]),
+    (9000, 512, [(1000, 1010), (5000, 5400)]),
+])
+def test_topk_concentrated_in_few_shares(n, top_k, spans):
+    """The scoring workgroups list their tokens down to a bin guessed from an even spread of the
+    Top-K over the context.  Here the Top-K is far from evenly spread: tokens of a few short spans
+    score several times higher than the rest, so the guess of the workgroups that own them stops
+    short and the head's last workgroup has to rebuild their lists.  The result is the oracle's
+    all the same."""
+    print(f"case topk concentrated n={n} k={top_k} spans={spans}", flush=True)
+    inp = make_layer(n, config=2, layer=4, seq=len(spans))
+    ch = static_channels(inp.k, 16)
+    k = inp.k.copy()
+    for a, b in spans:
+        # aligned with the summed query of each head's group on the critical channels: large positive scores
+        for h in range(8):
+            qsum = inp.q[4 * h:4 * h + 4].astype(np.float32).sum(axis=0)[ch[h]]
+            boost = 3.0 * np.sign(qsum) * np.abs(k[h, a:b][:, ch[h]].astype(np.float32))
+            k[h, a:b][:, ch[h]] = boost.astype(np.float16)
+    idx = _only_topk(inp, k, ch, top_k)
+    inside = sum(int(((idx[0] >= a) & (idx[0] < b)).sum()) for a, b in spans)
+    print(f"   {inside} of {top_k} selected tokens of head 0 lie in the spans", flush=True)
+    assert inside > top_k // 4
+
+
+def test_topk_heavy_ties_concentrated():
+    """Integer-valued scores (many exact ties at the threshold) with the large values packed into
+    one span: rebuilt lists and the tie rule (lower index first) together."""
+    rng = np.random.default_rng(12)
+    n, top_k = 30000, 1024
+    inp = make_layer(n, seq=44)
+    ch = static_channels(inp.k, 16)
+    k = inp.k.copy()
+    k[:] = rng.integers(-1, 2, size=k.shape).astype(np.float16)
+    k[:, 12000:13500] = rng.integers(1, 4, size=(8, 1500, 128)).astype(np.float16)
+    inp.q[:] = rng.integers(0, 3, size=inp.q.shape).astype(np.float16)
+    _only_topk(inp, k, ch, top_k)
