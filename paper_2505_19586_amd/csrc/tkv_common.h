@@ -114,16 +114,27 @@ inline int32_t device_view(const void* ptr, DevView mode, const void** dev) {
 // Partials cross workgroups through device-scope stores and loads (they bypass the caches
 // that are not coherent between workgroups).  Such loads are served slowly, one load
 // instruction after the other, so the merge uses as few and as wide ones as it can: all of
-// them are issued before the first is used.
+// them are issued before the first is used.  The partial maximum and sum of a chunk sit next
+// to each other (one 8-byte load), the weighted V sum starts on a 16-byte boundary.
 
 typedef float tkv_floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t tkv_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t tkv_u32x2 __attribute__((ext_vector_type(2)));
 
-// 16-byte device-scope load.  The compiler does not see it as a memory access: the value
-// may only be used after tkv_wait_x4 on it.
-__device__ inline void ld_agent_x4(tkv_floatx4& v, const float* ptr) {
-  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(ptr) : "memory");
-}
-__device__ inline void tkv_wait_x4(tkv_floatx4& v) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)::"memory"); }
+// Device-scope loads of 4, 8 or 16 bytes through a buffer descriptor over [base, base + bytes)
+// (base must be uniform over the wave; byte offsets are 32 bit).  The "sc1" cache policy makes
+// them device-scope like an agent-scope atomic load, but up to 16 bytes wide, and the compiler
+// itself tracks when their results arrive.  An offset at or beyond `bytes` reads nothing and
+// returns 0, which spares the callers a branch around loads they do not need (kNone).
+struct AgentBuf {
+  static constexpr uint32_t kNone = 0xFFFFFFF0u;
+  __amdgpu_buffer_rsrc_t r;
+  __device__ AgentBuf(const void* base, uint32_t bytes)
+      : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000)) {}
+  __device__ tkv_u32x4 x4(uint32_t off) const { return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 16); }
+  __device__ tkv_u32x2 x2(uint32_t off) const { return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 16); }
+  __device__ uint32_t x1(uint32_t off) const { return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 16); }
+};
 
 // head0: partials of the G heads of this KV head, [G][n_chunks][TKV_PART_STRIDE]; out0: fp16
 // [G][128].  lds: 3 * G * n_chunks + 4 * 4 * 128 + 4 floats.  Called by every thread of the
@@ -135,11 +146,15 @@ __device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __h
   float* red = cw + G * n_chunks;        // [4 heads][4 classes][128]
   float* Ls = red + 4 * 4 * TKV_D;       // [4]
   const int lane = tid % 64, wave = tid / 64;
+  const AgentBuf pb(head0, (uint32_t)((size_t)G * n_chunks * TKV_PART_STRIDE * sizeof(float)));
   // first pass: maxima and sums of all chunks, and (for up to 64 chunks) this thread's channels
   for (int i = tid; i < G * n_chunks; i += nthr) {
-    const float* pk = head0 + (size_t)i * TKV_PART_STRIDE;
-    ml[2 * i] = __hip_atomic_load(pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    ml[2 * i + 1] = __hip_atomic_load(pk + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const tkv_u32x2 v = pb.x2((uint32_t)i * TKV_PART_STRIDE * 4u);
+    // (elements copied out before the cast: a bit cast applied directly to a vector element
+    // reads element 0 with this compiler)
+    const uint32_t v_max = v.x, v_sum = v.y;
+    ml[2 * i] = __uint_as_float(v_max);
+    ml[2 * i + 1] = __uint_as_float(v_sum);
   }
   // item = (head, chunk class ks, channel quad c4): chunks ks, ks + 4, ...
   constexpr int kPer = 16;
@@ -148,15 +163,14 @@ __device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __h
     const bool on = item < G * TKV_D;
     const int hh = on ? item / TKV_D : 0, r = item % TKV_D;
     const int ks = r / 32, c4 = r % 32;
-    const float* base = head0 + (size_t)hh * n_chunks * TKV_PART_STRIDE + TKV_PART_O + 4 * c4;
+    const uint32_t base = (uint32_t)((hh * n_chunks) * TKV_PART_STRIDE + TKV_PART_O + 4 * c4) * 4u;
     tkv_floatx4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int k0 = 0; k0 < n_chunks; k0 += 4 * kPer) {
-      tkv_floatx4 ov[kPer];
+      tkv_u32x4 ov[kPer];
 #pragma unroll
       for (int y = 0; y < kPer; ++y) {
         const int k = k0 + 4 * y + ks;
-        ov[y] = tkv_floatx4{0.f, 0.f, 0.f, 0.f};
-        if (on && k < n_chunks) ld_agent_x4(ov[y], base + (size_t)k * TKV_PART_STRIDE);
+        ov[y] = pb.x4(on && k < n_chunks ? base + (uint32_t)k * TKV_PART_STRIDE * 4u : AgentBuf::kNone);
       }
       if (item0 == 0 && k0 == 0) {
         // weights: one wave per head (the loads above are in flight meanwhile)
@@ -180,9 +194,8 @@ __device__ inline void merge_chunks(const float* head0, int G, int n_chunks, __h
 #pragma unroll
       for (int y = 0; y < kPer; ++y) {
         const int k = k0 + 4 * y + ks;
-        tkv_wait_x4(ov[y]);
         const float w = (on && k < n_chunks) ? cw[hh * n_chunks + k] : 0.f;
-        acc += ov[y] * w;
+        acc += __builtin_bit_cast(tkv_floatx4, ov[y]) * w;
       }
     }
     if (on) *reinterpret_cast<tkv_floatx4*>(red + (hh * 4 + ks) * TKV_D + 4 * c4) = acc;

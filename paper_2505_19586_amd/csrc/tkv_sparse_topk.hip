@@ -3,33 +3,37 @@
 // cache, then exact Top-K (ties to the lower token index, output ascending).
 //
 // One launch.  A workgroup owns a contiguous share of a head's tokens (the entry point sizes
-// the shares so that the workgroups fill the machine a whole number of times) and scores it
-// in passes of 4096 tokens: the critical key cache is read once (token-major summary, or
-// channel-major rows), S(t) is computed in the pinned float32 order and kept in registers as
-// an order-preserving 32-bit key, together with an LDS histogram of the keys' 13-bit prefix.
-// No key is ever written to memory.  Then
-//   * the workgroup adds the part of its histogram that can matter to the head's histogram
-//     (bins at or above the bin of its own k-th key: the head's k-th key cannot be lower);
-//   * it lists, in token order, its tokens at or above a bin L of its own choice: the bin of
-//     its r-th largest key, r = 1.5 x its fair share of k plus 16.  If the head's Top-K were
-//     spread evenly, every workgroup would hold its fair share of it, so L almost always
-//     lies at or below the bin B of the head's k-th key and the list holds every token of
-//     this workgroup that can be selected;
-//   * the last workgroup of the head to arrive (arrival counter) reads the head's histogram,
-//     finds B exactly, and checks every workgroup's L <= B.  A workgroup whose list stops
-//     short of B (its tokens hold far more than their share of the Top-K) is re-scored by the
-//     last workgroup and its list rebuilt down to B: the result never depends on the guess,
-//     only the time does.  It then concatenates the lists (a few thousand entries, in LDS),
-//     finds the exact threshold by radix select on the remaining 19 key bits and writes the
-//     selected tokens in token order.
+// the shares so that the workgroups fill the machine a whole number of times) and scores it:
+// the critical key cache is read once (token-major summary, or channel-major rows), S(t) is
+// computed in the pinned float32 order and kept in registers as an order-preserving 32-bit
+// key, together with an LDS histogram of the keys' 13-bit prefix ("bin").  No key and no
+// histogram is ever written to memory.  Then
+//   * the workgroup lists, in token order, its tokens at or above a bin L of its own choice:
+//     the bin of its r-th largest key, r = 1.5 x its fair share of k plus 16.  If the head's
+//     Top-K were spread evenly, every workgroup would hold its fair share of it, so L almost
+//     always lies at or below the bin of the head's k-th key and the list holds every token of
+//     this workgroup that can be selected.  List, list length and L go to the workspace;
+//   * the last workgroup of the head to arrive (arrival counter) fetches all lists in one
+//     round of device-scope loads (a few thousand entries, held in registers), finds the k-th
+//     largest listed key T by radix select and checks that no list's L lies above T's bin:
+//     every list is complete down to its L, so T is then the head's exact k-th key.  It writes
+//     the tokens above T, and the lowest-numbered ones equal to T, in token order;
+//   * otherwise (some workgroup's tokens hold far more than their share of the Top-K, or lists
+//     longer than the round fetches: heavy ties) the last workgroup takes the slow path: lists
+//     concatenated in LDS, T from them, the workgroups whose L lies above T's bin re-scored and
+//     listed again down to that bin, T again: more entries can only raise T, so every list is
+//     now complete down to a bin at or below T's.  The result never depends on the guess, only
+//     the time does.
 // Optional riders of the launch: Eq. 10's channel selection at the start of every workgroup
 // (resident channel-major keys), and the decode step's cache update (Eq. 2) by one more
-// workgroup per head.  The histogram and counters in the workspace must be zero before the
-// first call; every call leaves them zero.
+// workgroup per head.  The counters in the workspace must be zero before the first call; every
+// call leaves them zero.
 // prescored + select: the same selection in two launches for scores that already exist (rows
 // of attention logits for the dense preference score): keys go through the workspace there.
 // Inside a launch, data crosses workgroups only through device-scope stores, loads and
 // atomics, ordered by waiting for them to complete before an arrival counter is bumped.
+#include <type_traits>
+
 #include "tkv_common.h"
 
 namespace {
@@ -40,7 +44,8 @@ constexpr int kThreads = 1024;
 constexpr int kWavesPerBlock = kThreads / 64;
 constexpr int kPer = 4;                // tokens per thread in the scoring phase
 constexpr int kTok = kThreads * kPer;  // tokens per workgroup and pass
-constexpr int kMaxPass = 2;            // a workgroup owns up to kMaxPass * kTok tokens (see the entry point)
+constexpr int kSub = kPer + 1;         // sub-tiles of kThreads tokens per workgroup: a full pass and one more sub-tile
+constexpr int kMaxTpw = kSub * kThreads;  // most tokens a workgroup owns (see the entry point)
 constexpr int kPrefixBits = 13;
 constexpr int kBins = 1 << kPrefixBits;  // 8192
 constexpr int kLowBits = 32 - kPrefixBits;  // 19
@@ -48,12 +53,12 @@ constexpr uint32_t kLowMask = (1u << kLowBits) - 1u;
 constexpr int kListCap = 8192;  // candidate entries kept in LDS; further ones go to the workspace
 constexpr int kScoreLds = kBins * 4;
 constexpr int kSelectLds = 1024 * 4 + kListCap * 8;
-constexpr int kSub = kMaxPass * kPer;  // sub-tiles of kThreads tokens per workgroup
 // fused kernel: local / head histogram, list offsets, list (the channel-major variant also
 // stages its keys there to put them into token order)
 constexpr int kFusedLds = kBins * 4 + 1024 * 4 + kListCap * 8;
-constexpr int kCountBits = 14;  // a workgroup's list length (<= kMaxPass * kTok) in its control word, L above it
-static_assert(kMaxPass * kTok < (1 << kCountBits), "list length field");
+constexpr int kFastShift = 14;  // first radix digit of the common path: key bits [14, 32) minus a base
+constexpr int kCountBits = 14;  // a workgroup's list length (<= kMaxTpw) in its control word, L above it
+static_assert(kMaxTpw < (1 << kCountBits), "list length field");
 
 enum Ctrl { kDone2 = 1, kCtrlWords = 8 };
 
@@ -69,7 +74,7 @@ struct TopkParams {
   int32_t* topk_count;
   tkv::SparseWs ws;
   int32_t hq, hkv, top_k, n_sink, n_window, capacity;
-  int32_t tpw;  // tokens per workgroup: a multiple of 4, at most kMaxPass * kTok
+  int32_t tpw;  // tokens per workgroup: a multiple of 16, at most kMaxTpw
   TkvSeqLens lens;
   // Eq. 2 in the same launch (app_k non-null): the last workgroup of every (sequence, KV head)
   // appends the step's new tokens; lens already counts them
@@ -160,52 +165,107 @@ __device__ inline void find_bin(const uint32_t* hist, uint32_t k, uint32_t* part
   above = scratch[kWavesPerBlock + 1];
 }
 
-// find_bin for two ranks at once (k1, k2 >= 1, both at most the number of keys in the
-// histogram): same two barriers.
-__device__ inline void find_bin2(const uint32_t* hist, uint32_t k1, uint32_t k2, uint32_t* part, uint32_t* scratch,
-                                 uint32_t& bin1, uint32_t& bin2) {
+// Inclusive prefix sum over the lanes of a wave (lane l gets the sum of lanes 0..l), on the
+// data-parallel-primitive cross-lane paths (no LDS traffic).
+#define TKV_DPP_ADD(v, ctrl, rows) \
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(v), ctrl, rows, 0xF, true)
+__device__ inline uint32_t wave_prefix_incl(uint32_t v) {
+  TKV_DPP_ADD(v, 0x111, 0xF);  // row_shr:1
+  TKV_DPP_ADD(v, 0x112, 0xF);  // row_shr:2
+  TKV_DPP_ADD(v, 0x114, 0xF);  // row_shr:4
+  TKV_DPP_ADD(v, 0x118, 0xF);  // row_shr:8
+  TKV_DPP_ADD(v, 0x142, 0xA);  // row_bcast:15 into rows 1 and 3
+  TKV_DPP_ADD(v, 0x143, 0xC);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+#undef TKV_DPP_ADD
+__device__ inline uint32_t read_lane(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
+
+// find_bin on counts held in registers: thread t owns the PER bins PER * kThreads - 1 -
+// (PER * t + i), i = 0 .. PER - 1 (descending keys), count c[i].  Up to NR ranks at once (rank
+// 0: skipped, result bin 0).  res: 2 * NR words of LDS that receive (bin, keys in higher bins)
+// per rank; wtot: kWavesPerBlock words of LDS.  Two barriers; results valid in every thread.
+template <int NR, int PER>
+__device__ inline void find_ranks(const uint32_t (&c)[PER], const uint32_t (&k)[NR], uint32_t* wtot, uint32_t* res,
+                                  int wave, int lane) {
   const int tid = threadIdx.x;
-  constexpr int per = kBins / kThreads;
-  constexpr int per_lane = kThreads / 64;
   uint32_t local = 0;
 #pragma unroll
-  for (int i = 0; i < per; ++i) local += hist[tid * per + i];
-  part[tid] = local;
+  for (int i = 0; i < PER; ++i) local += c[i];
+  const uint32_t incl = wave_prefix_incl(local);
+  if (lane == 63) wtot[wave] = incl;
+  if (tid < 2 * NR) res[tid] = 0u;
   __syncthreads();
-  if (tid < 64) {
-    uint32_t mine = 0;
-    for (int i = 0; i < per_lane; ++i) mine += part[tid * per_lane + i];
-    uint32_t incl = mine;
+  uint32_t base = 0;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_down(incl, d, 64);
-      if (tid + d < 64) incl += o;
-    }
-    const uint32_t excl = incl - mine;
+  for (int w = 0; w < kWavesPerBlock; ++w) base += w < wave ? wtot[w] : 0u;
+  const uint32_t excl = base + incl - local;  // keys in bins above this thread's
 #pragma unroll
-    for (int which = 0; which < 2; ++which) {
-      const uint32_t k = which ? k2 : k1;
-      if (excl < k && k <= incl) {  // exactly one lane per rank
-        uint32_t run = excl;
-        int t = tid * per_lane + per_lane - 1;
-        for (; t > tid * per_lane; --t) {
-          const uint32_t c = part[t];
-          if (run + c >= k) break;
-          run += c;
+  for (int r = 0; r < NR; ++r) {
+    if (k[r] != 0u && excl < k[r] && k[r] <= excl + local) {  // exactly one thread per rank
+      uint32_t run = excl;
+      int i = 0;
+#pragma unroll
+      for (int y = 0; y < PER - 1; ++y) {
+        if (i == y && run + c[y] < k[r]) {
+          run += c[y];
+          i = y + 1;
         }
-        int bsel = t * per + per - 1;
-        for (; bsel > t * per; --bsel) {
-          const uint32_t c = hist[bsel];
-          if (run + c >= k) break;
-          run += c;
-        }
-        scratch[kWavesPerBlock + 4 + which] = (uint32_t)bsel;
       }
+      res[2 * r] = (uint32_t)(PER * kThreads - 1 - (PER * tid + i));
+      res[2 * r + 1] = run;
     }
   }
   __syncthreads();
-  bin1 = scratch[kWavesPerBlock + 4];
-  bin2 = scratch[kWavesPerBlock + 5];
+}
+
+// Exclusive offsets, in (sub-tile, thread) order, of the set bits of kSub wave ballots per wave:
+// before[j] = set bits of sub-tiles < j plus those of sub-tile j in lower waves.  cnt: kSub x
+// kWavesPerBlock words of LDS that no thread still reads.  One barrier.  Returns the total.
+static_assert(kSub * kWavesPerBlock <= 128, "two count words per lane");
+__device__ inline uint32_t subtile_offsets(const unsigned long long (&mask)[kSub], uint32_t* cnt, int wave, int lane,
+                                           uint32_t (&before)[kSub]) {
+  constexpr int kFlat = kSub * kWavesPerBlock;
+  if (lane == 0) {
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) cnt[j * kWavesPerBlock + wave] = (uint32_t)__builtin_popcountll(mask[j]);
+  }
+  __syncthreads();
+  const uint32_t v0 = cnt[lane], v1 = 64 + lane < kFlat ? cnt[64 + lane] : 0u;
+  const uint32_t p0 = wave_prefix_incl(v0), p1 = wave_prefix_incl(v1);
+  const uint32_t t0 = read_lane(p0, 63);
+  const uint32_t e0 = p0 - v0, e1 = p1 - v1 + t0;
+#pragma unroll
+  for (int j = 0; j < kSub; ++j)
+    before[j] = j < 4 ? read_lane(e0, j * kWavesPerBlock + wave) : read_lane(e1, (j - 4) * kWavesPerBlock + wave);
+  return t0 + read_lane(p1, 63);
+}
+
+// subtile_offsets for two sets of ballots with one barrier.
+__device__ inline void subtile_offsets2(const unsigned long long (&ma)[kSub], const unsigned long long (&mb)[kSub],
+                                        uint32_t* cnt_a, uint32_t* cnt_b, int wave, int lane,
+                                        uint32_t (&before_a)[kSub], uint32_t (&before_b)[kSub]) {
+  constexpr int kFlat = kSub * kWavesPerBlock;
+  if (lane == 0) {
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) {
+      cnt_a[j * kWavesPerBlock + wave] = (uint32_t)__builtin_popcountll(ma[j]);
+      cnt_b[j * kWavesPerBlock + wave] = (uint32_t)__builtin_popcountll(mb[j]);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    const uint32_t* cnt = which ? cnt_b : cnt_a;
+    const uint32_t v0 = cnt[lane], v1 = 64 + lane < kFlat ? cnt[64 + lane] : 0u;
+    const uint32_t p0 = wave_prefix_incl(v0), p1 = wave_prefix_incl(v1);
+    const uint32_t e0 = p0 - v0, e1 = p1 - v1 + read_lane(p0, 63);
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) {
+      const uint32_t v = j < 4 ? read_lane(e0, j * kWavesPerBlock + wave) : read_lane(e1, (j - 4) * kWavesPerBlock + wave);
+      if (which) before_b[j] = v; else before_a[j] = v;
+    }
+  }
 }
 
 // find_bin for at most 1024 bins by the first wave alone (lane l owns the bins [l * per,
@@ -275,15 +335,15 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                            // kBins words
   uint32_t* offs = reinterpret_cast<uint32_t*>(smem + kBins * 4);                // 1024 words
   uint2* list_s = reinterpret_cast<uint2*>(smem + kBins * 4 + 1024 * 4);         // kListCap entries
-  uint32_t* stage = reinterpret_cast<uint32_t*>(list_s);                         // CM: kMaxPass * kTok keys
+  uint32_t* stage = reinterpret_cast<uint32_t*>(list_s);                         // CM: 2 * kTok keys
   __shared__ float qc[4][DS];
   __shared__ uint32_t scratch[kWavesPerBlock + 8];
-  __shared__ uint32_t part[kThreads];  // per-thread bin sums of find_bin
-  __shared__ uint32_t s_cnt[kSub][kWavesPerBlock];
+  __shared__ uint32_t s_cnt[kSub][kWavesPerBlock], s_cnt2[kSub][kWavesPerBlock];
+  __shared__ uint32_t s_wtot[kWavesPerBlock], s_res[2];
   __shared__ uint32_t s_nrep;
   __shared__ uint16_t s_rep[kThreads];
   const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int lane = tid % 64, wave = tid / 64;
+  const int lane = tid % 64, wave = __builtin_amdgcn_readfirstlane(tid / 64);
   const int n = p.lens.n[b];
   const size_t bh = (size_t)b * p.hkv + h;
   if (p.app_k != nullptr && blockIdx.x == gridDim.x - 1) {
@@ -336,7 +396,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   static_assert(DS % 4 == 0, "summary rows are read in 8-byte pieces");
   uint2 rows[kPer][DS / 4];  // (pairs of pieces merge into 16-byte loads where the row allows it)
   uint2 cols[DS];  // CM: four consecutive tokens of every channel row
-  auto load_pass = [&](int tb, int te) {
+  auto load_pass = [&](int tb, int te, auto n_rows) {
     if (CM) {
       static_assert(kPer == 4, "four tokens per 8-byte load");
       const int tq = min(tb + kPer * tid, (te - 1) & ~3);  // past the end: the share's last group of four
@@ -348,7 +408,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     } else {
       const __half* srow = p.summary + (bh * p.capacity) * DS;
 #pragma unroll
-      for (int it = 0; it < kPer; ++it) {
+      for (int it = 0; it < decltype(n_rows)::value; ++it) {
         const int t = min(tb + it * kThreads + tid, te - 1);  // past the end: the share's last row again
         if (DS % 8 == 0) {
 #pragma unroll
@@ -365,32 +425,38 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     }
   };
   if (k == 0) return;  // (after Stage 1: the channel list is reported even when no token is a candidate)
-  load_pass(t0, t_end);
+  load_pass(t0, t_end, std::integral_constant<int, kPer>{});
   __syncthreads();
   // query channels into registers (heads >= G are zero: adding their +0 sums changes nothing)
-  float qr[4][DS];
+  // kept as fp16 pairs: the multiply-adds below convert both operands on the fly (exactly)
+  uint32_t qr[4][DS / 2];
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int i = 0; i < DS; ++i) qr[j][i] = qc[j][i];
+    for (int i = 0; i < DS / 2; ++i)
+      qr[j][i] = __builtin_bit_cast(uint32_t, half2_t{(_Float16)qc[j][2 * i], (_Float16)qc[j][2 * i + 1]});
 
   // Keys of the loaded pass `ps` of the share [ts, te): kb[kPer * ps + j] is the key of token
   // ts + ps * kTok + j * kThreads + tid (0 for a non-candidate or past the share).  Token-major
   // keys are produced in that order; channel-major ones (token ts + ps * kTok + 4 tid + it) go
   // through `stage` and are put in order by collect_keys.
   uint32_t kb[kSub];
-  auto score_pass = [&](int ts, int te, int ps, bool count) {
+  // (q_from_lds: the re-scoring of another share in the slow path reads the query channels from
+  // LDS instead of keeping 64 registers alive through the common path)
+  auto score_pass = [&](int ts, int te, int ps, bool count, auto q_from_lds, auto n_rows) {
     const int tb = ts + ps * kTok;
+    int tid_again = tid;  // opaque copy: the token numbers are worked out again here rather than
+    asm volatile("" : "+v"(tid_again));  // kept in registers (or spilled) since the loads were issued
 #pragma unroll
-    for (int it = 0; it < kPer; ++it) {
-      const int t = CM ? tb + kPer * tid + it : tb + it * kThreads + tid;
-      float kx[DS];
+    for (int it = 0; it < (CM ? kPer : decltype(n_rows)::value); ++it) {
+      const int t = CM ? tb + kPer * tid_again + it : tb + it * kThreads + tid_again;
+      _Float16 kx[DS];
       if (CM) {
 #pragma unroll
         for (int i = 0; i < DS; ++i) {
           const uint32_t wy = it < 2 ? cols[i].x : cols[i].y;
           const half2_t hh = __builtin_bit_cast(half2_t, wy);
-          kx[i] = (float)hh[it % 2];
+          kx[i] = hh[it % 2];
         }
       } else {
 #pragma unroll
@@ -400,18 +466,35 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
           for (int y = 0; y < 2; ++y) {
             const uint32_t wy = w[y];
             const half2_t hh = __builtin_bit_cast(half2_t, wy);
-            kx[4 * x + 2 * y] = (float)hh[0];
-            kx[4 * x + 2 * y + 1] = (float)hh[1];
+            kx[4 * x + 2 * y] = hh[0];
+            kx[4 * x + 2 * y + 1] = hh[1];
           }
         }
       }
       float total = 0.f;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k
-        float a = qr[j][0] * kx[0];
+        // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k; the
+        // first term fma(q, k, +0) is the exact product (only the sign of a zero can differ,
+        // and the final + 0.0f removes that)
+        constexpr bool kLdsQ = decltype(q_from_lds)::value;
+        float a = 0.f;
 #pragma unroll
-        for (int i = 1; i < DS; ++i) a = __builtin_fmaf(qr[j][i], kx[i], a);
+        for (int i = 0; i < DS; i += 2) {
+          float q0, q1;
+          if (kLdsQ) {
+            q0 = qc[j][i], q1 = qc[j][i + 1];
+          } else {
+            // (opaque copy: keeps the pair packed in one register instead of two converted ones
+            // held across the whole pass)
+            uint32_t w = qr[j][i / 2];
+            asm volatile("" : "+v"(w));
+            const half2_t hq = __builtin_bit_cast(half2_t, w);
+            q0 = (float)hq[0], q1 = (float)hq[1];
+          }
+          a = __builtin_fmaf(q0, (float)kx[i], a);
+          a = __builtin_fmaf(q1, (float)kx[i + 1], a);
+        }
         total = j == 0 ? a : total + a;
       }
       total = total + 0.0f;
@@ -427,17 +510,17 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     }
   };
   // scores the whole share [ts, te) (the first pass already loaded if `loaded`)
-  auto score_share = [&](int ts, int te, bool loaded, bool count) {
-#pragma unroll
-    for (int ps = 0; ps < kMaxPass; ++ps) {
-      const int tb = ts + ps * kTok;
-      if (tb < te) {
-        if (ps != 0 || !loaded) load_pass(tb, te);
-        score_pass(ts, te, ps, count);
-      } else if (!CM) {
-#pragma unroll
-        for (int it = 0; it < kPer; ++it) kb[kPer * ps + it] = 0u;
-      }
+  // the first kTok tokens in one pass, the rest (at most one sub-tile) in a second, short one
+  auto score_share = [&](int ts, int te, bool loaded, bool count, auto q_from_lds) {
+    using Full = std::integral_constant<int, kPer>;
+    using One = std::integral_constant<int, 1>;
+    if (!loaded) load_pass(ts, te, Full{});
+    score_pass(ts, te, 0, count, q_from_lds, Full{});
+    if (ts + kTok < te) {
+      load_pass(ts + kTok, te, One{});
+      score_pass(ts, te, 1, count, q_from_lds, One{});
+    } else if (!CM) {
+      kb[kPer] = 0u;
     }
     if (CM) {
       __syncthreads();
@@ -450,59 +533,46 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   uint2* list_g = p.ws.cand + bh * p.ws.cand_stride;  // the workgroup of share x owns entries [x * tpw, +tpw)
   auto list_share = [&](int ts, uint32_t bin) -> uint32_t {
     unsigned long long mask[kSub];
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) mask[j] = __builtin_amdgcn_ballot_w64(kb[j] != 0u && (kb[j] >> kLowBits) >= bin);
+    uint32_t before[kSub];
     __syncthreads();  // s_cnt may still be read by the previous use
+    const uint32_t total = subtile_offsets(mask, &s_cnt[0][0], wave, lane, before);
 #pragma unroll
     for (int j = 0; j < kSub; ++j) {
-      mask[j] = __builtin_amdgcn_ballot_w64(kb[j] != 0u && (kb[j] >> kLowBits) >= bin);
-      if (lane == 0) s_cnt[j][wave] = (uint32_t)__builtin_popcountll(mask[j]);
-    }
-    __syncthreads();
-    uint32_t run = 0;  // entries of earlier sub-tiles
-#pragma unroll
-    for (int j = 0; j < kSub; ++j) {
-      uint32_t before = 0, all = 0;
-      for (int w = 0; w < kWavesPerBlock; ++w) {
-        const uint32_t c = s_cnt[j][w];
-        before += w < wave ? c : 0u;
-        all += c;
-      }
       if ((mask[j] >> lane) & 1ull) {
-        uint2* e = &list_g[(size_t)ts + run + before + rank_in(mask[j])];
+        uint2* e = &list_g[(size_t)ts + before[j] + rank_in(mask[j])];
         st_agent(&e->x, kb[j]);
         st_agent(&e->y, (uint32_t)(ts + j * kThreads + tid));
       }
-      run += all;
     }
-    return run;
+    return total;
   };
 
-  score_share(t0, t_end, true, true);
+  score_share(t0, t_end, true, true, std::false_type{});
   __syncthreads();
   TKV_PH(1);
-  // ---- this workgroup's two bins: `first_bin`, the bin of its own k-th key (lower bins cannot
-  // hold the head's k-th key and stay out of the head's histogram, which spares most global
-  // atomics), and `my_bin`, the bin of its r-th key, down to which it lists its tokens
+  // ---- `my_bin`: the bin of this workgroup's r-th key, down to which it lists its tokens
   uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
-  uint32_t* gh = p.ws.hist + bh * kBins;
   uint32_t* cnt_g = p.ws.blk + bh * p.ws.nblk_cap;
-  uint32_t first_bin = 0, my_bin = 0;
+  constexpr int kOwn = kBins / kThreads;  // bins per thread, descending: kBins - 1 - (kOwn * tid + i)
+  static_assert(kOwn == 8, "two 16-byte reads per thread");
   {
     const uint32_t mine = (uint32_t)max(0, min(hi, t_end) - max(lo, t0));  // candidates in this share
     // fair share of k, times 1.5, plus 16
     const uint32_t r = (uint32_t)(((unsigned long long)k * mine * 3ull) / (2ull * (unsigned long long)(hi - lo))) + 16u;
-    const uint32_t k1 = mine >= k ? k : 0u, k2 = r < mine ? r : 0u;
-    if (k1 != 0u && k2 != 0u) {
-      find_bin2(hist, k1, k2, part, scratch, first_bin, my_bin);
-    } else if (k1 != 0u || k2 != 0u) {
-      uint32_t above_unused, bsel;
-      find_bin(hist, k1 != 0u ? k1 : k2, part, scratch, bsel, above_unused);
-      if (k1 != 0u) first_bin = bsel; else my_bin = bsel;
+    const uint32_t ranks[1] = {r < mine ? r : 0u};  // (fewer candidates than that: all of them are listed)
+    uint32_t c[kOwn];
+    {
+      const uint4 w0 = *reinterpret_cast<const uint4*>(&hist[kBins - kOwn * tid - kOwn]);
+      const uint4 w1 = *reinterpret_cast<const uint4*>(&hist[kBins - kOwn * tid - kOwn + 4]);
+      c[7] = w0.x, c[6] = w0.y, c[5] = w0.z, c[4] = w0.w, c[3] = w1.x, c[2] = w1.y, c[1] = w1.z, c[0] = w1.w;
     }
+    find_ranks<1, kOwn>(c, ranks, s_wtot, s_res, wave, lane);
+    const uint32_t my_bin = s_res[0];
+    const uint32_t my_len = list_share(t0, my_bin);
+    if (tid == 0) st_agent(&cnt_g[blockIdx.x], (my_bin << kCountBits) | my_len);
   }
-  const uint32_t my_len = list_share(t0, my_bin);
-  if (tid == 0) st_agent(&cnt_g[blockIdx.x], (my_bin << kCountBits) | my_len);
-  for (int i = tid; i < kBins; i += kThreads)
-    if (i >= (int)first_bin && hist[i]) atomicAdd(&gh[i], hist[i]);
   TKV_PH(2);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -511,75 +581,174 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   TKV_PH(3);
   if (!scratch[kWavesPerBlock + 2]) return;
 
-  // ---- the head's last workgroup.  Head histogram and the workgroups' control words in one
-  // round of device-scope loads; histogram and counter are left zero for the next call.
-  if (tid == 0) st_agent(&ctrl[kDone2], 0u);
-  for (int i = (int)k + tid; i < p.top_k; i += kThreads) out[i] = -1;
-  if (tid == 0) p.topk_count[bh] = (int32_t)k;
-  uint32_t bin, above;
+  // ---- the head's last workgroup.  One round of device-scope loads brings the workgroups'
+  // control words and the first `spec` entries of every list (entry e = i * kThreads + tid of
+  // the round belongs to share e / spec, so ascending e is token order); spec is a power of two
+  // a quarter above the nominal list length, the round never fetches more than kSub entries per thread.
+  __shared__ uint32_t r1[2048], r2[2048], r3[1024];  // radix-select histograms: 11 + 11 + 10 key bits
+  __shared__ uint32_t lens[kThreads], lbin[kThreads];  // list length and bin L of every share
+  __shared__ uint32_t s_lmax, s_lmin, s_nsame;
+  int spec_shift = 0;
   {
-    uint32_t hv[kBins / kThreads];
+    const uint32_t nominal = (3u * k) / (2u * (uint32_t)nblk) + 16u;
+    while ((1u << spec_shift) < nominal + nominal / 4u) ++spec_shift;
+    while (spec_shift > 0 && ((size_t)nblk << spec_shift) > (size_t)kSub * kThreads) --spec_shift;
+  }
+  uint32_t ek[kSub], et[kSub];  // this thread's entries: key and token
+  bool fits;
+  {
+    const tkv::AgentBuf cb(cnt_g, (uint32_t)nblk * 4u), lb(list_g, (uint32_t)min((size_t)n * 8, (size_t)0xFFFFFFF0u));
+    const uint32_t cw = cb.x1((uint32_t)tid * 4u);  // 0 beyond the head's workgroups (fewer than 1024)
 #pragma unroll
-    for (int x = 0; x < kBins / kThreads; ++x) hv[x] = ld_agent(&gh[x * kThreads + tid]);
-    const uint32_t cw = tid < nblk ? ld_agent(&cnt_g[tid]) : 0u;  // the entry point launches < 1024 workgroups per head
+    for (int i = 0; i < kSub; ++i) {
+      const uint32_t e = (uint32_t)(i * kThreads + tid), x = e >> spec_shift, off = e & ((1u << spec_shift) - 1u);
+      const bool want = x < (uint32_t)nblk && off < (uint32_t)p.tpw;
+      const tkv::tkv_u32x2 v = lb.x2(want ? (x * (uint32_t)p.tpw + off) * 8u : tkv::AgentBuf::kNone);
+      ek[i] = v.x;
+      et[i] = v.y;
+    }
+    if (tid == 0) st_agent(&ctrl[kDone2], 0u);  // left zero for the next call
+    for (int i = (int)k + tid; i < p.top_k; i += kThreads) out[i] = -1;
+    if (tid == 0) p.topk_count[bh] = (int32_t)k;
+    for (int i = tid; i < 2048; i += kThreads) r1[i] = 0u, r2[i] = 0u;
+    r3[tid] = 0u;
+    if (tid == 0) s_lmax = 0u, s_lmin = kBins - 1;
+    __syncthreads();
+    const uint32_t len = cw & ((1u << kCountBits) - 1u);
+    lens[tid] = len;
+    lbin[tid] = cw >> kCountBits;
+    // largest L of the head: one atomic per wave
+    uint32_t lm = cw >> kCountBits;
 #pragma unroll
-    for (int x = 0; x < kBins / kThreads; ++x) {
-      hist[x * kThreads + tid] = hv[x];
-      if (hv[x] != 0u) st_agent(&gh[x * kThreads + tid], 0u);
+    for (int m = 32; m >= 1; m >>= 1) lm = max(lm, (uint32_t)__shfl_xor((int)lm, m, 64));
+    if (lane == 0 && lm != 0u) atomicMax(&s_lmax, lm);
+    // lowest L among the shares that list anything (every listed key lies in or above it)
+    uint32_t ln = tid < nblk && len != 0u ? cw >> kCountBits : (uint32_t)kBins - 1u;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) ln = min(ln, (uint32_t)__shfl_xor((int)ln, m, 64));
+    if (lane == 0) atomicMin(&s_lmin, ln);
+    fits = __syncthreads_or(len > (1u << spec_shift) ? 1 : 0) == 0;
+  }
+  TKV_PH(4);
+
+  // k-th largest key of a set of keys (each thread offers its own through `each`), by radix
+  // select over three digits of 11, 11 and s1 - 11 bits, the first being (key >> s1) - base,
+  // clamped to 2047; every search is done by the whole workgroup (two or one bin per thread).
+  // s1 = 21, base = 0 covers all 32 bits of any key.  The listed keys share their leading bits,
+  // though, and LDS atomics of a wave on one address are executed one after the other: with
+  // s1 = kFastShift and base = (lowest bin L of any list) << (kLowBits - kFastShift) the first
+  // digits spread over hundreds of values and few keys share the k-th key's digit, at the price
+  // of keys more than four binades above that bin being clamped: returns false if the k-th
+  // key is among those (the caller then falls back to s1 = 21).
+  // T: the key; take: how many keys equal to T belong to the k largest.  The three histograms
+  // must be zero.
+  auto kth_key = [&](auto each, int s1, uint32_t base, uint32_t& T, uint32_t& take) -> bool {
+    uint32_t k_rem = k;
+    auto search2 = [&](const uint32_t* hist, uint32_t& digit) {  // 2048 bins
+      const uint2 w = *reinterpret_cast<const uint2*>(&hist[2048 - 2 * tid - 2]);
+      const uint32_t c[2] = {w.y, w.x};
+      const uint32_t ranks[1] = {k_rem};
+      find_ranks<1, 2>(c, ranks, s_wtot, s_res, wave, lane);
+      digit = s_res[0];
+      k_rem -= s_res[1];
+    };
+    const int s2 = s1 - 11;
+    const uint32_t low_mask = (1u << s2) - 1u;
+    uint32_t d1, d2, d3;
+    each([&](uint32_t key) { if (key != 0u) atomicAdd(&r1[min((key >> s1) - base, 2047u)], 1u); });
+    __syncthreads();
+    TKV_PH(6);
+    search2(r1, d1);
+    if (s1 != 21 && d1 == 2047u) return false;
+    const uint32_t top = d1 + base;
+    // Keys that share the first digit: usually a few dozen.  Up to 1024 of them are collected
+    // in LDS (in any order) and ranked against each other directly; more go through two more
+    // digits.
+    const uint32_t n_same = r1[d1];
+    if (n_same <= (uint32_t)kThreads) {
+      if (tid == 0) s_nsame = 0u;
+      __syncthreads();
+      each([&](uint32_t key) { if (key != 0u && (key >> s1) == top) r2[atomicAdd(&s_nsame, 1u)] = key; });
+      __syncthreads();
+      // the k_rem-th largest of them: the key v with fewer than k_rem keys above it and at least
+      // k_rem keys at or above it (every thread that holds such a key reports the same result)
+      if ((uint32_t)tid < n_same) {
+        const uint32_t v = r2[tid];
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t y = 0; y < n_same; ++y) {
+          const uint32_t o = r2[y];
+          gt += o > v ? 1u : 0u;
+          ge += o >= v ? 1u : 0u;
+        }
+        if (gt < k_rem && k_rem <= ge) s_res[0] = v, s_res[1] = k_rem - gt;
+      }
+      __syncthreads();
+      T = s_res[0];
+      take = s_res[1];
+      return true;
     }
-    if (tid == 0) s_nrep = 0u;
+    each([&](uint32_t key) { if ((key >> s1) == top) atomicAdd(&r2[(key >> s2) & 0x7FFu], 1u); });
     __syncthreads();
-    find_bin(hist, k, part, scratch, bin, above);
-    TKV_PH(4);
-    // shares whose list stops above the head's bin: rebuilt here, down to that bin
-    offs[tid] = cw & ((1u << kCountBits) - 1u);  // list lengths for now
-    if (tid < nblk && (cw >> kCountBits) > bin) s_rep[atomicAdd(&s_nrep, 1u)] = (uint16_t)tid;
+    search2(r2, d2);
+    const uint32_t top2 = (top << 11) | d2;
+    each([&](uint32_t key) { if ((key >> s2) == top2) atomicAdd(&r3[key & low_mask], 1u); });
     __syncthreads();
-    const uint32_t nrep = s_nrep;
-    for (uint32_t r = 0; r < nrep; ++r) {
-      const int x = s_rep[r];
-      const int ts = x * p.tpw, te = min(n, ts + p.tpw);
-      score_share(ts, te, false, false);
-      const uint32_t len = list_share(ts, bin);
-      if (tid == 0) offs[x] = len;
+    {
+      const uint32_t c[1] = {r3[1023 - tid]};
+      const uint32_t ranks[1] = {k_rem};
+      find_ranks<1, 1>(c, ranks, s_wtot, s_res, wave, lane);
+      d3 = s_res[0];
+      take = k_rem - s_res[1];
     }
-    if (nrep != 0u) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the rebuilt lists are read back below
-    __syncthreads();
+    T = (top2 << s2) | d3;
+    return true;
+  };
+
+  if (fits) {
+    // ---- every list entry is in a register of some thread
+#pragma unroll
+    for (int i = 0; i < kSub; ++i) {
+      const uint32_t e = (uint32_t)(i * kThreads + tid), x = e >> spec_shift, off = e & ((1u << spec_shift) - 1u);
+      if (!(x < (uint32_t)nblk && off < lens[x])) ek[i] = 0u;  // beyond the list: below every key
+    }
+    uint32_t T, take;
+    const bool found = kth_key([&](auto f) {
+#pragma unroll
+      for (int i = 0; i < kSub; ++i) f(ek[i]);
+    }, kFastShift, s_lmin << (kLowBits - kFastShift), T, take);
+    TKV_PH(5);
+    // Every list is complete down to its bin L, so T is the head's exact k-th key if no L lies
+    // above T's bin (a token missing from a list is then below T).
+    if (found && (T >> kLowBits) >= s_lmax) {
+      // ordered compaction: every key above T, and the first `take` equal to T
+      unsigned long long mg[kSub], me[kSub];
+#pragma unroll
+      for (int i = 0; i < kSub; ++i) {
+        mg[i] = __builtin_amdgcn_ballot_w64(ek[i] > T);
+        me[i] = __builtin_amdgcn_ballot_w64(ek[i] == T);
+      }
+      uint32_t bg[kSub], be[kSub];
+      subtile_offsets2(mg, me, &s_cnt[0][0], &s_cnt2[0][0], wave, lane, bg, be);
+#pragma unroll
+      for (int i = 0; i < kSub; ++i) {
+        const uint32_t my_gt = bg[i] + rank_in(mg[i]), my_eq = be[i] + rank_in(me[i]);
+        if (ek[i] > T) {
+          out[my_gt + min(my_eq, take)] = (int32_t)et[i];
+        } else if (ek[i] == T && my_eq < take) {
+          out[my_gt + my_eq] = (int32_t)et[i];
+        }
+      }
+      TKV_PH(7);
+      return;
+    }
   }
 
-  // ---- concatenate the lists (wave w copies those of workgroups w, w + 16, ...).  Entry i of
-  // the concatenation lives in LDS if i < kListCap, else it is read from its workgroup's list
-  // in the workspace.
-  __shared__ uint32_t h2[1024], h3[512];  // radix-select histograms (below)
-  for (int i = tid; i < 1024; i += kThreads) h2[i] = 0u;
-  for (int i = tid; i < 512; i += kThreads) h3[i] = 0u;
-  if (tid < 64) {  // exclusive scan of the list lengths by one wave (in place)
-    uint32_t carry = 0;
-    for (int x0 = 0; x0 < nblk; x0 += 64) {
-      const int x = x0 + tid;
-      const uint32_t c = x < nblk ? offs[x] : 0u;
-      uint32_t incl = c;
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(incl, d, 64);
-        if (tid >= d) incl += o;
-      }
-      if (x < nblk) offs[x] = carry + incl - c;
-      carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-    }
-    if (tid == 0) offs[nblk] = carry;
-  }
-  __syncthreads();
-  const uint32_t M = offs[nblk];
-  for (int x = wave; x < nblk; x += kWavesPerBlock) {
-    const uint32_t o = offs[x], c = offs[x + 1] - o;
-    for (uint32_t i = lane; i < c; i += 64) {
-      if (o + i < (uint32_t)kListCap) {
-        const uint2* e = &list_g[(size_t)x * p.tpw + i];
-        list_s[o + i] = make_uint2(ld_agent(&e->x), ld_agent(&e->y));
-      }
-    }
-  }
+  // ---- slow path: lists longer than the round fetched, or lists that stop above the bin of the
+  // k-th key.  Round 0 works on the lists as they are; if its k-th key lies in a bin below some
+  // list's L, those shares are re-scored here and listed down to that bin, and round 1 is exact:
+  // more entries can only raise the k-th key, and every list is now complete down to a bin at or
+  // below it.
+  uint32_t T = 0, take = 0, M = 0;
   auto get = [&](uint32_t i) -> uint2 {
     if (i < (uint32_t)kListCap) return list_s[i];
     int x0 = 0, x1 = nblk;  // workgroup whose list holds entry i: offs[x0] <= i < offs[x0 + 1]
@@ -590,32 +759,58 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     const uint2* e = &list_g[(size_t)x0 * p.tpw + (i - offs[x0])];
     return make_uint2(ld_agent(&e->x), ld_agent(&e->y));
   };
-  __syncthreads();
-  TKV_PH(5);
-  uint32_t k_rem = k - above;  // 1 <= k_rem <= keys in the bin
-
-  // ---- exact threshold inside the bin: radix select on the low 19 key bits (10 + 9), each
-  // search done by one wave
-  for (uint32_t i = tid; i < M; i += kThreads) {
-    const uint32_t key = get(i).x;
-    if ((key >> kLowBits) == bin) atomicAdd(&h2[(key & kLowMask) >> 9], 1u);
+  for (int round = 0; round < 2; ++round) {
+    // concatenate the lists (wave w copies those of workgroups w, w + 16, ...): entry i of the
+    // concatenation lives in LDS if i < kListCap, else it is read from its list in the workspace
+    __syncthreads();
+    for (int i = tid; i < 2048; i += kThreads) r1[i] = 0u, r2[i] = 0u;
+    r3[tid] = 0u;
+    if (tid < 64) {  // exclusive scan of the list lengths by one wave
+      uint32_t carry = 0;
+      for (int x0 = 0; x0 < nblk; x0 += 64) {
+        const int x = x0 + tid;
+        const uint32_t c = x < nblk ? lens[x] : 0u;
+        const uint32_t incl = wave_prefix_incl(c);
+        if (x < nblk) offs[x] = carry + incl - c;
+        carry += read_lane(incl, 63);
+      }
+      if (tid == 0) offs[nblk] = carry;
+    }
+    __syncthreads();
+    M = offs[nblk];
+    for (int x = wave; x < nblk; x += kWavesPerBlock) {
+      const uint32_t o = offs[x], c = offs[x + 1] - o;
+      for (uint32_t i = lane; i < c; i += 64) {
+        if (o + i < (uint32_t)kListCap) {
+          const uint2* e = &list_g[(size_t)x * p.tpw + i];
+          list_s[o + i] = make_uint2(ld_agent(&e->x), ld_agent(&e->y));
+        }
+      }
+    }
+    __syncthreads();
+    kth_key([&](auto f) {
+      for (uint32_t i = tid; i < M; i += kThreads) f(get(i).x);
+    }, 21, 0u, T, take);
+    if (round == 1) break;
+    const uint32_t tbin = T >> kLowBits;
+    if (tid == 0) s_nrep = 0u;
+    __syncthreads();
+    if (tid < nblk && lbin[tid] > tbin) s_rep[atomicAdd(&s_nrep, 1u)] = (uint16_t)tid;
+    __syncthreads();
+    const uint32_t nrep = s_nrep;
+    if (nrep == 0u) break;
+    for (uint32_t r = 0; r < nrep; ++r) {
+      const int x = s_rep[r];
+      const int ts = x * p.tpw, te = min(n, ts + p.tpw);
+      score_share(ts, te, false, false, std::true_type{});
+      const uint32_t relen = list_share(ts, tbin);
+      if (tid == 0) lens[x] = relen, lbin[x] = tbin;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the rebuilt lists are read back in round 1
   }
-  __syncthreads();
-  uint32_t d1, a1;
-  find_bin_wave(h2, 1024, k_rem, scratch, d1, a1);
-  k_rem -= a1;
-  for (uint32_t i = tid; i < M; i += kThreads) {
-    const uint32_t key = get(i).x;
-    if ((key >> kLowBits) == bin && ((key & kLowMask) >> 9) == d1) atomicAdd(&h3[key & 0x1FFu], 1u);
-  }
-  __syncthreads();
-  uint32_t d2, a2;
-  find_bin_wave(h3, 512, k_rem, scratch, d2, a2);
-  const uint32_t take = k_rem - a2;                       // keys equal to T that are selected (lowest indices)
-  const uint32_t T = (bin << kLowBits) | (d1 << 9) | d2;  // threshold key
   TKV_PH(6);
 
-  // ---- ordered compaction of the list: every key above T, and the first `take` equal to T
+  // ordered compaction of the list: every key above T, and the first `take` equal to T
   uint32_t gt_run = 0, eq_run = 0;
   for (uint32_t base = 0; base < M; base += kThreads) {
     const uint32_t i = base + tid;
@@ -961,7 +1156,7 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   // the launch takes ceil(workgroups / compute units) rounds: with 4096 tokens each, a
   // context just past a multiple of 4096 * (compute units / heads) would pay a whole extra
   // round for a few tokens.  Instead the heads' tokens are split evenly over as many
-  // workgroups as fill the machine a whole number of times (each owning up to 8192 tokens),
+  // workgroups as fill the machine a whole number of times (each owning up to 4096 tokens),
   // or, when even one round is not filled, over more and smaller workgroups.  "The machine" is
   // what the stream may use of it.
   const int n_cus = tkv::stream_compute_units(s);  // of the stream's compute-unit mask, if it has one
@@ -978,10 +1173,11 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
       nblk = (full * bh_count / n_cus) * per_head;  // whole rounds, rounded down
     }
   }
-  int tpw = ((max_n + nblk - 1) / nblk + 3) & ~3;
-  if (tpw < 4) tpw = 4;
-  if (tpw > kMaxPass * kTok) {  // (only if the head count does not divide the compute units evenly)
-    tpw = kMaxPass * kTok;
+  // (a multiple of 16: every workgroup's list starts on a 128-byte line of its own)
+  int tpw = ((max_n + nblk - 1) / nblk + 15) & ~15;
+  if (tpw < 16) tpw = 16;
+  if (tpw > kMaxTpw) {
+    tpw = kMaxTpw;
   }
   nblk = (max_n + tpw - 1) / tpw;
   if (nblk < 1) nblk = 1;
@@ -1097,7 +1293,7 @@ int32_t topk_of_scores(const float* scores, size_t stride, int n_rows, int n, in
   p.lens.n[0] = n;
   p.app_k = nullptr;
   // many rows: as few workgroups per row as the kernels allow (their fixed cost dominates)
-  p.tpw = kMaxPass * kTok;
+  p.tpw = kMaxTpw;
   int nblk = (n + p.tpw - 1) / p.tpw;
   if (nblk < 1) nblk = 1;
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;
