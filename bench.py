@@ -57,9 +57,14 @@ def parse():
                          "many distinct caches (configs[1]: --per-call quant --context 32768 [--bits 4]; "
                          "configs[2]: --per-call sparse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["chained", "overlapped"], default="overlapped",
-                    help="overlapped (the benchmark's configuration): sparse-layer gathers on a side stream under "
-                         "the other layers' compute; chained: every call waits for the previous one")
+    ap.add_argument("--schedule", choices=["chained", "overlapped"], default="chained",
+                    help="chained (the headline): every call waits for the previous one, the only order a decoder "
+                         "can run, since a layer's query depends on the layer before; overlapped: sparse-layer "
+                         "gathers on side streams while the compute stream scores later layers (legal only because "
+                         "the synthetic queries of different layers are independent; reported as other_schedule)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the single-layer and batched configurations that the default run reports beside "
+                         "the headline (the `configs` object of the JSON line)")
     ap.add_argument("--one-schedule", action="store_true", help="time only --schedule (profiling runs)")
     ap.add_argument("--lookahead", type=int, default=4,
                     help="overlapped schedule: sparse layers whose scoring runs ahead of the attention")
@@ -137,7 +142,79 @@ def main():
     if args.identify:
         return identify(args, tkv, torch, dev)
     if args.per_call:
-        return per_call(args, tkv, torch, dev)
+        print(json.dumps(per_call(args, tkv, torch, dev)))
+        return
+    default_workload = (args.context == 131072 and args.batch == 1 and not args.ragged and not args.paper_setting
+                        and args.dynamic_channels == "off" and (args.bits, args.group) == (2, 32))
+    line = run_step(args, tkv, torch, dev)
+    if default_workload and not args.no_configs:
+        line["configs"] = other_configs(args, tkv, torch, dev)
+    print(json.dumps(line))
+
+
+def other_configs(args, tkv, torch, dev):
+    """The benchmark's other workloads, measured in the same run (the headline stays the 32-layer
+    step at 128k): single quantized layer at N = 32768 with 2 and 4 bit, single sparse layer at
+    N = 131072, batched ragged decode (batch 8, lengths in [16384, 32768]).  Every call is timed
+    with its data coming from HBM (round-robin over distinct caches)."""
+    import copy
+    import gc
+
+    def fresh(**kw):
+        a = copy.copy(args)
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return a
+
+    def cleanup():
+        gc.collect()
+        torch.cuda.empty_cache()
+        empty_host = getattr(torch._C, "_host_emptyCache", None)   # pinned blocks the finished configuration no longer needs
+        if empty_host is not None:
+            empty_host()
+
+    out = {}
+    cleanup()
+    for bits in (2, 4):
+        r = per_call(fresh(per_call="quant", context=32768, bits=bits, group=32), tkv, torch, dev)
+        c = r["calls"]
+        out["configs[1] quantized layer N=32768 %d bit" % bits] = {
+            "quant_attn_us": r["value"], "algorithmic_bytes": r["roofline"]["algorithmic_bytes"],
+            "GBs": r["roofline"]["achieved"], "frac_of_hbm_peak": r["roofline"]["frac"],
+            "read_sweep_same_bytes_us": c["read_sweep_same_bytes_us"], "hot_in_cache_us": c["quant_attn_hot_in_cache_us"],
+            "quantize_append_bulk_us": c["quantize_append_bulk_us"], "quantize_append_bulk_GBs": c["quantize_append_bulk_GBs"],
+            "quantize_append_1_token_us": c["quantize_append_1_token_us"], "distinct_caches": c["distinct_caches"]}
+        cleanup()
+    r = per_call(fresh(per_call="sparse", context=131072), tkv, torch, dev)
+    c = r["calls"]
+    out["configs[2] sparse layer N=131072"] = {
+        "estimate_topk_us": c["estimate_topk_us"], "estimate_topk_GBs": c["estimate_topk_GBs"],
+        "estimate_topk_frac_of_hbm_peak": c["estimate_topk_frac_of_hbm"],
+        "append_estimate_topk_us": c["append_estimate_topk_us"],
+        "gather_alone_us": c["gather_alone_us"], "gather_GBs": r["roofline"]["achieved"],
+        "gather_frac_of_h2d": r["roofline"]["frac"], "h2d_memcpy_GBs": c["h2d_memcpy_GBs"],
+        "gather_attn_fused_us": c["gather_attn_fused_us"], "attention_over_staged_rows_us": c["attention_over_staged_rows_us"],
+        "decode_fused_us": c.get("decode_fused_us"),
+        "distinct_summaries": c["distinct_summaries"], "distinct_host_caches": c["distinct_host_caches"]}
+    cleanup()
+    b = run_step(fresh(batch=8, context=32768, ragged=True, steps=max(4, args.steps // 4), warmup=2,
+                       no_cpu_baseline=True), tkv, torch, dev)
+    out["configs[4] batched ragged decode, batch 8"] = {
+        "workload": b["config"]["workload"], "schedule": b["config"]["schedule"], "ms_per_step": b["ms_per_step"],
+        "us_per_layer_token": b["value"], "other_schedule": b["other_schedule"],
+        "host_link": b["host_link"], "host_link_floor_ms": b["host_link_floor_ms"],
+        "quant_attn_us": b["quant_attn_us"], "quant_attn_frac_of_hbm_peak": b["roofline"]["frac"],
+        "quant_attn_bytes": b["roofline"]["algorithmic_bytes"], "estimate_topk_us": b["estimate_topk_us"],
+        "gather_us": b["gather_us"], "distinct_host_caches": b["config"]["distinct_host_caches"]}
+    cleanup()
+    return out
+
+
+def run_step(args, tkv, torch, dev):
+    """The 32-layer decode step (configs[3]; with --batch / --ragged configs[4]); returns the JSON line."""
+    import numpy as np
+
+    from synth.device import make_layer_device, static_channels_device
     if args.paper_setting:
         args.bits, args.group, args.top_k, args.channels, args.n_sink, args.n_window = 1, 64, 896, 12, 0, 128
         if args.dynamic_channels == "off":
@@ -213,7 +290,17 @@ def main():
             kv_host = None
             if si >= args.host_layers:
                 kv_host = host_pool[si % args.host_layers]
-            L = tkv.SparseLayer(capacity=CAP, device=dev, kv_host=kv_host, **sparse_kw)
+            try:
+                L = tkv.SparseLayer(capacity=CAP, device=dev, kv_host=kv_host, **sparse_kw)
+            except RuntimeError:
+                # no more pinned host memory: the remaining sparse layers share the host caches that
+                # exist (only the selected rows of a cache are ever read); stated in the JSON line
+                if kv_host is not None or not host_pool:
+                    raise
+                torch.cuda.synchronize()
+                args.host_layers = len(host_pool)
+                kv_host = host_pool[si % args.host_layers]
+                L = tkv.SparseLayer(capacity=CAP, device=dev, kv_host=kv_host, **sparse_kw)
             if args.dynamic_channels != "off":   # Stage 1 buffers see the keys before the layer's own append
                 shared = next(iter(stage1.values())).fetched if stage1 else None   # one double buffer for all layers
                 stage1[l] = tkv.Stage1(L, resident=args.dynamic_channels == "resident", fetched=shared)
@@ -455,6 +542,8 @@ def main():
     roof = {"bound": "hbm", "kernel": "tkv_quant_attn_decode", "achieved": quant_bytes / dur["quant"] / 1e3,
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "traffic": traffic_from_profile("quant_attn_mfma_kernel<2") if (N, B, args.bits, args.group) == (131072, 1, 2, 32) else None,
+            "traffic_source": "profiles/bench_hybrid_step_128k_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
+                              "earlier run of this command, not measured in this run)",
             "algorithmic_bytes": quant_bytes,
             # a kernel that only streams the same number of bytes (tkv_debug_read_sweep), timed the same way
             "read_sweep_us": dur["read_sweep"], "read_sweep_GBs": quant_bytes / dur["read_sweep"] / 1e3,
@@ -465,7 +554,11 @@ def main():
         "estimate_topk_GBs": summary_bytes / dur["topk"] / 1e3,
         "per_call_us": {"quant_attn": spread["quant"], "estimate_topk": spread["topk"], "gather": spread["gather"]},
         "other_schedule": None if ms_other is None else {
-            "schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS / B},
+            "schedule": other, "ms_per_step": ms_other, "us_per_layer_token": ms_other * 1e3 / N_LAYERS / B,
+            "note": "scoring runs %d sparse layers ahead of the attention: possible only because the synthetic "
+                    "queries of different layers are independent, not a schedule a decoder can run" % args.lookahead
+                    if other == "overlapped" else "every call waits for the previous one"},
+        "host_link_floor_ms": len(sparse_ids) * gather_bytes / h2d / 1e6,
         "host_link": {"bound": "host_link", "kernel": "tkv_sparse_gather", "achieved": gather_bytes / dur["gather"] / 1e3,
                       "peak": h2d, "unit": "GB/s", "frac": gather_bytes / dur["gather"] / 1e3 / h2d,
                       "peak_source": "pinned 1 GiB hipMemcpy H2D measured in this run"},
@@ -495,10 +588,13 @@ def main():
                    **({"gather_compute_units": args.gather_cus, "gather_streams": args.gather_streams}
                       if args.schedule == "overlapped" else {}),
                    "distinct_host_caches": len(host_pool),
+                   "host_caches_note": None if len(host_pool) == len(sparse_ids) else
+                   "pinned-memory fallback: %d sparse layers share %d pinned host caches" % (len(sparse_ids), len(host_pool)),
                    "build_s": round(t_build, 1)},
         "roofline": roof, "cpu_baseline": cpu, **extra,
     }
-    print(json.dumps(line))
+    del layers, stage1, host_pool, outs, qs
+    return line
 
 
 def identify(args, tkv, torch, dev):
@@ -670,9 +766,8 @@ def per_call(args, tkv, torch, dev):
         workload = (f"configs[2]: single sparse layer, batch 1, N={N}, d_s={args.channels}, k={args.top_k}, "
                     f"{args.n_sink} sinks, {args.n_window} window; {n_caches} distinct summaries, 8 distinct host caches")
         metric = "sparse gather us per call"
-    print(json.dumps({"metric": metric, "value": value, "unit": "us/call", "n_gpus": 1, "higher_is_better": False,
-                      "dtype": "f16", "data": "synthetic", "config": {"workload": workload}, "roofline": roof,
-                      "calls": calls}))
+    return {"metric": metric, "value": value, "unit": "us/call", "n_gpus": 1, "higher_is_better": False,
+            "dtype": "f16", "data": "synthetic", "config": {"workload": workload}, "roofline": roof, "calls": calls}
 
 
 def traffic_from_profile(kernel: str):
