@@ -62,6 +62,9 @@ def parse():
                          "can run, since a layer's query depends on the layer before; overlapped: sparse-layer "
                          "gathers on side streams while the compute stream scores later layers (legal only because "
                          "the synthetic queries of different layers are independent; reported as other_schedule)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="chained schedule: tkv_sparse_append_estimate_topk + tkv_sparse_gather_attn per sparse layer "
+                         "instead of the single tkv_sparse_decode launch")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the single-layer and batched configurations that the default run reports beside "
                          "the headline (the `configs` object of the JSON line)")
@@ -432,6 +435,10 @@ def run_step(args, tkv, torch, dev):
                     a, b = ev(), ev(); a.record()
                     L.estimate_topk(qs[l])
                     b.record(); rec["topk"].append((a, b))
+                elif not args.separate_calls:
+                    # one launch per sparse layer: append, scoring, Top-K, fetch of the rows, attention
+                    L.decode(qs[l], sm, new_k[l], new_v[l], out=outs[l])
+                    continue
                 else:                 # the scoring launch also appends the step's new token
                     L.append_estimate_topk(new_k[l], new_v[l], qs[l])
                 if rec is not None:   # per-call timing pass: the transfer on its own
@@ -585,6 +592,8 @@ def run_step(args, tkv, torch, dev):
                                f"{args.n_sink} sinks, {args.n_window} window)" + ("" if args.dynamic_channels == "off" else
                                                f", critical channels re-selected every step ({args.dynamic_channels})"),
                    "schedule": args.schedule,
+                   **({"sparse_layer_calls": "tkv_sparse_append_estimate_topk + tkv_sparse_gather_attn" if args.separate_calls
+                       else "tkv_sparse_decode (one launch)"} if args.schedule == "chained" and args.dynamic_channels == "off" else {}),
                    **({"gather_compute_units": args.gather_cus, "gather_streams": args.gather_streams}
                       if args.schedule == "overlapped" else {}),
                    "distinct_host_caches": len(host_pool),
@@ -754,11 +763,12 @@ def per_call(args, tkv, torch, dev):
         t_gather = timed(lambda: [L.gather() for L, _ in pairs], n_caches)
         t_attn = timed(lambda: [L.attn(q, sm, out=out) for L, q in pairs], n_caches)
         t_app = timed(lambda: [L.append_estimate_topk(k1, v1, q) for L, q in pairs[:8]], 8)
+        t_dec = timed(lambda: [L.decode(q, sm, k1, v1, out=out) for L, q in pairs[:8]], 8)
         gbytes = 8 * args.top_k * 512
         calls = {"estimate_topk_us": t_topk, "estimate_topk_GBs": sbytes / t_topk / 1e3,
                  "estimate_topk_frac_of_hbm": sbytes / t_topk / 1e3 / HBM_PEAK_GBS,
                  "gather_attn_fused_us": t_fused, "gather_alone_us": t_gather, "attention_over_staged_rows_us": t_attn,
-                 "append_estimate_topk_us": t_app, "distinct_summaries": n_caches, "distinct_host_caches": 8,
+                 "append_estimate_topk_us": t_app, "decode_fused_us": t_dec, "distinct_summaries": n_caches, "distinct_host_caches": 8,
                  "h2d_memcpy_GBs": h2d}
         value, roof = t_gather, {"bound": "host_link", "kernel": "tkv_sparse_gather", "achieved": gbytes / t_gather / 1e3,
                                  "peak": h2d, "unit": "GB/s", "frac": gbytes / t_gather / 1e3 / h2d, "traffic": None,

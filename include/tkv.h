@@ -255,6 +255,24 @@ int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* desc, tkv_sparse_
                                         size_t workspace_bytes, void* stream);
 
 /*
+ * A sparsity-friendly layer's whole decode step in ONE launch: Eq. 2 for the step's new tokens
+ * (n_new 0..min(8, n_window); n_new == 0: k_new, v_new, n_valid_host are ignored), Stage 2
+ * scoring and Top-K as in tkv_sparse_estimate_topk, fetch of the selected rows from the host
+ * cache and exact attention as in tkv_sparse_gather_attn (Sec. 4.2, Sec. 5.1; Eq. 3).  Same
+ * topk_idx / topk_count / out as the separate calls (attention within the same tolerance: the
+ * order of the float32 sums differs).  This is the form for a decoder, where a layer's
+ * calls cannot overlap with anything: the workgroup that finishes a head's selection goes on to
+ * fetch that head's rows and attends to them, so no launch boundary and no cross-workgroup
+ * hand-off sits between the selection and the transfer that cannot be hidden.
+ * The key summary must be token-major (cache->key_summary).  workspace: as for
+ * tkv_sparse_estimate_topk.  seq_len_host[b] += n_valid on success.
+ */
+int32_t tkv_sparse_decode(const tkv_sparse_desc* desc, tkv_sparse_cache* cache, const void* k_new,
+                          const void* v_new, int32_t n_new, const int32_t* n_valid_host, const void* q,
+                          int32_t* topk_idx, int32_t* topk_count, void* out, float sm_scale, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/*
  * Fetch of the Top-K tokens from the host cache (Sec. 4.2; the one transfer that
  * cannot be hidden) and exact attention (Eq. 3) of every query head over
  * sinks [0, n_sink) U selected U window [N - n_window, N) (Sec. 5.1: n_local + n_topk).

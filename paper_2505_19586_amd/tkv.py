@@ -97,6 +97,8 @@ def lib() -> C.CDLL:
                                                       C.POINTER(SparseStage1), vp, vp, vp, vp, vp, vp, sz, vp]
         L.tkv_sparse_append_dynamic.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), C.POINTER(SparseStage1),
                                                 vp, vp, i32, C.POINTER(i32), vp]
+        L.tkv_sparse_decode.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32, C.POINTER(i32),
+                                        vp, vp, vp, vp, C.c_float, vp, sz, vp]
         L.tkv_sparse_append_estimate_topk.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32,
                                                       C.POINTER(i32), vp, vp, vp, vp, sz, vp]
         L.tkv_dense_preference_sizes.argtypes = [C.POINTER(PrefDesc), C.POINTER(sz)]
@@ -114,7 +116,7 @@ def lib() -> C.CDLL:
                      "tkv_sparse_stage1_sizes", "tkv_sparse_stage1_append", "tkv_sparse_select_channels",
                      "tkv_sparse_prefetch_keys", "tkv_sparse_estimate_topk_cm",
                      "tkv_sparse_select_estimate_topk", "tkv_sparse_append_dynamic",
-                     "tkv_sparse_append_estimate_topk", "tkv_dense_preference_sizes", "tkv_dense_preference",
+                     "tkv_sparse_append_estimate_topk", "tkv_sparse_decode", "tkv_dense_preference_sizes", "tkv_dense_preference",
                      "tkv_classify_layer"):
             getattr(L, name).restype = C.c_int32
         _LIB = L
@@ -314,6 +316,31 @@ class SparseLayer:
             self.topk_idx.data_ptr(), self.topk_count.data_ptr(), self.workspace.data_ptr(), self.workspace_bytes,
             _stream(stream)), "tkv_sparse_append_estimate_topk")
         return self.topk_idx, self.topk_count
+
+    def decode(self, q: torch.Tensor, sm_scale: float, k_new: torch.Tensor | None = None,
+               v_new: torch.Tensor | None = None, n_valid=None, out: torch.Tensor | None = None, stream=None):
+        """tkv_sparse_decode: the step's append (if k_new is given), scoring, Top-K, fetch of the
+        selected rows and attention in one launch."""
+        d = self.desc
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        n_new, kp, vp_, nv = 0, None, None, None
+        if k_new is not None:
+            assert k_new.dtype == torch.float16 and k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous()
+            assert tuple(k_new.shape) == tuple(v_new.shape) and k_new.shape[0] == d.batch
+            assert tuple(k_new.shape[2:]) == (d.n_kv_heads, d.head_dim)
+            n_new, kp, vp_ = int(k_new.shape[1]), k_new.data_ptr(), v_new.data_ptr()
+            if n_valid is not None:
+                nv = np.ascontiguousarray(n_valid, dtype=np.int32)
+                assert nv.shape == (d.batch,)
+        if out is None:
+            out = torch.empty_like(q)
+        _check(lib().tkv_sparse_decode(
+            C.byref(d), C.byref(self.cache), kp, vp_, n_new,
+            None if nv is None else nv.ctypes.data_as(C.POINTER(C.c_int32)), q.data_ptr(),
+            self.topk_idx.data_ptr(), self.topk_count.data_ptr(), out.data_ptr(), float(sm_scale),
+            self.workspace.data_ptr(), self.workspace_bytes, _stream(stream)), "tkv_sparse_decode")
+        return out
 
     def gather_attn(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor | None = None,
                     gather_stream=None, compute_stream=None):
