@@ -51,16 +51,17 @@ struct MfmaParams {
   const __half* k_resid;
   const __half* v_resid;
   const __half* q;
-  float* parts;        // [B][Hq][n_chunks][D + 4]
+  float* parts;        // sequence after sequence: [Hq][chunks of the sequence][D + 4]
   uint32_t* arrivals;  // [B][Hkv], zero between calls
   __half* out;         // [B][Hq][D]
   float scale2;
   int32_t hq, hkv, residual, capacity;
-  int32_t n_chunks;
+  int32_t batch;
 #ifdef TKV_PHASE
   long long* prof;  // phase time stamps (profiling builds only)
 #endif
   TkvSeqLens lens;
+  TkvSeqLens chunks;  // split-K chunks of every sequence, in proportion to its length: blockIdx.x runs over all of them
 };
 
 __device__ inline floatx4 mfma(uintx4 a, uintx4 b, floatx4 c) {
@@ -321,7 +322,15 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
 #endif
   TKV_PH();  // 0 kernel start
 
-  const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
+  // blockIdx.x counts the chunks of all sequences: which sequence, which of its chunks
+  int b = 0, chunk = blockIdx.x, chunk_base = 0;
+  while (b + 1 < p.batch && chunk >= p.chunks.n[b]) {
+    chunk -= p.chunks.n[b];
+    chunk_base += p.chunks.n[b];
+    ++b;
+  }
+  const int n_chunks = p.chunks.n[b];
+  const int h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);  // wave-uniform: keeps group addresses scalar
   const int G = p.hq / p.hkv;
@@ -333,9 +342,9 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   const size_t kgrp_base = bh * (size_t)(p.capacity / GRP);      // first key group
   // Work split of this sequence: a 32-token piece of the tail counts as two groups and the
   // tail belongs to the last chunk, which gets correspondingly fewer quantized groups.
-  const bool has_tail = chunk == p.n_chunks - 1;
+  const bool has_tail = chunk == n_chunks - 1;
   const int tail_equiv = 2 * ((n - nq + 31) / 32);
-  const int gpc = max(1, (jq + tail_equiv + p.n_chunks - 1) / p.n_chunks);
+  const int gpc = max(1, (jq + tail_equiv + n_chunks - 1) / n_chunks);
   const int blk0 = min(chunk * gpc, jq);
   const int blk1 = has_tail ? jq : min(blk0 + gpc, jq);
   const int last = max(blk1 - 1, blk0);  // groups past the chunk are clamped (and ignored); jq >= 1 here
@@ -813,7 +822,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
       const float wgt = s_w[W + w][hh];
       O = __builtin_fmaf(wgt != 0.f ? tail_s[w].o[hh][c] : 0.f, wgt, O);
     }
-    float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * p.n_chunks + chunk) * TKV_PART_STRIDE;
+    float* dst = p.parts + (((size_t)chunk_base * p.hq + ((size_t)h * G + hh) * n_chunks) + chunk) * TKV_PART_STRIDE;
     // device-scope stores: visible to the merging workgroup without a cache write-back
     __hip_atomic_store(dst + TKV_PART_O + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
@@ -829,13 +838,13 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   TKV_PH();  // 6 partial written
   __syncthreads();
-  if (tid == 0) s_flag = atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(p.n_chunks - 1) ? 1u : 0u;
+  if (tid == 0) s_flag = atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(n_chunks - 1) ? 1u : 0u;
   __syncthreads();
   if (s_flag != 0u) {
     if (tid == 0) p.arrivals[bh] = 0u;
-    const float* head0 = p.parts + ((size_t)b * p.hq + (size_t)h * G) * p.n_chunks * TKV_PART_STRIDE;
+    const float* head0 = p.parts + ((size_t)chunk_base * p.hq + (size_t)h * G * n_chunks) * TKV_PART_STRIDE;
     float* scratch = reinterpret_cast<float*>(smem + C::oRing);  // the waves' results have been consumed
-    tkv::merge_chunks(head0, G, p.n_chunks, p.out + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, scratch, tid, C::kThreads);
+    tkv::merge_chunks(head0, G, n_chunks, p.out + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, scratch, tid, C::kThreads);
   }
   TKV_PH();  // 7 end
 #ifdef TKV_PHASE
@@ -876,19 +885,64 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   const int variant = d->bits * 100 + d->group_size;
   if (variant != 232 && variant != 432 && variant != 164 && variant != 264) return TKV_E_UNSUPPORTED;
   const int waves = d->bits == 4 ? 8 : 12;
-  const int bh = d->batch * d->n_kv_heads;
-  const int work = max_groups + 2 * ((max_tail + 31) / 32);  // in groups, as the kernel counts it
-  int n_chunks = (target_blocks + bh - 1) / bh;
-  const int c_work = (work + waves - 1) / waves;
-  if (n_chunks > c_work) n_chunks = c_work;
-  // at most 64 chunks, unless the tuning hook asks for more workgroups than that gives
-  const int chunk_cap = target_blocks > 64 * bh ? TKV_MAX_CHUNKS : 64;
-  if (n_chunks > chunk_cap) n_chunks = chunk_cap;
-  if (n_chunks < 1) n_chunks = 1;
-  if ((work + n_chunks - 1) / n_chunks > kMaxGpc) n_chunks = (work + kMaxGpc - 1) / kMaxGpc;
-  if (n_chunks > TKV_MAX_CHUNKS) return TKV_E_UNSUPPORTED;
-  if ((size_t)d->batch * d->n_q_heads * n_chunks * TKV_PART_STRIDE > parts_floats) return TKV_E_WORKSPACE;
+  // Chunks per KV head over the whole batch: about target_blocks workgroups in all, shared out
+  // among the sequences in proportion to their work (32-token blocks, a 32-token piece of the
+  // fp16 tail counting as two), so that every workgroup sweeps about the same number of blocks
+  // whatever the mix of lengths.  Per sequence: at least one block per wave, at most 64 chunks
+  // (unless the tuning hook asks for more workgroups than that gives), no more blocks per chunk
+  // than the zero-point table of a workgroup holds.
+  (void)max_groups;
+  (void)max_tail;
   MfmaParams p;
+  int per_head = (target_blocks + d->n_kv_heads - 1) / d->n_kv_heads;
+  if (per_head < d->batch) per_head = d->batch;
+  const int chunk_cap = target_blocks > 64 * d->batch * d->n_kv_heads ? TKV_MAX_CHUNKS : 64;
+  long long total_work = 0;
+  int work[TKV_MAX_BATCH];
+  for (int b = 0; b < d->batch; ++b) {
+    const int n = lens.n[b];
+    const int g = tkv::n_quantized(n, d->residual, d->group_size) / TKV_BLK;
+    work[b] = g + 2 * ((n - g * TKV_BLK + 31) / 32);
+    total_work += work[b];
+  }
+  int total_chunks = 0;
+  for (int b = 0; b < d->batch; ++b) {
+    int nc = total_work > 0 ? (int)(((long long)per_head * work[b] + total_work / 2) / total_work) : 1;
+    const int c_work = (work[b] + waves - 1) / waves;
+    if (nc > c_work) nc = c_work;
+    if (nc > chunk_cap) nc = chunk_cap;
+    if (nc < 1) nc = 1;
+    if ((work[b] + nc - 1) / nc > kMaxGpc) nc = (work[b] + kMaxGpc - 1) / kMaxGpc;
+    if (nc > TKV_MAX_CHUNKS) return TKV_E_UNSUPPORTED;
+    p.chunks.n[b] = nc;
+    total_chunks += nc;
+  }
+  // Rounding may leave a few chunks too many (a second round of workgroups for a handful of
+  // them) or too few (idle compute units): take them from the sequences whose chunks are the
+  // lightest, give them to those whose chunks are the heaviest.
+  while (total_chunks > per_head) {
+    int pick = -1;
+    for (int b = 0; b < d->batch; ++b) {
+      const int nc = p.chunks.n[b];
+      if (nc <= 1 || (work[b] + nc - 2) / (nc - 1) > kMaxGpc) continue;
+      if (pick < 0 || (long long)work[b] * (p.chunks.n[pick] - 1) < (long long)work[pick] * (nc - 1)) pick = b;
+    }
+    if (pick < 0) break;
+    --p.chunks.n[pick];
+    --total_chunks;
+  }
+  while (total_chunks < per_head) {
+    int pick = -1;
+    for (int b = 0; b < d->batch; ++b) {
+      const int nc = p.chunks.n[b];
+      if (nc >= chunk_cap || nc >= (work[b] + waves - 1) / waves) continue;
+      if (pick < 0 || (long long)work[b] * p.chunks.n[pick] > (long long)work[pick] * nc) pick = b;
+    }
+    if (pick < 0) break;
+    ++p.chunks.n[pick];
+    ++total_chunks;
+  }
+  if ((size_t)total_chunks * d->n_q_heads * TKV_PART_STRIDE > parts_floats) return TKV_E_WORKSPACE;
   p.k_codes = (const uint32_t*)c->k_codes;
   p.v_codes = (const uint32_t*)c->v_codes;
   p.k_scale = (const __half*)c->k_scale;
@@ -906,12 +960,12 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.hkv = d->n_kv_heads;
   p.residual = d->residual;
   p.capacity = d->capacity;
-  p.n_chunks = n_chunks;
+  p.batch = d->batch;
 #ifdef TKV_PHASE
   p.prof = (long long*)g_mfma_prof;
 #endif
   p.lens = lens;
-  const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
+  const dim3 grid(total_chunks, d->n_kv_heads, 1);
   switch (variant) {
     case 232: return launch_variant<2, 1, 12>(p, grid, s);
     case 432: return launch_variant<4, 1, 8>(p, grid, s);
