@@ -151,6 +151,12 @@ int32_t tkv_quantize_append_ragged(const tkv_quant_desc* desc, tkv_quant_cache* 
  * to about 1000 and query-times-key-scaler products up to 65504 are safe at every bit
  * width; far larger ones overflow fp16 and give wrong or non-finite outputs (the
  * reference kernel that tkv_debug.h can switch to has no such limit).
+ * Context length: the rounding error of the matrix-core path grows slowly with the number of
+ * tokens (the softmax weights enter the matrix cores as fp16); against a float64 evaluation it
+ * measures 5e-4 .. 1e-3 up to 32768 tokens, 1.0e-3 .. 1.5e-3 at 131072 and at 262144, the
+ * largest length the parity tests cover (bound 2e-3).
+ * Two calls on the same inputs can differ in the last bits of an output (up to about 8e-4 of a
+ * head's largest output): which 32-token blocks a wave processes is decided at run time.
  * The work is split over token chunks whose partial (max, sum, weighted V) results
  * go through `workspace` and are merged with a log-sum-exp merge.  The workspace must be
  * ZERO-FILLED by the caller before its first use (it ends in arrival counters that every

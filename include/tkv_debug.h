@@ -29,6 +29,17 @@ int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t target_blocks
  * stream that volume takes on the same machine, launch included. */
 int32_t tkv_debug_read_sweep(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream);
 
+/* Test aid: which parts of the workspaces may hold anything between calls.
+ * Quantized layers: bytes [0, *scratch_bytes) of the tkv_quant_attn_decode workspace are scratch
+ * (split-K partials, fully rewritten by every call before they are read); the rest holds the
+ * arrival counters, which must be zero before the first call and are left zero by every call.
+ * Sparse layers: region_offsets[0..6] are the byte offsets of: score keys (dense preference
+ * score only), candidate lists, histograms (dense preference score only), control words
+ * (arrival counters), list lengths, attention partials, end.  The histograms and control words
+ * must be zero before the first call and are left zero; everything else is scratch. */
+int32_t tkv_debug_quant_workspace(const tkv_quant_desc* desc, size_t* scratch_bytes);
+int32_t tkv_debug_sparse_workspace(const tkv_sparse_desc* desc, size_t region_offsets[7]);
+
 #ifdef __cplusplus
 }
 #endif

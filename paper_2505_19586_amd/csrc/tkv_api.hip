@@ -130,3 +130,21 @@ extern "C" int32_t tkv_debug_read_sweep(const void* src, size_t bytes, void* sin
   TKV_LAUNCH(read_sweep_kernel, dim3(n_workgroups), 256, 0, (hipStream_t)stream, (const uint4*)src, bytes / 16, (uint32_t*)sink);
   return TKV_OK;
 }
+
+extern "C" int32_t tkv_debug_quant_workspace(const tkv_quant_desc* d, size_t* scratch_bytes) {
+  const int32_t st = tkv::check_quant_desc(d);
+  if (st != TKV_OK) return st;
+  if (!scratch_bytes) return TKV_E_INVAL;
+  *scratch_bytes = (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE * sizeof(float);
+  return TKV_OK;
+}
+
+extern "C" int32_t tkv_debug_sparse_workspace(const tkv_sparse_desc* d, size_t region_offsets[7]) {
+  const int32_t st = tkv::check_sparse_desc(d);
+  if (st != TKV_OK) return st;
+  if (!region_offsets) return TKV_E_INVAL;
+  size_t off[6];
+  region_offsets[6] = tkv::sparse_ws_layout(d, off, nullptr);
+  for (int i = 0; i < 6; ++i) region_offsets[i] = off[i];
+  return TKV_OK;
+}
