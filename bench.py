@@ -56,6 +56,11 @@ def parse():
                     help="instead of the decode step, time the entry points of ONE layer kind on their own over "
                          "many distinct caches (configs[1]: --per-call quant --context 32768 [--bits 4]; "
                          "configs[2]: --per-call sparse)")
+    ap.add_argument("--prefill-offload", action="store_true",
+                    help="instead of the decode step, time the prefill-side build of the 32 layers' caches at "
+                         "--context: each sparse layer's K/V goes to pinned host memory on a side stream while the "
+                         "compute stream produces (and, for quantized layers, quantizes) the next layers' K/V; "
+                         "measured against a pinned device-to-host copy")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["chained", "overlapped"], default="chained",
                     help="chained (the headline): every call waits for the previous one, the only order a decoder "
@@ -144,6 +149,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.identify:
         return identify(args, tkv, torch, dev)
+    if args.prefill_offload:
+        print(json.dumps(prefill_offload(args, tkv, torch, dev)))
+        return
     if args.per_call:
         print(json.dumps(per_call(args, tkv, torch, dev)))
         return
@@ -636,6 +644,134 @@ def identify(args, tkv, torch, dev):
         "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": flops / ms / 1e9 / 2500.0, "traffic": None},
         "layer_score": score, "quantization_friendly": friendly, "workspace_MiB": dp.workspace_bytes / 2 ** 20}))
+
+
+def build_caches_overlapped(torch, layers, produce, side):
+    """Prefill-side build of the layers' caches, layer by layer (Sec. 4.2: the KV cache of a
+    sparsity-friendly layer is offloaded to CPU memory layer by layer during prefill; Sec. 4.3:
+    quantization-friendly layers are quantized on the spot).  produce(l) enqueues, on the current
+    stream, whatever makes layer l's keys and values (here: synthetic generation, standing in for
+    the prefill computation) and returns (k, v).  A quantized layer is quantized on the current
+    stream; a sparse layer's bulk append - host rows, key summary, resident rows - runs on the
+    `side` stream after the event that marks its inputs ready, so the device-to-host transfer of
+    layer l overlaps the production of layers l+1, l+2, ...  side=None: everything on the current
+    stream, one call after the other.  Returns the event after which every cache is complete."""
+    import paper_2505_19586_amd as tkv
+    compute = torch.cuda.current_stream()
+    for l, L in enumerate(layers):
+        k, v = produce(l)
+        if isinstance(L, tkv.QuantLayer) or side is None:
+            L.append(k, v)
+            continue
+        ready = torch.cuda.Event()
+        ready.record(compute)
+        side.wait_event(ready)
+        L.append(k, v, stream=side.cuda_stream)
+        k.record_stream(side)      # the inputs stay allocated until the side stream is through with them
+        v.record_stream(side)
+    done = torch.cuda.Event()
+    if side is not None:
+        done.record(side)
+        compute.wait_event(done)
+    done = torch.cuda.Event()
+    done.record(compute)
+    return done
+
+
+def prefill_offload(args, tkv, torch, dev):
+    """Times build_caches_overlapped for the 32-layer hybrid layout at --context (not the headline)."""
+    from synth.device import make_layer_device, static_channels_device
+    N = args.context
+    # measured device-to-host ceiling: one pinned 1 GiB copy
+    pin = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    d2h = 0.0
+    for _ in range(3):
+        e0.record(); pin.copy_(src, non_blocking=True); e1.record(); e1.synchronize()
+        d2h = max(d2h, (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del pin, src
+    kw = dict(top_k=args.top_k, n_channels=args.channels, n_sink=args.n_sink, n_window=args.n_window)
+    host_pool = []
+
+    def make_layers():
+        layers = []
+        for l in range(N_LAYERS):
+            if l in QUANT_LAYERS:
+                layers.append(tkv.QuantLayer(bits=args.bits, group_size=args.group, capacity=N, device=dev))
+            else:
+                si = l - len(QUANT_LAYERS)
+                L = tkv.SparseLayer(capacity=N, device=dev, kv_host=host_pool[si] if si < len(host_pool) else None, **kw)
+                if si >= len(host_pool):
+                    host_pool.append(L.kv_host)
+                layers.append(L)
+        return layers
+
+    chans = {}
+
+    def produce_for(layers):
+        def produce(l):
+            _, k, v = make_layer_device(N, seed=3000 + l, device=dev)
+            if isinstance(layers[l], tkv.SparseLayer):
+                if l not in chans:
+                    chans[l] = static_channels_device(k, args.channels)[None]
+                layers[l].set_channels(chans[l])
+            return k[None], v[None]
+        return produce
+
+    def run(side):
+        layers = make_layers()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        build_caches_overlapped(torch, layers, produce_for(layers), side).synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
+        del layers
+        return ms
+
+    # A kernel that shares compute units with the offload is slowed to the pace of the host link
+    # (its memory instructions queue behind the offload's stores to host memory), so the offload
+    # stream gets a few compute units of its own and the compute stream the rest, as in the
+    # overlapped decode schedule.
+    import contextlib
+    masked = cu_masked_streams(args.gather_cus, 1)
+    if masked is not None:
+        (side,), compute, destroy = masked
+        ctx = torch.cuda.stream(compute)
+    else:
+        side, destroy, ctx = torch.cuda.Stream(), None, contextlib.nullcontext()
+    with ctx:
+        run(side)                           # warm-up: allocations, first launches, channel lists
+        overlapped = min(run(side) for _ in range(2))
+        serial = min(run(None) for _ in range(2))
+    torch.cuda.synchronize()
+    if destroy is not None:
+        destroy()
+    # what the compute stream does on its own (generation + quantization), without any offload
+    layers = make_layers()
+    produce = produce_for(layers)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for l in range(N_LAYERS):
+        k, v = produce(l)
+        if l in QUANT_LAYERS:
+            layers[l].append(k, v)
+    torch.cuda.synchronize()
+    produce_ms = (time.perf_counter() - t0) * 1e3
+    del layers
+    n_sparse = N_LAYERS - len(QUANT_LAYERS)
+    offload_bytes = n_sparse * 8 * N * 512
+    return {"metric": "prefill-side cache build ms per 32-layer prompt", "value": overlapped, "unit": "ms", "n_gpus": 1,
+            "higher_is_better": False, "dtype": "f16", "data": "synthetic",
+            "config": {"workload": f"32-layer hybrid layout at N={N}: layers 0-1 quantized in bulk ({args.bits} bit, "
+                                   f"g={args.group}), layers 2-31 offloaded to pinned host memory in bulk (512 B per "
+                                   "token-head) with their key summaries and resident rows",
+                       "schedule": "offload of layer l on a side stream under the production of layers l+1, ...",
+                       "offload_compute_units": args.gather_cus if masked is not None else "no mask (shared with the compute stream)"},
+            "roofline": {"bound": "host_link", "kernel": "tkv_sparse_append (bulk)", "achieved": offload_bytes / overlapped / 1e6,
+                         "peak": d2h, "unit": "GB/s", "frac": offload_bytes / overlapped / 1e6 / d2h, "traffic": None,
+                         "peak_source": "pinned 1 GiB hipMemcpy D2H measured in this run"},
+            "serial_ms": serial, "production_and_quantization_alone_ms": produce_ms,
+            "offload_bytes": offload_bytes, "link_floor_ms": offload_bytes / d2h / 1e6}
 
 
 def quant_bytes_of(args, lens):

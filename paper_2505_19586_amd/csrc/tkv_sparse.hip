@@ -22,9 +22,15 @@ struct AppendParams {
   TkvSeqLens n_add;  // valid new rows per sequence
 };
 
+// One workgroup per new token up to kAppendGrid workgroups per sequence, which then walk the
+// tokens with the grid's stride: a bulk append (prefill) is bound by the device-to-host link,
+// and a launch that is no wider than the link needs leaves the rest of the machine to the
+// kernels of other streams (the next layers' computation) instead of parking tens of thousands
+// of workgroups that wait for the link on every compute unit.
+constexpr int kAppendGrid = 1024;
 __global__ __launch_bounds__(256) void sparse_append_kernel(AppendParams p) {
-  const int b = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
-  if (i >= p.n_add.n[b]) return;
+  const int b = blockIdx.y, tid = threadIdx.x;
+  for (int i = blockIdx.x; i < p.n_add.n[b]; i += gridDim.x) {
   const int n0 = p.n_old.n[b], n1 = n0 + p.n_add.n[b];
   const int tok = n0 + i;
   const int chunks = p.hkv * 16;
@@ -55,6 +61,7 @@ __global__ __launch_bounds__(256) void sparse_append_kernel(AppendParams p) {
       p.keys_cm[(bh * TKV_D + c) * (size_t)p.capacity + tok] = v;
       atomicMax(reinterpret_cast<uint32_t*>(p.k_absmax + bh * TKV_D + c), __float_as_uint(fabsf(__half2float(v))));
     }
+  }
   }
 }
 
@@ -361,7 +368,7 @@ extern "C" int32_t tkv_sparse_append_dynamic(const tkv_sparse_desc* d, tkv_spars
   p.n_window = d->n_window;
   p.capacity = d->capacity;
   p.n_stride = n_new;
-  TKV_LAUNCH(sparse_append_kernel, dim3(n_new, d->batch), 256, 0, (hipStream_t)stream, p);
+  TKV_LAUNCH(sparse_append_kernel, dim3(n_new < kAppendGrid ? n_new : kAppendGrid, d->batch), 256, 0, (hipStream_t)stream, p);
   for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += p.n_add.n[b];
   return TKV_OK;
 }
