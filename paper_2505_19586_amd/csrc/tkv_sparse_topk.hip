@@ -411,7 +411,11 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     auto fetch = [&](int i0, uint2 (&r)[R]) {
       const __half* kp = local0;
       const __half* vp = local0 + TKV_D;
-      {
+      if (i0 >= n_sk && i0 + R <= n_sk + cnt) {  // (uniform) the common pass: selected tokens only, rows of the host cache
+        const int tok = sel[i0 - n_sk + (lane < R ? lane : 0)];
+        kp = p.att_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D;
+        vp = kp + TKV_D;
+      } else {
         const int i = i0 + lane;
         if (lane < R && i < n_att) {
           int tok;
@@ -442,6 +446,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     // The rows of the next pass are requested before this pass is worked on: a wave that has
     // nothing in flight while it computes leaves the host link idle for that long.
     uint2 r[R], r_next[R];
+    TKV_PH(4);
     if (wave * R < n_att) fetch(wave * R, r);
     for (int i0 = wave * R; i0 < n_att; i0 += kWavesPerBlock * R) {
       const bool more = i0 + kWavesPerBlock * R < n_att;
@@ -526,7 +531,9 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
         for (int y = 0; y < R; ++y) r[y] = r_next[y];
       }
     }
+    TKV_PH(5);
     __syncthreads();  // the list area is free: the waves' results meet there
+    TKV_PH(6);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       float* dst = mrg + (wave * 4 + j) * (TKV_D + 4);
