@@ -403,7 +403,8 @@ typedef struct {
   int32_t batch;
 } tkv_pref_desc;
 
-/* Workspace bytes of tkv_dense_preference (grows with capacity * n_q * Hq / Hkv). */
+/* Workspace bytes of tkv_dense_preference: n_q * Hq rows, each with room for
+ * min(capacity, 32 * top_k) candidate logits and capacity / 32 partial maxima. */
 int32_t tkv_dense_preference_sizes(const tkv_pref_desc* desc, size_t* workspace_bytes);
 
 /*
@@ -412,10 +413,15 @@ int32_t tkv_dense_preference_sizes(const tkv_pref_desc* desc, size_t* workspace_
  *     mask), P = n_q - sum over the rows of their top_k largest entries (Eq. 7, 8).
  * q_last: fp16 [B][n_q][Hq][128] (device), the n_q most recent query vectors of the prompt;
  * k: fp16 [B][n][Hkv][128] (device), the prompt's keys (the layout of the append calls);
- * query head j reads KV head j / (Hq/Hkv).  p_out: float32 [B][Hq] (device).
- * Logits are float32 (fp16 products accumulated in float32); the Top-K of a row is exact on
- * those logits (ties: lower index).  workspace: ZERO-FILLED before its first use, left
- * consistent by every call; concurrent calls need separate workspaces.
+ * query head j reads KV head j / (Hq/Hkv), any group size.  p_out: float32 [B][Hq] (device).
+ * sm_scale > 0 (TKV_E_INVAL otherwise).
+ * Logits are float32 (fp16 products accumulated in float32) and are never written to memory:
+ * they are computed twice, once for a per-row lower bound of the top_k-th largest logit and
+ * once for the softmax denominator and the logits above that bound, among which the top_k
+ * largest are then selected exactly; the mass of a row's top_k entries does not depend on how
+ * ties are broken.  The result is the same bit for bit from call to call.  workspace:
+ * ZERO-FILLED before its first use, left consistent by every call; concurrent calls need
+ * separate workspaces.  Sequences of a batch are processed one after the other.
  */
 int32_t tkv_dense_preference(const tkv_pref_desc* desc, const void* q_last, const void* k, int32_t n,
                              float sm_scale, float* p_out, void* workspace, size_t workspace_bytes,

@@ -28,8 +28,6 @@
 // (resident channel-major keys), and the decode step's cache update (Eq. 2) by one more
 // workgroup per head.  The counters in the workspace must be zero before the first call; every
 // call leaves them zero.
-// prescored + select: the same selection in two launches for scores that already exist (rows
-// of attention logits for the dense preference score): keys go through the workspace there.
 // Inside a launch, data crosses workgroups only through device-scope stores, loads and
 // atomics, ordered by waiting for them to complete before an arrival counter is bumped.
 #include <type_traits>
@@ -49,10 +47,7 @@ constexpr int kMaxTpw = kSub * kThreads;  // most tokens a workgroup owns (see t
 constexpr int kPrefixBits = 13;
 constexpr int kBins = 1 << kPrefixBits;  // 8192
 constexpr int kLowBits = 32 - kPrefixBits;  // 19
-constexpr uint32_t kLowMask = (1u << kLowBits) - 1u;
 constexpr int kListCap = 8192;  // candidate entries kept in LDS; further ones go to the workspace
-constexpr int kScoreLds = kBins * 4;
-constexpr int kSelectLds = 1024 * 4 + kListCap * 8;
 // fused kernel: local / head histogram, list offsets, list (the channel-major variant also
 // stages its keys there to put them into token order)
 constexpr int kFusedLds = kBins * 4 + 1024 * 4 + kListCap * 8;
@@ -122,54 +117,6 @@ __device__ inline uint32_t rank_in(unsigned long long mask) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Finds, in a histogram of kBins counts where larger bin = larger key, the bin that holds the
-// k-th largest key: `above` keys lie in higher bins, above < k <= above + count[bin].  Two
-// levels: every thread sums its kBins / kThreads bins into `part` (kThreads words of LDS), the
-// first wave scans those sums (16 per lane) and walks down into the one thread's bins.
-// Result valid in every thread.  scratch holds kWavesPerBlock + 2 words.
-__device__ inline void find_bin(const uint32_t* hist, uint32_t k, uint32_t* part, uint32_t* scratch, uint32_t& bin,
-                                uint32_t& above) {
-  const int tid = threadIdx.x;
-  constexpr int per = kBins / kThreads;       // bins per thread
-  constexpr int per_lane = kThreads / 64;     // thread sums per lane of the first wave
-  uint32_t local = 0;
-#pragma unroll
-  for (int i = 0; i < per; ++i) local += hist[tid * per + i];
-  part[tid] = local;
-  __syncthreads();
-  if (tid < 64) {
-    uint32_t mine = 0;
-    for (int i = 0; i < per_lane; ++i) mine += part[tid * per_lane + i];
-    uint32_t incl = mine;  // keys in this lane's bins and in those of higher lanes
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_down(incl, d, 64);
-      if (tid + d < 64) incl += o;
-    }
-    const uint32_t excl = incl - mine;
-    if (excl < k && k <= incl) {  // exactly one lane
-      uint32_t run = excl;
-      int t = tid * per_lane + per_lane - 1;  // thread whose bins hold the k-th key
-      for (; t > tid * per_lane; --t) {
-        const uint32_t c = part[t];
-        if (run + c >= k) break;
-        run += c;
-      }
-      int bsel = t * per + per - 1;
-      for (; bsel > t * per; --bsel) {
-        const uint32_t c = hist[bsel];
-        if (run + c >= k) break;
-        run += c;
-      }
-      scratch[kWavesPerBlock] = (uint32_t)bsel;
-      scratch[kWavesPerBlock + 1] = run;
-    }
-  }
-  __syncthreads();
-  bin = scratch[kWavesPerBlock];
-  above = scratch[kWavesPerBlock + 1];
-}
-
 // Inclusive prefix sum over the lanes of a wave (lane l gets the sum of lanes 0..l), on the
 // data-parallel-primitive cross-lane paths (no LDS traffic).
 #define TKV_DPP_ADD(v, ctrl, rows) \
@@ -192,7 +139,8 @@ __device__ inline float swap_xor(float v) {
 }
 __device__ inline uint32_t read_lane(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
 
-// find_bin on counts held in registers: thread t owns the PER bins PER * kThreads - 1 -
+// Finds the bins that hold given ranks of the keys (rank r: the r-th largest), from bin counts
+// held in registers: thread t owns the PER bins PER * kThreads - 1 -
 // (PER * t + i), i = 0 .. PER - 1 (descending keys), count c[i].  Up to NR ranks at once (rank
 // 0: skipped, result bin 0).  res: 2 * NR words of LDS that receive (bin, keys in higher bins)
 // per rank; wtot: kWavesPerBlock words of LDS.  Two barriers; results valid in every thread.
@@ -277,40 +225,6 @@ __device__ inline void subtile_offsets2(const unsigned long long (&ma)[kSub], co
       if (which) before_b[j] = v; else before_a[j] = v;
     }
   }
-}
-
-// find_bin for at most 1024 bins by the first wave alone (lane l owns the bins [l * per,
-// (l + 1) * per), per = nbins / 64): one barrier instead of four.  The histogram must be
-// complete (barrier before the call); the result is valid in every thread after the call.
-__device__ inline void find_bin_wave(const uint32_t* hist, int nbins, uint32_t k, uint32_t* scratch, uint32_t& bin,
-                                     uint32_t& above) {
-  const int tid = threadIdx.x;
-  if (tid < 64) {
-    const int per = nbins / 64;  // 8 or 16
-    uint32_t local = 0;
-    for (int i = 0; i < per; ++i) local += hist[tid * per + i];
-    uint32_t incl = local;  // keys in this lane's bins and in those of higher lanes
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_down(incl, d, 64);
-      if (tid + d < 64) incl += o;
-    }
-    const uint32_t excl = incl - local;
-    if (excl < k && k <= incl) {  // exactly one lane
-      uint32_t run = excl;
-      int bsel = tid * per + per - 1;
-      for (; bsel > tid * per; --bsel) {
-        const uint32_t c = hist[bsel];
-        if (run + c >= k) break;
-        run += c;
-      }
-      scratch[kWavesPerBlock] = (uint32_t)bsel;
-      scratch[kWavesPerBlock + 1] = run;
-    }
-  }
-  __syncthreads();
-  bin = scratch[kWavesPerBlock];
-  above = scratch[kWavesPerBlock + 1];
 }
 
 // Cache update (Eq. 2) of one KV head by one workgroup: host rows, resident sink / window rows,
@@ -1058,248 +972,6 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   }
 }
 
-// The scoring launch for scores that already exist (float32 [rows][pre_stride], row = blockIdx.y):
-// keys, histogram and local bound exactly as in score_kernel.  Used by the dense preference
-// score (Sec. 4.1), whose rows are attention logits.
-__global__ __launch_bounds__(kThreads) void prescored_kernel(TopkParams p, const float* pre, size_t pre_stride) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
-  __shared__ uint32_t scratch[kWavesPerBlock + 8];
-  __shared__ uint32_t part[kThreads];  // per-thread bin sums of find_bin
-  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int n = p.lens.n[b];
-  const size_t bh = (size_t)b * p.hkv + h;
-  const int t0 = blockIdx.x * p.tpw;
-  if (t0 >= n) return;
-  const int t_end = min(n, t0 + p.tpw);
-  int lo, hi;
-  candidate_range(p, n, lo, hi);
-  const uint32_t k = (uint32_t)min(p.top_k, hi - lo);
-  for (int i = tid; i < kBins; i += kThreads) hist[i] = 0u;
-  __syncthreads();
-  const float* row = pre + bh * pre_stride;
-  uint32_t* keys = p.ws.keys + bh * p.capacity;
-  for (int t = t0 + tid; t < t_end; t += kThreads) {
-    uint32_t key = 0u;
-    if (t >= lo && t < hi) {
-      key = score_key(row[t] + 0.0f);
-      atomicAdd(&hist[key >> kLowBits], 1u);
-    }
-    keys[t] = key;
-  }
-  __syncthreads();
-  uint32_t first_bin = 0;
-  {
-    const int c_lo = max(lo, t0), c_hi = min(hi, t_end);
-    if (c_hi - c_lo >= (int)k && k > 0) {
-      uint32_t above_unused;
-      find_bin(hist, k, part, scratch, first_bin, above_unused);
-    }
-  }
-  uint32_t* gh = p.ws.hist + bh * kBins;
-  for (int i = tid; i < kBins; i += kThreads)
-    if (i >= (int)first_bin && hist[i]) atomicAdd(&gh[i], hist[i]);
-}
-
-__global__ __launch_bounds__(kThreads) void select_kernel(TopkParams p) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                // 1024 words
-  uint2* list_s = reinterpret_cast<uint2*>(smem + 1024 * 4);         // kListCap entries
-  __shared__ uint32_t scratch[kWavesPerBlock + 8];
-  __shared__ uint32_t s_cnt[kSub][kWavesPerBlock];
-  const int b = blockIdx.z, h = blockIdx.y, tid = threadIdx.x;
-  const int lane = tid % 64, wave = tid / 64;
-  const int n = p.lens.n[b];
-  const size_t bh = (size_t)b * p.hkv + h;
-  int32_t* out = p.topk_idx + bh * p.top_k;
-  int lo, hi;
-  candidate_range(p, n, lo, hi);
-  const uint32_t k = (uint32_t)min(p.top_k, hi - lo);
-  if (k == 0) {  // nothing to select: the first workgroup reports the empty result
-    if (blockIdx.x == 0) {
-      for (int i = tid; i < p.top_k; i += kThreads) out[i] = -1;
-      if (tid == 0) p.topk_count[bh] = 0;
-    }
-    return;
-  }
-  const int t0 = blockIdx.x * p.tpw;
-  if (t0 >= n) return;
-  TKV_PH(3);
-  const int t_end = min(n, t0 + p.tpw);
-  const int nsub = (t_end - t0 + kThreads - 1) / kThreads;  // <= kSub
-  uint32_t* ctrl = p.ws.ctrl + bh * kCtrlWords;
-  uint32_t* gh = p.ws.hist + bh * kBins;
-  const uint32_t* keys = p.ws.keys + bh * p.capacity;
-  uint2* list_g = p.ws.cand + bh * p.ws.cand_stride;  // workgroup x owns entries [x * tpw, +tpw)
-  uint32_t* cnt_g = p.ws.blk + bh * p.ws.nblk_cap;
-  const int nblk = (n + p.tpw - 1) / p.tpw;
-
-  // ---- bin of the head's k-th key, found by every workgroup for itself from the head's
-  // histogram (complete for every bin that can matter: see the scoring kernel); the keys of
-  // this workgroup are requested in the same round
-  uint32_t kb[kSub];
-#pragma unroll
-  for (int j = 0; j < kSub; ++j) {  // sub-tile j, element tid: token order = (j, tid)
-    const int t = t0 + j * kThreads + tid;
-    kb[j] = (j < nsub && t < t_end) ? keys[t] : 0u;
-  }
-  uint32_t bin, above;
-  {
-    uint32_t* h8 = reinterpret_cast<uint32_t*>(list_s);  // the list area is not in use yet
-    uint32_t hv[kBins / kThreads];
-#pragma unroll
-    for (int x = 0; x < kBins / kThreads; ++x) hv[x] = ld_agent(&gh[x * kThreads + tid]);
-#pragma unroll
-    for (int x = 0; x < kBins / kThreads; ++x) h8[x * kThreads + tid] = hv[x];
-    __syncthreads();
-    find_bin(h8, k, hist, scratch, bin, above);  // hist: not in use yet
-  }
-  TKV_PH(4);
-
-  // ---- this workgroup's tokens in or above the bin, in token order
-  {
-    unsigned long long mask[kSub];
-#pragma unroll
-    for (int j = 0; j < kSub; ++j) {
-      mask[j] = __builtin_amdgcn_ballot_w64(kb[j] != 0u && (kb[j] >> kLowBits) >= bin);
-      if (lane == 0) s_cnt[j][wave] = (uint32_t)__builtin_popcountll(mask[j]);
-    }
-    __syncthreads();
-    uint32_t run = 0;  // entries of earlier sub-tiles
-#pragma unroll
-    for (int j = 0; j < kSub; ++j) {
-      if (j >= nsub) break;
-      uint32_t before = 0, all = 0;
-      for (int w = 0; w < kWavesPerBlock; ++w) {
-        const uint32_t c = s_cnt[j][w];
-        before += w < wave ? c : 0u;
-        all += c;
-      }
-      if ((mask[j] >> lane) & 1ull) {
-        uint2* e = &list_g[(size_t)t0 + run + before + rank_in(mask[j])];
-        st_agent(&e->x, kb[j]);
-        st_agent(&e->y, (uint32_t)(t0 + j * kThreads + tid));
-      }
-      run += all;
-    }
-    if (tid == 0) st_agent(&cnt_g[blockIdx.x], run);
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  if (tid == 0) scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone2], 1u) == (uint32_t)nblk - 1u;
-  __syncthreads();
-  TKV_PH(5);
-  if (!scratch[kWavesPerBlock + 2]) return;
-  // every workgroup has read the histogram: leave it and the counter zero for the next call
-  if (tid == 0) st_agent(&ctrl[kDone2], 0u);
-  for (int i = tid; i < kBins; i += kThreads) st_agent(&gh[i], 0u);
-  for (int i = (int)k + tid; i < p.top_k; i += kThreads) out[i] = -1;
-  if (tid == 0) p.topk_count[bh] = (int32_t)k;
-
-  // ---- the head's last workgroup: concatenate the lists (wave w copies those of workgroups
-  // w, w + 16, ...).  Entry i of the concatenation lives in LDS if i < kListCap, else it is
-  // read from its workgroup's list in the workspace.
-  uint32_t* offs = hist;  // list offsets of the workgroups (the entry point launches < 1024), then the total
-  for (int x = tid; x <= nblk; x += kThreads) offs[x] = 0u;
-  __shared__ uint32_t h2[1024], h3[512];  // radix-select histograms (below)
-  for (int i = tid; i < 1024; i += kThreads) h2[i] = 0u;
-  for (int i = tid; i < 512; i += kThreads) h3[i] = 0u;
-  __syncthreads();
-  if (tid < 64) {  // exclusive scan of the counts by one wave
-    uint32_t carry = 0;
-    for (int x0 = 0; x0 < nblk; x0 += 64) {
-      const int x = x0 + tid;
-      const uint32_t c = x < nblk ? ld_agent(&cnt_g[x]) : 0u;
-      uint32_t incl = c;
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(incl, d, 64);
-        if (tid >= d) incl += o;
-      }
-      if (x < nblk) offs[x] = carry + incl - c;
-      carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-    }
-    if (tid == 0) offs[nblk] = carry;
-  }
-  __syncthreads();
-  const uint32_t M = offs[nblk];
-  for (int x = wave; x < nblk; x += kWavesPerBlock) {
-    const uint32_t o = offs[x], c = offs[x + 1] - o;
-    for (uint32_t i = lane; i < c; i += 64) {
-      if (o + i < (uint32_t)kListCap) {
-        const uint2* e = &list_g[(size_t)x * p.tpw + i];
-        list_s[o + i] = make_uint2(ld_agent(&e->x), ld_agent(&e->y));
-      }
-    }
-  }
-  auto get = [&](uint32_t i) -> uint2 {
-    if (i < (uint32_t)kListCap) return list_s[i];
-    int x0 = 0, x1 = nblk;  // workgroup whose list holds entry i: offs[x0] <= i < offs[x0 + 1]
-    while (x1 - x0 > 1) {
-      const int mid = (x0 + x1) / 2;
-      if (offs[mid] <= i) x0 = mid; else x1 = mid;
-    }
-    const uint2* e = &list_g[(size_t)x0 * p.tpw + (i - offs[x0])];
-    return make_uint2(ld_agent(&e->x), ld_agent(&e->y));
-  };
-  __syncthreads();
-  TKV_PH(6);
-  uint32_t k_rem = k - above;  // 1 <= k_rem <= keys in the bin
-
-  // ---- exact threshold inside the bin: radix select on the low 19 key bits (10 + 9).  The two
-  // histograms were cleared before the concatenation; each search is done by one wave.
-  for (uint32_t i = tid; i < M; i += kThreads) {
-    const uint32_t key = get(i).x;
-    if ((key >> kLowBits) == bin) atomicAdd(&h2[(key & kLowMask) >> 9], 1u);
-  }
-  __syncthreads();
-  uint32_t d1, a1;
-  find_bin_wave(h2, 1024, k_rem, scratch, d1, a1);
-  k_rem -= a1;
-  for (uint32_t i = tid; i < M; i += kThreads) {
-    const uint32_t key = get(i).x;
-    if ((key >> kLowBits) == bin && ((key & kLowMask) >> 9) == d1) atomicAdd(&h3[key & 0x1FFu], 1u);
-  }
-  __syncthreads();
-  uint32_t d2, a2;
-  find_bin_wave(h3, 512, k_rem, scratch, d2, a2);
-  const uint32_t take = k_rem - a2;                       // keys equal to T that are selected (lowest indices)
-  const uint32_t T = (bin << kLowBits) | (d1 << 9) | d2;  // threshold key
-
-  // ---- ordered compaction of the list: every key above T, and the first `take` equal to T
-  uint32_t gt_run = 0, eq_run = 0;
-  for (uint32_t base = 0; base < M; base += kThreads) {
-    const uint32_t i = base + tid;
-    uint2 e = make_uint2(0u, 0u);
-    if (i < M) e = get(i);
-    const bool gt = e.x > T, eq = e.x == T;  // T != 0: every real key has a non-zero prefix
-    const unsigned long long mg = __builtin_amdgcn_ballot_w64(gt), me = __builtin_amdgcn_ballot_w64(eq);
-    const int set = (int)((base / kThreads) & 1u) * 2;  // alternate the count rows: one barrier per tile
-    if (lane == 0) {
-      s_cnt[set][wave] = (uint32_t)__builtin_popcountll(mg);
-      s_cnt[set + 1][wave] = (uint32_t)__builtin_popcountll(me);
-    }
-    __syncthreads();
-    uint32_t pg = 0, pe = 0, tg = 0, te = 0;
-    for (int w = 0; w < kWavesPerBlock; ++w) {
-      const uint32_t cg = s_cnt[set][w], ce = s_cnt[set + 1][w];
-      pg += w < wave ? cg : 0u;
-      pe += w < wave ? ce : 0u;
-      tg += cg;
-      te += ce;
-    }
-    const uint32_t my_gt = gt_run + pg + rank_in(mg), my_eq = eq_run + pe + rank_in(me);
-    if (gt) {
-      out[my_gt + min(my_eq, take)] = (int32_t)e.y;
-    } else if (eq && my_eq < take) {
-      out[my_gt + my_eq] = (int32_t)e.y;
-    }
-    gt_run += tg;
-    eq_run += te;
-  }
-  TKV_PH(7);
-}
-
 }  // namespace
 
 #ifdef TKV_PHASE
@@ -1531,42 +1203,3 @@ extern "C" int32_t tkv_sparse_decode(const tkv_sparse_desc* d, tkv_sparse_cache*
     for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] -= app.app_add.n[b];
   return st;
 }
-
-namespace tkv {
-// Exact Top-K (ties to the lower index, ascending output, -1 padding) of every row of a float32
-// score matrix [n_rows][stride] over columns [0, n): the selection machinery of
-// tkv_sparse_estimate_topk on scores that already exist.  ws: carve_sparse_ws of a descriptor
-// with batch 1, n_rows KV heads and capacity >= n; zero-filled before first use.
-int32_t topk_of_scores(const float* scores, size_t stride, int n_rows, int n, int top_k, int capacity, SparseWs ws,
-                       int32_t* topk_idx, int32_t* topk_count, hipStream_t s) {
-  if (n_rows < 1 || n_rows > 65535 || n < 0 || n > capacity || top_k < 1 || top_k > 4096) return TKV_E_INVAL;
-  TopkParams p = {};
-  p.summary = nullptr;
-  p.rows_per_head = 0;
-  p.channel_idx = nullptr;
-  p.q = nullptr;
-  p.topk_idx = topk_idx;
-  p.topk_count = topk_count;
-  p.ws = ws;
-  p.hq = n_rows;
-  p.hkv = n_rows;
-  p.top_k = top_k;
-  p.n_sink = 0;
-  p.n_window = 0;
-  p.capacity = capacity;
-  p.lens.n[0] = n;
-  p.app_k = nullptr;
-  // many rows: as few workgroups per row as the kernels allow (their fixed cost dominates)
-  p.tpw = kMaxTpw;
-  int nblk = (n + p.tpw - 1) / p.tpw;
-  if (nblk < 1) nblk = 1;
-  if (nblk >= 1024) return TKV_E_UNSUPPORTED;
-  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLds) == hipSuccess;
-  if (!lds_ok) return TKV_E_HIP;
-  const dim3 grid(nblk, n_rows, 1);
-  TKV_LAUNCH(prescored_kernel, grid, kThreads, kScoreLds, s, p, scores, stride);
-  TKV_LAUNCH(select_kernel, grid, kThreads, kSelectLds, s, p);
-  return TKV_OK;
-}
-}  // namespace tkv

@@ -60,6 +60,53 @@ def test_closed_forms_on_the_gpu():
     assert np.abs(got).max() <= 1e-4
 
 
+def test_logits_sorted_along_the_sequence():
+    """Every query's logit grows with the token index, so a row's top-k keys are its last k
+    tokens: they sit in a few adjacent chunks, far more of them in one workgroup's share than its
+    per-row list holds (the path that appends straight to memory), and the lower bound from
+    the block maxima is at its loosest."""
+    n, n_q, k = 20000, 16, 512
+    rng = np.random.default_rng(7)
+    u = rng.standard_normal((8, 1, 128))
+    u /= np.linalg.norm(u, axis=-1, keepdims=True)
+    ramp = (np.arange(n, dtype=np.float64) / n)[None, :, None]
+    keys = (6.0 * ramp * u).astype(np.float16)
+    q_last = (4.0 * np.repeat(u[:, 0], 4, axis=0)[None] + 0.05 * rng.standard_normal((n_q, 32, 128))).astype(np.float16)
+    _, got, want = _run(q_last, keys, k)
+    print(f"   max |P - P_oracle| = {np.abs(got - want).max():.2e} (P {want.min():.3f} .. {want.max():.3f})", flush=True)
+    assert np.abs(got - want).max() <= 1e-4 * n_q
+    _, got, want = _run(q_last, keys[:, ::-1].copy(), k)        # and falling
+    assert np.abs(got - want).max() <= 1e-4 * n_q
+
+
+def test_few_distinct_logit_values():
+    """Keys drawn from three vectors per head: every row has three distinct logits with
+    thousands of ties each; the top-k boundary falls inside a tie class (its mass is shared out
+    by count), above it, or exactly on its edge."""
+    n, n_q = 6000, 16
+    rng = np.random.default_rng(8)
+    base = rng.standard_normal((8, 3, 128)).astype(np.float16)
+    which = rng.choice(3, size=n, p=[0.7, 0.2, 0.1])
+    keys = base[:, which]
+    q_last = rng.standard_normal((n_q, 32, 128)).astype(np.float16)
+    counts = np.bincount(which, minlength=3)
+    for k in (50, int(counts[2]), int(counts[2]) + 1, int(counts[1] + counts[2]), 3000):
+        _, got, want = _run(q_last, keys, k)
+        assert np.abs(got - want).max() <= 1e-4 * n_q, k
+
+
+def test_groups_of_eight_and_many_rows():
+    """Eight query heads per KV head, and n_q = 256 (1024 or 2048 rows per KV head: several slabs
+    of 256 rows)."""
+    rng = np.random.default_rng(9)
+    for hq, hkv, n_q, n, k in ((16, 2, 256, 3000, 200), (8, 1, 48, 5000, 1000), (4, 4, 256, 2500, 64)):
+        qs = rng.standard_normal((n_q, hq, 128)).astype(np.float16)
+        ks = (rng.standard_normal((hkv, n, 128)) * 1.5).astype(np.float16)
+        _, got, want = _run(qs, ks, k, shape=(hq, hkv))
+        print(f"   Hq={hq} Hkv={hkv} n_q={n_q}: max |P - P_oracle| = {np.abs(got - want).max():.2e}", flush=True)
+        assert np.abs(got - want).max() <= 1e-4 * n_q
+
+
 def test_other_head_groupings_and_batch():
     shape = HeadShape(16, 8, 128)
     n, n_q, top_k = 1500, 32, 100
