@@ -197,32 +197,55 @@ __global__ __launch_bounds__(kThreads) void pref_pass_kernel(PrefParams p) {
       }
       return;
     }
-    // PASS 2.  Few logits reach L (about one in a hundred): most of the time no lane of the wave
-    // has one.
+    // PASS 2.  About one logit in a hundred reaches L: a wave sees a few per tile, a lane almost
+    // never more than one.  One test per lane and tile (is its largest logit of a row at or above
+    // the row's L?), and only the lanes that pass look at their logits one by one.
+    bool any = false;
 #pragma unroll
     for (int qt = 0; qt < kQT; ++qt) {
       if (!FULL && qt >= nqt) continue;
+      float mx = -INFINITY;
 #pragma unroll
       for (int x = 0; x < 4; ++x) {
         const float v = acc[qt][x];
         const bool valid = FULL || key0 + 4 * kb + x < p.n;
         den[qt] += valid ? __builtin_amdgcn_exp2f(fmaf(v, p.scale2, mrow[qt])) : 0.f;
-        const bool hit = valid && v >= L[qt];
-        if (__builtin_amdgcn_ballot_w64(hit) != 0) {
-          if (hit) {
-            const int rl = g * (16 * kQT) + 16 * qt + col;
-            if (v > L[qt]) {
-              const uint32_t slot = lds_inc(&lcnt[rl]);
-              if (slot < (uint32_t)kListCap) {
-                llist[rl * kListCap + slot] = v;
-              } else {
-                const size_t gr = (size_t)h * R + slab * kSlabRows + rl;
-                const uint32_t gs = atomicAdd(&p.cursor[gr * 2], 1u);
-                if (gs < (uint32_t)p.cand_cap) p.cand[gr * p.cand_cap + gs] = v;
-              }
+        mx = max_f32(mx, valid ? v : -INFINITY);
+      }
+      any = any || mx >= L[qt];
+    }
+    if (__builtin_amdgcn_ballot_w64(any) != 0) {
+      if (any) {
+        uint32_t hits = 0;
+#pragma unroll
+        for (int qt = 0; qt < kQT; ++qt) {
+          if (!FULL && qt >= nqt) continue;
+#pragma unroll
+          for (int x = 0; x < 4; ++x)
+            hits |= ((FULL || key0 + 4 * kb + x < p.n) && acc[qt][x] >= L[qt]) ? 1u << (4 * qt + x) : 0u;
+        }
+        while (hits != 0) {
+          const int idx = __builtin_ctz(hits);
+          hits &= hits - 1;
+          float v = acc[0][0];
+#pragma unroll
+          for (int j = 1; j < 4 * kQT; ++j) v = idx == j ? acc[j / 4][j % 4] : v;
+          const int qt = idx >> 2;
+          float lq = L[0];
+#pragma unroll
+          for (int j = 1; j < kQT; ++j) lq = qt == j ? L[j] : lq;
+          const int rl = g * (16 * kQT) + 16 * qt + col;
+          if (v > lq) {
+            const uint32_t slot = lds_inc(&lcnt[rl]);
+            if (slot < (uint32_t)kListCap) {
+              llist[rl * kListCap + slot] = v;
             } else {
-              lds_inc(&leq[rl]);
+              const size_t gr = (size_t)h * R + slab * kSlabRows + rl;
+              const uint32_t gs = atomicAdd(&p.cursor[gr * 2], 1u);
+              if (gs < (uint32_t)p.cand_cap) p.cand[gr * p.cand_cap + gs] = v;
             }
+          } else {
+            lds_inc(&leq[rl]);
           }
         }
       }
