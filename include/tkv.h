@@ -27,7 +27,10 @@
  *     arrays; kernels receive them by value, so the arrays may be changed as soon as
  *     a call returns.  At most TKV_MAX_BATCH sequences per call.
  *   - fp16 is IEEE binary16 everywhere.  head_dim must be 128, the quantization
- *     group g 32 or 64, n_q_heads / n_kv_heads one of 1, 2, 4.
+ *     group g 32 or 64.  n_q_heads / n_kv_heads: any number from 1 to 8 for quantized
+ *     layers (the attention kernels take a group 4 query heads at a time; the parts of a
+ *     group of 5 to 8 read the codes once each); 1, 2 or 4 for sparse layers and their
+ *     Stage 1; any number for the dense preference score.
  *   - Token t of sequence b, KV head h.  "group j" is tokens [g j, g j + g); codes are
  *     stored in "blocks" of 32 tokens whatever g is.
  */
@@ -173,7 +176,8 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
  * counters live in a fixed device array inside the library image
  * (TKV_STATIC_MAX_HEADS * 4 + TKV_STATIC_PARTS_BYTES bytes on every GPU the library runs on,
  * held until the process ends).  The call allocates nothing and frees nothing.
- * Limits: batch * n_kv_heads <= TKV_STATIC_MAX_HEADS and the launch's partials
+ * Limits: batch * n_kv_heads (twice that for groups of more than 4 query heads) <=
+ * TKV_STATIC_MAX_HEADS and the launch's partials
  * (batch * n_q_heads * chunks * 528 bytes; chunks is about compute units / (batch * n_kv_heads),
  * at most 64) must fit in TKV_STATIC_PARTS_BYTES, else TKV_E_WORKSPACE and nothing is enqueued.
  * Batch 1 to 64 with 32 query heads fits at every context length.

@@ -55,9 +55,13 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
   __shared__ float red_m[4][4], red_l[4][4];
   __shared__ float red_o[4][4][TKV_D];
 
-  const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x + p.chunk_offset;
+  // Groups of more than 4 query heads per KV head are served 4 heads at a time: blockIdx.y runs
+  // over (KV head, quarter of its group).
+  const int split = (p.hq / p.hkv + 3) / 4;
+  const int b = blockIdx.z, h = blockIdx.y / split, chunk = blockIdx.x + p.chunk_offset;
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
-  const int G = p.hq / p.hkv;
+  const int qh0 = h * (p.hq / p.hkv) + 4 * (blockIdx.y % split);  // first query head of this workgroup
+  const int G = min(4, (h + 1) * (p.hq / p.hkv) - qh0);
   const int n = p.lens.n[b];
   const int nq = tkv::n_quantized(n, p.residual, p.group);
   const int jq = nq / TKV_BLK;  // packed blocks of 32 tokens
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
 
   for (int i = tid; i < 4 * TKV_D; i += 256) {
     const int hh = i / TKV_D, c = i % TKV_D;
-    qs[hh][c] = hh < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c]) : 0.f;
+    qs[hh][c] = hh < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)qh0 + hh) * TKV_D + c]) : 0.f;
   }
   __syncthreads();
 
@@ -215,7 +219,7 @@ __global__ __launch_bounds__(256) void quant_attn_generic_kernel(QuantAttnParams
       L += red_l[w][hh] * wgt;
       O += red_o[w][hh][c] * wgt;
     }
-    float* dst = p.parts + (((size_t)b * p.hq + (size_t)h * G + hh) * n_parts + chunk) * TKV_PART_STRIDE;
+    float* dst = p.parts + (((size_t)b * p.hq + (size_t)qh0 + hh) * n_parts + chunk) * TKV_PART_STRIDE;
     dst[TKV_PART_O + c] = O;
     if (c == 0) {
       dst[0] = M;
@@ -284,7 +288,7 @@ extern "C" int32_t tkv_debug_quant_attn_config(int32_t kernel_choice, int32_t ta
 namespace {
 
 // Body of both entry points.  parts: room for parts_floats floats of split-K partials; arrivals:
-// one zero word per (sequence, KV head).  TKV_E_WORKSPACE if the launch's partials do not fit.
+// one zero word per (sequence, KV head, four query heads of its group).  TKV_E_WORKSPACE if the launch's partials do not fit.
 int32_t quant_attn_decode_impl(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q, void* out,
                                float sm_scale, float* parts, size_t parts_floats, uint32_t* arrivals,
                                hipStream_t s) {
@@ -342,7 +346,8 @@ int32_t quant_attn_decode_impl(const tkv_quant_desc* d, const tkv_quant_cache* c
   // reference kernel: on request, and for the settings the matrix-core kernel is not built for
   if ((size_t)d->batch * d->n_q_heads * (n_chunks + 1) * TKV_PART_STRIDE > parts_floats) return TKV_E_WORKSPACE;
   p.chunk_offset = 0;
-  TKV_LAUNCH(quant_attn_generic_kernel, dim3(n_chunks + 1, d->n_kv_heads, d->batch), 256, 0, s, p);
+  const int split = (d->n_q_heads / d->n_kv_heads + 3) / 4;
+  TKV_LAUNCH(quant_attn_generic_kernel, dim3(n_chunks + 1, d->n_kv_heads * split, d->batch), 256, 0, s, p);
   return tkv::launch_attn_merge(p.parts, (__half*)out, d->batch * d->n_q_heads, n_chunks + 1, s);
 }
 
@@ -380,7 +385,7 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
 // kernels may use is looked up once per device with that device current.
 namespace {
 
-constexpr size_t kStaticCounterWords = TKV_STATIC_MAX_HEADS;   // one per (sequence, KV head)
+constexpr size_t kStaticCounterWords = TKV_STATIC_MAX_HEADS;   // one per (sequence, KV head, four query heads)
 constexpr size_t kStaticPartsBytes = TKV_STATIC_PARTS_BYTES;
 constexpr size_t kStaticBytes = kStaticCounterWords * sizeof(uint32_t) + kStaticPartsBytes;
 static __device__ __align__(256) unsigned char scratch[kStaticBytes];
@@ -415,7 +420,7 @@ extern "C" int32_t tkv_quant_attn_decode_static(const tkv_quant_desc* d, const t
                                                 void* out, float sm_scale, void* stream) {
   int32_t st = check_decode_args(d, c, q, out);
   if (st != TKV_OK) return st;
-  const int bh = d->batch * d->n_kv_heads;
+  const int bh = d->batch * d->n_kv_heads * ((d->n_q_heads / d->n_kv_heads + 3) / 4);
   if ((size_t)bh > kStaticCounterWords) return TKV_E_WORKSPACE;
   unsigned char* base = nullptr;
   st = static_scratch(&base);

@@ -1,5 +1,5 @@
 // Matrix-core kernel of tkv_quant_attn_decode (Sec. 2.1 Eq. 3 over the quantized cache
-// of Sec. 4.3) for gfx950, G = Hq/Hkv <= 4, D = 128, bits 1, 2 or 4, quantization group 32
+// of Sec. 4.3) for gfx950, 4 query heads of a KV head per workgroup, D = 128, bits 1, 2 or 4, quantization group 32
 // or 64 (Sec. 5.1 runs 1 and 2 bits with groups of 64).
 //
 // One wave64 owns one packed block of 32 tokens at a time (half a key group when the
@@ -52,7 +52,7 @@ struct MfmaParams {
   const __half* v_resid;
   const __half* q;
   float* parts;        // sequence after sequence: [Hq][chunks of the sequence][D + 4]
-  uint32_t* arrivals;  // [B][Hkv], zero between calls
+  uint32_t* arrivals;  // [B][Hkv * quarters of a group], zero between calls
   __half* out;         // [B][Hq][D]
   float scale2;
   int32_t hq, hkv, residual, capacity;
@@ -330,10 +330,15 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
     ++b;
   }
   const int n_chunks = p.chunks.n[b];
-  const int h = blockIdx.y;
+  // Groups of more than 4 query heads per KV head are served 4 heads at a time (the operand
+  // columns hold 4 heads): blockIdx.y runs over (KV head, quarter of its group), and the
+  // quarters of a head read the same codes.
+  const int split = (p.hq / p.hkv + 3) / 4;
+  const int h = blockIdx.y / split;
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);  // wave-uniform: keeps group addresses scalar
-  const int G = p.hq / p.hkv;
+  const int qh0 = h * (p.hq / p.hkv) + 4 * (blockIdx.y % split);  // first query head of this workgroup
+  const int G = min(4, (h + 1) * (p.hq / p.hkv) - qh0);
   const int n = p.lens.n[b];
   const int nq = tkv::n_quantized(n, p.residual, GRP);
   const int jq = nq / TKV_BLK;
@@ -351,7 +356,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
 
   const int slot = lane % 16, rb = lane / 16;
   const int hs = slot % 4, us = slot / 4;  // this lane's operand column: head, column group
-  const __half* qrow = p.q + ((size_t)b * p.hq + (size_t)h * G) * TKV_D;
+  const __half* qrow = p.q + ((size_t)b * p.hq + (size_t)qh0) * TKV_D;
   typedef uint32_t BkArr[2][4][kBkStride];
   uint32_t(*bk_s)[4][kBkStride] = reinterpret_cast<BkArr*>(smem)[wave];
   float* cz_s = reinterpret_cast<float*>(smem + C::oCz);
@@ -822,7 +827,7 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
       const float wgt = s_w[W + w][hh];
       O = __builtin_fmaf(wgt != 0.f ? tail_s[w].o[hh][c] : 0.f, wgt, O);
     }
-    float* dst = p.parts + (((size_t)chunk_base * p.hq + ((size_t)h * G + hh) * n_chunks) + chunk) * TKV_PART_STRIDE;
+    float* dst = p.parts + (((size_t)chunk_base * p.hq + ((size_t)qh0 + hh) * n_chunks) + chunk) * TKV_PART_STRIDE;
     // device-scope stores: visible to the merging workgroup without a cache write-back
     __hip_atomic_store(dst + TKV_PART_O + c, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (c == 0) {
@@ -838,13 +843,14 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   TKV_PH();  // 6 partial written
   __syncthreads();
-  if (tid == 0) s_flag = atomicAdd(&p.arrivals[bh], 1u) == (uint32_t)(n_chunks - 1) ? 1u : 0u;
+  uint32_t* arrival = p.arrivals + (size_t)b * gridDim.y + blockIdx.y;
+  if (tid == 0) s_flag = atomicAdd(arrival, 1u) == (uint32_t)(n_chunks - 1) ? 1u : 0u;
   __syncthreads();
   if (s_flag != 0u) {
-    if (tid == 0) p.arrivals[bh] = 0u;
-    const float* head0 = p.parts + ((size_t)chunk_base * p.hq + (size_t)h * G * n_chunks) * TKV_PART_STRIDE;
+    if (tid == 0) *arrival = 0u;
+    const float* head0 = p.parts + ((size_t)chunk_base * p.hq + (size_t)qh0 * n_chunks) * TKV_PART_STRIDE;
     float* scratch = reinterpret_cast<float*>(smem + C::oRing);  // the waves' results have been consumed
-    tkv::merge_chunks(head0, G, n_chunks, p.out + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, scratch, tid, C::kThreads);
+    tkv::merge_chunks(head0, G, n_chunks, p.out + ((size_t)b * p.hq + (size_t)qh0) * TKV_D, scratch, tid, C::kThreads);
   }
   TKV_PH();  // 7 end
 #ifdef TKV_PHASE
@@ -880,7 +886,6 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
                                float scale2, float* parts, size_t parts_floats, uint32_t* arrivals, int target_blocks,
                                int max_groups, int max_tail, const TkvSeqLens& lens, hipStream_t s) {
   if (d->head_dim != TKV_D) return TKV_E_UNSUPPORTED;
-  if (d->n_q_heads / d->n_kv_heads > 4) return TKV_E_UNSUPPORTED;
   // built: the benchmark's settings (2 and 4 bit, groups of 32) and the paper's (1 and 2 bit, groups of 64)
   const int variant = d->bits * 100 + d->group_size;
   if (variant != 232 && variant != 432 && variant != 164 && variant != 264) return TKV_E_UNSUPPORTED;
@@ -894,9 +899,11 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   (void)max_groups;
   (void)max_tail;
   MfmaParams p;
-  int per_head = (target_blocks + d->n_kv_heads - 1) / d->n_kv_heads;
+  const int split = (d->n_q_heads / d->n_kv_heads + 3) / 4;  // workgroups per KV head and chunk: 4 query heads each
+  const int heads = d->n_kv_heads * split;
+  int per_head = (target_blocks + heads - 1) / heads;
   if (per_head < d->batch) per_head = d->batch;
-  const int chunk_cap = target_blocks > 64 * d->batch * d->n_kv_heads ? TKV_MAX_CHUNKS : 64;
+  const int chunk_cap = target_blocks > 64 * d->batch * heads ? TKV_MAX_CHUNKS : 64;
   long long total_work = 0;
   int work[TKV_MAX_BATCH];
   for (int b = 0; b < d->batch; ++b) {
@@ -965,7 +972,7 @@ int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c
   p.prof = (long long*)g_mfma_prof;
 #endif
   p.lens = lens;
-  const dim3 grid(total_chunks, d->n_kv_heads, 1);
+  const dim3 grid(total_chunks, heads, 1);
   switch (variant) {
     case 232: return launch_variant<2, 1, 12>(p, grid, s);
     case 432: return launch_variant<4, 1, 8>(p, grid, s);

@@ -96,7 +96,8 @@ def test_sparse_sizes(L):
     (dict(bits=3), -2), (dict(bits=8), -2), (dict(bits=0), -1), (dict(head_dim=64), -2), (dict(group_size=16), -2),
     (dict(group_size=128), -2), (dict(group_size=64, residual=96), -1), (dict(group_size=64, capacity=4096 + 32), -1),
     (dict(residual=1024), -2), (dict(bits=1, group_size=64), 0), (dict(bits=1), 0), (dict(bits=4, group_size=64), 0),
-    (dict(n_q_heads=30), -1), (dict(n_q_heads=64), -2), (dict(batch=0), -1), (dict(batch=65), -2),
+    (dict(n_q_heads=30), -1), (dict(n_q_heads=64), 0), (dict(n_q_heads=56), 0), (dict(n_q_heads=72), -2),
+    (dict(batch=0), -1), (dict(batch=65), -2),
     (dict(capacity=100), -1), (dict(residual=100), -1), (dict(residual=0), -2), (dict(capacity=0), -1),
 ])
 def test_quant_desc_errors(L, kw, status):
@@ -117,6 +118,7 @@ def test_bad_struct_size_and_null(L):
 @pytest.mark.parametrize("kw,status", [
     (dict(n_channels=10), -2), (dict(n_channels=12), 0), (dict(n_channels=0), -1), (dict(top_k=0), -1), (dict(top_k=5000), -2),
     (dict(n_window=0), -1), (dict(n_sink=-1), -1), (dict(head_dim=96), -2),
+    (dict(n_q_heads=64), -2), (dict(n_q_heads=24), -2), (dict(n_q_heads=16), 0),   # groups of 1, 2 or 4 only
 ])
 def test_sparse_desc_errors(L, kw, status):
     assert L.tkv_sparse_cache_sizes(C.byref(_sdesc(**kw)), None, None) == status

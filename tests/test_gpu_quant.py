@@ -101,6 +101,44 @@ def test_empty_sequence_gives_zeros():
     assert (out == 0).all()
 
 
+@pytest.mark.parametrize("bits,g", [(2, 32), (4, 32), (1, 64)])
+@pytest.mark.parametrize("shape", [HeadShape(64, 8, 128), HeadShape(56, 8, 128), HeadShape(10, 2, 128),
+                                   HeadShape(6, 1, 128), HeadShape(3, 1, 128)])
+def test_groups_of_up_to_eight_query_heads(shape, bits, g):
+    """Groups of 5 to 8 query heads per KV head are served 4 heads at a time (two workgroups per
+    KV head and chunk); groups of 3 leave a column of the kernel's four unused."""
+    print(f"case quant attention Hq={shape.n_q_heads} Hkv={shape.n_kv_heads} bits={bits} g={g}", flush=True)
+    n = 2500
+    inp = make_layer(n, shape=shape, seq=3)
+    layer = tkv.QuantLayer(n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads, bits=bits, group_size=g,
+                           capacity=2560)
+    layer.append(to_new(inp.k), to_new(inp.v))
+    ref = check_quant_cache(layer, 0, inp.k, inp.v)
+    want = attention.quant_attention(inp.q, ref, SM)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    out = layer.attn_decode(q, SM)
+    assert attn_err(out[0], want) <= TOL
+    out2 = layer.attn_decode(q, SM)              # the arrival counters were left clean
+    assert attn_err(out2[0], want) <= TOL
+    assert attn_err(layer.attn_decode_static(q, SM, torch.empty_like(q))[0], want) <= TOL
+
+
+def test_group_of_eight_ragged_batch_long_context():
+    shape = HeadShape(16, 2, 128)
+    lens = [40000, 9000, 131]
+    layer = tkv.QuantLayer(n_q_heads=16, n_kv_heads=2, bits=2, capacity=40000 + 32, batch=3)
+    inps = [make_layer(n, shape=shape, seq=20 + i) for i, n in enumerate(lens)]
+    k, v = to_new_batch([i.k for i in inps], max(lens)), to_new_batch([i.v for i in inps], max(lens))
+    layer.append(k, v, n_valid=lens)
+    q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
+    out = layer.attn_decode(q, SM)
+    for b, inp in enumerate(inps):
+        ref = check_quant_cache(layer, b, inp.k, inp.v)
+        err = attn_err(out[b], attention.quant_attention(inp.q, ref, SM))
+        print(f"   n={lens[b]} err {err:.3e}", flush=True)
+        assert err <= TOL
+
+
 @pytest.mark.parametrize("shape", [HeadShape(8, 8, 128), HeadShape(16, 8, 128), HeadShape(4, 1, 128)])
 def test_other_head_groupings(shape):
     inp = make_layer(777, shape=shape, seq=8)
