@@ -49,6 +49,8 @@ def parse():
                     help="re-select the critical channels every step (Eq. 10): 'resident' scores in place over "
                          "channel-major keys kept on the GPU, 'host' fetches the critical key cache from a "
                          "pinned-host channel-major copy one layer ahead (the paper's design)")
+    ap.add_argument("--no-warm-next", dest="warm_next", action="store_false",
+                    help="chained schedule: tkv_sparse_decode without the hint that warms up the next layer's key summary")
     ap.add_argument("--identify", action="store_true",
                     help="instead of the decode step, time the offline identification of one layer (dense "
                          "preference score, Sec. 4.1) at --context with 64 query rows per head and k = --top-k")
@@ -445,7 +447,11 @@ def run_step(args, tkv, torch, dev):
                     b.record(); rec["topk"].append((a, b))
                 elif not args.separate_calls:
                     # one launch per sparse layer: append, scoring, Top-K, fetch of the rows, attention
-                    L.decode(qs[l], sm, new_k[l], new_v[l], out=outs[l])
+                    # (the next sparse layer's key summary is read once meanwhile: it does not depend
+                    # on that layer's query, and HBM is idle while this layer waits for the host link)
+                    nxt = layers[l + 1] if args.warm_next and l + 1 < len(layers) else None
+                    L.decode(qs[l], sm, new_k[l], new_v[l], out=outs[l],
+                             warm_next=nxt if isinstance(nxt, tkv.SparseLayer) else None)
                     continue
                 else:                 # the scoring launch also appends the step's new token
                     L.append_estimate_topk(new_k[l], new_v[l], qs[l])

@@ -276,11 +276,19 @@ int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* desc, tkv_sparse_
  * hand-off sits between the selection and the transfer that cannot be hidden.
  * The key summary must be token-major (cache->key_summary).  workspace: as for
  * tkv_sparse_estimate_topk.  seq_len_host[b] += n_valid on success.
+ * next_key_summary: NULL, or the key summary (device, same descriptor, hence same layout as
+ * cache->key_summary) of the layer whose tkv_sparse_decode is the next call on this stream - in a
+ * decoder the next sparsity-friendly layer; a key summary does not depend on its layer's query.
+ * The workgroups that are through with the selection read their own share of it once, while the
+ * heads' last workgroups wait for the host link and HBM is idle: the next launch finds the rows
+ * in the memory-side cache (about 1 us per call at 131072 tokens).  A hint: it is only read, and
+ * no result depends on it.
  */
 int32_t tkv_sparse_decode(const tkv_sparse_desc* desc, tkv_sparse_cache* cache, const void* k_new,
                           const void* v_new, int32_t n_new, const int32_t* n_valid_host, const void* q,
-                          int32_t* topk_idx, int32_t* topk_count, void* out, float sm_scale, void* workspace,
-                          size_t workspace_bytes, void* stream);
+                          int32_t* topk_idx, int32_t* topk_count, void* out, float sm_scale,
+                          const void* next_key_summary, void* workspace, size_t workspace_bytes,
+                          void* stream);
 
 /*
  * Fetch of the Top-K tokens from the host cache (Sec. 4.2; the one transfer that

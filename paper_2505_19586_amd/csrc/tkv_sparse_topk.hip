@@ -85,6 +85,10 @@ struct TopkParams {
   const __half* att_local;
   __half* att_out;          // [B][Hq][D]
   float att_scale2;         // sm_scale * log2(e)
+  // (ATT kernels) the key summary that the stream's next call will sweep, same layout as
+  // `summary`: read once by the workgroups that are through with the selection while the
+  // heads' last workgroups are busy with the host link
+  const __half* pf;
 #ifdef TKV_PHASE
   long long* prof;
 #endif
@@ -696,7 +700,26 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     if (tid == 0) scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone2], 1u) == (uint32_t)nblk - 1u;
     __syncthreads();
     TKV_PH(3);
-    if (!scratch[kWavesPerBlock + 2]) return false;
+    if (!scratch[kWavesPerBlock + 2]) {
+      if (ATT && p.pf != nullptr) {
+        // This workgroup's own share of that summary (the workgroup with the same number will
+        // score it in the next launch): HBM is idle from here on, and the next launch then finds
+        // the rows in the memory-side cache.  Eight 16-byte loads per thread in flight; the
+        // values are only combined so that the loads are not dropped.
+        const uint4* src = reinterpret_cast<const uint4*>(p.pf + (bh * p.capacity + (size_t)t0) * DS);
+        const int n_vec = max(0, t_end - t0) * DS / 8;
+        uint32_t mix = 0;
+        for (int i = tid; i < n_vec; i += 8 * kThreads) {
+          uint4 w[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) w[j] = src[min(i + j * kThreads, n_vec - 1)];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) mix ^= w[j].x ^ w[j].y ^ w[j].z ^ w[j].w;
+        }
+        asm volatile("" ::"v"(mix));
+      }
+      return false;
+    }
 
     // ---- the head's last workgroup.  One round of device-scope loads brings the workgroups'
     // control words and the first `spec` entries of every list (entry e = i * kThreads + tid of
@@ -1086,6 +1109,7 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
     p.att_local = att->att_local;
     p.att_out = att->att_out;
     p.att_scale2 = att->att_scale2;
+    p.pf = att->pf;
     if (d->n_channels == 16) return launch_fused<16, false, true>(p, grid, s);
     if (d->n_channels == 12) return launch_fused<12, false, true>(p, grid, s);
     return launch_fused<8, false, true>(p, grid, s);
@@ -1167,11 +1191,13 @@ extern "C" int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* d, tkv
 extern "C" int32_t tkv_sparse_decode(const tkv_sparse_desc* d, tkv_sparse_cache* c, const void* k_new,
                                      const void* v_new, int32_t n_new, const int32_t* n_valid_host, const void* q,
                                      int32_t* topk_idx, int32_t* topk_count, void* out, float sm_scale,
-                                     void* workspace, size_t workspace_bytes, void* stream) {
+                                     const void* next_key_summary, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
   int32_t st = tkv::check_sparse_desc(d);
   if (st != TKV_OK) return st;
   if (!c || !c->seq_len_host || !c->key_summary || !c->channel_idx || !c->kv_host || !c->kv_local || !out)
     return TKV_E_INVAL;
+  if ((uintptr_t)next_key_summary % 16 != 0) return TKV_E_INVAL;
   if (n_new < 0 || n_new > 8 || n_new > d->n_window) return TKV_E_INVAL;
   if (n_new > 0 && (!k_new || !v_new)) return TKV_E_INVAL;
   TopkParams app, att;
@@ -1195,6 +1221,7 @@ extern "C" int32_t tkv_sparse_decode(const tkv_sparse_desc* d, tkv_sparse_cache*
   att.att_local = (const __half*)c->kv_local;
   att.att_out = (__half*)out;
   att.att_scale2 = sm_scale * 1.44269504088896340736f;
+  att.pf = (const __half*)next_key_summary;
   // the kernels see the lengths after the append
   for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += app.app_add.n[b];
   st = estimate_topk_launch(d, c, q, c->key_summary, 0, c->channel_idx, topk_idx, topk_count, workspace,

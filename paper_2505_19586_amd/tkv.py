@@ -98,7 +98,7 @@ def lib() -> C.CDLL:
         L.tkv_sparse_append_dynamic.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), C.POINTER(SparseStage1),
                                                 vp, vp, i32, C.POINTER(i32), vp]
         L.tkv_sparse_decode.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32, C.POINTER(i32),
-                                        vp, vp, vp, vp, C.c_float, vp, sz, vp]
+                                        vp, vp, vp, vp, C.c_float, vp, vp, sz, vp]
         L.tkv_sparse_append_estimate_topk.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32,
                                                       C.POINTER(i32), vp, vp, vp, vp, sz, vp]
         L.tkv_dense_preference_sizes.argtypes = [C.POINTER(PrefDesc), C.POINTER(sz)]
@@ -318,9 +318,12 @@ class SparseLayer:
         return self.topk_idx, self.topk_count
 
     def decode(self, q: torch.Tensor, sm_scale: float, k_new: torch.Tensor | None = None,
-               v_new: torch.Tensor | None = None, n_valid=None, out: torch.Tensor | None = None, stream=None):
+               v_new: torch.Tensor | None = None, n_valid=None, out: torch.Tensor | None = None, stream=None,
+               warm_next: "SparseLayer | None" = None):
         """tkv_sparse_decode: the step's append (if k_new is given), scoring, Top-K, fetch of the
-        selected rows and attention in one launch."""
+        selected rows and attention in one launch.  warm_next: the sparse layer (same shape) whose
+        decode is the stream's next call: its key summary is read once while this call waits for
+        the host link."""
         d = self.desc
         assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
         assert tuple(q.shape) == (d.batch, d.n_q_heads, d.head_dim)
@@ -335,11 +338,16 @@ class SparseLayer:
                 assert nv.shape == (d.batch,)
         if out is None:
             out = torch.empty_like(q)
+        warm_ptr = None
+        if warm_next is not None:
+            assert bytes(warm_next.desc) == bytes(d), "warm_next must have this layer's descriptor"
+            warm_ptr = warm_next.key_summary.data_ptr()
         _check(lib().tkv_sparse_decode(
             C.byref(d), C.byref(self.cache), kp, vp_, n_new,
             None if nv is None else nv.ctypes.data_as(C.POINTER(C.c_int32)), q.data_ptr(),
             self.topk_idx.data_ptr(), self.topk_count.data_ptr(), out.data_ptr(), float(sm_scale),
-            self.workspace.data_ptr(), self.workspace_bytes, _stream(stream)), "tkv_sparse_decode")
+            warm_ptr, self.workspace.data_ptr(), self.workspace_bytes, _stream(stream)),
+            "tkv_sparse_decode")
         return out
 
     def gather_attn(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor | None = None,

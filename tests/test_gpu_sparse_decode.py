@@ -45,6 +45,15 @@ def test_decode_without_append(n, top_k):
     out2 = layer.decode(q, SM)          # same workspace again: counters were left clean
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    # the hint that warms up the next layer's key summary changes nothing (here: a second layer of
+    # the same shape, whose summary must come through untouched)
+    other = tkv.SparseLayer(top_k=top_k, capacity=max(n, 64) + 37)
+    other.key_summary.view(-1)[:] = 0.5
+    idx0 = layer.topk_idx.clone()
+    out3 = layer.decode(q, SM, warm_next=other)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out3.view(torch.int16)) and torch.equal(idx0, layer.topk_idx)
+    assert bool((other.key_summary == 0.5).all())
 
 
 @pytest.mark.parametrize("n0,steps", [(3000, [1] * 70 + [3, 8, 1]), (0, [1, 1, 2, 8, 1] * 15), (60, [1] * 12)])
