@@ -27,10 +27,11 @@
  *     arrays; kernels receive them by value, so the arrays may be changed as soon as
  *     a call returns.  At most TKV_MAX_BATCH sequences per call.
  *   - fp16 is IEEE binary16 everywhere.  head_dim must be 128, the quantization
- *     group g 32 or 64.  n_q_heads / n_kv_heads: any number from 1 to 8 for quantized
- *     layers (the attention kernels take a group 4 query heads at a time; the parts of a
- *     group of 5 to 8 read the codes once each); 1, 2 or 4 for sparse layers and their
- *     Stage 1; any number for the dense preference score.
+ *     group g 32 or 64.  n_q_heads / n_kv_heads: any number from 1 to 8 (quantized layers:
+ *     the attention kernels take a group 4 query heads at a time, and the parts of a group
+ *     of 5 to 8 read the codes once each; sparse layers: a row is fetched once whatever the
+ *     group, but tkv_sparse_decode is built for groups of up to 4 - TKV_E_UNSUPPORTED above,
+ *     use the separate calls); any number for the dense preference score.
  *   - Token t of sequence b, KV head h.  "group j" is tokens [g j, g j + g); codes are
  *     stored in "blocks" of 32 tokens whatever g is.
  */

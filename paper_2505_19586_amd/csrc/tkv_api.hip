@@ -16,23 +16,19 @@ extern "C" const char* tkv_strerror(int32_t status) {
 
 namespace tkv {
 
-// max_group: largest number of query heads per KV head the path is built for (any number up to
-// it for the quantized path, whose kernels take a group 4 heads at a time; 1, 2 or 4 for the
-// sparse path)
-static int32_t check_heads(int32_t hq, int32_t hkv, int32_t d, int32_t batch, int32_t max_group) {
+// Up to 8 query heads per KV head.
+static int32_t check_heads(int32_t hq, int32_t hkv, int32_t d, int32_t batch) {
   if (hq <= 0 || hkv <= 0 || d <= 0 || batch <= 0) return TKV_E_INVAL;
   if (hq % hkv != 0) return TKV_E_INVAL;
   if (batch > TKV_MAX_BATCH) return TKV_E_UNSUPPORTED;
   if (d != TKV_D) return TKV_E_UNSUPPORTED;
-  const int32_t g = hq / hkv;
-  if (g > max_group) return TKV_E_UNSUPPORTED;
-  if (max_group <= 4 && g != 1 && g != 2 && g != 4) return TKV_E_UNSUPPORTED;
+  if (hq / hkv > 8) return TKV_E_UNSUPPORTED;
   return TKV_OK;
 }
 
 int32_t check_quant_desc(const tkv_quant_desc* d) {
   if (!d || d->struct_size != sizeof(tkv_quant_desc)) return TKV_E_INVAL;
-  int32_t st = check_heads(d->n_q_heads, d->n_kv_heads, d->head_dim, d->batch, 8);
+  int32_t st = check_heads(d->n_q_heads, d->n_kv_heads, d->head_dim, d->batch);
   if (st != TKV_OK) return st;
   if (d->group_size <= 0 || d->residual < 0 || d->capacity <= 0 || d->bits <= 0) return TKV_E_INVAL;
   if (d->bits != 1 && d->bits != 2 && d->bits != 4) return TKV_E_UNSUPPORTED;
@@ -44,7 +40,7 @@ int32_t check_quant_desc(const tkv_quant_desc* d) {
 
 int32_t check_sparse_desc(const tkv_sparse_desc* d) {
   if (!d || d->struct_size != sizeof(tkv_sparse_desc)) return TKV_E_INVAL;
-  int32_t st = check_heads(d->n_q_heads, d->n_kv_heads, d->head_dim, d->batch, 4);
+  int32_t st = check_heads(d->n_q_heads, d->n_kv_heads, d->head_dim, d->batch);
   if (st != TKV_OK) return st;
   if (d->n_channels <= 0 || d->top_k <= 0 || d->n_sink < 0 || d->n_window <= 0 || d->capacity <= 0)
     return TKV_E_INVAL;

@@ -131,20 +131,22 @@ __device__ inline float half_wave_max(float v) {
 constexpr int kRowPitch = 2 * TKV_D * 2 + 16;  // LDS bytes per staged K|V row (padded against bank conflicts)
 
 // Exact attention over sinks + gathered rows + window.  One workgroup of W <= 4 waves
-// handles 32*W attended tokens of one KV head; lane (t, hp) scores token t for query heads
-// 2hp, 2hp+1; then every lane accumulates two output channels.
+// handles 32*W attended tokens of one KV head; lane (t, hp) scores token t for the query heads
+// [GH/2 hp, GH/2 hp + GH/2) of the group (GH = 4, or 8 for groups of 5 to 8 heads); then every
+// lane accumulates two output channels of all heads.
 // FUSED: the selected rows are not read from the staging buffer but fetched by this kernel
 // from pinned host memory (one 512-byte row per load instruction, all 32 rows of a wave in
 // flight) into LDS, so the transfer and the attention are one launch.
-template <bool FUSED>
+template <bool FUSED, int GH>
 __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char rows_s[];  // FUSED: [W][32][kRowPitch]
+  constexpr int HPH = GH / 2;  // heads per half-wave
   __shared__ const __half* src_s[4][32];
-  __shared__ float qs[4][TKV_D];
-  __shared__ float pw[4][4][32];
+  __shared__ float qs[GH][TKV_D];
+  __shared__ float pw[4][GH][32];
   __shared__ const __half* vrow_s[4][32];
-  __shared__ float red_m[4][4], red_l[4][4];
-  __shared__ float red_o[4][4][TKV_D];
+  __shared__ float red_m[4][GH], red_l[4][GH];
+  __shared__ float red_o[4][GH][TKV_D];
   const int b = blockIdx.z, h = blockIdx.y, chunk = blockIdx.x;
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int G = p.hq / p.hkv;
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   const int n_att = n_sk + cnt + (n - w0);
 
   const int nthr = blockDim.x, W = nthr / 64;
-  for (int i = tid; i < 4 * TKV_D; i += nthr) {
+  for (int i = tid; i < GH * TKV_D; i += nthr) {
     const int hh = i / TKV_D, c = i % TKV_D;
     qs[hh][c] = hh < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + hh) * TKV_D + c]) : 0.f;
   }
@@ -193,9 +195,13 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
     for (int y = 0; y < 32; ++y) *reinterpret_cast<uint2*>(rows + y * kRowPitch + 8 * lane) = r[y];
     krow = reinterpret_cast<const __half*>(rows + t * kRowPitch);
   }
-  float x0 = -INFINITY, x1 = -INFINITY;
+  float xs[HPH];
+#pragma unroll
+  for (int y = 0; y < HPH; ++y) xs[y] = -INFINITY;
   if (valid) {
-    float a0 = 0.f, a1 = 0.f;
+    float a[HPH];
+#pragma unroll
+    for (int y = 0; y < HPH; ++y) a[y] = 0.f;
     for (int c8 = 0; c8 < TKV_D / 8; ++c8) {
       union {
         uint4 v;
@@ -205,25 +211,27 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
         const float kx = __half2float(u.hx[x]);
-        a0 += qs[2 * hp][c8 * 8 + x] * kx;
-        a1 += qs[2 * hp + 1][c8 * 8 + x] * kx;
+#pragma unroll
+        for (int y = 0; y < HPH; ++y) a[y] += qs[HPH * hp + y][c8 * 8 + x] * kx;
       }
     }
-    x0 = a0 * p.scale2;
-    x1 = a1 * p.scale2;
+#pragma unroll
+    for (int y = 0; y < HPH; ++y) xs[y] = a[y] * p.scale2;
   }
-  const float m0 = half_wave_max(x0), m1 = half_wave_max(x1);
-  const bool any = m0 != -INFINITY;  // this wave has at least one valid token (uniform per wave)
-  pw[wave][2 * hp][t] = valid ? exp2f(x0 - m0) : 0.f;
-  pw[wave][2 * hp + 1][t] = valid ? exp2f(x1 - m1) : 0.f;
+  bool any = false;  // this wave has at least one valid token (uniform per wave)
+#pragma unroll
+  for (int y = 0; y < HPH; ++y) {
+    const float m = half_wave_max(xs[y]);
+    any = m != -INFINITY;
+    pw[wave][HPH * hp + y][t] = valid ? exp2f(xs[y] - m) : 0.f;
+    if (t == 0) red_m[wave][HPH * hp + y] = m;
+  }
   if (hp == 0) vrow_s[wave][t] = krow + TKV_D;
-  if (t == 0) {
-    red_m[wave][2 * hp] = m0;
-    red_m[wave][2 * hp + 1] = m1;
-  }
   __syncthreads();
   const int c0 = 2 * lane;
-  float o0[4] = {0.f, 0.f, 0.f, 0.f}, o1[4] = {0.f, 0.f, 0.f, 0.f}, ls[4] = {0.f, 0.f, 0.f, 0.f};
+  float o0[GH], o1[GH], ls[GH];
+#pragma unroll
+  for (int hh = 0; hh < GH; ++hh) o0[hh] = 0.f, o1[hh] = 0.f, ls[hh] = 0.f;
   if (any) {
 #pragma unroll
     for (int t8 = 0; t8 < 32; t8 += 8) {
@@ -234,7 +242,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
       for (int y = 0; y < 8; ++y) {
         const float v0 = __low2float(v2[y]), v1 = __high2float(v2[y]);
 #pragma unroll
-        for (int hh = 0; hh < 4; ++hh) {
+        for (int hh = 0; hh < GH; ++hh) {
           const float pp = pw[wave][hh][t8 + y];
           o0[hh] += pp * v0;
           o1[hh] += pp * v1;
@@ -243,7 +251,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
       }
     }
   }
-  for (int hh = 0; hh < 4; ++hh) {
+  for (int hh = 0; hh < GH; ++hh) {
     red_o[wave][hh][c0] = o0[hh];
     red_o[wave][hh][c0 + 1] = o1[hh];
     if (lane == 0) red_l[wave][hh] = ls[hh];
@@ -280,8 +288,13 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   if (tid == 0) __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __shared__ float merge_s[3 * 4 * 64 + 4 * 4 * TKV_D + 4];
   const float* head0 = p.parts + ((size_t)b * p.hq + (size_t)h * G) * p.n_chunks * TKV_PART_STRIDE;
-  if (nthr >= 64 * G) {
-    tkv::merge_chunks(head0, G, p.n_chunks, p.out + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, merge_s, tid, nthr);
+  if (nthr >= 64 * min(G, 4)) {
+    // (four heads at a time: the merge's LDS scratch is laid out for that many)
+    for (int g0 = 0; g0 < G; g0 += 4) {
+      if (g0 > 0) __syncthreads();
+      tkv::merge_chunks(head0 + (size_t)g0 * p.n_chunks * TKV_PART_STRIDE, min(4, G - g0), p.n_chunks,
+                        p.out + ((size_t)b * p.hq + (size_t)h * G + g0) * TKV_D, merge_s, tid, nthr);
+    }
   } else {  // one-wave workgroups (few attended tokens): plain loop over the chunks
     auto ld = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
     for (int x = tid; x < G * TKV_D; x += nthr) {
@@ -447,6 +460,7 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
   p.n_window = d->n_window;
   p.n_chunks = n_chunks;
   hipStream_t s = (hipStream_t)stream;
+  const bool big_group = d->n_q_heads / d->n_kv_heads > 4;  // 5 to 8 query heads per KV head
   p.kv_host = nullptr;
   p.topk_idx = nullptr;
   p.capacity = d->capacity;
@@ -458,13 +472,22 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
     if (st != TKV_OK) return st;
     p.kv_host = (const __half*)host_dev;
     p.topk_idx = topk_idx_fused;
-    static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<true>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                   kAttnMaxWaves * 32 * kRowPitch) == hipSuccess;
+    static const bool lds_ok =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<true, 4>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kAttnMaxWaves * 32 * kRowPitch) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<true, 8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kAttnMaxWaves * 32 * kRowPitch) == hipSuccess;
     if (!lds_ok) return TKV_E_HIP;
-    TKV_LAUNCH(sparse_attn_kernel<true>, dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, W * 32 * kRowPitch, s, p);
+    const dim3 grid(n_chunks, d->n_kv_heads, d->batch);
+    if (big_group) {
+      TKV_LAUNCH((sparse_attn_kernel<true, 8>), grid, 64 * W, W * 32 * kRowPitch, s, p);
+    } else {
+      TKV_LAUNCH((sparse_attn_kernel<true, 4>), grid, 64 * W, W * 32 * kRowPitch, s, p);
+    }
+  } else if (big_group) {
+    TKV_LAUNCH((sparse_attn_kernel<false, 8>), dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s, p);
   } else {
-    TKV_LAUNCH(sparse_attn_kernel<false>, dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s, p);
+    TKV_LAUNCH((sparse_attn_kernel<false, 4>), dim3(n_chunks, d->n_kv_heads, d->batch), 64 * W, 0, s, p);
   }
   return TKV_OK;
 }

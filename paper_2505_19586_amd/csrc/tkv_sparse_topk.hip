@@ -258,14 +258,17 @@ __device__ inline void append_tokens(const TopkParams& p, int b, int h, int tid)
 
 // CM: the critical key cache is channel-major (one row of `capacity` tokens per channel):
 // a thread then scores four consecutive tokens, one 8-byte load per channel row.
-template <int DS, bool CM, bool ATT>
+// GH: query heads per KV head the scores are summed over: 4 (groups of up to 4; their channels
+// sit in registers), or 8 (groups of 5 to 8: read from LDS term by term; no ATT form).
+template <int DS, bool CM, bool ATT, int GH = 4>
 __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
+  static_assert(GH == 4 || (GH == 8 && !ATT), "the attention phase holds four heads per lane");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem);                            // kBins words
   uint32_t* offs = reinterpret_cast<uint32_t*>(smem + kBins * 4);                // 1024 words
   uint2* list_s = reinterpret_cast<uint2*>(smem + kBins * 4 + 1024 * 4);         // kListCap entries
   uint32_t* stage = reinterpret_cast<uint32_t*>(list_s);                         // CM: 2 * kTok keys
-  __shared__ float qc[4][DS];
+  __shared__ float qc[GH][DS];
   __shared__ uint32_t scratch[kWavesPerBlock + 8];
   __shared__ uint32_t s_cnt[kSub][kWavesPerBlock], s_cnt2[kSub][kWavesPerBlock];
   __shared__ uint32_t s_wtot[kWavesPerBlock], s_res[2];
@@ -495,19 +498,19 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     if (dyn) {
       __shared__ float s_s[TKV_D];
       __shared__ uint32_t s_sel[TKV_D];
-      __shared__ __half q_all[4][TKV_D];  // whole query rows, fetched while the list is being made
-      if (tid >= kThreads - 4 * TKV_D / 2) {
-        const int x = tid - (kThreads - 4 * TKV_D / 2), j = x / (TKV_D / 2), w = x % (TKV_D / 2);
+      __shared__ __half q_all[GH][TKV_D];  // whole query rows, fetched while the list is being made
+      if (tid >= kThreads - GH * TKV_D / 2) {
+        const int x = tid - (kThreads - GH * TKV_D / 2), j = x / (TKV_D / 2), w = x % (TKV_D / 2);
         const uint32_t v = j < G ? reinterpret_cast<const uint32_t*>(p.q + ((size_t)b * p.hq + (size_t)h * G + j) * TKV_D)[w] : 0u;
         reinterpret_cast<uint32_t*>(&q_all[j][0])[w] = v;
       }
       tkv::select_channels_block(p.q_hat + ((size_t)b * p.hq + (size_t)h * G) * TKV_D, G, p.k_absmax + bh * TKV_D, DS,
                                  s_s, s_sel, s_chan, blockIdx.x == 0 ? p.channel_out + bh * DS : nullptr);
-      if (tid < 4 * DS) {
+      if (tid < GH * DS) {
         const int j = tid / DS, i = tid % DS;
         qc[j][i] = __half2float(q_all[j][s_chan[i]]);  // rows of heads >= G are zero
       }
-    } else if (tid < 4 * DS) {
+    } else if (tid < GH * DS) {
       const int j = tid / DS, i = tid % DS;
       const int c = p.channel_idx[bh * DS + i];
       qc[j][i] = j < G ? __half2float(p.q[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c]) : 0.f;
@@ -555,7 +558,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     for (int j = 0; j < 4; ++j)
   #pragma unroll
       for (int i = 0; i < DS / 2; ++i)
-        qr[j][i] = __builtin_bit_cast(uint32_t, half2_t{(_Float16)qc[j][2 * i], (_Float16)qc[j][2 * i + 1]});
+        qr[j][i] = GH == 4 ? __builtin_bit_cast(uint32_t, half2_t{(_Float16)qc[j][2 * i], (_Float16)qc[j][2 * i + 1]}) : 0u;
 
     // Keys of the loaded pass `ps` of the share [ts, te): kb[kPer * ps + j] is the key of token
     // ts + ps * kTok + j * kThreads + tid (0 for a non-candidate or past the share).  Token-major
@@ -593,12 +596,15 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
           }
         }
         float total = 0.f;
+        // (groups of 5 to 8: the query channels are read from LDS again for every token rather than
+        // held in 128 registers across the pass)
+        if (GH > 4) asm volatile("" ::: "memory");
   #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < GH; ++j) {
           // left-to-right sum of exact products: fma(q, k, a) rounds once, like a + q*k; the
           // first term fma(q, k, +0) is the exact product (only the sign of a zero can differ,
           // and the final + 0.0f removes that)
-          constexpr bool kLdsQ = decltype(q_from_lds)::value;
+          constexpr bool kLdsQ = GH > 4 || decltype(q_from_lds)::value;
           float a = 0.f;
   #pragma unroll
           for (int i = 0; i < DS; i += 2) {
@@ -608,7 +614,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
             } else {
               // (opaque copy: keeps the pair packed in one register instead of two converted ones
               // held across the whole pass)
-              uint32_t w = qr[j][i / 2];
+              uint32_t w = qr[j % 4][i / 2];
               asm volatile("" : "+v"(w));
               const half2_t hq = __builtin_bit_cast(half2_t, w);
               q0 = (float)hq[0], q1 = (float)hq[1];
@@ -1003,13 +1009,13 @@ extern "C" void tkv_debug_set_dump_topk(void* ptr) { g_topk_prof = ptr; }
 #endif
 
 namespace {
-template <int DS, bool CM, bool ATT>
+template <int DS, bool CM, bool ATT, int GH = 4>
 int32_t launch_fused(const TopkParams& p, dim3 grid, hipStream_t s) {
   // more than 64 KiB of dynamic LDS needs an opt-in, once per kernel
-  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_select_kernel<DS, CM, ATT>),
+  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_select_kernel<DS, CM, ATT, GH>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds) == hipSuccess;
   if (!lds_ok) return TKV_E_HIP;
-  TKV_LAUNCH((score_select_kernel<DS, CM, ATT>), grid, kThreads, kFusedLds, s, p);
+  TKV_LAUNCH((score_select_kernel<DS, CM, ATT, GH>), grid, kThreads, kFusedLds, s, p);
   return TKV_OK;
 }
 
@@ -1104,7 +1110,9 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   }
   const dim3 grid(nblk + (app != nullptr ? 1 : 0), d->n_kv_heads, d->batch);
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;  // 4 Mi tokens per sequence
+  const bool big_group = d->n_q_heads / d->n_kv_heads > 4;  // 5 to 8 query heads per KV head
   if (att != nullptr) {  // token-major summary only
+    if (big_group) return TKV_E_UNSUPPORTED;  // (the attention phase holds four heads per lane)
     p.att_host = att->att_host;
     p.att_local = att->att_local;
     p.att_out = att->att_out;
@@ -1113,6 +1121,13 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
     if (d->n_channels == 16) return launch_fused<16, false, true>(p, grid, s);
     if (d->n_channels == 12) return launch_fused<12, false, true>(p, grid, s);
     return launch_fused<8, false, true>(p, grid, s);
+  }
+  if (big_group) {
+    if (d->n_channels == 16)
+      return cm ? launch_fused<16, true, false, 8>(p, grid, s) : launch_fused<16, false, false, 8>(p, grid, s);
+    if (d->n_channels == 12)
+      return cm ? launch_fused<12, true, false, 8>(p, grid, s) : launch_fused<12, false, false, 8>(p, grid, s);
+    return cm ? launch_fused<8, true, false, 8>(p, grid, s) : launch_fused<8, false, false, 8>(p, grid, s);
   }
   if (d->n_channels == 16)
     return cm ? launch_fused<16, true, false>(p, grid, s) : launch_fused<16, false, false>(p, grid, s);

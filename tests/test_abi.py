@@ -118,7 +118,7 @@ def test_bad_struct_size_and_null(L):
 @pytest.mark.parametrize("kw,status", [
     (dict(n_channels=10), -2), (dict(n_channels=12), 0), (dict(n_channels=0), -1), (dict(top_k=0), -1), (dict(top_k=5000), -2),
     (dict(n_window=0), -1), (dict(n_sink=-1), -1), (dict(head_dim=96), -2),
-    (dict(n_q_heads=64), -2), (dict(n_q_heads=24), -2), (dict(n_q_heads=16), 0),   # groups of 1, 2 or 4 only
+    (dict(n_q_heads=64), 0), (dict(n_q_heads=24), 0), (dict(n_q_heads=72), -2),   # groups of up to 8
 ])
 def test_sparse_desc_errors(L, kw, status):
     assert L.tkv_sparse_cache_sizes(C.byref(_sdesc(**kw)), None, None) == status

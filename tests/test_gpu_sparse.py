@@ -149,6 +149,31 @@ def test_other_shapes(shape, n_channels):
     _check_layer(layer, 0, inp, ch, q, out)
 
 
+@pytest.mark.parametrize("shape,n_channels", [(HeadShape(64, 8, 128), 16), (HeadShape(56, 8, 128), 16),
+                                              (HeadShape(10, 2, 128), 12), (HeadShape(6, 1, 128), 8),
+                                              (HeadShape(3, 1, 128), 16)])
+def test_groups_of_up_to_eight_query_heads(shape, n_channels):
+    """Groups of 5 to 8 query heads per KV head: the scores are summed over all of them (their
+    channels read from LDS), the attention kernels hold eight heads per KV row.  Every form of the
+    attention call: rows fetched inside the launch, gathered on a side stream, staged first."""
+    print(f"case sparse Hq={shape.n_q_heads} Hkv={shape.n_kv_heads} d_s={n_channels}", flush=True)
+    for n, top_k in ((6000, 512), (300, 64)):
+        inp = make_layer(n, shape=shape, seq=5)
+        layer, ch = _build(inp, top_k=top_k, capacity=n + 8, n_channels=n_channels, shape=shape)
+        q = torch.from_numpy(inp.q)[None].cuda()
+        layer.estimate_topk(q)
+        _check_layer(layer, 0, inp, ch, q, layer.gather_attn(q, SM))
+        side = torch.cuda.Stream()
+        _check_layer(layer, 0, inp, ch, q, layer.gather_attn(q, SM, gather_stream=side.cuda_stream))
+        layer.gather()
+        _check_layer(layer, 0, inp, ch, q, layer.attn(q, SM))
+        if shape.n_q_heads // shape.n_kv_heads > 4:
+            with pytest.raises(tkv.TkvError):        # the one-launch step holds four heads per lane
+                layer.decode(q, SM)
+        else:
+            _check_layer(layer, 0, inp, ch, q, layer.decode(q, SM))
+
+
 def test_ties_beyond_the_on_chip_list():
     """All scores equal at a length where the candidates (every token) do not fit the
     selection kernel's on-chip list: indices are still n_sink .. n_sink + k - 1."""

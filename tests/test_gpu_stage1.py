@@ -153,6 +153,34 @@ def test_ragged_batch_other_grouping_and_eight_channels():
         assert attn_err(out[b], want) <= TOL
 
 
+@pytest.mark.parametrize("resident", [False, True])
+def test_groups_of_eight_query_heads(resident):
+    """Eq. 10 sums |q| over all eight heads of a group; Stage 2 over the fetched or resident
+    channel-major keys."""
+    shape = HeadShape(16, 2, 128)
+    n = 3000
+    inp = make_layer(n, config=4, layer=1, seq=3, shape=shape)
+    layer, s1 = _layer(inp, top_k=256, capacity=n + 8, resident=resident, shape=shape)
+    _append(layer, s1, inp.k, inp.v, [n - 1, 1], both=True)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    if resident:
+        s1.select_estimate_topk(q, q)
+        ch_dev = s1.channel_idx
+    else:
+        ch_dev = s1.select_channels(q)
+        s1.prefetch(0)
+        s1.estimate_topk(q, 0)
+    out = layer.gather_attn(q, SM)
+    torch.cuda.synchronize()
+    ch = sparse.select_channels(inp.q, sparse.channel_absmax(inp.k), 16)
+    assert np.array_equal(ch_dev[0].cpu().numpy(), ch)
+    idx, cnt = sparse.estimate_topk(inp.q, sparse.key_summary(inp.k, ch), ch, n, top_k=256, n_sink=4, n_window=64)
+    assert np.array_equal(layer.topk_count[0].cpu().numpy(), cnt)
+    assert np.array_equal(layer.topk_idx[0].cpu().numpy(), idx)
+    want = sparse.sparse_attention(inp.q, inp.k, inp.v, idx, cnt, n, SM, n_sink=4, n_window=64)
+    assert attn_err(out[0], want) <= TOL
+
+
 def test_the_papers_long_context_setting():
     """Sec. 5.1 / App. D: 12 critical channels, n_local = 128 (no separate sinks), n_topk = 896,
     channels re-selected from the query, keys fetched from the host copy."""
