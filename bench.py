@@ -150,7 +150,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.identify:
-        return identify(args, tkv, torch, dev)
+        print(json.dumps(identify(args, tkv, torch, dev)))
+        return
     if args.prefill_offload:
         print(json.dumps(prefill_offload(args, tkv, torch, dev)))
         return
@@ -219,6 +220,12 @@ def other_configs(args, tkv, torch, dev):
         "quant_attn_us": b["quant_attn_us"], "quant_attn_frac_of_hbm_peak": b["roofline"]["frac"],
         "quant_attn_bytes": b["roofline"]["algorithmic_bytes"], "estimate_topk_us": b["estimate_topk_us"],
         "gather_us": b["gather_us"], "distinct_host_caches": b["config"]["distinct_host_caches"]}
+    cleanup()
+    # off the decode path: which layers are quantization-friendly (Sec. 4.1), one layer of a 131072-token prompt
+    i = identify(fresh(context=131072), tkv, torch, dev)
+    out["offline identification, dense preference score of one layer at N=131072"] = {
+        "workload": i["config"]["workload"], "ms_per_layer": i["value"], "TFLOPs": i["roofline"]["achieved"],
+        "frac_of_fp16_mfma_peak": i["roofline"]["frac"], "workspace_MiB": i["workspace_MiB"]}
     cleanup()
     return out
 
@@ -643,13 +650,13 @@ def identify(args, tkv, torch, dev):
     ms = e0.elapsed_time(e1) / reps
     friendly, score = dp.classify(out[0], 0.2)
     flops = 2.0 * 32 * n_q * n * 128
-    print(json.dumps({
+    return {
         "metric": "offline identification ms per layer", "value": ms, "unit": "ms/layer", "n_gpus": 1,
         "higher_is_better": False, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"dense preference score, 32 query / 8 KV heads, n={n}, n_q={n_q}, k={args.top_k}"},
         "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": flops / ms / 1e9 / 2500.0, "traffic": None},
-        "layer_score": score, "quantization_friendly": friendly, "workspace_MiB": dp.workspace_bytes / 2 ** 20}))
+        "layer_score": score, "quantization_friendly": friendly, "workspace_MiB": dp.workspace_bytes / 2 ** 20}
 
 
 def build_caches_overlapped(torch, layers, produce, side):
