@@ -94,9 +94,11 @@ struct TopkParams {
 #endif
 };
 #ifdef TKV_PHASE
-#define TKV_PH(i) do { __builtin_amdgcn_sched_barrier(0); if (p.prof && tid == 0) p.prof[(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define TKV_PH(i) do { __builtin_amdgcn_sched_barrier(0); if (p.prof && tid == 0) p.prof[(blockIdx.y * gridDim.x + blockIdx.x) * 32 + (i)] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define TKV_PHW(i) do { __builtin_amdgcn_sched_barrier(0); if (p.prof && lane == 0) p.prof[(blockIdx.y * gridDim.x + blockIdx.x) * 32 + (i)] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
 #define TKV_PH(i) do {} while (0)
+#define TKV_PHW(i) do {} while (0)
 #endif
 
 // Larger float <-> larger unsigned key; +0 and -0 were already merged by "+ 0.0f".
@@ -278,12 +280,13 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   const int lane = tid % 64, wave = __builtin_amdgcn_readfirstlane(tid / 64);
   const int n = p.lens.n[b];
   const size_t bh = (size_t)b * p.hkv + h;
-  if (p.app_k != nullptr && blockIdx.x == gridDim.x - 1) {
-    // The new tokens are newer than every Top-K candidate (at most n_window of them): the
-    // scoring workgroups read their summary rows at most to discard the result.
-    append_tokens<DS>(p, b, h, tid);
-    return;
-  }
+  // The step's new tokens (if any) are appended by one workgroup of the head once it has nothing
+  // else left to do: the head's first workgroup to arrive, which then only waits for the others
+  // (a workgroup of its own would take a compute unit that a scoring workgroup then waits for,
+  // the grid being one workgroup per compute unit).  The new tokens are newer than every Top-K
+  // candidate (at most n_window of them): the scoring workgroups read their summary rows at most
+  // to discard the result, and the attention takes their rows from the call's arguments.
+  bool appends = false;
   int32_t* out = p.topk_idx + bh * p.top_k;
   int lo, hi;
   candidate_range(p, n, lo, hi);
@@ -361,17 +364,14 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
       for (int y = 0; y < R; ++y) {
         const uint64_t ka = (uint64_t)read_lane((uint32_t)(uintptr_t)kp, y) | ((uint64_t)read_lane((uint32_t)((uintptr_t)kp >> 32), y) << 32);
         const uint64_t va = (uint64_t)read_lane((uint32_t)(uintptr_t)vp, y) | ((uint64_t)read_lane((uint32_t)((uintptr_t)vp >> 32), y) << 32);
-        r[y] = reinterpret_cast<const uint2*>(half == 0 ? ka : va)[l32];
+        // (named as global memory, which pinned host memory is too: loads through generic pointers
+        // cannot be counted one by one, and every wait for a row would wait for all rows in flight)
+        const tkv::tkv_u32x2 w = reinterpret_cast<const __attribute__((address_space(1))) tkv::tkv_u32x2*>(half == 0 ? ka : va)[l32];
+        r[y] = make_uint2(w.x, w.y);
       }
     };
-    // The rows of the next pass are requested before this pass is worked on: a wave that has
-    // nothing in flight while it computes leaves the host link idle for that long.
-    uint2 r[R], r_next[R];
-    TKV_PH(4);
-    if (wave * R < n_att) fetch(wave * R, r);
-    for (int i0 = wave * R; i0 < n_att; i0 += kWavesPerBlock * R) {
-      const bool more = i0 + kWavesPerBlock * R < n_att;
-      if (more) fetch(i0 + kWavesPerBlock * R, r_next);
+    // one pass: the wave's R rows that start at attended token i0
+    auto pass = [&](int i0, const uint2 (&r)[R]) {
       // partial logits of this lane's 4 channels: v[4 y + j]
       float v[R * 4];
 #pragma unroll
@@ -447,34 +447,61 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
           for (int c = 0; c < 4; ++c) o_run[j][c] = __builtin_fmaf(pw, vf[y][c], o_run[j][c]);
         }
       }
-      if (more) {
-#pragma unroll
-        for (int y = 0; y < R; ++y) r[y] = r_next[y];
-      }
+    };
+    // Two passes of rows are in flight while a third is worked on: a wave that has nothing on its
+    // way while it computes leaves the host link idle for that long.  Every request is issued
+    // whether or not the pass exists (past the end: the head's first resident row, unused), so
+    // that the number of loads behind the rows a pass waits for is the same on every path.
+    constexpr int kStride = kWavesPerBlock * R;
+    uint2 ra[R], rb[R];
+    TKV_PH(8);
+    fetch(wave * R, ra);
+    fetch(wave * R + kStride, rb);
+    for (int i0 = wave * R; i0 < n_att; i0 += 2 * kStride) {
+      pass(i0, ra);
+      fetch(i0 + 2 * kStride, ra);
+      if (i0 + kStride < n_att) pass(i0 + kStride, rb);
+      fetch(i0 + 3 * kStride, rb);
     }
-    TKV_PH(5);
-    __syncthreads();  // the list area is free: the waves' results meet there
-    TKV_PH(6);
+    TKV_PH(9);
+    TKV_PHW(16 + wave);
+    // The waves' results meet in the list area, which nothing has used since the selection.
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       float* dst = mrg + (wave * 4 + j) * (TKV_D + 4);
-      if (lane == 0) dst[0] = m_run[j], dst[1] = l_run[j];
+      if (lane == 0) *reinterpret_cast<float2*>(dst) = make_float2(m_run[j], l_run[j]);
       if (half == 1) *reinterpret_cast<float4*>(dst + 4 + 4 * l32) = make_float4(o_run[j][0], o_run[j][1], o_run[j][2], o_run[j][3]);
     }
     __syncthreads();
-    if (tid < G * TKV_D) {
-      const int j = tid / TKV_D, c = tid % TKV_D;
+    TKV_PH(10);
+    // one thread per query head and four channels: 16-byte reads of the waves' partial sums,
+    // every element summed over the waves in ascending order
+    if (tid < 4 * (TKV_D / 4) && tid / (TKV_D / 4) < G) {
+      const int j = tid / (TKV_D / 4), c4 = tid % (TKV_D / 4);
+      float2 ml[kWavesPerBlock];
       float M = -INFINITY;
-      for (int w = 0; w < kWavesPerBlock; ++w) M = fmaxf(M, mrg[(w * 4 + j) * (TKV_D + 4)]);
-      float L = 0.f, O = 0.f;
+#pragma unroll
       for (int w = 0; w < kWavesPerBlock; ++w) {
-        const float* src = mrg + (w * 4 + j) * (TKV_D + 4);
-        const float wgt = src[0] == -INFINITY ? 0.f : exp2f(src[0] - M);
-        L = __builtin_fmaf(src[1], wgt, L);
-        O = __builtin_fmaf(src[4 + c], wgt, O);
+        ml[w] = *reinterpret_cast<const float2*>(mrg + (w * 4 + j) * (TKV_D + 4));
+        M = fmaxf(M, ml[w].x);
       }
-      p.att_out[((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + c] = __float2half_rn(L > 0.f ? O / L : 0.f);
+      float L = 0.f, O[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        const float4 o = *reinterpret_cast<const float4*>(mrg + (w * 4 + j) * (TKV_D + 4) + 4 + 4 * c4);
+        const float wgt = ml[w].x == -INFINITY ? 0.f : exp2f(ml[w].x - M);
+        L = __builtin_fmaf(ml[w].y, wgt, L);
+        O[0] = __builtin_fmaf(o.x, wgt, O[0]), O[1] = __builtin_fmaf(o.y, wgt, O[1]);
+        O[2] = __builtin_fmaf(o.z, wgt, O[2]), O[3] = __builtin_fmaf(o.w, wgt, O[3]);
+      }
+      __half r[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) r[c] = __float2half_rn(L > 0.f ? O[c] / L : 0.f);
+      uint2 packed;
+      __builtin_memcpy(&packed, r, 8);
+      *reinterpret_cast<uint2*>(p.att_out + ((size_t)b * p.hq + (size_t)h * G + j) * TKV_D + 4 * c4) = packed;
     }
+    TKV_PH(11);
   };
 
   // Scoring, listing and, in the head's last workgroup, the selection.  Returns true in the
@@ -485,6 +512,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
       if (tid == 0) p.topk_count[bh] = 0;
     }
     const int t0 = blockIdx.x * p.tpw;
+    appends = k == 0 && blockIdx.x == 0;  // no candidates, no arrivals
     if (ATT && k == 0) return blockIdx.x == 0;  // ... and attends to what is resident
     if (t0 >= n) return false;
     const int t_end = min(n, t0 + p.tpw);  // this workgroup's tokens: [t0, t_end), kTok per pass
@@ -703,8 +731,13 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     TKV_PH(2);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (tid == 0) scratch[kWavesPerBlock + 2] = atomicAdd(&ctrl[kDone2], 1u) == (uint32_t)nblk - 1u;
+    if (tid == 0) {
+      const uint32_t before = atomicAdd(&ctrl[kDone2], 1u);
+      scratch[kWavesPerBlock + 2] = before == (uint32_t)nblk - 1u;
+      scratch[kWavesPerBlock + 3] = before == 0u;
+    }
     __syncthreads();
+    appends = scratch[kWavesPerBlock + 3] != 0u;
     TKV_PH(3);
     if (!scratch[kWavesPerBlock + 2]) {
       if (ATT && p.pf != nullptr) {
@@ -712,6 +745,10 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
         // score it in the next launch): HBM is idle from here on, and the next launch then finds
         // the rows in the memory-side cache.  Eight 16-byte loads per thread in flight; the
         // values are only combined so that the loads are not dropped.
+        // (not at once: the head's last workgroup is about to read the lists through the same
+        // memory system, and the selection waits for that round trip)
+        __builtin_amdgcn_s_sleep(127);
+        __builtin_amdgcn_s_sleep(127);
         const uint4* src = reinterpret_cast<const uint4*>(p.pf + (bh * p.capacity + (size_t)t0) * DS);
         const int n_vec = max(0, t_end - t0) * DS / 8;
         uint32_t mix = 0;
@@ -999,6 +1036,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     __syncthreads();  // the selected tokens are in LDS, the scratch areas of the selection are free
     attend(sel_s, (int)k);
   }
+  if (p.app_k != nullptr && appends) append_tokens<DS>(p, b, h, tid);  // Eq. 2
 }
 
 }  // namespace
@@ -1108,7 +1146,7 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
     p.app_stride = app->app_stride;
     p.app_add = app->app_add;
   }
-  const dim3 grid(nblk + (app != nullptr ? 1 : 0), d->n_kv_heads, d->batch);
+  const dim3 grid(nblk, d->n_kv_heads, d->batch);
   if (nblk >= 1024) return TKV_E_UNSUPPORTED;  // 4 Mi tokens per sequence
   const bool big_group = d->n_q_heads / d->n_kv_heads > 4;  // 5 to 8 query heads per KV head
   if (att != nullptr) {  // token-major summary only
