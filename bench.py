@@ -439,6 +439,11 @@ def run_step(args, tkv, torch, dev):
         if rec is None and args.dynamic_channels != "off":
             return step_dynamic()
         for l, L in enumerate(layers):
+            if l in QUANT_LAYERS and rec is None and not args.separate_calls:
+                # one call per quantized layer: the step's new token joins the cache (Eq. 2) in the
+                # attention's launch (a launch of its own only when it completes a quantization group)
+                L.decode(qs[l], sm, new_k[l], new_v[l], out=outs[l])
+                continue
             if l in QUANT_LAYERS or rec is not None:
                 L.append(new_k[l], new_v[l])      # Eq. 2: the step's new token joins the cache first
             if l in QUANT_LAYERS:
@@ -614,7 +619,10 @@ def run_step(args, tkv, torch, dev):
                                                f", critical channels re-selected every step ({args.dynamic_channels})"),
                    "schedule": args.schedule,
                    **({"sparse_layer_calls": "tkv_sparse_append_estimate_topk + tkv_sparse_gather_attn" if args.separate_calls
-                       else "tkv_sparse_decode (one launch)"} if args.schedule == "chained" and args.dynamic_channels == "off" else {}),
+                       else "tkv_sparse_decode (one launch)",
+                       "quant_layer_calls": "tkv_quantize_append + tkv_quant_attn_decode" if args.separate_calls
+                       else "tkv_quant_decode (one launch unless the token completes a group)"}
+                      if args.schedule == "chained" and args.dynamic_channels == "off" else {}),
                    **({"gather_compute_units": args.gather_cus, "gather_streams": args.gather_streams}
                       if args.schedule == "overlapped" else {}),
                    "distinct_host_caches": len(host_pool),

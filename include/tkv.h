@@ -171,6 +171,24 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
                               void* stream);
 
 /*
+ * The decode step of a quantization-friendly layer in one call: Eq. 2 (the step's new tokens
+ * join the cache, as tkv_quantize_append_ragged with the same k_new, v_new, n_new,
+ * n_valid_host) and then Eq. 3 over the grown cache (as tkv_quant_attn_decode with the same q,
+ * out, sm_scale, workspace).  Same cache contents, same seq_len_host and the same results (to
+ * tkv_quant_attn_decode's run-to-run variation) as the two calls one after the other.  When no
+ * sequence completes a quantization group with these tokens -- all but one decode step in
+ * group_size -- the whole step is ONE launch: the attention kernel reads the new rows from
+ * k_new / v_new and writes them into the fp16 ring itself; otherwise the append's launches come
+ * first.  k_new, v_new must stay valid until the call has run on the stream.  n_new == 0: the
+ * attention alone.  Errors: those of the two calls; on an error nothing has been enqueued and
+ * seq_len_host is unchanged, except that an error of the attention after a separate append
+ * leaves the tokens appended.
+ */
+int32_t tkv_quant_decode(const tkv_quant_desc* desc, tkv_quant_cache* cache, const void* k_new,
+                         const void* v_new, int32_t n_new, const int32_t* n_valid_host, const void* q,
+                         void* out, float sm_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * tkv_quant_attn_decode for callers that cannot allocate or pass a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
  * kernels and same results as tkv_quant_attn_decode, but the split-K partials and arrival

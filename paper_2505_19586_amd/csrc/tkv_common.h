@@ -36,6 +36,15 @@ struct TkvSeqLens {
 
 namespace tkv {
 
+// The new tokens of a step that a quantized layer's attention call also appends:
+// k_new, v_new fp16 [B][n_stride][Hkv][D], the first n_add[b] rows of sequence b.
+struct QuantNewTokens {
+  const __half* k_new;
+  const __half* v_new;
+  int32_t n_stride;
+  TkvSeqLens n_add;
+};
+
 // Number of quantized tokens of a sequence of n tokens (residual w, group g).
 __host__ __device__ inline int32_t n_quantized(int32_t n, int32_t w, int32_t g) {
   return n >= w ? ((n - w) / g) * g : 0;

@@ -11,7 +11,8 @@ namespace tkv {
 // shape is not one it is built for.
 int32_t launch_quant_attn_mfma(const tkv_quant_desc* d, const tkv_quant_cache* c, const __half* q, __half* out,
                                float scale2, float* parts, size_t parts_floats, uint32_t* arrivals, int target_blocks,
-                               int max_groups, int max_tail, const TkvSeqLens& lens, hipStream_t s);
+                               int max_groups, int max_tail, const TkvSeqLens& lens, const QuantNewTokens* fresh,
+                               hipStream_t s);
 }  // namespace tkv
 
 namespace {
@@ -289,9 +290,12 @@ namespace {
 
 // Body of both entry points.  parts: room for parts_floats floats of split-K partials; arrivals:
 // one zero word per (sequence, KV head, four query heads of its group).  TKV_E_WORKSPACE if the launch's partials do not fit.
+// fresh: the step's new tokens, already counted in seq_len_host but not yet in the fp16 ring (the
+// matrix-core kernel reads them from the caller's buffers and writes them into the ring); only
+// with the matrix-core kernel (TKV_E_UNSUPPORTED otherwise, before anything is launched).
 int32_t quant_attn_decode_impl(const tkv_quant_desc* d, const tkv_quant_cache* c, const void* q, void* out,
                                float sm_scale, float* parts, size_t parts_floats, uint32_t* arrivals,
-                               hipStream_t s) {
+                               hipStream_t s, const tkv::QuantNewTokens* fresh = nullptr) {
   QuantAttnParams p;
   int max_groups = 0, max_tail = 0;
   for (int b = 0; b < d->batch; ++b) {
@@ -340,9 +344,10 @@ int32_t quant_attn_decode_impl(const tkv_quant_desc* d, const tkv_quant_cache* c
     // mask a launch sized for the whole machine would leave a few workgroups for a second round
     if (target_blocks == 0) target_blocks = tkv::stream_compute_units(s);
     const int32_t st = tkv::launch_quant_attn_mfma(d, c, p.q, (__half*)out, p.scale2, p.parts, parts_floats, arrivals,
-                                                   target_blocks, max_groups, max_tail, p.lens, s);
+                                                   target_blocks, max_groups, max_tail, p.lens, fresh, s);
     if (st != TKV_E_UNSUPPORTED) return st;
   }
+  if (fresh != nullptr) return TKV_E_UNSUPPORTED;
   // reference kernel: on request, and for the settings the matrix-core kernel is not built for
   if ((size_t)d->batch * d->n_q_heads * (n_chunks + 1) * TKV_PART_STRIDE > parts_floats) return TKV_E_WORKSPACE;
   p.chunk_offset = 0;
@@ -376,6 +381,55 @@ extern "C" int32_t tkv_quant_attn_decode(const tkv_quant_desc* d, const tkv_quan
   const size_t parts_floats = (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE;
   uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_floats * sizeof(float) + 255) & ~(size_t)255));
   return quant_attn_decode_impl(d, c, q, out, sm_scale, (float*)workspace, parts_floats, arrivals, (hipStream_t)stream);
+}
+
+// ---- tkv_quant_decode: Eq. 2 and Eq. 3 of a quantized layer's decode step in one call ----------
+extern "C" int32_t tkv_quant_decode(const tkv_quant_desc* d, tkv_quant_cache* c, const void* k_new,
+                                    const void* v_new, int32_t n_new, const int32_t* n_valid_host, const void* q,
+                                    void* out, float sm_scale, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+  int32_t st = check_decode_args(d, c, q, out);
+  if (st != TKV_OK) return st;
+  if (!workspace || n_new < 0 || (n_new > 0 && (!k_new || !v_new))) return TKV_E_INVAL;
+  size_t need = 0;
+  tkv_quant_cache_sizes(d, nullptr, &need);
+  if (workspace_bytes < need) return TKV_E_WORKSPACE;
+  if (n_new == 0) return tkv_quant_attn_decode(d, c, q, out, sm_scale, workspace, workspace_bytes, stream);
+  // One launch when no sequence completes a quantization group with these tokens (the new rows
+  // then only join the fp16 ring, which the attention kernel does itself) and the matrix-core
+  // kernel serves the descriptor; else the append's launches, then the attention's.
+  tkv::QuantNewTokens fresh;
+  fresh.k_new = (const __half*)k_new;
+  fresh.v_new = (const __half*)v_new;
+  fresh.n_stride = n_new;
+  bool one_launch = g_kernel_choice.load() == 0 && d->head_dim == TKV_D;
+  {
+    const int variant = d->bits * 100 + d->group_size;
+    if (variant != 232 && variant != 432 && variant != 164 && variant != 264) one_launch = false;
+  }
+  for (int b = 0; b < d->batch; ++b) {
+    const int64_t n0 = c->seq_len_host[b];
+    const int32_t add = n_valid_host ? n_valid_host[b] : n_new;
+    if (n0 < 0 || add < 0 || add > n_new) return TKV_E_INVAL;
+    if (n0 + add > d->capacity) return TKV_E_CAPACITY;
+    fresh.n_add.n[b] = add;
+    const int32_t g = d->group_size;
+    if (tkv::n_quantized((int32_t)n0 + add, d->residual, g) != tkv::n_quantized((int32_t)n0, d->residual, g))
+      one_launch = false;
+  }
+  if (!one_launch) {
+    st = tkv_quantize_append_ragged(d, c, k_new, v_new, n_new, n_valid_host, stream);
+    if (st != TKV_OK) return st;
+    return tkv_quant_attn_decode(d, c, q, out, sm_scale, workspace, workspace_bytes, stream);
+  }
+  const size_t parts_floats = (size_t)d->batch * d->n_q_heads * (TKV_MAX_CHUNKS + 1) * TKV_PART_STRIDE;
+  uint32_t* arrivals = (uint32_t*)((char*)workspace + ((parts_floats * sizeof(float) + 255) & ~(size_t)255));
+  for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] += fresh.n_add.n[b];
+  st = quant_attn_decode_impl(d, c, q, out, sm_scale, (float*)workspace, parts_floats, arrivals, (hipStream_t)stream,
+                              &fresh);
+  if (st != TKV_OK)  // nothing was launched: the cache is as it was
+    for (int b = 0; b < d->batch; ++b) c->seq_len_host[b] -= fresh.n_add.n[b];
+  return st;
 }
 
 // ---- tkv_quant_attn_decode for callers that cannot hand over a workspace -----------------

@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
         L.tkv_sparse_append_ragged.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32,
                                                C.POINTER(i32), vp]
         L.tkv_quant_attn_decode.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, C.c_float, vp, sz, vp]
+        L.tkv_quant_decode.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, i32, C.POINTER(i32), vp, vp,
+                                       C.c_float, vp, sz, vp]
         L.tkv_quant_attn_decode_static.argtypes = [C.POINTER(QuantDesc), C.POINTER(QuantCache), vp, vp, C.c_float, vp]
         L.tkv_sparse_cache_sizes.argtypes = [C.POINTER(SparseDesc), C.POINTER(sz), C.POINTER(sz)]
         L.tkv_sparse_append.argtypes = [C.POINTER(SparseDesc), C.POINTER(SparseCache), vp, vp, i32, vp]
@@ -207,6 +209,30 @@ class QuantLayer:
         _check(lib().tkv_quant_attn_decode(C.byref(d), C.byref(self.cache), q.data_ptr(), out.data_ptr(),
                                            float(sm_scale), self.workspace.data_ptr(), self.workspace_bytes,
                                            _stream(stream)), "tkv_quant_attn_decode")
+        return out
+
+    def decode(self, q: torch.Tensor, sm_scale: float, k_new: torch.Tensor, v_new: torch.Tensor, n_valid=None,
+               out: torch.Tensor | None = None, stream=None):
+        """tkv_quant_decode: the step's append and the attention over the grown cache in one call
+        (one launch unless the new tokens complete a quantization group)."""
+        d = self.desc
+        assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (d.batch, d.n_q_heads, d.head_dim)
+        assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16
+        assert k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous()
+        assert tuple(k_new.shape) == tuple(v_new.shape) and k_new.shape[0] == d.batch
+        assert tuple(k_new.shape[2:]) == (d.n_kv_heads, d.head_dim)
+        nv = None
+        if n_valid is not None:
+            nv = np.ascontiguousarray(n_valid, dtype=np.int32)
+            assert nv.shape == (d.batch,)
+        if out is None:
+            out = torch.empty_like(q)
+        _check(lib().tkv_quant_decode(C.byref(d), C.byref(self.cache), k_new.data_ptr(), v_new.data_ptr(),
+                                      int(k_new.shape[1]),
+                                      None if nv is None else nv.ctypes.data_as(C.POINTER(C.c_int32)),
+                                      q.data_ptr(), out.data_ptr(), float(sm_scale), self.workspace.data_ptr(),
+                                      self.workspace_bytes, _stream(stream)), "tkv_quant_decode")
         return out
 
     def attn_decode_static(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor, stream=None):

@@ -144,6 +144,18 @@ def test_call_errors_before_any_gpu_work(L):
     # workspace too small / NULL
     assert L.tkv_quant_attn_decode(C.byref(d), C.byref(cache), fake, fake, 0.1, fake, 16, None) == -4
     assert L.tkv_quant_attn_decode(C.byref(d), C.byref(cache), fake, None, 0.1, fake, 1 << 30, None) == -1
+    # the decode step in one call: the append's and the attention's checks, nothing enqueued, lengths kept
+    L.tkv_quant_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+    qd = lambda *a: L.tkv_quant_decode(C.byref(d), C.byref(cache), *a)
+    assert qd(None, fake, 1, None, fake, fake, 0.1, fake, 1 << 30, None) == -1
+    assert qd(fake, fake, -1, None, fake, fake, 0.1, fake, 1 << 30, None) == -1
+    assert qd(fake, fake, 1, None, None, fake, 0.1, fake, 1 << 30, None) == -1
+    assert qd(fake, fake, 1, None, fake, fake, 0.1, None, 1 << 30, None) == -1
+    assert qd(fake, fake, 1, None, fake, fake, 0.1, fake, 16, None) == -4
+    assert qd(fake, fake, 9, None, fake, fake, 0.1, fake, 1 << 30, None) == -3
+    assert qd(fake, fake, 4, C.addressof(nv), fake, fake, 0.1, fake, 1 << 30, None) == -1
+    assert lens[0] == 2040
     lens[0] = 5000
     assert L.tkv_quant_attn_decode(C.byref(d), C.byref(cache), fake, fake, 0.1, fake, 1 << 30, None) == -3
 

@@ -67,6 +67,59 @@ def test_incremental_append_equals_bulk(bits, g):
     assert pos == total
 
 
+@pytest.mark.parametrize("bits,g", MAIN_SETTINGS + [(1, 32)])
+def test_decode_step_in_one_call(bits, g):
+    """tkv_quant_decode over 70 single-token steps (which cross group boundaries: those steps take
+    the separate append) and a few multi-token ones: after every step the attention output is
+    within the bound of the oracle's over the grown prefix; the cache is the oracle's cache bit
+    for bit at checkpoints.  (1, 32) is served by the reference kernel only: always two calls.)"""
+    print(f"case decode step bits={bits} g={g}", flush=True)
+    n0 = 3000
+    steps = [1] * 70 + [3, 1, 1, 40, 1, 1]
+    total = n0 + sum(steps)
+    inp = make_layer(total, config=0, layer=0, seq=11)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=4096)
+    kd, vd = to_new(inp.k), to_new(inp.v)
+    layer.append(kd[:, :n0].contiguous(), vd[:, :n0].contiguous())
+    q = torch.from_numpy(inp.q)[None].cuda()
+    pos = n0
+    for i, s in enumerate(steps):
+        out = layer.decode(q, SM, kd[:, pos:pos + s].contiguous(), vd[:, pos:pos + s].contiguous())
+        pos += s
+        assert int(layer.seq_len[0]) == pos
+        if i % 9 == 0 or i >= 68:
+            ref = check_quant_cache(layer, 0, inp.k[:, :pos], inp.v[:, :pos])
+            err = attn_err(out[0], attention.quant_attention(inp.q, ref, SM))
+            print(f"   step {i} n={pos} err {err:.3e}", flush=True)
+            assert err <= TOL
+    assert pos == total
+
+
+def test_decode_step_ragged_batch_and_groups_of_eight():
+    """tkv_quant_decode on a padded batch (one sequence gets no token, one completes a group in
+    some steps) with 8 query heads per KV head (two workgroups per KV head read the new rows,
+    one writes them)."""
+    shape = HeadShape(16, 2, 128)
+    lens = [700, 129, 2040, 333]
+    adds = [[1, 0, 1, 1]] * 12 + [[2, 1, 0, 3]] * 3
+    grow = [sum(a[b] for a in adds) for b in range(4)]
+    inps = [make_layer(n + grow[b], shape=shape, seq=40 + b) for b, n in enumerate(lens)]
+    layer = tkv.QuantLayer(n_q_heads=16, n_kv_heads=2, bits=2, capacity=2560, batch=4)
+    layer.append(to_new_batch([i.k[:, :n] for i, n in zip(inps, lens)], 2048),
+                 to_new_batch([i.v[:, :n] for i, n in zip(inps, lens)], 2048), n_valid=lens)
+    q = torch.from_numpy(np.stack([i.q for i in inps])).cuda()
+    pos = list(lens)
+    for a in adds:
+        w = max(a)
+        kn = to_new_batch([i.k[:, p:p + x] for i, p, x in zip(inps, pos, a)], w)
+        vn = to_new_batch([i.v[:, p:p + x] for i, p, x in zip(inps, pos, a)], w)
+        out = layer.decode(q, SM, kn, vn, n_valid=a)
+        pos = [p + x for p, x in zip(pos, a)]
+    for b, inp in enumerate(inps):
+        ref = check_quant_cache(layer, b, inp.k[:, :pos[b]], inp.v[:, :pos[b]])
+        assert attn_err(out[b], attention.quant_attention(inp.q, ref, SM)) <= TOL
+
+
 @pytest.mark.parametrize("bits,g", [(2, 32), (1, 64)])
 def test_append_from_empty_in_small_steps(bits, g):
     inp = make_layer(400, seq=6)
