@@ -177,9 +177,9 @@ int32_t tkv_quant_attn_decode(const tkv_quant_desc* desc, const tkv_quant_cache*
  * out, sm_scale, workspace).  Same cache contents, same seq_len_host and the same results (to
  * tkv_quant_attn_decode's run-to-run variation) as the two calls one after the other.  When no
  * sequence completes a quantization group with these tokens -- all but one decode step in
- * group_size -- the whole step is ONE launch: the attention kernel reads the new rows from
- * k_new / v_new and writes them into the fp16 ring itself; otherwise the append's launches come
- * first.  k_new, v_new must stay valid until the call has run on the stream.  n_new == 0: the
+ * group_size -- the whole step is ONE launch: the attention kernel copies the new rows from
+ * k_new / v_new into the fp16 ring itself before it reads the ring; otherwise the append's
+ * launches come first.  k_new, v_new must stay valid until the call has run on the stream.  n_new == 0: the
  * attention alone.  Errors: those of the two calls; on an error nothing has been enqueued and
  * seq_len_host is unchanged, except that an error of the attention after a separate append
  * leaves the tokens appended.

@@ -63,8 +63,8 @@ struct MfmaParams {
   TkvSeqLens lens;
   TkvSeqLens chunks;  // split-K chunks of every sequence, in proportion to its length: blockIdx.x runs over all of them
   // The step's new tokens, when the call also appends them (Eq. 2): the last n_add[b] tokens of
-  // sequence b are read from k_new / v_new [B][n_stride][Hkv][D] instead of the fp16 ring, and
-  // copied into the ring by the workgroup that owns the head's tail.  k_new == nullptr: none.
+  // sequence b, rows k_new / v_new [B][n_stride][Hkv][D], are copied into the fp16 ring by the
+  // workgroups that own the head's tail before they read it.  k_new == nullptr: none.
   const __half* k_new;
   const __half* v_new;
   int32_t n_stride;
@@ -222,14 +222,8 @@ struct Cfg {
 // its partial result in `te`.  Lane = (token, channel half) for the logits, lane = channel
 // pair for the weighted sum.
 __device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint32_t* q_h, size_t bh, int nq, int n,
-                                 int n_old, int ring, int wave, int lane) {
+                                 int ring, int wave, int lane) {
   const int r_total = n - nq;
-  // row of token tok (K, or V): tokens from n_old on are the call's new ones
-  const int b = (int)(bh / (size_t)p.hkv), h = (int)(bh % (size_t)p.hkv);
-  auto row_of = [&](const __half* resid, const __half* fresh, int tok) -> const __half* {
-    return tok >= n_old ? fresh + (((size_t)b * p.n_stride + (size_t)(tok - n_old)) * p.hkv + h) * TKV_D
-                        : resid + (bh * ring + (size_t)(tok % ring)) * TKV_D;
-  };
   const int t = lane / 2, half = lane % 2;
   float M[4], Ls[4], acc[4][2];
 #pragma unroll
@@ -240,7 +234,7 @@ __device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint3
     float x[4];
     {
       const int tok = t0 + min(t, cnt - 1);
-      const uintx4* krow = reinterpret_cast<const uintx4*>(row_of(p.k_resid, p.k_new, tok) + 64 * half);
+      const uintx4* krow = reinterpret_cast<const uintx4*>(p.k_resid + (bh * ring + (size_t)(tok % ring)) * TKV_D + 64 * half);
       uintx4 kv[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) kv[i] = krow[i];
@@ -283,7 +277,7 @@ __device__ inline void tail_wave(const MfmaParams& p, TailEntry& te, const uint3
 #pragma unroll
     for (int y = 0; y < 32; ++y) {
       const int tokv = t0 + min(y, cnt - 1);  // rows past the end re-read the last one with weight 0
-      v2[y] = reinterpret_cast<const uint32_t*>(row_of(p.v_resid, p.v_new, tokv))[lane];
+      v2[y] = reinterpret_cast<const uint32_t*>(p.v_resid + (bh * ring + (size_t)(tokv % ring)) * TKV_D)[lane];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -430,6 +424,20 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   uint32_t q2[4];   // K-prep role: this lane owns channels 2*lane, 2*lane+1
   uintx4 bq[4];     // exact fp16 query as MFMA B operand (zero-point term)
   uintx4 az[4];     // zero-point rows of 16 groups as MFMA A operand
+  if (has_tail && p.k_new != nullptr) {
+    // Eq. 2 in this launch: the step's new rows go into the fp16 ring (slots whose tokens were
+    // quantized long ago: nothing reads them) before the workgroup's set-up barrier, behind which
+    // the tail waves read the ring.  Every workgroup that reads the head's tail writes the rows
+    // itself (the workgroups of a group of more than 4 query heads write the same bytes).
+    const int add = p.n_add.n[b], ring = p.residual + GRP;
+    for (int x = tid; x < add * 32; x += 64 * W) {
+      const int i = x / 32, kv = (x % 32) / 16, part = x % 16;
+      const uintx4 v = reinterpret_cast<const uintx4*>((kv ? p.v_new : p.k_new) +
+                                                       (((size_t)b * p.n_stride + i) * p.hkv + h) * TKV_D)[part];
+      __half* dst = const_cast<__half*>(kv ? p.v_resid : p.k_resid) + (bh * ring + (size_t)((n - add + i) % ring)) * TKV_D;
+      reinterpret_cast<uintx4*>(dst)[part] = v;
+    }
+  }
 #pragma unroll
   for (int hh = 0; hh < 4; ++hh)  // heads >= G re-read head G-1 (in bounds) and are zeroed below
     q2[hh] = reinterpret_cast<const uint32_t*>(qrow + (size_t)(hh < G ? hh : G - 1) * TKV_D)[lane];
@@ -500,21 +508,8 @@ __global__ __launch_bounds__(64 * W) void quant_attn_mfma_kernel(MfmaParams p) {
   __syncthreads();  // cz table, tail slots, query copy and group counter are in place
   TKV_PH();  // 2 set-up done
 
-  const int n_old = p.k_new != nullptr ? n - p.n_add.n[b] : n;
   if (has_tail && wave < kTailWaves && wave * 32 < n - nq)
-    tail_wave(p, tail_s[wave], q_h, bh, nq, n, n_old, p.residual + GRP, wave, lane);
-  if (has_tail && n_old < n && wave == W - 1 && blockIdx.y % split == 0) {
-    // Eq. 2: the new tokens' rows go into the fp16 ring, into slots whose tokens were quantized
-    // long ago (no workgroup of this launch reads them).  16 lanes per 256-byte row.
-    const int ring = p.residual + GRP;
-    for (int x = lane; x < (n - n_old) * 32; x += 64) {
-      const int i = x / 32, kv = (x % 32) / 16, part = x % 16;
-      const uintx4 v = reinterpret_cast<const uintx4*>((kv ? p.v_new : p.k_new) +
-                                                       (((size_t)b * p.n_stride + i) * p.hkv + h) * TKV_D)[part];
-      __half* dst = const_cast<__half*>(kv ? p.v_resid : p.k_resid) + (bh * ring + (size_t)((n_old + i) % ring)) * TKV_D;
-      reinterpret_cast<uintx4*>(dst)[part] = v;
-    }
-  }
+    tail_wave(p, tail_s[wave], q_h, bh, nq, n, p.residual + GRP, wave, lane);
   TKV_PH();  // 3 tail done
 
   // codes carry 2^-24, query side 2^kEK, so S = acc * 2^(24-kEK)
