@@ -422,6 +422,13 @@ extern "C" int32_t tkv_sparse_gather(const tkv_sparse_desc* d, const tkv_sparse_
   return TKV_OK;
 }
 
+namespace tkv {
+// tkv_sparse_topk.hip: the one-launch step's fetch + attention phase for a selection made earlier
+int32_t launch_fetch_attn(const tkv_sparse_desc* d, const TkvSeqLens& lens, const __half* q, const int32_t* topk_idx,
+                          const int32_t* topk_count, const __half* host_rows, const __half* local_rows, __half* out,
+                          float scale2, hipStream_t s);
+}  // namespace tkv
+
 namespace {
 // Attention over sinks + selected rows + window.  topk_idx_fused == nullptr: the selected
 // rows are in `staging`; otherwise they are fetched from the pinned host cache by the
@@ -472,6 +479,11 @@ int32_t sparse_attn_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c, 
     if (st != TKV_OK) return st;
     p.kv_host = (const __half*)host_dev;
     p.topk_idx = topk_idx_fused;
+    // Groups of up to 4 query heads: one workgroup per head whose 16 waves keep two passes of
+    // rows in flight each (the attention phase of tkv_sparse_decode): the link-bound loop without
+    // a cross-workgroup merge behind it.
+    st = tkv::launch_fetch_attn(d, p.lens, p.q, topk_idx_fused, topk_count, p.kv_host, p.kv_local, p.out, p.scale2, s);
+    if (st != TKV_E_UNSUPPORTED) return st;
     static const bool lds_ok =
         hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<true, 4>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kAttnMaxWaves * 32 * kRowPitch) == hipSuccess &&

@@ -89,6 +89,9 @@ struct TopkParams {
   // `summary`: read once by the workgroups that are through with the selection while the
   // heads' last workgroups are busy with the host link
   const __half* pf;
+  // (ATT kernels) non-zero: topk_idx / topk_count are INPUTS, the selection of an earlier call;
+  // the launch (one workgroup per sequence and KV head) only fetches the rows and attends
+  int32_t given;
 #ifdef TKV_PHASE
   long long* prof;
 #endif
@@ -506,7 +509,14 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
 
   // Scoring, listing and, in the head's last workgroup, the selection.  Returns true in the
   // workgroup that holds the head's selected tokens at the end (false everywhere else).
+  int given_cnt = 0;
   auto select_tokens = [&]() -> bool {
+    if (ATT && p.given != 0) {  // selected by an earlier call: copy the list, then fetch and attend
+      if (blockIdx.x != 0) return false;
+      given_cnt = max(0, min(p.topk_count[bh], p.top_k));
+      for (int i = tid; i < given_cnt; i += kThreads) sel_s[i] = out[i];
+      return true;
+    }
     if (k == 0 && blockIdx.x == 0) {  // nothing to select: the first workgroup reports the empty result
       for (int i = tid; i < p.top_k; i += kThreads) out[i] = -1;
       if (tid == 0) p.topk_count[bh] = 0;
@@ -1034,7 +1044,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   const bool holds_selection = select_tokens();
   if (ATT && holds_selection) {
     __syncthreads();  // the selected tokens are in LDS, the scratch areas of the selection are free
-    attend(sel_s, (int)k);
+    attend(sel_s, p.given != 0 ? given_cnt : (int)k);
   }
   if (p.app_k != nullptr && appends) append_tokens<DS>(p, b, h, tid);  // Eq. 2
 }
@@ -1101,6 +1111,7 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   p.n_sink = d->n_sink;
   p.n_window = d->n_window;
   p.capacity = d->capacity;
+  p.given = 0;
 #ifdef TKV_PHASE
   p.prof = (long long*)g_topk_prof;
 #endif
@@ -1174,6 +1185,36 @@ int32_t estimate_topk_launch(const tkv_sparse_desc* d, const tkv_sparse_cache* c
   return cm ? launch_fused<8, true, false>(p, grid, s) : launch_fused<8, false, false>(p, grid, s);
 }
 }  // namespace
+
+namespace tkv {
+// Fetch of the rows of a selection made earlier (topk_idx / topk_count of the same descriptor)
+// from the pinned host cache and exact attention, by the attention phase of the one-launch step:
+// one workgroup per (sequence, KV head).  Groups of up to 4 query heads, top_k <= 8192 (the list
+// is staged in LDS); TKV_E_UNSUPPORTED otherwise, nothing launched.
+int32_t launch_fetch_attn(const tkv_sparse_desc* d, const TkvSeqLens& lens, const __half* q, const int32_t* topk_idx,
+                          const int32_t* topk_count, const __half* host_rows, const __half* local_rows, __half* out,
+                          float scale2, hipStream_t s) {
+  if (d->n_q_heads / d->n_kv_heads > 4 || d->top_k > kBins) return TKV_E_UNSUPPORTED;
+  TopkParams p = {};
+  p.q = q;
+  p.topk_idx = const_cast<int32_t*>(topk_idx);
+  p.topk_count = const_cast<int32_t*>(topk_count);
+  p.hq = d->n_q_heads;
+  p.hkv = d->n_kv_heads;
+  p.top_k = d->top_k;
+  p.n_sink = d->n_sink;
+  p.n_window = d->n_window;
+  p.capacity = d->capacity;
+  p.tpw = kMaxTpw;
+  p.lens = lens;
+  p.att_host = host_rows;
+  p.att_local = local_rows;
+  p.att_out = out;
+  p.att_scale2 = scale2;
+  p.given = 1;
+  return launch_fused<16, false, true>(p, dim3(1, d->n_kv_heads, d->batch), s);
+}
+}  // namespace tkv
 
 extern "C" int32_t tkv_sparse_estimate_topk(const tkv_sparse_desc* d, const tkv_sparse_cache* c, const void* q,
                                             int32_t* topk_idx, int32_t* topk_count, void* workspace,
