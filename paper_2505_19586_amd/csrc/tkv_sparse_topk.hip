@@ -71,8 +71,8 @@ struct TopkParams {
   int32_t hq, hkv, top_k, n_sink, n_window, capacity;
   int32_t tpw;  // tokens per workgroup: a multiple of 16, at most kMaxTpw
   TkvSeqLens lens;
-  // Eq. 2 in the same launch (app_k non-null): the last workgroup of every (sequence, KV head)
-  // appends the step's new tokens; lens already counts them
+  // Eq. 2 in the same launch (app_k non-null): one workgroup of every (sequence, KV head), the
+  // first to have handed in its list, appends the step's new tokens; lens already counts them
   const __half* app_k;
   const __half* app_v;
   __half* app_host;     // device-visible view of the pinned host cache
@@ -299,13 +299,13 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
   // ---- exact attention (Eq. 3) over sinks + selected + window by this workgroup (ATT only):
   // fetch of the selected rows from the pinned host cache (the transfer that cannot be hidden,
   // Sec. 4.2) and attention in the launch that selected them.  A wave takes 4 attended tokens
-  // per pass (and has the next 4 on their way): one load instruction per 512-byte row (lanes 0..31 its K half, lanes 32..63 its V
-  // half: the request shape the host link serves fastest), the 4 x 4 logits
-  // are partial sums of 4 channels per lane, reduced over the 32 key lanes by a butterfly that
-  // halves the number of values with every exchange; online softmax per wave, the waves'
-  // results meet in LDS.  Rows of the step's new tokens come from the call's k_new / v_new (the
-  // workgroup that appends them runs beside this one), everything else that is resident from
-  // kv_local.  sel: the selected tokens in LDS (ascending), cnt of them.
+  // per pass and has the next two passes on their way: one load instruction per 512-byte row
+  // (lanes 0..31 its K half, lanes 32..63 its V half: the request shape the host link serves
+  // fastest), the 4 x 4 logits are partial sums of 4 channels per lane, reduced over the 32 key
+  // lanes by a butterfly that halves the number of values with every exchange; online softmax
+  // per wave, the waves' results meet in LDS.  Rows of the step's new tokens come from the
+  // call's k_new / v_new (another workgroup writes them to the cache meanwhile), everything else
+  // that is resident from kv_local.  sel: the selected tokens in LDS (ascending), cnt of them.
   auto attend = [&](const int32_t* sel, int cnt) {
     constexpr int R = 4;  // rows per wave and pass
     float* xs = reinterpret_cast<float*>(smem + kBins * 4) + wave * (R * 4);                   // [R][4] logits of this wave
