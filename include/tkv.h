@@ -30,8 +30,8 @@
  *     group g 32 or 64.  n_q_heads / n_kv_heads: any number from 1 to 8 (quantized layers:
  *     the attention kernels take a group 4 query heads at a time, and the parts of a group
  *     of 5 to 8 read the codes once each; sparse layers: a row is fetched once whatever the
- *     group, but tkv_sparse_decode is built for groups of up to 4 - TKV_E_UNSUPPORTED above,
- *     use the separate calls); any number for the dense preference score.
+ *     group; tkv_sparse_decode is one launch for groups of up to 4 and two above); any number
+ *     for the dense preference score.
  *   - Token t of sequence b, KV head h.  "group j" is tokens [g j, g j + g); codes are
  *     stored in "blocks" of 32 tokens whatever g is.
  */
@@ -293,6 +293,9 @@ int32_t tkv_sparse_append_estimate_topk(const tkv_sparse_desc* desc, tkv_sparse_
  * calls cannot overlap with anything: the workgroup that finishes a head's selection goes on to
  * fetch that head's rows and attends to them, so no launch boundary and no cross-workgroup
  * hand-off sits between the selection and the transfer that cannot be hidden.
+ * Groups of 5 to 8 query heads per KV head: the same call, same results, as two launches
+ * (tkv_sparse_append_estimate_topk, then tkv_sparse_gather_attn on this stream); the hint is
+ * not used then.
  * The key summary must be token-major (cache->key_summary).  workspace: as for
  * tkv_sparse_estimate_topk.  seq_len_host[b] += n_valid on success.
  * next_key_summary: NULL, or the key summary (device, same descriptor, hence same layout as

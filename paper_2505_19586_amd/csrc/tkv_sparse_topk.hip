@@ -1294,6 +1294,18 @@ extern "C" int32_t tkv_sparse_decode(const tkv_sparse_desc* d, tkv_sparse_cache*
   if ((uintptr_t)next_key_summary % 16 != 0) return TKV_E_INVAL;
   if (n_new < 0 || n_new > 8 || n_new > d->n_window) return TKV_E_INVAL;
   if (n_new > 0 && (!k_new || !v_new)) return TKV_E_INVAL;
+  if (d->n_q_heads / d->n_kv_heads > 4) {
+    // Groups of 5 to 8 query heads: the attention phase of the one-launch kernel holds four heads
+    // per lane.  Two launches instead: append + scoring + Top-K, then fetch + attention (the
+    // selection's outputs are the second launch's inputs; `staging` is not used on one stream).
+    if (!q || !topk_idx || !topk_count || !workspace) return TKV_E_INVAL;
+    st = n_new > 0 ? tkv_sparse_append_estimate_topk(d, c, k_new, v_new, n_new, n_valid_host, q, topk_idx, topk_count,
+                                                     workspace, workspace_bytes, stream)
+                   : tkv_sparse_estimate_topk(d, c, q, topk_idx, topk_count, workspace, workspace_bytes, stream);
+    if (st != TKV_OK) return st;
+    return tkv_sparse_gather_attn(d, c, q, topk_idx, topk_count, out, sm_scale, /*staging=*/workspace, workspace,
+                                  workspace_bytes, stream, stream);
+  }
   TopkParams app, att;
   for (int b = 0; b < d->batch; ++b) {
     const int64_t n0 = c->seq_len_host[b];

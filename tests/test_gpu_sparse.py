@@ -1,5 +1,7 @@
 """GPU parity of the sparse path against the oracle (through the C ABI).
 Top-K indices and counts: bit-exact.  Attention: <= 2e-3."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -167,11 +169,18 @@ def test_groups_of_up_to_eight_query_heads(shape, n_channels):
         _check_layer(layer, 0, inp, ch, q, layer.gather_attn(q, SM, gather_stream=side.cuda_stream))
         layer.gather()
         _check_layer(layer, 0, inp, ch, q, layer.attn(q, SM))
-        if shape.n_q_heads // shape.n_kv_heads > 4:
-            with pytest.raises(tkv.TkvError):        # the one-launch step holds four heads per lane
-                layer.decode(q, SM)
-        else:
-            _check_layer(layer, 0, inp, ch, q, layer.decode(q, SM))
+        # tkv_sparse_decode: one launch for groups of up to 4, two launches behind the same call above
+        layer.topk_idx.fill_(-7)
+        _check_layer(layer, 0, inp, ch, q, layer.decode(q, SM))
+        # ... and with the step's append: one more token, then the same checks on the grown prefix
+        if n == 6000:
+            rng = np.random.default_rng(n)
+            extra_k = rng.standard_normal((shape.n_kv_heads, 1, 128)).astype(np.float16)
+            extra_v = rng.standard_normal((shape.n_kv_heads, 1, 128)).astype(np.float16)
+            grown = dataclasses.replace(inp, k=np.concatenate([inp.k, extra_k], axis=1),
+                                        v=np.concatenate([inp.v, extra_v], axis=1))
+            out = layer.decode(q, SM, to_new(extra_k), to_new(extra_v))
+            _check_layer(layer, 0, grown, ch, q, out)
 
 
 def test_ties_beyond_the_on_chip_list():
