@@ -38,6 +38,16 @@ def test_quant_layer_full_size(n, bits, g):
     a = layer.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
     b = layer2.attn_decode(torch.from_numpy(inp.q)[None].cuda(), SM)
     assert attn_err(a[0], b[0].float().cpu().numpy().astype(np.float64)) <= TOL
+    # ... and a third through tkv_quant_decode (append inside the attention launch: what the
+    # benchmark's chained step runs), against the oracle over the grown cache
+    new3 = make_layer(1, config=1, layer=2, seq=bits)
+    out3 = layer.decode(torch.from_numpy(inp.q)[None].cuda(), SM, to_new(new3.k), to_new(new3.v))
+    k3 = np.concatenate([k2, new3.k], axis=1)
+    v3 = np.concatenate([v2, new3.v], axis=1)
+    ref3 = check_quant_cache(layer, 0, k3, v3)
+    err3 = attn_err(out3[0], attention.quant_attention(inp.q, ref3, SM))
+    print(f"   one-call step err {err3:.3e}", flush=True)
+    assert err3 <= TOL
 
 
 def test_sparse_layer_full_size():
