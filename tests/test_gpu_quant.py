@@ -95,6 +95,21 @@ def test_decode_step_in_one_call(bits, g):
     assert pos == total
 
 
+@pytest.mark.parametrize("bits,g", [(2, 32), (1, 64)])
+def test_decode_steps_from_an_empty_cache(bits, g):
+    """tkv_quant_decode from the first token on: no quantized group yet, then the first ones."""
+    total = 300
+    inp = make_layer(total, seq=9)
+    layer = tkv.QuantLayer(bits=bits, group_size=g, capacity=512)
+    kd, vd = to_new(inp.k), to_new(inp.v)
+    q = torch.from_numpy(inp.q)[None].cuda()
+    for pos in range(total):
+        out = layer.decode(q, SM, kd[:, pos:pos + 1].contiguous(), vd[:, pos:pos + 1].contiguous())
+        if pos in (0, 1, 31, 127, 128, 159, 160, 191, 192, 255, 299):
+            ref = check_quant_cache(layer, 0, inp.k[:, :pos + 1], inp.v[:, :pos + 1])
+            assert attn_err(out[0], attention.quant_attention(inp.q, ref, SM)) <= TOL, pos
+
+
 def test_decode_step_ragged_batch_and_groups_of_eight():
     """tkv_quant_decode on a padded batch (one sequence gets no token, one completes a group in
     some steps) with 8 query heads per KV head (two workgroups per KV head read the new rows,
