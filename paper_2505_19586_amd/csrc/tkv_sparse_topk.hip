@@ -696,12 +696,12 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     // Lists the keys kb of the share starting at token ts that lie in or above `bin`, in token
     // order, from entry ts of the head's list area; returns the list length (in every thread).
     uint2* list_g = p.ws.cand + bh * p.ws.cand_stride;  // the workgroup of share x owns entries [x * tpw, +tpw)
-    auto list_share = [&](int ts, uint32_t bin) -> uint32_t {
+    auto list_share = [&](int ts, uint32_t bin, bool first_use) -> uint32_t {
       unsigned long long mask[kSub];
   #pragma unroll
       for (int j = 0; j < kSub; ++j) mask[j] = __builtin_amdgcn_ballot_w64(kb[j] != 0u && (kb[j] >> kLowBits) >= bin);
       uint32_t before[kSub];
-      __syncthreads();  // s_cnt may still be read by the previous use
+      if (!first_use) __syncthreads();  // s_cnt may still be read by the previous use
       const uint32_t total = subtile_offsets(mask, &s_cnt[0][0], wave, lane, before);
   #pragma unroll
       for (int j = 0; j < kSub; ++j) {
@@ -735,10 +735,18 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
       }
       find_ranks<1, kOwn>(c, ranks, s_wtot, s_res, wave, lane);
       const uint32_t my_bin = s_res[0];
-      const uint32_t my_len = list_share(t0, my_bin);
+      const uint32_t my_len = list_share(t0, my_bin, true);
       if (tid == 0) st_agent(&cnt_g[blockIdx.x], (my_bin << kCountBits) | my_len);
     }
     TKV_PH(2);
+    // (what the head's last workgroup needs cleared is cleared by every workgroup here, under the
+    // wait for the list stores: one barrier less on the path that everything after waits for)
+    __shared__ uint32_t r1[2048], r2[2048], r3[1024];  // radix-select histograms: 11 + 11 + 10 key bits
+    __shared__ uint32_t lens[kThreads], lbin[kThreads];  // list length and bin L of every share
+    __shared__ uint32_t s_lmax, s_lmin, s_nsame;
+    for (int i = tid; i < 2048; i += kThreads) r1[i] = 0u, r2[i] = 0u;
+    r3[tid] = 0u;
+    if (tid == 0) s_lmax = 0u, s_lmin = kBins - 1, s_nsame = 0u;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
@@ -778,9 +786,6 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     // control words and the first `spec` entries of every list (entry e = i * kThreads + tid of
     // the round belongs to share e / spec, so ascending e is token order); spec is a power of two
     // a quarter above the nominal list length, the round never fetches more than kSub entries per thread.
-    __shared__ uint32_t r1[2048], r2[2048], r3[1024];  // radix-select histograms: 11 + 11 + 10 key bits
-    __shared__ uint32_t lens[kThreads], lbin[kThreads];  // list length and bin L of every share
-    __shared__ uint32_t s_lmax, s_lmin, s_nsame;
     int spec_shift = 0;
     {
       const uint32_t nominal = (3u * k) / (2u * (uint32_t)nblk) + 16u;
@@ -803,10 +808,6 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
       if (tid == 0) st_agent(&ctrl[kDone2], 0u);  // left zero for the next call
       for (int i = (int)k + tid; i < p.top_k; i += kThreads) out[i] = -1;
       if (tid == 0) p.topk_count[bh] = (int32_t)k;
-      for (int i = tid; i < 2048; i += kThreads) r1[i] = 0u, r2[i] = 0u;
-      r3[tid] = 0u;
-      if (tid == 0) s_lmax = 0u, s_lmin = kBins - 1;
-      __syncthreads();
       const uint32_t len = cw & ((1u << kCountBits) - 1u);
       lens[tid] = len;
       lbin[tid] = cw >> kCountBits;
@@ -834,7 +835,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     // of keys more than four binades above that bin being clamped: returns false if the k-th
     // key is among those (the caller then falls back to s1 = 21).
     // T: the key; take: how many keys equal to T belong to the k largest.  The three histograms
-    // must be zero.
+    // and s_nsame must be zero.
     auto kth_key = [&](auto each, int s1, uint32_t base, uint32_t& T, uint32_t& take) -> bool {
       uint32_t k_rem = k;
       auto search2 = [&](const uint32_t* hist, uint32_t& digit) {  // 2048 bins
@@ -859,8 +860,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
       // digits.
       const uint32_t n_same = r1[d1];
       if (n_same <= (uint32_t)kThreads) {
-        if (tid == 0) s_nsame = 0u;
-        __syncthreads();
+        // (s_nsame is zero: cleared with the histograms)
         each([&](uint32_t key) { if (key != 0u && (key >> s1) == top) r2[atomicAdd(&s_nsame, 1u)] = key; });
         __syncthreads();
         // the k_rem-th largest of them: the key v with fewer than k_rem keys above it and at least
@@ -960,6 +960,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
       __syncthreads();
       for (int i = tid; i < 2048; i += kThreads) r1[i] = 0u, r2[i] = 0u;
       r3[tid] = 0u;
+      if (tid == 0) s_nsame = 0u;
       if (tid < 64) {  // exclusive scan of the list lengths by one wave
         uint32_t carry = 0;
         for (int x0 = 0; x0 < nblk; x0 += 64) {
@@ -998,7 +999,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
         const int x = s_rep[r];
         const int ts = x * p.tpw, te = min(n, ts + p.tpw);
         score_share(ts, te, false, false, std::true_type{});
-        const uint32_t relen = list_share(ts, tbin);
+        const uint32_t relen = list_share(ts, tbin, false);
         if (tid == 0) lens[x] = relen, lbin[x] = tbin;
       }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the rebuilt lists are read back in round 1
