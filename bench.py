@@ -568,6 +568,19 @@ def run_step(args, tkv, torch, dev):
     torch.cuda.synchronize()
     dur["gather_in_step"] = dur["gather"]
     dur["gather"] = g0.elapsed_time(g1) * 1e3 / (2 * len(sparse_ids))
+    # scoring + Top-K alone, the same way: every sparse layer's summary (distinct, so each sweep comes
+    # from HBM), twice
+    for l in sparse_ids[:4]:
+        layers[l].estimate_topk(qs[l])
+    t0, t1 = ev(), ev()
+    t0.record()
+    for _ in range(2):
+        for l in sparse_ids:
+            layers[l].estimate_topk(qs[l])
+    t1.record()
+    torch.cuda.synchronize()
+    dur["topk_in_step"] = dur["topk"]
+    dur["topk"] = t0.elapsed_time(t1) * 1e3 / (2 * len(sparse_ids))
 
     quant_bytes = quant_bytes_of(args, lens)
     summary_bytes = 8 * tot * args.channels * 2
@@ -583,7 +596,7 @@ def run_step(args, tkv, torch, dev):
             "time_vs_read_sweep": dur["quant"] / dur["read_sweep"]}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {
-        "quant_attn_us": dur["quant"], "quant_attn_in_step_us": dur["quant_in_step"], "estimate_topk_us": dur["topk"], "gather_us": dur["gather"], "gather_in_step_us": dur["gather_in_step"],
+        "quant_attn_us": dur["quant"], "quant_attn_in_step_us": dur["quant_in_step"], "estimate_topk_us": dur["topk"], "estimate_topk_in_step_us": dur["topk_in_step"], "gather_us": dur["gather"], "gather_in_step_us": dur["gather_in_step"],
         "estimate_topk_GBs": summary_bytes / dur["topk"] / 1e3,
         "per_call_us": {"quant_attn": spread["quant"], "estimate_topk": spread["topk"], "gather": spread["gather"]},
         "other_schedule": None if ms_other is None else {
