@@ -339,7 +339,9 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
       const __half* kp = local0;
       const __half* vp = local0 + TKV_D;
       if (i0 >= n_sk && i0 + R <= n_sk + cnt) {  // (uniform) the common pass: selected tokens only, rows of the host cache
-        const int tok = sel[i0 - n_sk + (lane < R ? lane : 0)];
+        // (kept inside the cache whatever a caller's index list holds: with a given selection the
+        // entries are the caller's)
+        const int tok = min(max(sel[i0 - n_sk + (lane < R ? lane : 0)], 0), p.capacity - 1);
         kp = p.att_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D;
         vp = kp + TKV_D;
       } else {
@@ -348,7 +350,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
           int tok;
           bool host = false;
           if (i < n_sk) tok = i;
-          else if (i < n_sk + cnt) tok = sel[i - n_sk], host = true;
+          else if (i < n_sk + cnt) tok = min(max(sel[i - n_sk], 0), p.capacity - 1), host = true;
           else tok = w0 + (i - n_sk - cnt);
           if (host) {
             kp = p.att_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D;
