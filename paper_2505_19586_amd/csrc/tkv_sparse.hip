@@ -86,7 +86,8 @@ constexpr int kGatherRows = 4;  // rows in flight per wave
 __global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
   const int b = blockIdx.z, h = blockIdx.y;
   const size_t bh = (size_t)b * p.hkv + h;
-  const int cnt = p.topk_count[bh];
+  // (count and indices are the caller's data: kept inside the buffers whatever they hold)
+  const int cnt = min(max(p.topk_count[bh], 0), p.top_k);
   const int part = threadIdx.x % 64, wave = threadIdx.x / 64;
   constexpr int kPerBlock = 4 * kGatherRows;
   for (int r0 = blockIdx.x * kPerBlock; r0 < cnt; r0 += gridDim.x * kPerBlock) {
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
 #pragma unroll
     for (int j = 0; j < kGatherRows; ++j) {
       const int row = min(r0 + 4 * j + wave, cnt - 1);
-      const int tok = p.topk_idx[bh * p.top_k + row];
+      const int tok = min(max(p.topk_idx[bh * p.top_k + row], 0), p.capacity - 1);
       v[j] = reinterpret_cast<const uint2*>(p.kv_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D)[part];
     }
 #pragma unroll
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
   const size_t bh = (size_t)b * p.hkv + h;
   const int n = p.lens.n[b];
   const int n_sk = min(p.n_sink, n);
-  const int cnt = p.topk_count[bh];
+  const int cnt = min(max(p.topk_count[bh], 0), p.top_k);  // (the caller's data: kept inside the buffers)
   const int w0 = max(n - p.n_window, n_sk);
   const int n_att = n_sk + cnt + (n - w0);
 
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(SparseAttnParams p) {
       krow = p.kv_local + (bh * (p.n_sink + p.n_window) + i) * 2 * TKV_D;
     else if (i < n_sk + cnt) {
       if (FUSED) {
-        const int tok = p.topk_idx[bh * p.top_k + (i - n_sk)];
+        const int tok = min(max(p.topk_idx[bh * p.top_k + (i - n_sk)], 0), p.capacity - 1);
         krow = p.kv_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D;
       } else {
         krow = p.staging + (bh * p.top_k + (size_t)(i - n_sk)) * 2 * TKV_D;
