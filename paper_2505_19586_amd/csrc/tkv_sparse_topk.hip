@@ -311,7 +311,10 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     float* xs = reinterpret_cast<float*>(smem + kBins * 4) + wave * (R * 4);                   // [R][4] logits of this wave
     float* mrg = reinterpret_cast<float*>(smem + kBins * 4 + 1024 * 4);                         // [waves][4][TKV_D + 4]
     const int n_sk = min(p.n_sink, n), w0 = max(n - p.n_window, n_sk);
-    const int n_att = n_sk + cnt + (n - w0);
+    // order of the attended tokens: sinks, window, selected -- the resident rows first, worked on
+    // while the first host rows are on their way
+    const int n_res = n_sk + (n - w0);
+    const int n_att = n_res + cnt;
     const int n_old = p.app_k != nullptr ? n - p.app_add.n[b] : n;  // tokens below are in kv_local / the host cache
     const int n_loc = p.n_sink + p.n_window;
     const __half* local0 = p.att_local + bh * (size_t)n_loc * 2 * TKV_D;
@@ -338,10 +341,10 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
     auto fetch = [&](int i0, uint2 (&r)[R]) {
       const __half* kp = local0;
       const __half* vp = local0 + TKV_D;
-      if (i0 >= n_sk && i0 + R <= n_sk + cnt) {  // (uniform) the common pass: selected tokens only, rows of the host cache
+      if (i0 >= n_res && i0 + R <= n_att) {  // (uniform) the common pass: selected tokens only, rows of the host cache
         // (kept inside the cache whatever a caller's index list holds: with a given selection the
         // entries are the caller's)
-        const int tok = min(max(sel[i0 - n_sk + (lane < R ? lane : 0)], 0), p.capacity - 1);
+        const int tok = min(max(sel[i0 - n_res + (lane < R ? lane : 0)], 0), p.capacity - 1);
         kp = p.att_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D;
         vp = kp + TKV_D;
       } else {
@@ -350,8 +353,8 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(TopkParams p) {
           int tok;
           bool host = false;
           if (i < n_sk) tok = i;
-          else if (i < n_sk + cnt) tok = min(max(sel[i - n_sk], 0), p.capacity - 1), host = true;
-          else tok = w0 + (i - n_sk - cnt);
+          else if (i < n_res) tok = w0 + (i - n_sk);
+          else tok = min(max(sel[i - n_res], 0), p.capacity - 1), host = true;
           if (host) {
             kp = p.att_host + (bh * p.capacity + (size_t)tok) * 2 * TKV_D;
             vp = kp + TKV_D;
